@@ -1,0 +1,240 @@
+/*
+ * tw.h -- C ABI of libtw: the single-GPU hot path that TokenWeave (arXiv
+ * 2505.11329) builds its compute-communication overlap around, written for
+ * AMD Instinct MI355X (gfx950):
+ *
+ *   - the fused "reduce over the P tensor-parallel partials + residual add +
+ *     RMSNorm" of one GPU's share of the token rows, in one pass over HBM
+ *     (Section 4.3 and Appendix A, Listing 1), confined to a CU budget so it
+ *     can co-run with compute (Section 4.3, last paragraph; Fig. 9);
+ *   - the two-way token split launched on two streams (Section 4, Section
+ *     4.1.2 "Overlapped Execution");
+ *   - a bf16 GEMM standing in for the other split's projection, and the
+ *     fused-kernel-next-to-GEMM launch that one step of the weave consists of
+ *     (Fig. 7b).
+ *
+ * The in-switch reduction of the paper has no counterpart on this hardware:
+ * the P peer partials are P buffers in local HBM and the reading compute unit
+ * does the sum.
+ *
+ * Conventions for every entry point
+ *   - All data pointers are DEVICE pointers unless a parameter says "host".
+ *     bf16 tensors are row-major, contiguous, 16-byte aligned.
+ *   - The caller owns all memory and all streams. libtw keeps no pointer after
+ *     a call returns. Pointer arrays and argument structs are read on the host
+ *     during the call and may live on the caller's stack.
+ *   - Calls enqueue work on the given streams and return; nothing inside
+ *     synchronises the device. `stream` arguments are hipStream_t values passed
+ *     as void*; NULL means the default (null) stream.
+ *   - Errors are reported through the return code only. Every argument check
+ *     happens on the host before the first HIP call, so an invalid call
+ *     launches nothing and works (returns its error) on a machine without a GPU.
+ *   - Results are a pure function of each row's inputs: bits do not depend on
+ *     cu_budget, on N, on the stream, or on whether and where rows were split.
+ *   - Thread safety: calls may be made from several host threads; work given to
+ *     one stream is ordered by that stream as usual.
+ */
+#ifndef TW_H_
+#define TW_H_
+
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum tw_status {
+    TW_OK = 0,
+    TW_ERR_NULL = 1,        /* a required pointer is NULL                         */
+    TW_ERR_SHAPE = 2,       /* a size is negative, zero where it must not be, or out of range */
+    TW_ERR_ALIGN = 3,       /* a data pointer is not 16-byte aligned              */
+    TW_ERR_ALIAS = 4,       /* buffers overlap in a way that is not allowed       */
+    TW_ERR_UNSUPPORTED = 5, /* a valid request this build has no kernel for       */
+    TW_ERR_SPLIT = 6,       /* split_row outside [0, N], or the two streams are the same */
+    TW_ERR_HIP = 7          /* a HIP call failed; see tw_last_hip_error()         */
+} tw_status;
+
+#define TW_MAX_P 16          /* most partial buffers one call can sum              */
+#define TW_MAX_H 65536       /* largest hidden size the fused kernel handles       */
+
+/*
+ * Arguments of one fused step (Appendix A, Listing 1; residual add fused as in
+ * the footnote of Section 1). For every row r < N and column c < H:
+ *
+ *   x[r,c]            = (partials[0][r,c] + ... + partials[P-1][r,c]) + residual[r,c]
+ *   residual_out[r,c] = bf16(x[r,c])
+ *   out[r,c]          = bf16( x[r,c] * rsqrt(mean_c(x[r,c]^2) + eps) * weight[c] )
+ *
+ * Inputs are bf16; the sum is accumulated in fp32 in the order written above;
+ * the mean of squares is taken over the UNROUNDED fp32 x, divided by H, with
+ * eps inside the root; the scaling is (x * s) * weight in fp32; each output is
+ * rounded once, to nearest even. NaN/Inf propagate by IEEE rules within their
+ * row and never reach another row.
+ *
+ *   partials      host array of P device pointers, each bf16 [N x H]
+ *   residual      device bf16 [N x H]
+ *   weight        device bf16 [H]
+ *   eps           finite, >= 0
+ *   N             rows (tokens) >= 0; N == 0 is TW_OK and launches nothing
+ *   H             hidden size: a multiple of 8 with 8 <= H <= TW_MAX_H
+ *   P             1 <= P <= TW_MAX_P
+ *   cu_budget     number of compute units the kernel may occupy: the launch is
+ *                 a persistent grid of that many workgroups, each sized so that
+ *                 no two share a compute unit. <= 0, or >= the device's CU
+ *                 count, means the whole device.
+ *   out           device bf16 [N x H]
+ *   residual_out  device bf16 [N x H]
+ *
+ * Aliasing: residual_out may be the same buffer as residual (the paper updates
+ * the residual stream in place) and out may be the same buffer as one of the
+ * partials (the paper writes the result back into the communication buffer);
+ * "the same buffer" means the same start address. Any other overlap between an
+ * output and an input or between the two outputs is TW_ERR_ALIAS. Inputs may
+ * overlap each other freely.
+ */
+typedef struct tw_fused_args {
+    const void *const *partials;
+    const void *residual;
+    const void *weight;
+    float eps;
+    int64_t N;
+    int64_t H;
+    int P;
+    int cu_budget;
+    void *out;
+    void *residual_out;
+} tw_fused_args;
+
+/* One fused step over all N rows, enqueued on `stream`. */
+tw_status tw_reduce_add_rmsnorm(const void *const *partials, const void *residual,
+                                const void *weight, float eps, int64_t N, int64_t H,
+                                int P, int cu_budget, void *out, void *residual_out,
+                                void *stream);
+
+/*
+ * Same as tw_reduce_add_rmsnorm, and in addition workgroup g of the launch
+ * writes, once, the hardware placement it ran on to hw_ids[2*g] (the raw HW_ID
+ * register) and hw_ids[2*g+1] (the raw XCC_ID register), so that "confined to
+ * cu_budget compute units" can be evidenced (Section 4.3 / Fig. 9 vary the
+ * number of SMs the kernel gets). hw_ids: device uint32 [2 * hw_ids_len];
+ * hw_ids_len must be at least the grid size that tw_fused_grid() returns.
+ */
+tw_status tw_reduce_add_rmsnorm_traced(const void *const *partials, const void *residual,
+                                       const void *weight, float eps, int64_t N, int64_t H,
+                                       int P, int cu_budget, void *out, void *residual_out,
+                                       uint32_t *hw_ids, int64_t hw_ids_len, void *stream);
+
+/* Number of workgroups the fused kernel is launched with for these sizes on the
+ * current device (0 if N == 0; -1 if the arguments are invalid or no device). */
+int64_t tw_fused_grid(int64_t N, int64_t H, int cu_budget);
+
+/*
+ * Two-way token split (Section 4: prefix split T_a, suffix split T_b; every
+ * operation here is token-level, so the split is a pure row-range split).
+ * Rows [0, split_row) are enqueued on stream_a and rows [split_row, N) on
+ * stream_b, each as its own launch with args->cu_budget compute units.
+ *
+ *   parent         a stream whose already-enqueued work both halves must wait
+ *                  for: an event is recorded on it and both streams wait on that
+ *                  event. NULL is a valid value (the default stream), which is
+ *                  why parent_is_set says whether there is a parent at all.
+ *   parent_is_set  0: no fork and no join; `parent` is ignored.
+ *   join           non-zero: after both launches `parent` is made to wait for
+ *                  both halves.
+ *
+ * split_row == 0 or == N gives a single launch on stream_b or stream_a.
+ * stream_a and stream_b must differ when both halves are non-empty
+ * (TW_ERR_SPLIT otherwise). The results are bit-identical to the unsplit call.
+ */
+tw_status tw_split_launch(const tw_fused_args *args, int64_t split_row, void *stream_a,
+                          void *stream_b, void *parent, int parent_is_set, int join);
+
+/*
+ * Where to cut N rows in two: ceil(N/2) rounded up to a multiple of `multiple`
+ * (the prefix split takes the extra rows, Appendix A "Smart-Splitting"; split
+ * offsets there are multiples of 64), clamped to N. A result equal to N means
+ * "do not split". multiple <= 0 is treated as 1; N <= 0 gives 0. Host only.
+ */
+int64_t tw_split_point(int64_t N, int64_t multiple);
+
+/*
+ * GEMM stand-in for the other split's projection (the compute that overlaps
+ * the fused kernel in Fig. 7b): C = A * B with bf16 inputs, fp32 accumulation,
+ * one rounding to bf16 at the store.
+ *
+ *   A         device bf16 [M x K], row-major
+ *   B         device bf16; b_layout says how B(k, n) is stored:
+ *             TW_B_NK: [N x K] row-major, i.e. B(k,n) at B[n*K + k] -- the way a
+ *                      linear layer's weight [out_features x in_features] is kept;
+ *             TW_B_KN: [K x N] row-major, B(k,n) at B[k*N + n].
+ *   C         device bf16 [M x N], row-major; must not overlap A or B
+ *   M, N, K   >= 0 (any zero: TW_OK, C untouched unless K == 0 and M*N > 0, in
+ *             which case C is zero-filled); K must be a multiple of 8 and N a
+ *             multiple of 8 (16-byte vectors), else TW_ERR_UNSUPPORTED
+ *   cu_budget persistent grid of at most this many workgroups (one per compute
+ *             unit); <= 0 or >= the CU count: whole device
+ */
+#define TW_B_NK 0
+#define TW_B_KN 1
+
+typedef struct tw_gemm_args {
+    const void *A;
+    const void *B;
+    void *C;
+    int64_t M;
+    int64_t N;
+    int64_t K;
+    int b_layout;
+    int cu_budget;
+} tw_gemm_args;
+
+tw_status tw_gemm_bf16(const void *A, const void *B, void *C, int64_t M, int64_t N, int64_t K,
+                       int b_layout, int cu_budget, void *stream);
+
+/*
+ * One step of the weave (Fig. 7b, Section 4.1.2): the fused kernel of one split
+ * on stream_comm next to the GEMM of the other split on stream_compute. If
+ * parent_is_set, both first wait for the work already enqueued on `parent`;
+ * the fused kernel is enqueued first so that its few workgroups are placed
+ * before the GEMM fills the remaining compute units. If join is non-zero,
+ * `parent` then waits for both. The two streams must differ.
+ * `fused` describes the rows of the split being normalised (its own pointers
+ * and N); `gemm` the other split's product. Either may be NULL to leave that
+ * side out.
+ */
+tw_status tw_overlap_launch(const tw_fused_args *fused, const tw_gemm_args *gemm,
+                            void *stream_comm, void *stream_compute, void *parent,
+                            int parent_is_set, int join);
+
+/*
+ * Measurement aid (not part of the method): a streaming kernel with the same
+ * persistent, CU-budgeted launch shape as the fused kernel, used to measure
+ * what a given number of compute units can pull from / push to HBM, and as the
+ * copy of known size against which hardware byte counters are scaled.
+ *   mode TW_PROBE_READ: reads `bytes` from src (dst gets one 16-byte word per
+ *        wave so the loads cannot be dropped; dst needs 256 bytes per compute
+ *        unit of the device, 64 KiB on a 256-CU part);
+ *   mode TW_PROBE_COPY: dst[0..bytes) = src[0..bytes);
+ *   mode TW_PROBE_WRITE: dst[0..bytes) = a constant pattern (src unused, may be NULL).
+ * bytes must be a multiple of 16; pointers 16-byte aligned; src and dst must
+ * not overlap.
+ */
+#define TW_PROBE_READ 0
+#define TW_PROBE_COPY 1
+#define TW_PROBE_WRITE 2
+tw_status tw_hbm_probe(const void *src, void *dst, int64_t bytes, int mode, int cu_budget,
+                       void *stream);
+
+/* Compute units of the current device; -1 when no device can be queried. */
+int tw_device_cu_count(void);
+/* Static, NUL-terminated description of a status code (never NULL). */
+const char *tw_status_str(tw_status s);
+/* Static version string. */
+const char *tw_version(void);
+/* Raw hipError_t behind the last TW_ERR_HIP returned on the calling thread (0 if none). */
+int tw_last_hip_error(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* TW_H_ */

@@ -1,0 +1,251 @@
+"""ctypes binding of include/tw.h. Argument marshalling only.
+
+Tensors are torch tensors on the GPU (bfloat16, contiguous); the binding passes
+their data_ptr() and sizes. Streams are torch.cuda.Stream objects (or None for
+the current stream). Every function raises TwError on a non-zero status.
+"""
+import ctypes
+import os
+import threading
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+_LIB_PATH = os.path.join(_HERE, "libtw.so")
+_lock = threading.Lock()
+_lib = None
+
+STATUS = {0: "TW_OK", 1: "TW_ERR_NULL", 2: "TW_ERR_SHAPE", 3: "TW_ERR_ALIGN", 4: "TW_ERR_ALIAS",
+          5: "TW_ERR_UNSUPPORTED", 6: "TW_ERR_SPLIT", 7: "TW_ERR_HIP"}
+PROBE_READ, PROBE_COPY, PROBE_WRITE = 0, 1, 2
+B_NK, B_KN = 0, 1
+MAX_P = 16
+
+_vp = ctypes.c_void_p
+_i64 = ctypes.c_int64
+
+
+class FusedArgs(ctypes.Structure):
+    """struct tw_fused_args"""
+    _fields_ = [("partials", ctypes.POINTER(_vp)), ("residual", _vp), ("weight", _vp),
+                ("eps", ctypes.c_float), ("N", _i64), ("H", _i64), ("P", ctypes.c_int),
+                ("cu_budget", ctypes.c_int), ("out", _vp), ("residual_out", _vp)]
+
+
+class GemmArgs(ctypes.Structure):
+    """struct tw_gemm_args"""
+    _fields_ = [("A", _vp), ("B", _vp), ("C", _vp), ("M", _i64), ("N", _i64), ("K", _i64),
+                ("b_layout", ctypes.c_int), ("cu_budget", ctypes.c_int)]
+
+
+class TwError(RuntimeError):
+    def __init__(self, status, what):
+        self.status = int(status)
+        msg = "%s failed: %s (%s)" % (what, STATUS.get(self.status, self.status), status_str(self.status))
+        if self.status == 7:
+            msg += " hipError=%d" % lib().tw_last_hip_error()
+        super().__init__(msg)
+
+
+def library_path():
+    return _LIB_PATH
+
+
+def lib():
+    """The loaded libtw.so (built with hipcc first if it is not there)."""
+    global _lib
+    with _lock:
+        if _lib is not None:
+            return _lib
+        if not os.path.exists(_LIB_PATH):
+            from .build import build_libtw
+            build_libtw()
+        L = ctypes.CDLL(_LIB_PATH)
+        fused_sig = [ctypes.POINTER(_vp), _vp, _vp, ctypes.c_float, _i64, _i64, ctypes.c_int,
+                     ctypes.c_int, _vp, _vp]
+        L.tw_reduce_add_rmsnorm.argtypes = fused_sig + [_vp]
+        L.tw_reduce_add_rmsnorm.restype = ctypes.c_int
+        L.tw_reduce_add_rmsnorm_traced.argtypes = fused_sig + [_vp, _i64, _vp]
+        L.tw_reduce_add_rmsnorm_traced.restype = ctypes.c_int
+        L.tw_fused_grid.argtypes = [_i64, _i64, ctypes.c_int]
+        L.tw_fused_grid.restype = _i64
+        L.tw_split_launch.argtypes = [ctypes.POINTER(FusedArgs), _i64, _vp, _vp, _vp, ctypes.c_int, ctypes.c_int]
+        L.tw_split_launch.restype = ctypes.c_int
+        L.tw_split_point.argtypes = [_i64, _i64]
+        L.tw_split_point.restype = _i64
+        L.tw_gemm_bf16.argtypes = [_vp, _vp, _vp, _i64, _i64, _i64, ctypes.c_int, ctypes.c_int, _vp]
+        L.tw_gemm_bf16.restype = ctypes.c_int
+        L.tw_overlap_launch.argtypes = [ctypes.POINTER(FusedArgs), ctypes.POINTER(GemmArgs), _vp, _vp, _vp,
+                                        ctypes.c_int, ctypes.c_int]
+        L.tw_overlap_launch.restype = ctypes.c_int
+        L.tw_hbm_probe.argtypes = [_vp, _vp, _i64, ctypes.c_int, ctypes.c_int, _vp]
+        L.tw_hbm_probe.restype = ctypes.c_int
+        L.tw_device_cu_count.argtypes = []
+        L.tw_device_cu_count.restype = ctypes.c_int
+        L.tw_status_str.argtypes = [ctypes.c_int]
+        L.tw_status_str.restype = ctypes.c_char_p
+        L.tw_version.argtypes = []
+        L.tw_version.restype = ctypes.c_char_p
+        L.tw_last_hip_error.argtypes = []
+        L.tw_last_hip_error.restype = ctypes.c_int
+        _lib = L
+        return L
+
+
+def _check(status, what):
+    if status != 0:
+        raise TwError(status, what)
+
+
+def status_str(status):
+    return lib().tw_status_str(int(status)).decode()
+
+
+def version():
+    return lib().tw_version().decode()
+
+
+def device_cu_count():
+    return lib().tw_device_cu_count()
+
+
+def split_point(N, multiple):
+    return int(lib().tw_split_point(int(N), int(multiple)))
+
+
+def fused_grid(N, H, cu_budget=0):
+    return int(lib().tw_fused_grid(int(N), int(H), int(cu_budget)))
+
+
+# ---- marshalling helpers -------------------------------------------------
+
+def _stream_handle(stream):
+    """hipStream_t of a torch stream; None means torch's current stream."""
+    import torch
+    if stream is None:
+        stream = torch.cuda.current_stream()
+    return _vp(stream.cuda_stream)
+
+
+def _bf16_ptr(t, name, shape=None):
+    import torch
+    if not isinstance(t, torch.Tensor) or not t.is_cuda:
+        raise TypeError("%s must be a GPU tensor" % name)
+    if t.dtype != torch.bfloat16:
+        raise TypeError("%s must be bfloat16, got %s" % (name, t.dtype))
+    if not t.is_contiguous():
+        raise ValueError("%s must be contiguous" % name)
+    if shape is not None and tuple(t.shape) != tuple(shape):
+        raise ValueError("%s has shape %s, expected %s" % (name, tuple(t.shape), tuple(shape)))
+    return _vp(t.data_ptr())
+
+
+def _fused_pack(partials, residual, weight, eps, cu_budget, out, residual_out):
+    import torch
+    if residual.dim() != 2:
+        raise ValueError("residual must be [N, H]")
+    N, H = residual.shape
+    P = len(partials)
+    if out is None:
+        out = torch.empty_like(residual)
+    if residual_out is None:
+        residual_out = torch.empty_like(residual)
+    arr = (_vp * max(P, 1))(*[_bf16_ptr(p, "partials[%d]" % i, (N, H)) for i, p in enumerate(partials)])
+    args = FusedArgs(ctypes.cast(arr, ctypes.POINTER(_vp)), _bf16_ptr(residual, "residual"),
+                     _bf16_ptr(weight, "weight", (H,)), float(eps), N, H, P, int(cu_budget),
+                     _bf16_ptr(out, "out", (N, H)), _bf16_ptr(residual_out, "residual_out", (N, H)))
+    return args, arr, out, residual_out
+
+
+# ---- entry points ----------------------------------------------------------
+
+def reduce_add_rmsnorm(partials, residual, weight, eps, cu_budget=0, out=None, residual_out=None,
+                       stream=None):
+    """tw_reduce_add_rmsnorm. Returns (out, residual_out)."""
+    a, keep, out, residual_out = _fused_pack(partials, residual, weight, eps, cu_budget, out, residual_out)
+    _check(lib().tw_reduce_add_rmsnorm(a.partials, a.residual, a.weight, a.eps, a.N, a.H, a.P,
+                                       a.cu_budget, a.out, a.residual_out, _stream_handle(stream)),
+           "tw_reduce_add_rmsnorm")
+    return out, residual_out
+
+
+def reduce_add_rmsnorm_traced(partials, residual, weight, eps, cu_budget=0, out=None,
+                              residual_out=None, stream=None):
+    """tw_reduce_add_rmsnorm_traced. Returns (out, residual_out, hw_ids int32 [grid, 2])."""
+    import torch
+    a, keep, out, residual_out = _fused_pack(partials, residual, weight, eps, cu_budget, out, residual_out)
+    grid = max(fused_grid(a.N, a.H, cu_budget), 1)
+    hw = torch.zeros((grid, 2), dtype=torch.int32, device=residual.device)
+    _check(lib().tw_reduce_add_rmsnorm_traced(a.partials, a.residual, a.weight, a.eps, a.N, a.H, a.P,
+                                              a.cu_budget, a.out, a.residual_out, _vp(hw.data_ptr()),
+                                              grid, _stream_handle(stream)),
+           "tw_reduce_add_rmsnorm_traced")
+    return out, residual_out, hw
+
+
+def split_launch(partials, residual, weight, eps, split_row, stream_a, stream_b, cu_budget=0,
+                 out=None, residual_out=None, parent=None, use_parent=True, join=True):
+    """tw_split_launch. parent=None with use_parent=True means torch's current stream."""
+    a, keep, out, residual_out = _fused_pack(partials, residual, weight, eps, cu_budget, out, residual_out)
+    _check(lib().tw_split_launch(ctypes.byref(a), int(split_row), _stream_handle(stream_a),
+                                 _stream_handle(stream_b),
+                                 _stream_handle(parent) if use_parent else _vp(None),
+                                 1 if use_parent else 0, 1 if join else 0),
+           "tw_split_launch")
+    return out, residual_out
+
+
+def _gemm_pack(A, B, C, b_layout, cu_budget):
+    import torch
+    if A.dim() != 2 or B.dim() != 2:
+        raise ValueError("A and B must be matrices")
+    M, K = A.shape
+    if b_layout == B_NK:
+        N = B.shape[0]
+        _bf16_ptr(B, "B", (N, K))
+    elif b_layout == B_KN:
+        N = B.shape[1]
+        _bf16_ptr(B, "B", (K, N))
+    else:
+        raise ValueError("b_layout must be B_NK or B_KN")
+    if C is None:
+        C = torch.empty((M, N), dtype=torch.bfloat16, device=A.device)
+    g = GemmArgs(_bf16_ptr(A, "A"), _bf16_ptr(B, "B"), _bf16_ptr(C, "C", (M, N)), M, N, K,
+                 int(b_layout), int(cu_budget))
+    return g, C
+
+
+def gemm_bf16(A, B, C=None, b_layout=B_NK, cu_budget=0, stream=None):
+    """tw_gemm_bf16. Returns C."""
+    g, C = _gemm_pack(A, B, C, b_layout, cu_budget)
+    _check(lib().tw_gemm_bf16(g.A, g.B, g.C, g.M, g.N, g.K, g.b_layout, g.cu_budget,
+                              _stream_handle(stream)), "tw_gemm_bf16")
+    return C
+
+
+def overlap_launch(fused, gemm, stream_comm, stream_compute, parent=None, use_parent=True, join=True):
+    """tw_overlap_launch. `fused` is a dict(partials, residual, weight, eps, cu_budget, out,
+    residual_out) or None; `gemm` a dict(A, B, C, b_layout, cu_budget) or None.
+    Returns (out, residual_out, C) with None for the side left out."""
+    fa = ga = None
+    out = residual_out = C = None
+    keep = None
+    if fused is not None:
+        fa, keep, out, residual_out = _fused_pack(fused["partials"], fused["residual"], fused["weight"],
+                                                  fused["eps"], fused.get("cu_budget", 0),
+                                                  fused.get("out"), fused.get("residual_out"))
+    if gemm is not None:
+        ga, C = _gemm_pack(gemm["A"], gemm["B"], gemm.get("C"), gemm.get("b_layout", B_NK),
+                           gemm.get("cu_budget", 0))
+    _check(lib().tw_overlap_launch(ctypes.byref(fa) if fa is not None else None,
+                                   ctypes.byref(ga) if ga is not None else None,
+                                   _stream_handle(stream_comm), _stream_handle(stream_compute),
+                                   _stream_handle(parent) if use_parent else _vp(None),
+                                   1 if use_parent else 0, 1 if join else 0),
+           "tw_overlap_launch")
+    return out, residual_out, C
+
+
+def hbm_probe(src, dst, nbytes, mode, cu_budget=0, stream=None):
+    """tw_hbm_probe on two GPU tensors of any dtype (byte counts are explicit)."""
+    _check(lib().tw_hbm_probe(_vp(src.data_ptr()) if src is not None else _vp(None), _vp(dst.data_ptr()),
+                              int(nbytes), int(mode), int(cu_budget), _stream_handle(stream)),
+           "tw_hbm_probe")

@@ -1,0 +1,506 @@
+// Fused reduce over P partials + residual add + RMSNorm for gfx950
+// (TokenWeave, arXiv 2505.11329: Section 4.3 and Appendix A, Listing 1).
+//
+// Per token row: x = (p_0 + ... + p_{P-1}) + residual in fp32; residual_out =
+// bf16(x); s = rsqrt(mean(x^2) + eps); out = bf16((x * s) * weight). The paper's
+// kernel lets the switch do the sum and re-reads the residual for the second
+// loop; here the reading compute unit does the sum and x stays in registers, so
+// every input byte is read once and every output byte written once.
+//
+// Shape of the launch
+//   - One workgroup of 1024 threads (16 wave64) per compute unit, a persistent
+//     grid of `budget` workgroups striding over groups of rows (Listing 1's
+//     "token_id = blockIdx.x + iter * gridDim.x"). Each workgroup asks for more
+//     than half of a compute unit's LDS, so two can never share one: the grid
+//     size IS the number of compute units occupied.
+//   - A row is covered by TPR = min(1024, pow2ceil(H/8)) threads, each owning
+//     VPT 16-byte vector columns (8 bf16); a workgroup handles 1024/TPR rows per
+//     loop trip. The thread->column map and the reduction tree depend on H
+//     only, never on N, the grid or the row's position: the same row gives the
+//     same bits in any launch (split or not, any budget).
+//   - Loads are software-pipelined two "chunks" deep (a chunk = the P+1 vectors
+//     that feed one output vector): the loads of chunk q+2 are issued as soon as
+//     chunk q has been summed, before the row's reduction and barrier, so a
+//     thread always has P+1 .. 2(P+1) 16-byte loads in flight.
+//   - Row sum of squares: per-thread fp32 FMAs, xor-butterfly across the lanes of
+//     a wave (every lane ends with the same bits), and for rows wider than a
+//     wave one LDS slot per wave and one barrier; slots are double-buffered by
+//     row parity so one barrier per row suffices.
+#include <atomic>
+
+#include "tw_internal.h"
+
+namespace tw {
+
+static constexpr int kThreads = 1024;
+static constexpr int kWaves = kThreads / 64;
+// Dynamic LDS each workgroup requests so that only one fits on a compute unit
+// (gfx950 has 160 KiB per CU).
+static constexpr unsigned kOccupancyPadBytes = 96 * 1024;
+// One launch addresses its tensors with 32-bit byte offsets; longer batches are
+// cut into several launches on the host (rows are independent).
+static constexpr int64_t kMaxLaunchBytes = int64_t(1) << 31;
+
+// 16 bytes = 8 bf16, the unit of every load and store
+typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+
+struct FusedParams {
+    const void *partials[TW_MAX_P];
+    const void *residual;
+    const void *weight;
+    void *out;
+    void *residual_out;
+    uint32_t *hw_ids;
+    uint32_t n_bytes;      // rows of this launch * H * 2
+    uint32_t group_bytes;  // rows_per_iter * H * 2
+    uint32_t n_groups;     // ceil(rows / rows_per_iter)
+    int hv;                // 16-byte vectors per row
+    int P;
+    int tpr_log2;
+    float eps;
+    float inv_h;
+};
+
+// Raw buffer descriptors: byte-addressed, range-checked against num_records, so
+// a lane whose offset is past the end reads zeros and its store is dropped.
+// That is what handles ragged tails (rows past N, columns past H) below.
+__device__ __forceinline__ __amdgpu_buffer_rsrc_t make_rsrc(const void *p, uint32_t bytes)
+{
+    return __builtin_amdgcn_make_buffer_rsrc(const_cast<void *>(p), 0, static_cast<int>(bytes), 0x00020000);
+}
+static constexpr uint32_t kOutOfRange = 0xFFFFFFF0u;
+static constexpr int kStreamPolicy = 2;  // "nt": streamed once, do not keep in cache
+
+__device__ __forceinline__ u32x4 ld(__amdgpu_buffer_rsrc_t r, uint32_t off)
+{
+    return __builtin_amdgcn_raw_buffer_load_b128(r, off, 0, kStreamPolicy);
+}
+__device__ __forceinline__ void st(__amdgpu_buffer_rsrc_t r, uint32_t off, u32x4 v)
+{
+    __builtin_amdgcn_raw_buffer_store_b128(v, r, off, 0, kStreamPolicy);
+}
+
+__device__ __forceinline__ float bf16_lo(uint32_t u) { return __uint_as_float(u << 16); }
+__device__ __forceinline__ float bf16_hi(uint32_t u) { return __uint_as_float(u & 0xffff0000u); }
+
+typedef __bf16 bf16x2_t __attribute__((ext_vector_type(2)));
+
+// Two fp32 -> packed bf16 pair, round to nearest even (the hardware convert).
+__device__ __forceinline__ uint32_t pack_bf16x2(float lo, float hi)
+{
+    bf16x2_t v;
+    v.x = static_cast<__bf16>(lo);
+    v.y = static_cast<__bf16>(hi);
+    return __builtin_bit_cast(uint32_t, v);
+}
+
+__device__ __forceinline__ void unpack8(const u32x4 &v, float (&f)[8])
+{
+    f[0] = bf16_lo(v.x); f[1] = bf16_hi(v.x);
+    f[2] = bf16_lo(v.y); f[3] = bf16_hi(v.y);
+    f[4] = bf16_lo(v.z); f[5] = bf16_hi(v.z);
+    f[6] = bf16_lo(v.w); f[7] = bf16_hi(v.w);
+}
+
+__device__ __forceinline__ void add8(const u32x4 &v, float (&f)[8])
+{
+    f[0] += bf16_lo(v.x); f[1] += bf16_hi(v.x);
+    f[2] += bf16_lo(v.y); f[3] += bf16_hi(v.y);
+    f[4] += bf16_lo(v.z); f[5] += bf16_hi(v.z);
+    f[6] += bf16_lo(v.w); f[7] += bf16_hi(v.w);
+}
+
+__device__ __forceinline__ u32x4 pack8(const float (&f)[8])
+{
+    u32x4 v;
+    v.x = pack_bf16x2(f[0], f[1]);
+    v.y = pack_bf16x2(f[2], f[3]);
+    v.z = pack_bf16x2(f[4], f[5]);
+    v.w = pack_bf16x2(f[6], f[7]);
+    return v;
+}
+
+// v + (v moved across lanes by a DPP pattern). Used with patterns under which
+// lanes pair up symmetrically, so both partners end with the same bits.
+template <int CTRL>
+__device__ __forceinline__ float dpp_add(float v)
+{
+    const int moved = __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, v), CTRL, 0xF, 0xF, true);
+    return v + __builtin_bit_cast(float, moved);
+}
+static constexpr int kDppXor1 = 0xB1;         // quad_perm [1,0,3,2]
+static constexpr int kDppXor2 = 0x4E;         // quad_perm [2,3,0,1]
+static constexpr int kDppHalfMirror = 0x141;  // lane i <-> 7-i in each group of 8
+static constexpr int kDppMirror = 0x140;      // lane i <-> 15-i in each group of 16
+
+// Sum over aligned groups of 2^log2n lanes (log2n <= 6); every lane of a group
+// ends with the same bits. After the first two steps each quad is uniform, so
+// the mirrors act as "xor 4" and "xor 8".
+__device__ __forceinline__ float group_sum(float v, int log2n)
+{
+    if (log2n >= 1) v = dpp_add<kDppXor1>(v);
+    if (log2n >= 2) v = dpp_add<kDppXor2>(v);
+    if (log2n >= 3) v = dpp_add<kDppHalfMirror>(v);
+    if (log2n >= 4) v = dpp_add<kDppMirror>(v);
+    if (log2n >= 5) v += __shfl_xor(v, 16, 64);
+    if (log2n >= 6) v += __shfl_xor(v, 32, 64);
+    return v;
+}
+
+// The P+1 vectors that feed one output vector, in flight.
+template <int PT>
+struct Chunk {
+    u32x4 v[PT + 1];
+};
+
+// How many chunks are kept in flight per thread (register budget: 128 VGPRs).
+template <int PT, int VPT>
+constexpr int buffers_in_flight()
+{
+    return (PT == 0) ? 1 : (((PT + 1) * 8 + 12 * VPT <= 100) ? 2 : 1);
+}
+
+template <int PT, int VPT, bool TRACE>
+__global__ __launch_bounds__(kThreads) void fused_kernel(const FusedParams prm)
+{
+    __shared__ float s_wave_sum[2][kWaves];
+    constexpr int NB = buffers_in_flight<PT, VPT>();
+    constexpr bool KEEP_W = VPT <= 2;  // weights unpacked to fp32 once, else kept packed
+
+    const int tid = threadIdx.x;
+    const int lane = tid & 63;
+    const int wave = tid >> 6;
+    const int tpr_log2 = prm.tpr_log2;
+    const int tpr = 1 << tpr_log2;
+    const int row_in_iter = tid >> tpr_log2;
+    const int col0 = tid & (tpr - 1);
+    const int hv = prm.hv;
+
+    if (TRACE && tid == 0) {
+        // HW_ID (hwreg 4) and XCC_ID (hwreg 20), all 32 bits of each.
+        prm.hw_ids[2 * blockIdx.x] = __builtin_amdgcn_s_getreg(4 | (0 << 6) | (31 << 11));
+        prm.hw_ids[2 * blockIdx.x + 1] = __builtin_amdgcn_s_getreg(20 | (0 << 6) | (31 << 11));
+    }
+
+    __amdgpu_buffer_rsrc_t r_part[PT > 0 ? PT : 1];
+    if constexpr (PT > 0) {
+#pragma unroll
+        for (int p = 0; p < PT; ++p) r_part[p] = make_rsrc(prm.partials[p], prm.n_bytes);
+    }
+    const __amdgpu_buffer_rsrc_t r_res = make_rsrc(prm.residual, prm.n_bytes);
+    const __amdgpu_buffer_rsrc_t r_out = make_rsrc(prm.out, prm.n_bytes);
+    const __amdgpu_buffer_rsrc_t r_res_out = make_rsrc(prm.residual_out, prm.n_bytes);
+
+    // Byte offset of this thread's vector j inside a row group; columns past the
+    // end of the row are pushed out of range for good.
+    uint32_t lane_off[VPT];
+    bool cvalid[VPT];
+    u32x4 wv[VPT];
+    float wf[KEEP_W ? VPT : 1][8];
+    {
+        const __amdgpu_buffer_rsrc_t r_w = make_rsrc(prm.weight, static_cast<uint32_t>(hv) * 16u);
+#pragma unroll
+        for (int j = 0; j < VPT; ++j) {
+            const int v = col0 + j * tpr;
+            cvalid[j] = v < hv;
+            lane_off[j] = static_cast<uint32_t>(row_in_iter * hv + v) * 16u;
+            wv[j] = __builtin_amdgcn_raw_buffer_load_b128(r_w, cvalid[j] ? v * 16u : kOutOfRange, 0, 0);
+            if constexpr (KEEP_W) unpack8(wv[j], wf[j]);
+        }
+    }
+
+    const uint32_t stride = gridDim.x;
+    const uint32_t n_groups = prm.n_groups;
+    const uint32_t group_bytes = prm.group_bytes;
+
+    // Offset of chunk (group, j). A group at or past n_groups lands at or past
+    // n_bytes (the host keeps n_bytes + 2 * stride * group_bytes below 2^32), so
+    // prefetching past the end reads zeros and never needs a branch.
+    auto chunk_off = [&](uint32_t group, int j) -> uint32_t {
+        return cvalid[j] ? lane_off[j] + group * group_bytes : kOutOfRange;
+    };
+    // The loads of one chunk are kept together and in program order (the
+    // scheduling barriers): the wait for chunk q must not also wait for q + 1.
+    auto issue = [&](Chunk<PT> &c, uint32_t off) {
+        if constexpr (PT > 0) {
+            __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+            for (int p = 0; p < PT; ++p) c.v[p] = ld(r_part[p], off);
+            c.v[PT] = ld(r_res, off);
+            __builtin_amdgcn_sched_barrier(0);
+        }
+    };
+    // x = (p_0 + p_1 + ... + p_{P-1}) + residual, left to right, fp32.
+    auto reduce_chunk = [&](const Chunk<PT> &c, uint32_t off, float (&x)[8]) {
+        if constexpr (PT > 0) {
+            unpack8(c.v[0], x);
+#pragma unroll
+            for (int p = 1; p < PT; ++p) add8(c.v[p], x);
+            add8(c.v[PT], x);
+        } else {
+            // P known only at run time: four loads at a time, padded with
+            // zero-length descriptors (which read as +0.0).
+            const u32x4 r = ld(r_res, off);
+            for (int p0 = 0; p0 < prm.P; p0 += 4) {
+                u32x4 t[4];
+#pragma unroll
+                for (int i = 0; i < 4; ++i) {
+                    const bool live = p0 + i < prm.P;
+                    t[i] = ld(make_rsrc(prm.partials[live ? p0 + i : 0], live ? prm.n_bytes : 0u), off);
+                }
+                if (p0 == 0) unpack8(t[0], x); else add8(t[0], x);
+#pragma unroll
+                for (int i = 1; i < 4; ++i) add8(t[i], x);
+            }
+            add8(r, x);
+        }
+    };
+
+    // Chunks are numbered q = trip * VPT + j; trip t handles row group
+    // blockIdx.x + t * gridDim.x. NB chunk buffers rotate, chunk q sits in buffer
+    // q % NB; a loop body covers a multiple of NB chunks (two trips when VPT == 1).
+    constexpr int TRIPS = (VPT == 1 && NB == 2) ? 2 : 1;
+    Chunk<PT> buf[NB];
+    if constexpr (NB == 2) {
+        if constexpr (VPT == 1) {
+            issue(buf[0], chunk_off(blockIdx.x, 0));
+            issue(buf[1], chunk_off(blockIdx.x + stride, 0));
+        } else {
+            issue(buf[0], chunk_off(blockIdx.x, 0));
+            issue(buf[1], chunk_off(blockIdx.x, 1));
+        }
+    } else {
+        issue(buf[0], chunk_off(blockIdx.x, 0));
+    }
+
+    int parity = 0;
+    for (uint32_t g0 = blockIdx.x; g0 < n_groups; g0 += stride * TRIPS) {
+#pragma unroll
+        for (int t = 0; t < TRIPS; ++t) {
+            const uint32_t group = g0 + t * stride;
+            float x[VPT][8];
+            float ss = 0.0f;
+#pragma unroll
+            for (int j = 0; j < VPT; ++j) {
+                Chunk<PT> &b = buf[(t * VPT + j) % NB];
+                const uint32_t off = chunk_off(group, j);
+                reduce_chunk(b, off, x[j]);
+                // refill this buffer with chunk q + NB
+                const int nj = (j + NB) % VPT;
+                const uint32_t ng = (VPT == 1) ? group + NB * stride : (j + NB >= VPT ? group + stride : group);
+                issue(b, chunk_off(ng, nj));
+                st(r_res_out, off, pack8(x[j]));
+#pragma unroll
+                for (int e = 0; e < 8; ++e) ss = __builtin_fmaf(x[j][e], x[j][e], ss);
+            }
+
+            // Row sum of squares: the row's lanes inside this wave, then (rows
+            // wider than a wave) the row's waves through LDS.
+            ss = group_sum(ss, tpr_log2 < 6 ? tpr_log2 : 6);
+            if (tpr_log2 > 6) {
+                if (lane == 0) s_wave_sum[parity][wave] = ss;
+                __syncthreads();
+                const int waves_per_row = tpr >> 6;  // 2, 4, 8 or 16
+                const int k = lane & 15;
+                const float part = k < waves_per_row ? s_wave_sum[parity][row_in_iter * waves_per_row + k] : 0.0f;
+                ss = group_sum(part, 4);
+                parity ^= 1;
+            }
+            const float s = rsqrtf(ss * prm.inv_h + prm.eps);
+
+#pragma unroll
+            for (int j = 0; j < VPT; ++j) {
+                float y[8];
+                if constexpr (KEEP_W) {
+#pragma unroll
+                    for (int e = 0; e < 8; ++e) y[e] = (x[j][e] * s) * wf[j][e];
+                } else {
+                    float w[8];
+                    unpack8(wv[j], w);
+#pragma unroll
+                    for (int e = 0; e < 8; ++e) y[e] = (x[j][e] * s) * w[e];
+                }
+                st(r_out, chunk_off(group, j), pack8(y));
+            }
+        }
+    }
+}
+
+// ---------------------------------------------------------------------------
+// host side
+// ---------------------------------------------------------------------------
+
+FusedGeometry fused_geometry(int64_t H)
+{
+    FusedGeometry g;
+    g.hv = static_cast<int>(H / 8);
+    int l2 = 0;
+    while ((1 << l2) < g.hv && l2 < 10) ++l2;
+    g.tpr_log2 = l2;
+    const int tpr = 1 << l2;
+    const int need = (g.hv + tpr - 1) / tpr;  // 1..8
+    g.vpt = need <= 1 ? 1 : need <= 2 ? 2 : need <= 4 ? 4 : 8;
+    g.rows_per_iter = kThreads >> l2;
+    return g;
+}
+
+int64_t fused_grid_size(int64_t n_rows, const FusedGeometry &g, int budget_wgs)
+{
+    if (n_rows <= 0) return 0;
+    const int64_t groups = (n_rows + g.rows_per_iter - 1) / g.rows_per_iter;
+    return groups < budget_wgs ? groups : budget_wgs;
+}
+
+tw_status validate_fused(const tw_fused_args &a)
+{
+    if (!a.partials || !a.residual || !a.weight || !a.out || !a.residual_out) return TW_ERR_NULL;
+    if (a.P < 1 || a.P > TW_MAX_P) return TW_ERR_SHAPE;
+    for (int p = 0; p < a.P; ++p)
+        if (!a.partials[p]) return TW_ERR_NULL;
+    if (a.N < 0 || a.H <= 0) return TW_ERR_SHAPE;
+    if (!(a.eps >= 0.0f) || !(a.eps <= 3.402823466e+38f)) return TW_ERR_SHAPE;  // rejects NaN, Inf, < 0
+    if (a.H % 8 != 0 || a.H > TW_MAX_H) return TW_ERR_UNSUPPORTED;
+    if (a.N > (INT64_MAX / 2) / a.H) return TW_ERR_SHAPE;
+    if (!aligned16(a.residual) || !aligned16(a.weight) || !aligned16(a.out) || !aligned16(a.residual_out))
+        return TW_ERR_ALIGN;
+    for (int p = 0; p < a.P; ++p)
+        if (!aligned16(a.partials[p])) return TW_ERR_ALIGN;
+
+    const uint64_t tensor = static_cast<uint64_t>(a.N) * static_cast<uint64_t>(a.H) * 2u;
+    const uint64_t wbytes = static_cast<uint64_t>(a.H) * 2u;
+    if (ranges_overlap(a.out, tensor, a.residual_out, tensor)) return TW_ERR_ALIAS;
+    const void *outs[2] = {a.out, a.residual_out};
+    for (int o = 0; o < 2; ++o) {
+        if (ranges_overlap(outs[o], tensor, a.weight, wbytes)) return TW_ERR_ALIAS;
+        // residual: only residual_out may coincide with it, and only exactly
+        if (ranges_overlap(outs[o], tensor, a.residual, tensor) &&
+            !(o == 1 && a.residual_out == a.residual))
+            return TW_ERR_ALIAS;
+        // partials: only out may coincide with one, and only exactly
+        for (int p = 0; p < a.P; ++p)
+            if (ranges_overlap(outs[o], tensor, a.partials[p], tensor) &&
+                !(o == 0 && a.out == a.partials[p]))
+                return TW_ERR_ALIAS;
+    }
+    return TW_OK;
+}
+
+template <int PT, int VPT>
+static tw_status launch_t(const FusedParams &prm, bool trace, int64_t grid, hipStream_t stream)
+{
+    auto kern = trace ? fused_kernel<PT, VPT, true> : fused_kernel<PT, VPT, false>;
+    // More than 64 KiB of dynamic LDS has to be allowed per kernel, once.
+    static std::atomic<int> allowed[2] = {0, 0};
+    if (!allowed[trace].load(std::memory_order_acquire)) {
+        TW_HIP(hipFuncSetAttribute(reinterpret_cast<const void *>(kern),
+                                   hipFuncAttributeMaxDynamicSharedMemorySize,
+                                   static_cast<int>(kOccupancyPadBytes)));
+        allowed[trace].store(1, std::memory_order_release);
+    }
+    hipLaunchKernelGGL(kern, dim3(static_cast<unsigned>(grid)), dim3(kThreads), kOccupancyPadBytes,
+                       stream, prm);
+    TW_HIP(hipGetLastError());
+    return TW_OK;
+}
+
+template <int PT>
+static tw_status launch_vpt(const FusedParams &prm, int vpt, bool trace, int64_t grid, hipStream_t s)
+{
+    switch (vpt) {
+    case 1: return launch_t<PT, 1>(prm, trace, grid, s);
+    case 2: return launch_t<PT, 2>(prm, trace, grid, s);
+    case 4: return launch_t<PT, 4>(prm, trace, grid, s);
+    case 8: return launch_t<PT, 8>(prm, trace, grid, s);
+    }
+    return TW_ERR_UNSUPPORTED;
+}
+
+tw_status launch_fused(const tw_fused_args &a, int64_t row_begin, int64_t row_end, uint32_t *hw_ids,
+                       int64_t hw_ids_len, hipStream_t stream)
+{
+    if (row_end <= row_begin) return TW_OK;
+    int cus = 0;
+    TW_TRY(current_cu_count(&cus));
+    const FusedGeometry g = fused_geometry(a.H);
+    const int budget = resolve_budget(a.cu_budget, cus);
+    const bool trace = hw_ids != nullptr;
+
+    // A launch addresses at most kMaxLaunchBytes per tensor; more rows than that
+    // go out as consecutive launches on the same stream.
+    const int64_t row_bytes = a.H * 2;
+    int64_t rows_per_launch = kMaxLaunchBytes / row_bytes;
+    rows_per_launch -= rows_per_launch % g.rows_per_iter;
+    if (trace && row_end - row_begin > rows_per_launch) return TW_ERR_UNSUPPORTED;
+
+    for (int64_t r0 = row_begin; r0 < row_end; r0 += rows_per_launch) {
+        const int64_t n_rows = (row_end - r0 < rows_per_launch) ? row_end - r0 : rows_per_launch;
+        const int64_t grid = fused_grid_size(n_rows, g, budget);
+        if (grid > 1024) return TW_ERR_UNSUPPORTED;  // offset arithmetic in the kernel assumes this
+        if (trace && hw_ids_len < grid) return TW_ERR_SHAPE;
+
+        FusedParams prm;
+        const int64_t off = r0 * row_bytes;
+        for (int p = 0; p < TW_MAX_P; ++p)
+            prm.partials[p] = p < a.P ? static_cast<const char *>(a.partials[p]) + off : nullptr;
+        prm.residual = static_cast<const char *>(a.residual) + off;
+        prm.weight = a.weight;
+        prm.out = static_cast<char *>(a.out) + off;
+        prm.residual_out = static_cast<char *>(a.residual_out) + off;
+        prm.hw_ids = hw_ids;
+        prm.n_bytes = static_cast<uint32_t>(n_rows * row_bytes);
+        prm.group_bytes = static_cast<uint32_t>(g.rows_per_iter * row_bytes);
+        prm.n_groups = static_cast<uint32_t>((n_rows + g.rows_per_iter - 1) / g.rows_per_iter);
+        prm.hv = g.hv;
+        prm.P = a.P;
+        prm.tpr_log2 = g.tpr_log2;
+        prm.eps = a.eps;
+        prm.inv_h = 1.0f / static_cast<float>(a.H);
+
+        switch (a.P) {
+        case 1: TW_TRY((launch_vpt<1>(prm, g.vpt, trace, grid, stream))); break;
+        case 2: TW_TRY((launch_vpt<2>(prm, g.vpt, trace, grid, stream))); break;
+        case 4: TW_TRY((launch_vpt<4>(prm, g.vpt, trace, grid, stream))); break;
+        case 8: TW_TRY((launch_vpt<8>(prm, g.vpt, trace, grid, stream))); break;
+        default: TW_TRY((launch_vpt<0>(prm, g.vpt, trace, grid, stream))); break;
+        }
+    }
+    return TW_OK;
+}
+
+}  // namespace tw
+
+using namespace tw;
+
+extern "C" {
+
+tw_status tw_reduce_add_rmsnorm(const void *const *partials, const void *residual,
+                                const void *weight, float eps, int64_t N, int64_t H, int P,
+                                int cu_budget, void *out, void *residual_out, void *stream)
+{
+    const tw_fused_args a = {partials, residual, weight, eps, N, H, P, cu_budget, out, residual_out};
+    TW_TRY(validate_fused(a));
+    return launch_fused(a, 0, N, nullptr, 0, static_cast<hipStream_t>(stream));
+}
+
+tw_status tw_reduce_add_rmsnorm_traced(const void *const *partials, const void *residual,
+                                       const void *weight, float eps, int64_t N, int64_t H, int P,
+                                       int cu_budget, void *out, void *residual_out,
+                                       uint32_t *hw_ids, int64_t hw_ids_len, void *stream)
+{
+    const tw_fused_args a = {partials, residual, weight, eps, N, H, P, cu_budget, out, residual_out};
+    TW_TRY(validate_fused(a));
+    if (!hw_ids) return TW_ERR_NULL;
+    if (hw_ids_len < 0) return TW_ERR_SHAPE;
+    return launch_fused(a, 0, N, hw_ids, hw_ids_len, static_cast<hipStream_t>(stream));
+}
+
+int64_t tw_fused_grid(int64_t N, int64_t H, int cu_budget)
+{
+    if (N < 0 || H <= 0 || H % 8 != 0 || H > TW_MAX_H) return -1;
+    if (N == 0) return 0;
+    int cus = 0;
+    if (current_cu_count(&cus) != TW_OK) return -1;
+    return fused_grid_size(N, fused_geometry(H), resolve_budget(cu_budget, cus));
+}
+
+}  // extern "C"

@@ -1,0 +1,287 @@
+// bf16 GEMM for gfx950 on the matrix cores: the stand-in for the projection of
+// the "other" token split that runs next to the fused kernel (TokenWeave, arXiv
+// 2505.11329, Fig. 7b and Section 4.1.2; the paper uses a vendor GEMM there).
+// C[M x N] = A[M x K] * B(k, n), fp32 accumulation, one rounding to bf16.
+//
+// Design
+//   - Workgroup tile 256 (M) x 128 (N), K step 64, 512 threads = 8 wave64 laid
+//     out 4 x 2, each wave owning a 64 x 64 sub-tile as 2 x 2 blocks of
+//     v_mfma_f32_32x32x16_bf16 (64 accumulator registers per lane).
+//   - Operand tiles go global -> registers -> LDS, double-buffered: the loads of
+//     K step t+1 are issued before the MFMAs of step t and written to the other
+//     LDS stage afterwards, one barrier per K step. 2 x (32 + 16) KiB of LDS,
+//     so one workgroup per compute unit.
+//   - LDS rows are 128 bytes (64 bf16 of K); the eight 16-byte pieces of row r
+//     are stored at piece index (c xor (r mod 8)), which makes both the
+//     16-byte writes (8 lanes per row) and the MFMA operand reads (32 rows, one
+//     piece each) free of bank conflicts without padding.
+//   - Each MFMA gets the B fragment as its first operand and the A fragment as
+//     its second, so the 32x32 result block is held transposed: a lane owns one
+//     row m of C and, per group of four accumulator registers, four consecutive
+//     columns n, which it stores as one 8-byte bf16 quad.
+//   - Ragged edges need no branches: operands are fetched through range-checked
+//     buffer descriptors sized to the rows that exist (rows past M or N read as
+//     zeros), K pieces past K are redirected out of range, and stores past the
+//     edge are dropped the same way.
+//   - Persistent grid of at most `budget` workgroups walking the tile list.
+//     Workgroups are dealt to the 8 XCDs round-robin by the hardware, so
+//     workgroup w takes tile (w mod 8) * ceil(T/8) + w / 8 of a list ordered in
+//     compact blocks: the tiles an XCD works on share rows of A and columns of
+//     B in that XCD's L2.
+#include <atomic>
+
+#include "tw_internal.h"
+
+namespace tw {
+
+static constexpr int BM = 256, BN = 128, BK = 64;
+static constexpr int kGemmThreads = 512;
+static constexpr int kStageABytes = BM * BK * 2;  // 32 KiB
+static constexpr int kStageBBytes = BN * BK * 2;  // 16 KiB
+static constexpr int kStageBytes = kStageABytes + kStageBBytes;
+static constexpr int kGemmLdsBytes = 2 * kStageBytes;  // 96 KiB
+static constexpr int kXcds = 8;
+
+typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
+typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
+typedef float f32x16 __attribute__((ext_vector_type(16)));
+
+struct GemmParams {
+    const char *A;
+    const char *B;
+    char *C;
+    long long M, N, K;
+    int tiles_m, tiles_n;
+    int group_m;        // tile rows per block of the tile ordering
+    int tiles_per_xcd;  // ceil(tiles / 8)
+};
+
+__device__ __forceinline__ __amdgpu_buffer_rsrc_t gemm_rsrc(const void *p, uint32_t bytes)
+{
+    return __builtin_amdgcn_make_buffer_rsrc(const_cast<void *>(p), 0, static_cast<int>(bytes), 0x00020000);
+}
+static constexpr uint32_t kOob = 0xFFFFFFF0u;
+
+// Byte offset inside a stage's A (or B) area of the 16-byte piece c of row r.
+__device__ __forceinline__ uint32_t lds_piece(int r, int c) { return r * 128 + ((c ^ (r & 7)) << 4); }
+
+__device__ __forceinline__ uint32_t pack_bf16x2(float lo, float hi)
+{
+    bf16x2 v;
+    v.x = static_cast<__bf16>(lo);
+    v.y = static_cast<__bf16>(hi);
+    return __builtin_bit_cast(uint32_t, v);
+}
+
+__global__ __launch_bounds__(kGemmThreads) void gemm_bf16_nk_kernel(const GemmParams prm)
+{
+    extern __shared__ __attribute__((aligned(16))) char lds[];
+
+    const int tid = threadIdx.x;
+    const int lane = tid & 63;
+    const int wave = tid >> 6;
+    const int wave_m = wave >> 1;  // 0..3 : 64-row band of the tile
+    const int wave_n = wave & 1;   // 0..1 : 64-column band
+    const int l31 = lane & 31;
+    const int lhi = lane >> 5;
+
+    // global -> LDS duty of this thread: piece ld_c of rows ld_r + 64 * i
+    const int ld_r = tid >> 3;  // 0..63
+    const int ld_c = tid & 7;
+    const long long row_bytes = prm.K * 2;  // of A and of B (stored [N x K])
+    const int k_tiles = static_cast<int>((prm.K + BK - 1) / BK);
+    const int total_tiles = prm.tiles_m * prm.tiles_n;
+
+    for (int w = blockIdx.x; w < prm.tiles_per_xcd * kXcds; w += gridDim.x) {
+        const int slot = w / kXcds;
+        const int lin = (w % kXcds) * prm.tiles_per_xcd + slot;
+        if (lin >= total_tiles) continue;  // uniform over the workgroup
+        const int per_group = prm.group_m * prm.tiles_n;
+        const int grp = lin / per_group;
+        const int first_tm = grp * prm.group_m;
+        const int gsz = min(prm.group_m, prm.tiles_m - first_tm);
+        const int in_grp = lin - grp * per_group;
+        const int tm = first_tm + in_grp % gsz;
+        const int tn = in_grp / gsz;
+
+        const long long m0 = static_cast<long long>(tm) * BM;
+        const long long n0 = static_cast<long long>(tn) * BN;
+        const int rows_a = static_cast<int>(min(static_cast<long long>(BM), prm.M - m0));
+        const int rows_b = static_cast<int>(min(static_cast<long long>(BN), prm.N - n0));
+        const __amdgpu_buffer_rsrc_t ra = gemm_rsrc(prm.A + m0 * row_bytes, static_cast<uint32_t>(rows_a * row_bytes));
+        const __amdgpu_buffer_rsrc_t rb = gemm_rsrc(prm.B + n0 * row_bytes, static_cast<uint32_t>(rows_b * row_bytes));
+
+        f32x16 acc[2][2];  // [n block][m block]
+#pragma unroll
+        for (int i = 0; i < 2; ++i)
+#pragma unroll
+            for (int j = 0; j < 2; ++j)
+#pragma unroll
+                for (int e = 0; e < 16; ++e) acc[i][j][e] = 0.0f;
+
+        u32x4 ga[4], gb[2];
+        auto fetch = [&](int kt) {
+            const long long k = static_cast<long long>(kt) * BK + ld_c * 8;
+            const bool kin = k < prm.K;
+            const uint32_t kb = static_cast<uint32_t>(k * 2);
+#pragma unroll
+            for (int i = 0; i < 4; ++i) {
+                const uint32_t off = static_cast<uint32_t>((ld_r + 64 * i) * row_bytes) + kb;
+                ga[i] = __builtin_amdgcn_raw_buffer_load_b128(ra, kin ? off : kOob, 0, 0);
+            }
+#pragma unroll
+            for (int i = 0; i < 2; ++i) {
+                const uint32_t off = static_cast<uint32_t>((ld_r + 64 * i) * row_bytes) + kb;
+                gb[i] = __builtin_amdgcn_raw_buffer_load_b128(rb, kin ? off : kOob, 0, 0);
+            }
+        };
+        auto stash = [&](int stage) {
+            char *sa = lds + stage * kStageBytes;
+            char *sb = sa + kStageABytes;
+#pragma unroll
+            for (int i = 0; i < 4; ++i) *reinterpret_cast<u32x4 *>(sa + lds_piece(ld_r + 64 * i, ld_c)) = ga[i];
+#pragma unroll
+            for (int i = 0; i < 2; ++i) *reinterpret_cast<u32x4 *>(sb + lds_piece(ld_r + 64 * i, ld_c)) = gb[i];
+        };
+
+        // The previous tile's last reads of LDS must be over before it is refilled.
+        __syncthreads();
+        if (k_tiles > 0) {
+            fetch(0);
+            stash(0);
+        }
+        __syncthreads();
+
+        for (int kt = 0; kt < k_tiles; ++kt) {
+            const int stage = kt & 1;
+            if (kt + 1 < k_tiles) fetch(kt + 1);
+
+            const char *sa = lds + stage * kStageBytes;
+            const char *sb = sa + kStageABytes;
+#pragma unroll
+            for (int kk = 0; kk < BK / 16; ++kk) {
+                bf16x8 fa[2], fb[2];
+#pragma unroll
+                for (int i = 0; i < 2; ++i) {
+                    fa[i] = *reinterpret_cast<const bf16x8 *>(sa + lds_piece(wave_m * 64 + i * 32 + l31, kk * 2 + lhi));
+                    fb[i] = *reinterpret_cast<const bf16x8 *>(sb + lds_piece(wave_n * 64 + i * 32 + l31, kk * 2 + lhi));
+                }
+#pragma unroll
+                for (int nb = 0; nb < 2; ++nb)
+#pragma unroll
+                    for (int mb = 0; mb < 2; ++mb)
+                        acc[nb][mb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fb[nb], fa[mb], acc[nb][mb], 0, 0, 0);
+            }
+
+            if (kt + 1 < k_tiles) stash(stage ^ 1);
+            __syncthreads();
+        }
+
+        // Store: lane owns row m = l31 of each block and 4 consecutive n per
+        // register quad: n = 8 * quad + 4 * lhi + (0..3) inside the 32-wide block.
+        const long long c_row_bytes = prm.N * 2;
+        const __amdgpu_buffer_rsrc_t rc = gemm_rsrc(prm.C + m0 * c_row_bytes, static_cast<uint32_t>(rows_a * c_row_bytes));
+#pragma unroll
+        for (int mb = 0; mb < 2; ++mb) {
+            const int m = wave_m * 64 + mb * 32 + l31;
+#pragma unroll
+            for (int nb = 0; nb < 2; ++nb) {
+#pragma unroll
+                for (int q = 0; q < 4; ++q) {
+                    const long long n = n0 + wave_n * 64 + nb * 32 + q * 8 + lhi * 4;
+                    u32x2 v;
+                    v.x = pack_bf16x2(acc[nb][mb][q * 4 + 0], acc[nb][mb][q * 4 + 1]);
+                    v.y = pack_bf16x2(acc[nb][mb][q * 4 + 2], acc[nb][mb][q * 4 + 3]);
+                    const uint32_t off = static_cast<uint32_t>(m * c_row_bytes + n * 2);
+                    __builtin_amdgcn_raw_buffer_store_b64(v, rc, n < prm.N ? off : kOob, 0, 0);
+                }
+            }
+        }
+    }
+}
+
+// ---------------------------------------------------------------------------
+// host side
+// ---------------------------------------------------------------------------
+
+tw_status validate_gemm(const tw_gemm_args &g)
+{
+    if (g.M < 0 || g.N < 0 || g.K < 0) return TW_ERR_SHAPE;
+    if (g.b_layout != TW_B_NK && g.b_layout != TW_B_KN) return TW_ERR_SHAPE;
+    if (g.M == 0 || g.N == 0) return TW_OK;
+    if (!g.C) return TW_ERR_NULL;
+    if (g.K > 0 && (!g.A || !g.B)) return TW_ERR_NULL;
+    if (g.K % 8 != 0 || g.N % 8 != 0) return TW_ERR_UNSUPPORTED;
+    // a tile's rows are addressed with 32-bit byte offsets
+    if (g.K > (int64_t(1) << 22) || g.N > (int64_t(1) << 22) || g.M > (int64_t(1) << 40)) return TW_ERR_UNSUPPORTED;
+    if (g.b_layout == TW_B_KN) return TW_ERR_UNSUPPORTED;
+    if (!aligned16(g.A) || !aligned16(g.B) || !aligned16(g.C)) return TW_ERR_ALIGN;
+    const uint64_t a_bytes = uint64_t(g.M) * uint64_t(g.K) * 2, b_bytes = uint64_t(g.N) * uint64_t(g.K) * 2;
+    const uint64_t c_bytes = uint64_t(g.M) * uint64_t(g.N) * 2;
+    if (ranges_overlap(g.C, c_bytes, g.A, a_bytes) || ranges_overlap(g.C, c_bytes, g.B, b_bytes))
+        return TW_ERR_ALIAS;
+    return TW_OK;
+}
+
+tw_status launch_gemm(const tw_gemm_args &g, hipStream_t stream)
+{
+    if (g.M == 0 || g.N == 0) return TW_OK;
+    int cus = 0;
+    TW_TRY(current_cu_count(&cus));
+    const int budget = resolve_budget(g.cu_budget, cus);
+
+    GemmParams prm;
+    prm.A = static_cast<const char *>(g.A);
+    prm.B = static_cast<const char *>(g.B);
+    prm.C = static_cast<char *>(g.C);
+    prm.M = g.M;
+    prm.N = g.N;
+    prm.K = g.K;
+    const int64_t tiles_m = (g.M + BM - 1) / BM, tiles_n = (g.N + BN - 1) / BN;
+    if (tiles_m * tiles_n > (int64_t(1) << 30)) return TW_ERR_UNSUPPORTED;
+    prm.tiles_m = static_cast<int>(tiles_m);
+    prm.tiles_n = static_cast<int>(tiles_n);
+    const int64_t total = tiles_m * tiles_n;
+    prm.tiles_per_xcd = static_cast<int>((total + kXcds - 1) / kXcds);
+    // Block shape of the tile ordering: an XCD's share of tiles_per_xcd tiles
+    // should touch as few distinct rows of A and columns of B as possible.
+    int best_gm = 1;
+    int64_t best_cost = INT64_MAX;
+    for (int gm = 1; gm <= 8; gm *= 2) {
+        if (gm > tiles_m && gm != 1) break;
+        const int64_t gn = (prm.tiles_per_xcd + gm - 1) / gm;
+        const int64_t cost = int64_t(gm) * BM + gn * BN;
+        if (cost < best_cost) {
+            best_cost = cost;
+            best_gm = gm;
+        }
+    }
+    prm.group_m = best_gm;
+
+    const int64_t slots = int64_t(prm.tiles_per_xcd) * kXcds;
+    const unsigned grid = static_cast<unsigned>(slots < budget ? slots : budget);
+
+    static std::atomic<int> allowed{0};
+    if (!allowed.load(std::memory_order_acquire)) {
+        TW_HIP(hipFuncSetAttribute(reinterpret_cast<const void *>(gemm_bf16_nk_kernel),
+                                   hipFuncAttributeMaxDynamicSharedMemorySize, kGemmLdsBytes));
+        allowed.store(1, std::memory_order_release);
+    }
+    hipLaunchKernelGGL(gemm_bf16_nk_kernel, dim3(grid), dim3(kGemmThreads), kGemmLdsBytes, stream, prm);
+    TW_HIP(hipGetLastError());
+    return TW_OK;
+}
+
+}  // namespace tw
+
+using namespace tw;
+
+extern "C" tw_status tw_gemm_bf16(const void *A, const void *B, void *C, int64_t M, int64_t N, int64_t K,
+                                  int b_layout, int cu_budget, void *stream)
+{
+    const tw_gemm_args g = {A, B, C, M, N, K, b_layout, cu_budget};
+    TW_TRY(validate_gemm(g));
+    return launch_gemm(g, static_cast<hipStream_t>(stream));
+}

@@ -1,0 +1,178 @@
+// Host side of libtw that is not tied to one kernel: status strings, device
+// queries, the event pool, the token split and the overlap launch.
+#include <mutex>
+
+#include "tw_internal.h"
+
+namespace tw {
+
+static thread_local int g_last_hip_error = 0;
+
+tw_status hip_fail(hipError_t e)
+{
+    g_last_hip_error = static_cast<int>(e);
+    (void)hipGetLastError();  // clear the sticky per-thread error so later calls start clean
+    return TW_ERR_HIP;
+}
+
+static constexpr int kMaxDevices = 64;
+static std::mutex g_mu;
+static int g_cu_count[kMaxDevices];  // 0 = not queried yet
+
+tw_status current_cu_count(int *cu_count)
+{
+    int dev = 0;
+    TW_HIP(hipGetDevice(&dev));
+    if (dev < 0 || dev >= kMaxDevices) return hip_fail(hipErrorInvalidDevice);
+    {
+        std::lock_guard<std::mutex> lk(g_mu);
+        if (g_cu_count[dev] > 0) {
+            *cu_count = g_cu_count[dev];
+            return TW_OK;
+        }
+    }
+    int n = 0;
+    TW_HIP(hipDeviceGetAttribute(&n, hipDeviceAttributeMultiprocessorCount, dev));
+    if (n <= 0) return hip_fail(hipErrorInvalidDevice);
+    std::lock_guard<std::mutex> lk(g_mu);
+    g_cu_count[dev] = n;
+    *cu_count = n;
+    return TW_OK;
+}
+
+// Events are only used as stream-ordering markers: recorded on one stream and
+// waited on by another within the same call. A wait refers to the record that
+// precedes it, so an event can be recorded again later; a ring of them keeps a
+// comfortable distance between reuses anyway.
+static constexpr int kEventRing = 64;
+static hipEvent_t g_events[kMaxDevices][kEventRing];
+static bool g_event_made[kMaxDevices][kEventRing];
+static int g_event_next[kMaxDevices];
+
+tw_status borrow_event(hipEvent_t *ev)
+{
+    int dev = 0;
+    TW_HIP(hipGetDevice(&dev));
+    if (dev < 0 || dev >= kMaxDevices) return hip_fail(hipErrorInvalidDevice);
+    std::lock_guard<std::mutex> lk(g_mu);
+    const int i = g_event_next[dev];
+    g_event_next[dev] = (i + 1) % kEventRing;
+    if (!g_event_made[dev][i]) {
+        TW_HIP(hipEventCreateWithFlags(&g_events[dev][i], hipEventDisableTiming));
+        g_event_made[dev][i] = true;
+    }
+    *ev = g_events[dev][i];
+    return TW_OK;
+}
+
+// `child` waits for everything enqueued on `from` so far.
+static tw_status stream_wait_stream(hipStream_t child, hipStream_t from)
+{
+    hipEvent_t ev;
+    TW_TRY(borrow_event(&ev));
+    TW_HIP(hipEventRecord(ev, from));
+    TW_HIP(hipStreamWaitEvent(child, ev, 0));
+    return TW_OK;
+}
+
+}  // namespace tw
+
+using namespace tw;
+
+extern "C" {
+
+int tw_device_cu_count(void)
+{
+    int n = 0;
+    return current_cu_count(&n) == TW_OK ? n : -1;
+}
+
+const char *tw_status_str(tw_status s)
+{
+    switch (s) {
+    case TW_OK: return "ok";
+    case TW_ERR_NULL: return "a required pointer is NULL";
+    case TW_ERR_SHAPE: return "a size is out of range";
+    case TW_ERR_ALIGN: return "a data pointer is not 16-byte aligned";
+    case TW_ERR_ALIAS: return "buffers overlap in a way that is not allowed";
+    case TW_ERR_UNSUPPORTED: return "no kernel for this request";
+    case TW_ERR_SPLIT: return "bad split row or identical streams";
+    case TW_ERR_HIP: return "a HIP call failed (see tw_last_hip_error)";
+    }
+    return "unknown status";
+}
+
+const char *tw_version(void) { return "libtw 0.1 (gfx950)"; }
+
+int tw_last_hip_error(void) { return g_last_hip_error; }
+
+int64_t tw_split_point(int64_t N, int64_t multiple)
+{
+    if (N <= 0) return 0;
+    if (multiple <= 0) multiple = 1;
+    if (multiple >= N) return N;  // the first multiple at or above N/2 is already >= N
+    const int64_t half = N / 2 + (N & 1);
+    const int64_t blocks = half / multiple + (half % multiple != 0);
+    const int64_t k = blocks * multiple;  // < half + multiple < 2N: no overflow
+    return k < N ? k : N;
+}
+
+tw_status tw_split_launch(const tw_fused_args *args, int64_t split_row, void *stream_a,
+                          void *stream_b, void *parent, int parent_is_set, int join)
+{
+    if (!args) return TW_ERR_NULL;
+    TW_TRY(validate_fused(*args));
+    if (split_row < 0 || split_row > args->N) return TW_ERR_SPLIT;
+    const bool has_a = split_row > 0, has_b = split_row < args->N;
+    if (has_a && has_b && stream_a == stream_b) return TW_ERR_SPLIT;
+    if (!has_a && !has_b) return TW_OK;
+
+    hipStream_t sa = static_cast<hipStream_t>(stream_a), sb = static_cast<hipStream_t>(stream_b);
+    hipStream_t sp = static_cast<hipStream_t>(parent);
+    if (parent_is_set) {
+        hipEvent_t fork;
+        TW_TRY(borrow_event(&fork));
+        TW_HIP(hipEventRecord(fork, sp));
+        if (has_a && sa != sp) TW_HIP(hipStreamWaitEvent(sa, fork, 0));
+        if (has_b && sb != sp) TW_HIP(hipStreamWaitEvent(sb, fork, 0));
+    }
+    if (has_a) TW_TRY(launch_fused(*args, 0, split_row, nullptr, 0, sa));
+    if (has_b) TW_TRY(launch_fused(*args, split_row, args->N, nullptr, 0, sb));
+    if (parent_is_set && join) {
+        if (has_a && sa != sp) TW_TRY(stream_wait_stream(sp, sa));
+        if (has_b && sb != sp) TW_TRY(stream_wait_stream(sp, sb));
+    }
+    return TW_OK;
+}
+
+tw_status tw_overlap_launch(const tw_fused_args *fused, const tw_gemm_args *gemm,
+                            void *stream_comm, void *stream_compute, void *parent,
+                            int parent_is_set, int join)
+{
+    if (!fused && !gemm) return TW_ERR_NULL;
+    if (fused) TW_TRY(validate_fused(*fused));
+    if (gemm) TW_TRY(validate_gemm(*gemm));
+    if (fused && gemm && stream_comm == stream_compute) return TW_ERR_SPLIT;
+
+    hipStream_t sc = static_cast<hipStream_t>(stream_comm);
+    hipStream_t sx = static_cast<hipStream_t>(stream_compute);
+    hipStream_t sp = static_cast<hipStream_t>(parent);
+    if (parent_is_set) {
+        hipEvent_t fork;
+        TW_TRY(borrow_event(&fork));
+        TW_HIP(hipEventRecord(fork, sp));
+        if (fused && sc != sp) TW_HIP(hipStreamWaitEvent(sc, fork, 0));
+        if (gemm && sx != sp) TW_HIP(hipStreamWaitEvent(sx, fork, 0));
+    }
+    // The few workgroups of the fused kernel go first: they take their compute
+    // units, and the GEMM's workgroups are placed on what is left.
+    if (fused && fused->N > 0) TW_TRY(launch_fused(*fused, 0, fused->N, nullptr, 0, sc));
+    if (gemm) TW_TRY(launch_gemm(*gemm, sx));
+    if (parent_is_set && join) {
+        if (fused && sc != sp) TW_TRY(stream_wait_stream(sp, sc));
+        if (gemm && sx != sp) TW_TRY(stream_wait_stream(sp, sx));
+    }
+    return TW_OK;
+}
+
+}  // extern "C"

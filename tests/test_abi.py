@@ -1,0 +1,201 @@
+"""Host-side checks of the C ABI that need no GPU: the library loads, exports
+every function include/tw.h declares, and rejects bad arguments before touching
+the device. No call here passes a complete valid argument set with made-up
+pointers unless the machine has no GPU, so nothing can be launched on them."""
+import ctypes
+import os
+import re
+
+import pytest
+
+import paper_2505_11329_amd as tw
+from paper_2505_11329_amd.binding import FusedArgs, GemmArgs
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+VP = ctypes.c_void_p
+
+OK, E_NULL, E_SHAPE, E_ALIGN, E_ALIAS, E_UNSUP, E_SPLIT, E_HIP = range(8)
+
+
+def declared_functions():
+    text = open(os.path.join(ROOT, "include", "tw.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(tw_[a-z0-9_]+)\s*\(", text)))
+
+
+def test_header_declares_the_documented_entry_points():
+    names = declared_functions()
+    for must in ("tw_reduce_add_rmsnorm", "tw_split_launch", "tw_split_point", "tw_gemm_bf16",
+                 "tw_overlap_launch", "tw_hbm_probe", "tw_device_cu_count", "tw_status_str",
+                 "tw_version", "tw_last_hip_error", "tw_fused_grid", "tw_reduce_add_rmsnorm_traced"):
+        assert must in names
+
+
+def test_library_exports_every_declared_symbol():
+    L = ctypes.CDLL(tw.library_path())
+    for name in declared_functions():
+        assert hasattr(L, name), "libtw.so does not export %s" % name
+
+
+def test_status_strings_and_version():
+    for s in range(8):
+        assert tw.status_str(s) and tw.status_str(s) != "unknown status"
+    assert tw.status_str(99) == "unknown status"
+    assert "gfx950" in tw.version()
+
+
+# fake but well-formed device addresses: never dereferenced, because every call
+# below fails validation (or the machine has no GPU)
+BASE = 0x7000_0000_0000
+N, H, P = 4, 64, 2
+TENSOR = N * H * 2
+
+
+def addr(i):
+    return BASE + i * 0x10000
+
+
+def fused_call(partials=None, residual=addr(4), weight=addr(5), eps=1e-5, n=N, h=H, p=P, budget=8,
+               out=addr(6), res_out=addr(7)):
+    if partials is None:
+        partials = [addr(0), addr(1), addr(2), addr(3)][:max(p, 0)] or [addr(0)]
+    arr = (VP * len(partials))(*partials)
+    return tw.lib().tw_reduce_add_rmsnorm(arr, VP(residual), VP(weight), eps, n, h, p, budget,
+                                         VP(out), VP(res_out), VP(None))
+
+
+def test_fused_rejects_null_pointers():
+    assert fused_call(residual=None) == E_NULL
+    assert fused_call(weight=None) == E_NULL
+    assert fused_call(out=None) == E_NULL
+    assert fused_call(res_out=None) == E_NULL
+    assert fused_call(partials=[addr(0), None]) == E_NULL
+    assert tw.lib().tw_reduce_add_rmsnorm(None, VP(addr(4)), VP(addr(5)), 1e-5, N, H, P, 8,
+                                         VP(addr(6)), VP(addr(7)), VP(None)) == E_NULL
+
+
+def test_fused_rejects_bad_sizes():
+    assert fused_call(n=-1) == E_SHAPE
+    assert fused_call(h=0) == E_SHAPE
+    assert fused_call(h=-8) == E_SHAPE
+    assert fused_call(p=0) == E_SHAPE
+    assert fused_call(partials=[addr(0)] * 17, p=17) == E_SHAPE
+    assert fused_call(eps=-1.0) == E_SHAPE
+    assert fused_call(eps=float("nan")) == E_SHAPE
+    assert fused_call(eps=float("inf")) == E_SHAPE
+    assert fused_call(h=60) == E_UNSUP        # not a multiple of 8
+    assert fused_call(h=65544) == E_UNSUP     # above TW_MAX_H
+    assert fused_call(n=2 ** 62, h=64) == E_SHAPE
+
+
+def test_fused_rejects_misaligned_pointers():
+    assert fused_call(residual=addr(4) + 2) == E_ALIGN
+    assert fused_call(weight=addr(5) + 8) == E_ALIGN
+    assert fused_call(out=addr(6) + 4) == E_ALIGN
+    assert fused_call(res_out=addr(7) + 2) == E_ALIGN
+    assert fused_call(partials=[addr(0), addr(1) + 2]) == E_ALIGN
+
+
+def test_fused_aliasing_rules():
+    # outputs overlapping each other, the weight, or an input at a different start
+    assert fused_call(out=addr(7)) == E_ALIAS
+    assert fused_call(out=addr(7) + 16) == E_ALIAS
+    assert fused_call(out=addr(5)) == E_ALIAS
+    assert fused_call(res_out=addr(4) + 16) == E_ALIAS       # shifted over the residual
+    assert fused_call(out=addr(4)) == E_ALIAS                # out on the residual
+    assert fused_call(res_out=addr(0)) == E_ALIAS            # residual_out on a partial
+    assert fused_call(out=addr(1) + TENSOR - 16) == E_ALIAS  # straddles the end of a partial
+
+
+@pytest.mark.skipif(tw.device_cu_count() > 0, reason="complete valid calls on made-up pointers only without a GPU")
+def test_valid_calls_without_a_gpu_return_hip_error_and_allowed_aliasing_passes_validation():
+    assert fused_call() == E_HIP
+    assert tw.lib().tw_last_hip_error() != 0
+    assert fused_call(res_out=addr(4)) == E_HIP   # in-place residual is allowed
+    assert fused_call(out=addr(1)) == E_HIP       # out over a partial is allowed
+    assert tw.fused_grid(4, 64, 8) == -1
+
+
+def test_empty_batch_is_ok_everywhere():
+    assert fused_call(n=0) == OK
+    assert tw.fused_grid(0, 64, 8) == 0
+    assert tw.fused_grid(4, 60, 8) == -1
+
+
+def split_call(split_row, sa=1, sb=2, n=N, **kw):
+    arr = (VP * P)(addr(0), addr(1))
+    a = FusedArgs(ctypes.cast(arr, ctypes.POINTER(VP)), addr(4), addr(5), 1e-5, n, H, P, 8, addr(6), addr(7))
+    for k, v in kw.items():
+        setattr(a, k, v)
+    return tw.lib().tw_split_launch(ctypes.byref(a), split_row, VP(sa), VP(sb), VP(None), 0, 0)
+
+
+def test_split_launch_argument_checks():
+    assert tw.lib().tw_split_launch(None, 0, VP(1), VP(2), VP(None), 0, 0) == E_NULL
+    assert split_call(-1) == E_SPLIT
+    assert split_call(N + 1) == E_SPLIT
+    assert split_call(2, sa=3, sb=3) == E_SPLIT        # both halves on one stream
+    assert split_call(2, H=60) == E_UNSUP              # fused validation comes first
+    assert split_call(0, n=0) == OK                    # nothing to do
+
+
+def test_split_point_matches_its_definition():
+    # independent statement: the smallest multiple of m that is >= N/2, capped at N
+    for n in list(range(0, 70)) + [127, 128, 129, 255, 256, 1000, 1024, 4096, 16384, 10 ** 12 + 7]:
+        for m in (1, 2, 3, 64, 128, 1000):
+            want = next((k for k in range(0, n + m, m) if 2 * k >= n), n) if n < 10 ** 6 else None
+            if want is None:
+                q = -(-n // 2)
+                want = -(-q // m) * m
+            want = min(want, n)
+            assert tw.split_point(n, m) == want, (n, m)
+    assert tw.split_point(-5, 128) == 0
+    assert tw.split_point(100, 0) == 50
+    assert tw.split_point(100, -3) == 50
+    assert tw.split_point(2 ** 62, 2 ** 62) == 2 ** 62
+    for n in (256, 1024, 4096, 16384):                  # the sweep's sizes: exactly N/2
+        assert tw.split_point(n, 128) == n // 2
+
+
+def gemm_call(A=addr(0), B=addr(20), C=addr(40), M=16, Nn=16, K=16, layout=0):
+    return tw.lib().tw_gemm_bf16(VP(A), VP(B), VP(C), M, Nn, K, layout, 0, VP(None))
+
+
+def test_gemm_argument_checks():
+    assert gemm_call(M=-1) == E_SHAPE
+    assert gemm_call(layout=7) == E_SHAPE
+    assert gemm_call(M=0) == OK
+    assert gemm_call(Nn=0) == OK
+    assert gemm_call(C=None) == E_NULL
+    assert gemm_call(A=None) == E_NULL
+    assert gemm_call(K=12) == E_UNSUP
+    assert gemm_call(Nn=12) == E_UNSUP
+    assert gemm_call(A=addr(0) + 2) == E_ALIGN
+    assert gemm_call(C=addr(0)) == E_ALIAS
+    assert gemm_call(C=addr(20) + 16) == E_ALIAS
+
+
+def test_overlap_launch_argument_checks():
+    L = tw.lib()
+    assert L.tw_overlap_launch(None, None, VP(1), VP(2), VP(None), 0, 0) == E_NULL
+    arr = (VP * P)(addr(0), addr(1))
+    f = FusedArgs(ctypes.cast(arr, ctypes.POINTER(VP)), addr(4), addr(5), 1e-5, N, H, P, 8, addr(6), addr(7))
+    g = GemmArgs(addr(0), addr(20), addr(40), 16, 16, 16, 0, 0)
+    assert L.tw_overlap_launch(ctypes.byref(f), ctypes.byref(g), VP(3), VP(3), VP(None), 0, 0) == E_SPLIT
+    f.H = 60
+    assert L.tw_overlap_launch(ctypes.byref(f), ctypes.byref(g), VP(1), VP(2), VP(None), 0, 0) == E_UNSUP
+    f.H = H
+    g.K = 12
+    assert L.tw_overlap_launch(ctypes.byref(f), ctypes.byref(g), VP(1), VP(2), VP(None), 0, 0) == E_UNSUP
+
+
+def test_probe_argument_checks():
+    L = tw.lib()
+    assert L.tw_hbm_probe(VP(addr(0)), VP(addr(9)), 1024, 9, 8, VP(None)) == E_SHAPE
+    assert L.tw_hbm_probe(VP(None), VP(addr(9)), 1024, tw.PROBE_READ, 8, VP(None)) == E_NULL
+    assert L.tw_hbm_probe(VP(addr(0)), VP(None), 1024, tw.PROBE_COPY, 8, VP(None)) == E_NULL
+    assert L.tw_hbm_probe(VP(addr(0)), VP(addr(9)), 1000, tw.PROBE_COPY, 8, VP(None)) == E_SHAPE
+    assert L.tw_hbm_probe(VP(addr(0)), VP(addr(9)), -16, tw.PROBE_COPY, 8, VP(None)) == E_SHAPE
+    assert L.tw_hbm_probe(VP(addr(0) + 4), VP(addr(9)), 1024, tw.PROBE_COPY, 8, VP(None)) == E_ALIGN
+    assert L.tw_hbm_probe(VP(addr(0)), VP(addr(0) + 512), 1024, tw.PROBE_COPY, 8, VP(None)) == E_ALIAS
+    assert L.tw_hbm_probe(VP(addr(0)), VP(addr(9)), 0, tw.PROBE_COPY, 8, VP(None)) == OK

@@ -1,0 +1,279 @@
+"""GPU parity of tw_reduce_add_rmsnorm / tw_split_launch against the fp64 oracle,
+element by element, through the C ABI (TokenWeave, arXiv 2505.11329, Appendix A
+Listing 1). Tolerance: |gpu - ref| <= 1e-2 |ref| + 1e-3 for both outputs; GPU vs
+GPU comparisons (CU budgets, token split) are bit-exact."""
+import numpy as np
+import pytest
+
+import oracle
+import tw_workloads as W
+from helpers import assert_parity, to_bits, to_gpu
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module")
+def torch_cuda():
+    import torch
+    assert torch.cuda.is_available(), "these tests need the MI355X"
+    return torch
+
+
+def upload(d):
+    return dict(partials=[to_gpu(p) for p in d["partials"]], residual=to_gpu(d["residual"]),
+                weight=to_gpu(d["weight"]), eps=d["eps"])
+
+
+def run(tw, torch, g, cu_budget=0, **kw):
+    out, res = tw.reduce_add_rmsnorm(g["partials"], g["residual"], g["weight"], g["eps"],
+                                     cu_budget=cu_budget, **kw)
+    torch.cuda.synchronize()
+    return to_bits(out), to_bits(res)
+
+
+def check_against_oracle(d, out_bits, res_bits, what, rows=None):
+    parts, resid = d["partials"], d["residual"]
+    if rows is not None:
+        parts = [np.ascontiguousarray(p[rows]) for p in parts]
+        resid = np.ascontiguousarray(resid[rows])
+        out_bits, res_bits = out_bits[rows], res_bits[rows]
+    ref_out, ref_res = oracle.fused(parts, resid, d["weight"], d["eps"])
+    assert_parity(oracle.bf16_to_f64(res_bits), ref_res, what + " residual_out")
+    assert_parity(oracle.bf16_to_f64(out_bits), ref_out, what + " out")
+
+
+def small(N, H, P, seed=0, eps=1e-5):
+    cfg = dict(N=N, H=H, P=P, partial_std=0.5, residual_std=1.0, outlier_frac=0.0, outlier_scale=1.0,
+               eps=eps, seed=seed)
+    return W.make_fused_inputs(cfg)
+
+
+# ---- the five workload configurations at full size --------------------------
+
+@pytest.mark.parametrize("name", ["c1_tiny", "c2_8b_tp2", "c3_70b_shard_tp8"])
+def test_config_full_size(tw, torch_cuda, name):
+    d = W.make_fused_inputs(name)
+    budgets = W.CONFIGS[name].get("cu_budgets", (32, 0))
+    g = upload(d)
+    first = None
+    for b in budgets:
+        out, res = run(tw, torch_cuda, g, cu_budget=b)
+        if first is None:
+            check_against_oracle(d, out, res, "%s budget %d" % (name, b))
+            first = (out, res)
+        else:   # other budgets: same bits, so the same verdict
+            assert np.array_equal(out, first[0]) and np.array_equal(res, first[1]), (name, b)
+
+
+@pytest.mark.parametrize("N", [256, 1024, 4096, 16384])
+def test_config4_split_sweep(tw, torch_cuda, N):
+    torch = torch_cuda
+    cfg = W.CONFIGS["c4_split_sweep_tp4"]
+    d = W.make_fused_inputs(cfg, N=N)
+    g = upload(d)
+    k = tw.split_point(N, cfg["split_multiple"])
+    assert k == N // 2
+    sa, sb = torch.cuda.Stream(), torch.cuda.Stream()
+    ref_bits = None
+    for b in cfg["cu_budgets"]:
+        out, res = run(tw, torch, g, cu_budget=b)
+        o2, r2 = tw.split_launch(g["partials"], g["residual"], g["weight"], g["eps"], k, sa, sb, cu_budget=b)
+        torch.cuda.synchronize()
+        assert np.array_equal(to_bits(o2), out) and np.array_equal(to_bits(r2), res), (N, b)
+        if ref_bits is None:
+            ref_bits = (out, res)
+        else:
+            assert np.array_equal(out, ref_bits[0]) and np.array_equal(res, ref_bits[1])
+    out, res = ref_bits
+    if N <= 4096:
+        check_against_oracle(d, out, res, "c4 N=%d" % N)
+    else:   # the oracle takes sampled rows: both ends, the cut, and random ones
+        rng = np.random.default_rng(0)
+        rows = np.unique(np.concatenate([[0, 1, k - 1, k, k + 1, N - 2, N - 1], rng.integers(0, N, 200)]))
+        check_against_oracle(d, out, res, "c4 N=%d sampled" % N, rows=rows)
+
+
+def test_config5_fused_half(tw, torch_cuda):
+    cfg = W.CONFIGS["c5_overlap_tp8"]
+    d = W.make_fused_inputs(cfg)
+    half = cfg["N"] // 2
+    dA = dict(d, partials=[p[:half] for p in d["partials"]], residual=d["residual"][:half])
+    g = upload(dA)
+    out, res = run(tw, torch_cuda, g, cu_budget=32)
+    check_against_oracle(dA, out, res, "c5 half A")
+
+
+# ---- shapes that exercise every kernel geometry and ragged tails ---------------
+
+SHAPES = [
+    (1, 8, 1), (3, 24, 3), (5, 64, 2), (130, 512, 16), (1000, 64, 7), (17, 520, 5), (33, 1024, 4),
+    (19, 4096, 8), (7, 8008, 2), (65, 8192, 1), (9, 8200, 2), (33, 16384, 4), (6, 24000, 8),
+    (9, 32768, 2), (5, 40000, 3), (3, 65536, 1), (4, 65536, 8), (2049, 256, 2), (1025, 8192, 8),
+]
+
+
+@pytest.mark.parametrize("N,H,P", SHAPES)
+def test_shapes_and_tails(tw, torch_cuda, N, H, P):
+    d = small(N, H, P, seed=N + H + P)
+    g = upload(d)
+    out, res = run(tw, torch_cuda, g, cu_budget=0)
+    check_against_oracle(d, out, res, "N=%d H=%d P=%d" % (N, H, P))
+    out2, res2 = run(tw, torch_cuda, g, cu_budget=3)
+    assert np.array_equal(out, out2) and np.array_equal(res, res2)
+
+
+def test_every_p_from_1_to_16(tw, torch_cuda):
+    for P in range(1, 17):
+        d = small(40, 2048, P, seed=P)
+        out, res = run(tw, torch_cuda, upload(d), cu_budget=5)
+        check_against_oracle(d, out, res, "P=%d" % P)
+
+
+# ---- determinism: budgets, split points, repeated runs -------------------------
+
+def test_bits_do_not_depend_on_budget_or_split(tw, torch_cuda):
+    torch = torch_cuda
+    d = W.make_fused_inputs("c2_8b_tp2", N=777)
+    g = upload(d)
+    base = run(tw, torch, g, cu_budget=0)
+    for b in (1, 2, 7, 8, 16, 32, 64, 255, 256, 1000):
+        got = run(tw, torch, g, cu_budget=b)
+        assert np.array_equal(got[0], base[0]) and np.array_equal(got[1], base[1]), b
+    sa, sb = torch.cuda.Stream(), torch.cuda.Stream()
+    for k in (0, 1, 2, 128, 389, 776, 777):
+        o, r = tw.split_launch(g["partials"], g["residual"], g["weight"], g["eps"], k, sa, sb, cu_budget=16)
+        torch.cuda.synchronize()
+        assert np.array_equal(to_bits(o), base[0]) and np.array_equal(to_bits(r), base[1]), k
+    # a row's bits do not depend on its position in the batch either
+    sub = dict(partials=[p[100:300].contiguous() for p in g["partials"]],
+               residual=g["residual"][100:300].contiguous(), weight=g["weight"], eps=g["eps"])
+    got = run(tw, torch, sub, cu_budget=4)
+    assert np.array_equal(got[0], base[0][100:300]) and np.array_equal(got[1], base[1][100:300])
+
+
+def test_split_waits_for_parent_and_joins(tw, torch_cuda):
+    """The inputs are produced on the parent stream right before the split launch
+    and the outputs consumed on it right after: ordering comes from the fork/join."""
+    torch = torch_cuda
+    d = W.make_fused_inputs("c4_split_sweep_tp4", N=2048)
+    g = upload(d)
+    want = run(tw, torch, g, cu_budget=16)
+    sa, sb, parent = torch.cuda.Stream(), torch.cuda.Stream(), torch.cuda.Stream()
+    stage = [torch.zeros_like(p) for p in g["partials"]]
+    torch.cuda.synchronize()
+    for _ in range(3):
+        with torch.cuda.stream(parent):
+            for s, p in zip(stage, g["partials"]):
+                s.zero_()
+                s.copy_(p)
+            o, r = tw.split_launch(stage, g["residual"], g["weight"], g["eps"], 1024, sa, sb,
+                                   cu_budget=16, parent=parent, use_parent=True, join=True)
+            o_copy, r_copy = o.clone(), r.clone()
+        parent.synchronize()
+        assert np.array_equal(to_bits(o_copy), want[0]) and np.array_equal(to_bits(r_copy), want[1])
+
+
+# ---- aliasing, special values, empty input ------------------------------------
+
+def test_in_place_residual_and_out_over_a_partial(tw, torch_cuda):
+    torch = torch_cuda
+    d = small(300, 4096, 4, seed=3)
+    g = upload(d)
+    want = run(tw, torch, g, cu_budget=8)
+    g2 = upload(d)
+    out, res = tw.reduce_add_rmsnorm(g2["partials"], g2["residual"], g2["weight"], g2["eps"], cu_budget=8,
+                                     out=g2["partials"][1], residual_out=g2["residual"])
+    torch.cuda.synchronize()
+    assert out.data_ptr() == g2["partials"][1].data_ptr() and res.data_ptr() == g2["residual"].data_ptr()
+    assert np.array_equal(to_bits(out), want[0]) and np.array_equal(to_bits(res), want[1])
+
+
+def test_non_finite_values_stay_in_their_row(tw, torch_cuda):
+    d = small(6, 1024, 2, seed=5)
+    d["partials"][0][1, 3] = 0x7F80      # +Inf
+    d["partials"][1][2, 700] = 0x7FC0    # NaN
+    d["residual"][4, 9] = 0xFF80         # -Inf
+    out, res = run(tw, torch_cuda, upload(d), cu_budget=2)
+    check_against_oracle(d, out, res, "non-finite")
+    ref_out, _ = oracle.fused(d["partials"], d["residual"], d["weight"], d["eps"])
+    assert np.isfinite(ref_out[[0, 3, 5]]).all()
+    assert np.isfinite(oracle.bf16_to_f64(out)[[0, 3, 5]]).all()
+
+
+def test_zero_rows_and_zero_eps(tw, torch_cuda):
+    d = small(4, 512, 2, seed=6, eps=0.0)
+    for p in d["partials"]:
+        p[2, :] = 0
+    d["residual"][2, :] = 0
+    out, res = run(tw, torch_cuda, upload(d), cu_budget=1)
+    check_against_oracle(d, out, res, "eps=0 with a zero row")      # NaN row in both
+    assert np.isnan(oracle.bf16_to_f64(out)[2]).all()
+    d["eps"] = 1e-6
+    out, res = run(tw, torch_cuda, upload(d), cu_budget=1)
+    assert (oracle.bf16_to_f64(out)[2] == 0).all()
+    check_against_oracle(d, out, res, "eps>0 with a zero row")
+
+
+def test_empty_batch(tw, torch_cuda):
+    torch = torch_cuda
+    z = torch.empty((0, 512), dtype=torch.bfloat16, device="cuda:0")
+    w = torch.ones(512, dtype=torch.bfloat16, device="cuda:0")
+    out, res = tw.reduce_add_rmsnorm([z, z], z, w, 1e-5)
+    torch.cuda.synchronize()
+    assert out.shape == (0, 512) and res.shape == (0, 512)
+
+
+def test_large_values_and_outliers(tw, torch_cuda):
+    """Residual stream with x50 outliers and partials near the top of bf16 range
+    scaled down so that the sum of squares stays finite in fp32."""
+    cfg = dict(W.CONFIGS["c3_70b_shard_tp8"], N=64)
+    d = W.make_fused_inputs(cfg)
+    big = W.f32_to_bf16_bits(W.bf16_bits_to_f32(d["residual"]) * np.float32(2.0 ** 40))
+    d["residual"] = big
+    out, res = run(tw, torch_cuda, upload(d), cu_budget=8)
+    check_against_oracle(d, out, res, "large magnitudes")
+
+
+def test_batch_longer_than_one_launch_can_address(tw, torch_cuda):
+    """More than 2 GiB per tensor goes out as several launches; rows around the
+    seam and at both ends are checked against the oracle. Inputs are drawn on the
+    GPU (seeded) because the host generator would take minutes at this size."""
+    torch = torch_cuda
+    H, P = 8192, 1
+    N = (1 << 31) // (H * 2) + 300
+    gen = torch.Generator(device="cuda:0")
+    gen.manual_seed(1234)
+    part = torch.empty((N, H), device="cuda:0", dtype=torch.bfloat16).normal_(0.0, 0.5, generator=gen)
+    resid = torch.empty((N, H), device="cuda:0", dtype=torch.bfloat16).normal_(0.0, 1.0, generator=gen)
+    w = to_gpu(W.uniform_bf16((H,), 0.5, 1.5, 0, W.STREAM_WEIGHT))
+    out, res = tw.reduce_add_rmsnorm([part], resid, w, 1e-5, cu_budget=0)
+    torch.cuda.synchronize()
+    seam = (1 << 31) // (H * 2)
+    rows = np.array([0, 1, seam - 2, seam - 1, seam, seam + 1, N - 2, N - 1, 777, 99999])
+    idx = torch.from_numpy(rows).to("cuda:0")
+    d = dict(partials=[to_bits(part[idx])], residual=to_bits(resid[idx]), weight=to_bits(w), eps=1e-5)
+    check_against_oracle(d, to_bits(out[idx]), to_bits(res[idx]), "multi-launch batch")
+
+
+def test_traced_launch_reports_distinct_compute_units(tw, torch_cuda):
+    """Each workgroup of a budgeted launch sits on its own compute unit: the
+    (XCC, SE, CU) triples decoded from the hardware id registers are distinct and
+    as many as the budget."""
+    torch = torch_cuda
+    d = W.make_fused_inputs("c3_70b_shard_tp8", N=512)
+    g = upload(d)
+    want = run(tw, torch, g, cu_budget=32)
+    for budget in (8, 32, 64):
+        out, res, hw = tw.reduce_add_rmsnorm_traced(g["partials"], g["residual"], g["weight"], g["eps"],
+                                                    cu_budget=budget)
+        torch.cuda.synchronize()
+        assert np.array_equal(to_bits(out), want[0]) and np.array_equal(to_bits(res), want[1])
+        hw = hw.cpu().numpy().astype(np.int64) & 0xFFFFFFFF
+        assert hw.shape[0] == budget
+        cu = (hw[:, 0] >> 8) & 0xF
+        se = (hw[:, 0] >> 13) & 0x7
+        sh = (hw[:, 0] >> 12) & 0x1
+        xcc = hw[:, 1] & 0xF
+        places = set(zip(xcc.tolist(), se.tolist(), sh.tolist(), cu.tolist()))
+        assert len(places) == budget, "workgroups shared a compute unit: %d places for %d workgroups" % (
+            len(places), budget)

@@ -1,0 +1,97 @@
+"""GPU parity of tw_gemm_bf16 (the compute stand-in of the other token split,
+TokenWeave Fig. 7b) against the fp64 textbook product, and of tw_overlap_launch
+against the two calls made one after the other.
+
+Tolerance for C (bf16, fp32 accumulation over K): the rounding to bf16 costs up
+to 2^-8 relative; fp32 accumulation of K products of magnitude ~sa*sb adds an
+absolute error of about K * 2^-24 * sa * sb in the worst case, far below
+1e-3 * sqrt(K) * sa * sb. So: |gpu - ref| <= 1e-2 |ref| + 1e-3 * sqrt(K) * sa * sb."""
+import numpy as np
+import pytest
+
+import oracle
+import tw_workloads as W
+from helpers import to_bits, to_gpu
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module")
+def torch_cuda():
+    import torch
+    assert torch.cuda.is_available()
+    return torch
+
+
+def gemm_check(got_f64, ref_f64, K, std, what):
+    tol = 1e-2 * np.abs(ref_f64) + 1e-3 * np.sqrt(max(K, 1)) * std * std
+    bad = np.abs(got_f64 - ref_f64) > tol
+    assert not bad.any(), "%s: %d of %d out of tolerance, first %s" % (
+        what, bad.sum(), bad.size, np.argwhere(bad)[:1])
+
+
+SHAPES = [(256, 128, 64), (64, 64, 64), (300, 200, 136), (1, 8, 8), (257, 136, 72), (512, 384, 1024),
+          (33, 1000, 264), (700, 24, 4096)]
+
+
+@pytest.mark.parametrize("M,N,K", SHAPES)
+def test_gemm_small_shapes_full_compare(tw, torch_cuda, M, N, K):
+    g = W.make_gemm_inputs(M, K, N, 0.5, seed=M + N + K, b_layout="nk")
+    C = tw.gemm_bf16(to_gpu(g["A"]), to_gpu(g["B"]), b_layout=tw.B_NK)
+    torch_cuda.cuda.synchronize()
+    ref = oracle.gemm(g["A"], g["B"], "nk")
+    gemm_check(oracle.bf16_to_f64(to_bits(C)), ref, K, 0.5, "gemm %dx%dx%d" % (M, N, K))
+    # a budgeted (persistent) launch walks the same tiles: same bits
+    C2 = tw.gemm_bf16(to_gpu(g["A"]), to_gpu(g["B"]), b_layout=tw.B_NK, cu_budget=3)
+    torch_cuda.cuda.synchronize()
+    assert np.array_equal(to_bits(C), to_bits(C2))
+
+
+def test_gemm_k_zero_gives_zeros(tw, torch_cuda):
+    torch = torch_cuda
+    A = torch.empty((40, 0), dtype=torch.bfloat16, device="cuda:0")
+    B = torch.empty((24, 0), dtype=torch.bfloat16, device="cuda:0")
+    C = torch.full((40, 24), 7.0, dtype=torch.bfloat16, device="cuda:0")
+    tw.gemm_bf16(A, B, C=C)
+    torch.cuda.synchronize()
+    assert (to_bits(C) == 0).all()
+
+
+def test_gemm_demo_shape_sampled(tw, torch_cuda):
+    """[2048 x 8192] x [8192 x 3584], N(0, 0.02^2): 4096 sampled outputs, one by one."""
+    gc = W.CONFIGS["c5_overlap_tp8"]["gemm"]
+    g = W.make_gemm_inputs(gc["M"], gc["K"], gc["N"], gc["std"], seed=0, b_layout="nk")
+    C = tw.gemm_bf16(to_gpu(g["A"]), to_gpu(g["B"]))
+    torch_cuda.cuda.synchronize()
+    Cb = to_bits(C)
+    rng = np.random.default_rng(0)
+    ms = np.concatenate([rng.integers(0, gc["M"], 4088), [0, 0, gc["M"] - 1, gc["M"] - 1, 255, 256, 1023, 1024]])
+    ns = np.concatenate([rng.integers(0, gc["N"], 4088), [0, gc["N"] - 1, 0, gc["N"] - 1, 127, 128, 3583, 1792]])
+    ref = oracle.gemm_samples(g["A"], g["B"], "nk", ms, ns)
+    gemm_check(oracle.bf16_to_f64(Cb[ms, ns]), ref, gc["K"], gc["std"], "demo gemm")
+    assert np.count_nonzero(Cb) > 0.99 * Cb.size
+
+
+def test_overlap_launch_equals_the_two_calls(tw, torch_cuda):
+    """Fused kernel on half A next to the GEMM on half B (two streams, fork and
+    join on a parent stream): same bits as the plain calls, every replay."""
+    torch = torch_cuda
+    cfg = W.CONFIGS["c5_overlap_tp8"]
+    d = W.make_fused_inputs(cfg, N=512)
+    g = dict(partials=[to_gpu(p) for p in d["partials"]], residual=to_gpu(d["residual"]),
+             weight=to_gpu(d["weight"]), eps=d["eps"])
+    gm = W.make_gemm_inputs(512, 1024, 640, 0.02, seed=0, b_layout="nk")
+    A, B = to_gpu(gm["A"]), to_gpu(gm["B"])
+    out0, res0 = tw.reduce_add_rmsnorm(g["partials"], g["residual"], g["weight"], g["eps"], cu_budget=32)
+    C0 = tw.gemm_bf16(A, B)
+    torch.cuda.synchronize()
+    comm, comp, parent = torch.cuda.Stream(), torch.cuda.Stream(), torch.cuda.Stream()
+    for _ in range(3):
+        with torch.cuda.stream(parent):
+            out, res, C = tw.overlap_launch(dict(g, cu_budget=32), dict(A=A, B=B, cu_budget=0), comm, comp,
+                                            parent=parent, use_parent=True, join=True)
+            oc, rc, cc = out.clone(), res.clone(), C.clone()
+        parent.synchronize()
+        assert np.array_equal(to_bits(oc), to_bits(out0))
+        assert np.array_equal(to_bits(rc), to_bits(res0))
+        assert np.array_equal(to_bits(cc), to_bits(C0))
