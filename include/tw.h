@@ -75,7 +75,8 @@ typedef enum tw_status {
  *   residual      device bf16 [N x H]
  *   weight        device bf16 [H]
  *   eps           finite, >= 0
- *   N             rows (tokens) >= 0; N == 0 is TW_OK and launches nothing
+ *   N             rows (tokens) >= 0; N == 0 is TW_OK, launches nothing, and the
+ *                 [N x H] pointers are then not looked at (they may be NULL)
  *   H             hidden size: a multiple of 8 with 8 <= H <= TW_MAX_H
  *   P             1 <= P <= TW_MAX_P
  *   cu_budget     number of compute units the kernel may occupy: the launch is
@@ -233,6 +234,8 @@ const char *tw_status_str(tw_status s);
 const char *tw_version(void);
 /* Raw hipError_t behind the last TW_ERR_HIP returned on the calling thread (0 if none). */
 int tw_last_hip_error(void);
+/* Source location and expression of that failing HIP call ("" if none). Static storage. */
+const char *tw_last_hip_error_where(void);
 
 #ifdef __cplusplus
 }

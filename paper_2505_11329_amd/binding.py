@@ -41,7 +41,7 @@ class TwError(RuntimeError):
         self.status = int(status)
         msg = "%s failed: %s (%s)" % (what, STATUS.get(self.status, self.status), status_str(self.status))
         if self.status == 7:
-            msg += " hipError=%d" % lib().tw_last_hip_error()
+            msg += " hipError=%d at %s" % (lib().tw_last_hip_error(), lib().tw_last_hip_error_where().decode())
         super().__init__(msg)
 
 
@@ -58,6 +58,12 @@ def lib():
         if not os.path.exists(_LIB_PATH):
             from .build import build_libtw
             build_libtw()
+        # libtw must share ONE HIP runtime with PyTorch (streams and device
+        # pointers cross the boundary). PyTorch ships its own libamdhip64 with
+        # the same soname as the system one: importing torch first puts that
+        # copy in the process, and the loader then resolves libtw's dependency
+        # to it instead of opening a second runtime.
+        import torch  # noqa: F401
         L = ctypes.CDLL(_LIB_PATH)
         fused_sig = [ctypes.POINTER(_vp), _vp, _vp, ctypes.c_float, _i64, _i64, ctypes.c_int,
                      ctypes.c_int, _vp, _vp]
@@ -86,6 +92,8 @@ def lib():
         L.tw_version.restype = ctypes.c_char_p
         L.tw_last_hip_error.argtypes = []
         L.tw_last_hip_error.restype = ctypes.c_int
+        L.tw_last_hip_error_where.argtypes = []
+        L.tw_last_hip_error_where.restype = ctypes.c_char_p
         _lib = L
         return L
 

@@ -353,16 +353,19 @@ int64_t fused_grid_size(int64_t n_rows, const FusedGeometry &g, int budget_wgs)
 
 tw_status validate_fused(const tw_fused_args &a)
 {
-    if (!a.partials || !a.residual || !a.weight || !a.out || !a.residual_out) return TW_ERR_NULL;
     if (a.P < 1 || a.P > TW_MAX_P) return TW_ERR_SHAPE;
-    for (int p = 0; p < a.P; ++p)
-        if (!a.partials[p]) return TW_ERR_NULL;
     if (a.N < 0 || a.H <= 0) return TW_ERR_SHAPE;
     if (!(a.eps >= 0.0f) || !(a.eps <= 3.402823466e+38f)) return TW_ERR_SHAPE;  // rejects NaN, Inf, < 0
     if (a.H % 8 != 0 || a.H > TW_MAX_H) return TW_ERR_UNSUPPORTED;
     if (a.N > (INT64_MAX / 2) / a.H) return TW_ERR_SHAPE;
-    if (!aligned16(a.residual) || !aligned16(a.weight) || !aligned16(a.out) || !aligned16(a.residual_out))
-        return TW_ERR_ALIGN;
+    if (!a.weight) return TW_ERR_NULL;
+    if (!aligned16(a.weight)) return TW_ERR_ALIGN;
+    // The [N x H] tensors of an empty batch have no storage to point at.
+    if (a.N == 0) return TW_OK;
+    if (!a.partials || !a.residual || !a.out || !a.residual_out) return TW_ERR_NULL;
+    for (int p = 0; p < a.P; ++p)
+        if (!a.partials[p]) return TW_ERR_NULL;
+    if (!aligned16(a.residual) || !aligned16(a.out) || !aligned16(a.residual_out)) return TW_ERR_ALIGN;
     for (int p = 0; p < a.P; ++p)
         if (!aligned16(a.partials[p])) return TW_ERR_ALIGN;
 
@@ -397,9 +400,8 @@ static tw_status launch_t(const FusedParams &prm, bool trace, int64_t grid, hipS
                                    static_cast<int>(kOccupancyPadBytes)));
         allowed[trace].store(1, std::memory_order_release);
     }
-    hipLaunchKernelGGL(kern, dim3(static_cast<unsigned>(grid)), dim3(kThreads), kOccupancyPadBytes,
-                       stream, prm);
-    TW_HIP(hipGetLastError());
+    TW_HIP(launch_kernel(kern, dim3(static_cast<unsigned>(grid)), dim3(kThreads), kOccupancyPadBytes,
+                         stream, prm));
     return TW_OK;
 }
 

@@ -269,8 +269,7 @@ tw_status launch_gemm(const tw_gemm_args &g, hipStream_t stream)
                                    hipFuncAttributeMaxDynamicSharedMemorySize, kGemmLdsBytes));
         allowed.store(1, std::memory_order_release);
     }
-    hipLaunchKernelGGL(gemm_bf16_nk_kernel, dim3(grid), dim3(kGemmThreads), kGemmLdsBytes, stream, prm);
-    TW_HIP(hipGetLastError());
+    TW_HIP(launch_kernel(gemm_bf16_nk_kernel, dim3(grid), dim3(kGemmThreads), kGemmLdsBytes, stream, prm));
     return TW_OK;
 }
 

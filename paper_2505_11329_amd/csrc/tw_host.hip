@@ -7,10 +7,12 @@
 namespace tw {
 
 static thread_local int g_last_hip_error = 0;
+static thread_local const char *g_last_hip_where = "";
 
-tw_status hip_fail(hipError_t e)
+tw_status hip_fail(hipError_t e, const char *where)
 {
     g_last_hip_error = static_cast<int>(e);
+    g_last_hip_where = where;
     (void)hipGetLastError();  // clear the sticky per-thread error so later calls start clean
     return TW_ERR_HIP;
 }
@@ -23,7 +25,7 @@ tw_status current_cu_count(int *cu_count)
 {
     int dev = 0;
     TW_HIP(hipGetDevice(&dev));
-    if (dev < 0 || dev >= kMaxDevices) return hip_fail(hipErrorInvalidDevice);
+    if (dev < 0 || dev >= kMaxDevices) return hip_fail(hipErrorInvalidDevice, "tw_host.hip: device id out of range");
     {
         std::lock_guard<std::mutex> lk(g_mu);
         if (g_cu_count[dev] > 0) {
@@ -33,7 +35,7 @@ tw_status current_cu_count(int *cu_count)
     }
     int n = 0;
     TW_HIP(hipDeviceGetAttribute(&n, hipDeviceAttributeMultiprocessorCount, dev));
-    if (n <= 0) return hip_fail(hipErrorInvalidDevice);
+    if (n <= 0) return hip_fail(hipErrorInvalidDevice, "tw_host.hip: device id out of range");
     std::lock_guard<std::mutex> lk(g_mu);
     g_cu_count[dev] = n;
     *cu_count = n;
@@ -53,7 +55,7 @@ tw_status borrow_event(hipEvent_t *ev)
 {
     int dev = 0;
     TW_HIP(hipGetDevice(&dev));
-    if (dev < 0 || dev >= kMaxDevices) return hip_fail(hipErrorInvalidDevice);
+    if (dev < 0 || dev >= kMaxDevices) return hip_fail(hipErrorInvalidDevice, "tw_host.hip: device id out of range");
     std::lock_guard<std::mutex> lk(g_mu);
     const int i = g_event_next[dev];
     g_event_next[dev] = (i + 1) % kEventRing;
@@ -105,6 +107,8 @@ const char *tw_status_str(tw_status s)
 const char *tw_version(void) { return "libtw 0.1 (gfx950)"; }
 
 int tw_last_hip_error(void) { return g_last_hip_error; }
+
+const char *tw_last_hip_error_where(void) { return g_last_hip_where; }
 
 int64_t tw_split_point(int64_t N, int64_t multiple)
 {

@@ -8,14 +8,29 @@
 
 namespace tw {
 
-// Records e as the calling thread's last HIP error and returns TW_ERR_HIP.
-tw_status hip_fail(hipError_t e);
+// Records e (and where it happened) as the calling thread's last HIP error and
+// returns TW_ERR_HIP.
+tw_status hip_fail(hipError_t e, const char *where);
 
+#define TW_STR2(x) #x
+#define TW_STR(x) TW_STR2(x)
 #define TW_HIP(expr)                                  \
     do {                                              \
         hipError_t tw_e_ = (expr);                    \
-        if (tw_e_ != hipSuccess) return ::tw::hip_fail(tw_e_); \
+        if (tw_e_ != hipSuccess)                      \
+            return ::tw::hip_fail(tw_e_, __FILE_NAME__ ":" TW_STR(__LINE__) ": " #expr); \
     } while (0)
+
+// Launches through the runtime's C entry point, whose return value belongs to
+// this launch alone (the triple-chevron form reports through the thread's sticky
+// "last error", which may be somebody else's).
+template <typename... Params, typename... Args>
+inline hipError_t launch_kernel(void (*kern)(Params...), dim3 grid, dim3 block, unsigned lds_bytes,
+                                hipStream_t stream, Args... args)
+{
+    void *argv[] = {const_cast<void *>(static_cast<const void *>(&args))...};
+    return hipLaunchKernel(reinterpret_cast<const void *>(kern), grid, block, argv, lds_bytes, stream);
+}
 
 #define TW_TRY(expr)                                  \
     do {                                              \

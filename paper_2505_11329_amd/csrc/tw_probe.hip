@@ -72,10 +72,9 @@ static tw_status launch_probe(const void *src, void *dst, int64_t bytes, unsigne
                                    static_cast<int>(kProbePadBytes)));
         allowed.store(1, std::memory_order_release);
     }
-    hipLaunchKernelGGL(kern, dim3(grid), dim3(kProbeThreads), kProbePadBytes, stream,
-                       static_cast<const u32x4 *>(src), static_cast<u32x4 *>(dst),
-                       static_cast<long long>(bytes / 16));
-    TW_HIP(hipGetLastError());
+    TW_HIP(launch_kernel(kern, dim3(grid), dim3(kProbeThreads), kProbePadBytes, stream,
+                         static_cast<const u32x4 *>(src), static_cast<u32x4 *>(dst),
+                         static_cast<long long>(bytes / 16)));
     return TW_OK;
 }
 

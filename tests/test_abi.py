@@ -118,6 +118,9 @@ def test_valid_calls_without_a_gpu_return_hip_error_and_allowed_aliasing_passes_
 
 def test_empty_batch_is_ok_everywhere():
     assert fused_call(n=0) == OK
+    assert fused_call(n=0, residual=None, out=None, res_out=None, partials=[None, None]) == OK
+    assert fused_call(n=0, weight=None) == E_NULL
+    assert fused_call(n=0, h=60) == E_UNSUP
     assert tw.fused_grid(0, 64, 8) == 0
     assert tw.fused_grid(4, 60, 8) == -1
 
