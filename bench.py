@@ -1,0 +1,321 @@
+#!/usr/bin/env python3
+"""Benchmark of libtw's hot path on one MI355X.
+
+Headline (`value`): algorithmic GB/s of the fused reduce + residual-add + RMSNorm
+(TokenWeave, arXiv 2505.11329, Appendix A Listing 1) on the 70B-class one-GPU
+shard (N=1024 rows, H=8192, P=8 partial buffers) inside a 32-CU budget, inputs
+resident in HBM, four rotating buffer sets (738 MB) so that no step re-reads
+data left in the 256 MB Infinity Cache. A step is one call of
+tw_reduce_add_rmsnorm. Algorithmic bytes per step = (P + 3) * 2 * H * N.
+
+The same JSON line carries: `roofline` (HBM, against the 8 TB/s vendor peak,
+from HIP events around every launch of the timed region), `cpu_baseline` (the
+fp64 oracle timed on this machine's host cores), `budgets` (GB/s per CU budget next
+to what a plain streaming kernel reaches with the same budget), `split` (two-
+stream token split vs one launch) and `overlap` (fused kernel next to the bf16
+MFMA GEMM vs the two run back to back).
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0        # MI355X vendor figure
+MFMA_BF16_PEAK_TFLOPS = 2500.0
+WORKLOAD = "c3_70b_shard_tp8"
+HEADLINE_BUDGET = 32
+# HBM bytes per launch of the headline kernel from hardware counters (FETCH_SIZE and
+# WRITE_SIZE, each scaled by what the same counter reads for a 192 MiB copy); the
+# figures and commands are in profiles/fused_kernel_c3_70b_shard_tp8_budget32.md.
+MEASURED_TRAFFIC_BYTES = {(WORKLOAD, 32): (147650 + 32768) * 1024}
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=400)
+    ap.add_argument("--warmup", type=int, default=40)
+    ap.add_argument("--budget", type=int, default=HEADLINE_BUDGET, help="CU budget of the timed steps")
+    ap.add_argument("--no-extras", action="store_true", help="only the timed region (for profilers)")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--counters-run", action="store_true",
+                    help="for rocprofv3 --pmc: a few fused launches plus plain copy launches of known size "
+                         "(tw_hbm_probe, 192 MiB read + 192 MiB written each) to scale the byte counters by")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on ONE GPU (no collectives, no sharding); --gpus %d is not "
+              "supported. `value` is the one GPU's throughput." % args.gpus, file=sys.stderr)
+        sys.exit(2)
+
+    import numpy as np
+    import torch
+    import paper_2505_11329_amd as tw
+    import tw_workloads as W
+
+    assert torch.cuda.is_available(), "bench.py needs the GPU"
+    dev = "cuda:0"
+    torch.cuda.set_device(0)
+    stream = torch.cuda.Stream()
+
+    def gpu(bits):
+        return torch.from_numpy(np.ascontiguousarray(bits).view(np.int16)).view(torch.bfloat16).to(dev)
+
+    def fused_sets(name, nsets, N=None):
+        sets = []
+        for k in range(nsets):
+            d = W.make_fused_inputs(name, N=N, seed=k)
+            s = dict(partials=[gpu(p) for p in d["partials"]], residual=gpu(d["residual"]),
+                     weight=gpu(d["weight"]), eps=d["eps"], N=d["N"], H=d["H"], P=d["P"])
+            s["out"] = torch.empty_like(s["residual"])
+            s["res_out"] = torch.empty_like(s["residual"])
+            sets.append(s)
+        return sets
+
+    def algo_bytes(s, rows=None):
+        return (s["P"] + 3) * 2 * s["H"] * (s["N"] if rows is None else rows)
+
+    def event_times(fns, iters, warm, on_stream):
+        """Per-launch durations (us) from HIP event pairs recorded on the launch stream."""
+        for i in range(warm):
+            fns[i % len(fns)]()
+        on_stream.synchronize()
+        evs = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(iters)]
+        for i in range(iters):
+            evs[i][0].record(on_stream)
+            fns[i % len(fns)]()
+            evs[i][1].record(on_stream)
+        on_stream.synchronize()
+        return np.array([a.elapsed_time(b) for a, b in evs]) * 1e3
+
+    if args.counters_run:
+        sets = fused_sets(WORKLOAD, 4)
+        pb = 192 << 20
+        src = torch.empty(pb, dtype=torch.uint8, device=dev).random_()
+        dst = torch.empty(pb, dtype=torch.uint8, device=dev)
+        torch.cuda.synchronize()
+        for i in range(12):
+            s = sets[i % 4]
+            tw.reduce_add_rmsnorm(s["partials"], s["residual"], s["weight"], s["eps"], cu_budget=args.budget,
+                                  out=s["out"], residual_out=s["res_out"], stream=stream)
+            tw.hbm_probe(src, dst, pb, tw.PROBE_COPY, cu_budget=args.budget, stream=stream)
+        torch.cuda.synchronize()
+        print(json.dumps({"counters_run": True, "fused_algorithmic_bytes": algo_bytes(sets[0]),
+                          "copy_bytes_read": pb, "copy_bytes_written": pb, "cu_budget": args.budget}))
+        return
+
+    # ---------------- timed region: K steps of the headline workload ----------------
+    sets = fused_sets(WORKLOAD, 4)
+    nbytes = algo_bytes(sets[0])
+    launches = [tw.prepare_reduce_add_rmsnorm(s["partials"], s["residual"], s["weight"], s["eps"],
+                                              cu_budget=args.budget, out=s["out"], residual_out=s["res_out"],
+                                              stream=stream)[0] for s in sets]
+    for i in range(args.warmup):
+        launches[i % 4]()
+    stream.synchronize()
+    torch.cuda.synchronize()
+    evs = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(args.steps)]
+    t0 = time.perf_counter()
+    for i in range(args.steps):
+        evs[i][0].record(stream)
+        launches[i % 4]()
+        evs[i][1].record(stream)
+    stream.synchronize()
+    torch.cuda.synchronize()
+    t1 = time.perf_counter()
+    ms_per_step = (t1 - t0) * 1e3 / args.steps
+    kern_us = np.array([a.elapsed_time(b) for a, b in evs]) * 1e3
+    avg_us = float(kern_us.mean())
+    value = nbytes / (ms_per_step * 1e-3) / 1e9
+    achieved = nbytes / (avg_us * 1e-6) / 1e9
+
+    result = {
+        "metric": "fused reduce+add+RMSNorm GB/s at a fixed CU budget",
+        "value": round(value, 1), "unit": "GB/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": round(ms_per_step, 5), "higher_is_better": True, "scaling": "weak",
+        "vs_baseline": None, "dtype": "bf16 in/out, f32 accumulate", "data": "synthetic",
+        "config": {"workload": "%s: N=1024 rows (1/8 of 8192 tokens), H=8192, P=8" % WORKLOAD,
+                   "cu_budget": args.budget, "eps": sets[0]["eps"],
+                   "buffer_sets_rotated": 4, "algorithmic_bytes_per_step": nbytes,
+                   "clocks": "not locked (non-root)"},
+        "roofline": {"bound": "hbm", "achieved": round(achieved, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                     "frac": round(achieved / HBM_PEAK_GBS, 4),
+                     "traffic": (round(MEASURED_TRAFFIC_BYTES[(WORKLOAD, args.budget)] / (avg_us * 1e-6) / 1e9, 1)
+                                 if (WORKLOAD, args.budget) in MEASURED_TRAFFIC_BYTES else None),
+                     "traffic_bytes_per_launch": MEASURED_TRAFFIC_BYTES.get((WORKLOAD, args.budget)),
+                     "kernel": "tw::fused_kernel<8,1,false>", "avg_launch_us": round(avg_us, 2),
+                     "p10_us": round(float(np.percentile(kern_us, 10)), 2),
+                     "p50_us": round(float(np.percentile(kern_us, 50)), 2),
+                     "p90_us": round(float(np.percentile(kern_us, 90)), 2)},
+    }
+
+    if not args.no_extras:
+        extras(result, tw, W, torch, np, stream, sets, fused_sets, algo_bytes, event_times, gpu)
+    del sets, launches
+    torch.cuda.empty_cache()
+    if not args.no_cpu_baseline:
+        result["cpu_baseline"] = cpu_baseline(W, np)
+    print(json.dumps(result))
+
+
+def extras(result, tw, W, torch, np, stream, sets, fused_sets, algo_bytes, event_times, gpu):
+    """Per-budget table, probe ceilings, split sweep, overlap demo. All outside the timed region."""
+    nbytes = algo_bytes(sets[0])
+
+    def fused_fns(ss, budget, st=stream):
+        return [tw.prepare_reduce_add_rmsnorm(s["partials"], s["residual"], s["weight"], s["eps"], cu_budget=budget,
+                                              out=s["out"], residual_out=s["res_out"], stream=st)[0] for s in ss]
+
+    # what a budget can stream: read-only and copy probes over 192 MiB buffers, rotated
+    pb = 192 << 20
+    srcs = [torch.empty(pb, dtype=torch.uint8, device="cuda:0").random_() for _ in range(4)]
+    dsts = [torch.empty(pb, dtype=torch.uint8, device="cuda:0") for _ in range(4)]
+    budgets = {}
+    for b in (8, 16, 32, 64, 128, 256):
+        t = event_times(fused_fns(sets, b), 60, 8, stream)
+        row = {"us": round(float(np.median(t)), 1), "GBps": round(nbytes / np.median(t) / 1e3, 1),
+               "frac_hbm_peak": round(nbytes / np.median(t) / 1e3 / HBM_PEAK_GBS, 4)}
+        for mode, key, mult in ((tw.PROBE_READ, "probe_read_GBps", 1), (tw.PROBE_COPY, "probe_copy_GBps", 2)):
+            fns = [(lambda i=i, mode=mode: tw.hbm_probe(srcs[i], dsts[i], pb, mode, cu_budget=b, stream=stream))
+                   for i in range(4)]
+            tp = event_times(fns, 20, 4, stream)
+            row[key] = round(mult * pb / np.median(tp) / 1e3, 1)
+        budgets[str(b)] = row
+    result["budgets"] = {"workload": WORKLOAD, "per_budget": budgets,
+                         "note": "probe_* = plain streaming kernel with the same budgeted launch shape"}
+    del srcs, dsts
+    torch.cuda.empty_cache()
+
+    # 8B-class shape (config 2) per budget
+    s2 = fused_sets("c2_8b_tp2", 6)
+    nb2 = algo_bytes(s2[0])
+    c2 = {}
+    for b in (8, 16, 32, 256):
+        t = event_times(fused_fns(s2, b), 60, 8, stream)
+        c2[str(b)] = {"us": round(float(np.median(t)), 1), "GBps": round(nb2 / np.median(t) / 1e3, 1)}
+    result["config2_8b_tp2"] = c2
+    del s2
+    torch.cuda.empty_cache()
+
+    # token split (config 4): one launch vs two halves on two streams, makespan on the parent
+    sa, sb = torch.cuda.Stream(), torch.cuda.Stream()
+    split = {}
+    cfg4 = W.CONFIGS["c4_split_sweep_tp4"]
+    for N in (1024, 4096):
+        nsets = 4 if N <= 1024 else 2
+        s4 = fused_sets("c4_split_sweep_tp4", nsets, N=N)
+        nb4 = algo_bytes(s4[0])
+        k = tw.split_point(N, cfg4["split_multiple"])
+        for b in cfg4["cu_budgets"]:
+            t1 = event_times(fused_fns(s4, b), 40, 6, stream)
+
+            def split_fn(s, b=b, k=k):
+                def f():
+                    with torch.cuda.stream(stream):
+                        tw.split_launch(s["partials"], s["residual"], s["weight"], s["eps"], k, sa, sb, cu_budget=b,
+                                        out=s["out"], residual_out=s["res_out"], parent=stream, use_parent=True,
+                                        join=True)
+                return f
+            t2 = event_times([split_fn(s) for s in s4], 40, 6, stream)
+            split["N%d_b%d" % (N, b)] = {"unsplit_us": round(float(np.median(t1)), 1),
+                                         "split_us": round(float(np.median(t2)), 1),
+                                         "unsplit_GBps": round(nb4 / np.median(t1) / 1e3, 1),
+                                         "split_GBps": round(nb4 / np.median(t2) / 1e3, 1)}
+        del s4
+        torch.cuda.empty_cache()
+    result["split"] = {"workload": "c4_split_sweep_tp4 (H=8192, P=4, k=N/2)", "per_case": split,
+                       "note": "each half gets the budget, so the split run occupies 2x the CUs"}
+
+    # overlap demo (config 5): fused(A, 32 CUs) next to GEMM(B) vs back to back
+    cfg5 = W.CONFIGS["c5_overlap_tp8"]
+    gc = cfg5["gemm"]
+    half = cfg5["N"] // 2
+    s5 = fused_sets("c5_overlap_tp8", 2, N=half)
+    nb5 = algo_bytes(s5[0])
+    g = W.make_gemm_inputs(gc["M"], gc["K"], gc["N"], gc["std"], 0, "nk")
+    A, B = gpu(g["A"]), gpu(g["B"])
+    C = torch.empty((gc["M"], gc["N"]), dtype=torch.bfloat16, device="cuda:0")
+    flops = 2.0 * gc["M"] * gc["K"] * gc["N"]
+    comm, comp = torch.cuda.Stream(), torch.cuda.Stream()
+    tf = event_times(fused_fns(s5, 32), 30, 5, stream)
+    tg = event_times([lambda: tw.gemm_bf16(A, B, C=C, cu_budget=0, stream=stream)], 30, 5, stream)
+
+    def serial_fn(s):
+        def f():
+            tw.reduce_add_rmsnorm(s["partials"], s["residual"], s["weight"], s["eps"], cu_budget=32,
+                                  out=s["out"], residual_out=s["res_out"], stream=stream)
+            tw.gemm_bf16(A, B, C=C, cu_budget=0, stream=stream)
+        return f
+
+    def overlap_fn(s, gemm_budget):
+        def f():
+            with torch.cuda.stream(stream):
+                tw.overlap_launch(dict(partials=s["partials"], residual=s["residual"], weight=s["weight"],
+                                       eps=s["eps"], cu_budget=32, out=s["out"], residual_out=s["res_out"]),
+                                  dict(A=A, B=B, C=C, cu_budget=gemm_budget), comm, comp, parent=stream,
+                                  use_parent=True, join=True)
+        return f
+    # interleave serial and overlapped trials
+    ts, to = [], []
+    for rep in range(6):
+        ts.append(event_times([serial_fn(s) for s in s5], 10, 2, stream))
+        to.append(event_times([overlap_fn(s, 0) for s in s5], 10, 2, stream))
+    ts, to = np.concatenate(ts), np.concatenate(to)
+    # fused duration inside the overlapped run: event pair on the comm stream
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    cont = []
+    for rep in range(20):
+        s = s5[rep % 2]
+        stream.synchronize()
+        tw.gemm_bf16(A, B, C=C, cu_budget=0, stream=comp)      # GEMM already running on the other stream
+        e0.record(comm)
+        tw.reduce_add_rmsnorm(s["partials"], s["residual"], s["weight"], s["eps"], cu_budget=32, out=s["out"],
+                              residual_out=s["res_out"], stream=comm)
+        e1.record(comm)
+        torch.cuda.synchronize()
+        cont.append(e0.elapsed_time(e1) * 1e3)
+    result["overlap"] = {
+        "workload": "c5_overlap_tp8: fused N=2048,H=8192,P=8 @32 CUs || GEMM [2048x8192]x[8192x3584] bf16",
+        "fused_alone_us": round(float(np.median(tf)), 1), "gemm_alone_us": round(float(np.median(tg)), 1),
+        "gemm_alone_TFLOPs": round(flops / np.median(tg) / 1e6, 1),
+        "gemm_frac_mfma_peak": round(flops / np.median(tg) / 1e6 / MFMA_BF16_PEAK_TFLOPS, 4),
+        "serial_us": round(float(np.median(ts)), 1), "overlapped_us": round(float(np.median(to)), 1),
+        "gain": round(float(np.median(ts) / np.median(to)), 3),
+        "fused_under_contention_us": round(float(np.median(cont)), 1),
+        "fused_under_contention_GBps": round(nb5 / np.median(cont) / 1e3, 1),
+        "note": "serial = both on one stream; overlapped = tw_overlap_launch on two streams with fork/join; "
+                "trials interleaved",
+    }
+
+
+def cpu_baseline(W, np):
+    """The fp64 oracle, as it stands, timed on this machine's host cores on the headline
+    workload (all 1024 rows), single-threaded and row-parallel."""
+    import oracle
+    d = W.make_fused_inputs(WORKLOAD)
+    nbytes = (d["P"] + 3) * 2 * d["H"] * d["N"]
+    threads = max(1, min(os.cpu_count() or 1, int(os.environ.get("OMP_NUM_THREADS", "0") or 0) or 64))
+
+    def timed(nt, budget_s):
+        times = []
+        t_end = time.perf_counter() + budget_s
+        while len(times) < 3 or time.perf_counter() < t_end:
+            t = time.perf_counter()
+            oracle.fused_mt(d["partials"], d["residual"], d["weight"], d["eps"], nt)
+            times.append(time.perf_counter() - t)
+        return float(np.median(times)), len(times)
+
+    t1, n1 = timed(1, 6.0)
+    tn, nn = timed(threads, 6.0)
+    return {"value": round(nbytes / tn / 1e9, 3), "unit": "GB/s", "cores": threads, "kind": "oracle",
+            "sample": "all 1024 rows of %s, median of %d runs (row-parallel pthreads, output allocation included)"
+                      % (WORKLOAD, nn),
+            "single_thread_GBps": round(nbytes / t1 / 1e9, 3), "single_thread_runs": n1}
+
+
+if __name__ == "__main__":
+    main()

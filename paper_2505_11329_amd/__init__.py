@@ -12,6 +12,7 @@ from .binding import (  # noqa: F401
     split_point,
     fused_grid,
     reduce_add_rmsnorm,
+    prepare_reduce_add_rmsnorm,
     reduce_add_rmsnorm_traced,
     split_launch,
     gemm_bf16,

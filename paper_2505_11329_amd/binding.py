@@ -175,6 +175,26 @@ def reduce_add_rmsnorm(partials, residual, weight, eps, cu_budget=0, out=None, r
     return out, residual_out
 
 
+def prepare_reduce_add_rmsnorm(partials, residual, weight, eps, cu_budget=0, out=None, residual_out=None,
+                               stream=None):
+    """Marshals the arguments of tw_reduce_add_rmsnorm once and returns
+    (launch, out, residual_out); launch() enqueues the call again with the same
+    tensors and stream (for loops that must not pay for marshalling every time).
+    The tensors are kept alive by the returned closure."""
+    a, keep, out, residual_out = _fused_pack(partials, residual, weight, eps, cu_budget, out, residual_out)
+    fn = lib().tw_reduce_add_rmsnorm
+    sh = _stream_handle(stream)
+    alive = (partials, residual, weight, out, residual_out, keep)
+    argv = (a.partials, a.residual, a.weight, a.eps, a.N, a.H, a.P, a.cu_budget, a.out, a.residual_out, sh)
+
+    def launch(_alive=alive):
+        st = fn(*argv)
+        if st != 0:
+            raise TwError(st, "tw_reduce_add_rmsnorm")
+
+    return launch, out, residual_out
+
+
 def reduce_add_rmsnorm_traced(partials, residual, weight, eps, cu_budget=0, out=None,
                               residual_out=None, stream=None):
     """tw_reduce_add_rmsnorm_traced. Returns (out, residual_out, hw_ids int32 [grid, 2])."""
