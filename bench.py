@@ -43,9 +43,10 @@ def main():
     ap.add_argument("--budget", type=int, default=HEADLINE_BUDGET, help="CU budget of the timed steps")
     ap.add_argument("--no-extras", action="store_true", help="only the timed region (for profilers)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
-    ap.add_argument("--counters-run", action="store_true",
-                    help="for rocprofv3 --pmc: a few fused launches plus plain copy launches of known size "
-                         "(tw_hbm_probe, 192 MiB read + 192 MiB written each) to scale the byte counters by")
+    ap.add_argument("--counters-run", choices=("fused", "gemm"), default=None,
+                    help="for rocprofv3 --pmc. fused: a few fused launches plus plain copy launches of known "
+                         "size (tw_hbm_probe, 192 MiB read + 192 MiB written each) to scale the byte counters "
+                         "by. gemm: a few launches of the bf16 GEMM on the overlap demo's shape")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on ONE GPU (no collectives, no sharding); --gpus %d is not "
@@ -92,7 +93,17 @@ def main():
         on_stream.synchronize()
         return np.array([a.elapsed_time(b) for a, b in evs]) * 1e3
 
-    if args.counters_run:
+    if args.counters_run == "gemm":
+        gc = W.CONFIGS["c5_overlap_tp8"]["gemm"]
+        g = W.make_gemm_inputs(gc["M"], gc["K"], gc["N"], gc["std"], 0, "nk")
+        A, B = gpu(g["A"]), gpu(g["B"])
+        C = torch.empty((gc["M"], gc["N"]), dtype=torch.bfloat16, device=dev)
+        for i in range(12):
+            tw.gemm_bf16(A, B, C=C, cu_budget=0, stream=stream)
+        torch.cuda.synchronize()
+        print(json.dumps({"counters_run": "gemm", "flops_per_launch": 2.0 * gc["M"] * gc["K"] * gc["N"]}))
+        return
+    if args.counters_run == "fused":
         sets = fused_sets(WORKLOAD, 4)
         pb = 192 << 20
         src = torch.empty(pb, dtype=torch.uint8, device=dev).random_()
@@ -179,14 +190,23 @@ def extras(result, tw, W, torch, np, stream, sets, fused_sets, algo_bytes, event
         t = event_times(fused_fns(sets, b), 60, 8, stream)
         row = {"us": round(float(np.median(t)), 1), "GBps": round(nbytes / np.median(t) / 1e3, 1),
                "frac_hbm_peak": round(nbytes / np.median(t) / 1e3 / HBM_PEAK_GBS, 4)}
-        for mode, key, mult in ((tw.PROBE_READ, "probe_read_GBps", 1), (tw.PROBE_COPY, "probe_copy_GBps", 2)):
-            fns = [(lambda i=i, mode=mode: tw.hbm_probe(srcs[i], dsts[i], pb, mode, cu_budget=b, stream=stream))
-                   for i in range(4)]
-            tp = event_times(fns, 20, 4, stream)
-            row[key] = round(mult * pb / np.median(tp) / 1e3, 1)
+        fns = [(lambda i=i: tw.hbm_probe(srcs[i], dsts[i], pb, tw.PROBE_READ, cu_budget=b, stream=stream))
+               for i in range(4)]
+        tp = event_times(fns, 20, 4, stream)
+        row["probe_read_GBps"] = round(pb / np.median(tp) / 1e3, 1)
+        # the fused kernel's own mix: P+1 streams read, 2 written, 16 MiB each, no arithmetic
+        sb = pb // 12
+        sb -= sb % 16384
+        fns = [(lambda i=i: tw.hbm_probe_mixed(srcs[i], dsts[i], sb, 9, 2, cu_budget=b, stream=stream))
+               for i in range(4)]
+        tp = event_times(fns, 20, 4, stream)
+        row["probe_mix_9r2w_GBps"] = round(11 * sb / np.median(tp) / 1e3, 1)
+        row["frac_of_mix_probe"] = round(row["GBps"] / row["probe_mix_9r2w_GBps"], 3)
         budgets[str(b)] = row
     result["budgets"] = {"workload": WORKLOAD, "per_budget": budgets,
-                         "note": "probe_* = plain streaming kernel with the same budgeted launch shape"}
+                         "note": "probe_read = one stream read; probe_mix_9r2w = 9 streams read + 2 written with "
+                                 "the fused kernel's launch shape and access pattern but no arithmetic: the "
+                                 "ceiling that this many compute units allow"}
     del srcs, dsts
     torch.cuda.empty_cache()
 

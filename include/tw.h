@@ -226,6 +226,19 @@ tw_status tw_overlap_launch(const tw_fused_args *fused, const tw_gemm_args *gemm
 tw_status tw_hbm_probe(const void *src, void *dst, int64_t bytes, int mode, int cu_budget,
                        void *stream);
 
+/*
+ * Measurement aid: the fused kernel's traffic shape without its arithmetic.
+ * With the same budgeted launch, every workgroup walks 16 KiB rows; per row it
+ * reads n_read streams (src + r * stream_bytes, r < n_read) and writes n_write
+ * streams (dst + w * stream_bytes) at the same offset. What
+ * it reaches is the ceiling of any kernel with that mix of loads and stores on
+ * that many compute units. stream_bytes: a multiple of 16384, at most 2 GiB;
+ * 0 <= n_read <= TW_MAX_P + 1, 0 <= n_write <= 4, not both zero. With
+ * n_write == 0, dst still needs 16 KiB. src and dst ranges must not overlap.
+ */
+tw_status tw_hbm_probe_mixed(const void *src, void *dst, int64_t stream_bytes, int n_read,
+                             int n_write, int cu_budget, void *stream);
+
 /* Compute units of the current device; -1 when no device can be queried. */
 int tw_device_cu_count(void);
 /* Static, NUL-terminated description of a status code (never NULL). */

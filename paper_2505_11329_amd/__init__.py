@@ -18,6 +18,7 @@ from .binding import (  # noqa: F401
     gemm_bf16,
     overlap_launch,
     hbm_probe,
+    hbm_probe_mixed,
     FusedArgs,
     GemmArgs,
     STATUS,

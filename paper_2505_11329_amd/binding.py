@@ -84,6 +84,8 @@ def lib():
         L.tw_overlap_launch.restype = ctypes.c_int
         L.tw_hbm_probe.argtypes = [_vp, _vp, _i64, ctypes.c_int, ctypes.c_int, _vp]
         L.tw_hbm_probe.restype = ctypes.c_int
+        L.tw_hbm_probe_mixed.argtypes = [_vp, _vp, _i64, ctypes.c_int, ctypes.c_int, ctypes.c_int, _vp]
+        L.tw_hbm_probe_mixed.restype = ctypes.c_int
         L.tw_device_cu_count.argtypes = []
         L.tw_device_cu_count.restype = ctypes.c_int
         L.tw_status_str.argtypes = [ctypes.c_int]
@@ -277,3 +279,10 @@ def hbm_probe(src, dst, nbytes, mode, cu_budget=0, stream=None):
     _check(lib().tw_hbm_probe(_vp(src.data_ptr()) if src is not None else _vp(None), _vp(dst.data_ptr()),
                               int(nbytes), int(mode), int(cu_budget), _stream_handle(stream)),
            "tw_hbm_probe")
+
+
+def hbm_probe_mixed(src, dst, stream_bytes, n_read, n_write, cu_budget=0, stream=None):
+    """tw_hbm_probe_mixed: n_read streams read from src, n_write written to dst."""
+    _check(lib().tw_hbm_probe_mixed(_vp(src.data_ptr()) if src is not None else _vp(None), _vp(dst.data_ptr()),
+                                    int(stream_bytes), int(n_read), int(n_write), int(cu_budget),
+                                    _stream_handle(stream)), "tw_hbm_probe_mixed")

@@ -202,3 +202,17 @@ def test_probe_argument_checks():
     assert L.tw_hbm_probe(VP(addr(0) + 4), VP(addr(9)), 1024, tw.PROBE_COPY, 8, VP(None)) == E_ALIGN
     assert L.tw_hbm_probe(VP(addr(0)), VP(addr(0) + 512), 1024, tw.PROBE_COPY, 8, VP(None)) == E_ALIAS
     assert L.tw_hbm_probe(VP(addr(0)), VP(addr(9)), 0, tw.PROBE_COPY, 8, VP(None)) == OK
+
+
+def test_mixed_probe_argument_checks():
+    L = tw.lib()
+    sb = 1 << 20
+    assert L.tw_hbm_probe_mixed(VP(addr(0)), VP(addr(2000)), sb, 0, 0, 8, VP(None)) == E_SHAPE
+    assert L.tw_hbm_probe_mixed(VP(addr(0)), VP(addr(2000)), sb, 18, 2, 8, VP(None)) == E_SHAPE
+    assert L.tw_hbm_probe_mixed(VP(addr(0)), VP(addr(2000)), sb, 9, 5, 8, VP(None)) == E_SHAPE
+    assert L.tw_hbm_probe_mixed(VP(addr(0)), VP(addr(2000)), sb + 16, 9, 2, 8, VP(None)) == E_SHAPE
+    assert L.tw_hbm_probe_mixed(VP(None), VP(addr(2000)), sb, 9, 2, 8, VP(None)) == E_NULL
+    assert L.tw_hbm_probe_mixed(VP(addr(0)), VP(None), sb, 9, 2, 8, VP(None)) == E_NULL
+    assert L.tw_hbm_probe_mixed(VP(addr(0) + 8), VP(addr(2000)), sb, 9, 2, 8, VP(None)) == E_ALIGN
+    assert L.tw_hbm_probe_mixed(VP(addr(0)), VP(addr(0) + 8 * sb), sb, 9, 2, 8, VP(None)) == E_ALIAS
+    assert L.tw_hbm_probe_mixed(VP(addr(0)), VP(addr(2000)), 0, 9, 2, 8, VP(None)) == OK
