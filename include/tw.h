@@ -208,6 +208,69 @@ tw_status tw_overlap_launch(const tw_fused_args *fused, const tw_gemm_args *gemm
                             int parent_is_set, int join);
 
 /*
+ * One tensor-parallel block boundary as the paper weaves it (Fig. 7b, Section
+ * 4.1.2 "Overlapped Execution"), for one GPU's T token rows:
+ *
+ *   G1: partials[0] = X1 * W1^T   [T x K1] x [H x K1]^T  this GPU's projection output
+ *   F : the fused step of tw_fused_args over all P partials and the residual
+ *   G2: Y = out * W2^T            [T x H] x [N2 x H]^T   the next projection
+ *
+ * run for the two token splits a = [0, split_row) and b = [split_row, T). GEMMs
+ * go to stream_compute in the order G1(a) G1(b) G2(a) G2(b), fused kernels to
+ * stream_comm in the order F(a) F(b); events make F(s) wait for G1(s) and G2(s)
+ * wait for F(s), so F(a) runs next to G1(b) and F(b) next to G2(a). With
+ * split_row == 0 or == T the chain G1, F, G2 runs unsplit (nothing overlaps).
+ * Results are bit-identical for every split_row.
+ *
+ *   X1, W1, K1   device bf16 [T x K1] and [H x K1] (TW_B_NK), K1 a multiple of 8
+ *   fused        as for tw_reduce_add_rmsnorm with N = T; fused.partials[0] is
+ *                WRITTEN by G1 (the const in the struct is cast away) and then
+ *                read by F like the other partials; fused.cu_budget is F's budget
+ *   W2, N2, Y    device bf16 [N2 x H] and [T x N2], N2 a multiple of 8
+ *   gemm_cu_budget  persistent grid of the GEMMs; pass (CU count - fused.cu_budget)
+ *                so that the fused kernel always finds its compute units free
+ *   parent, parent_is_set, join   as for tw_split_launch
+ * The two streams must differ. Buffers must satisfy the aliasing rules of the
+ * three operations they take part in.
+ */
+typedef struct tw_layer_args {
+    const void *X1;
+    const void *W1;
+    int64_t K1;
+    tw_fused_args fused;
+    const void *W2;
+    int64_t N2;
+    void *Y;
+    int gemm_cu_budget;
+} tw_layer_args;
+
+tw_status tw_weave_layer(const tw_layer_args *layer, int64_t split_row, void *stream_compute,
+                         void *stream_comm, void *parent, int parent_is_set, int join);
+
+/*
+ * Wave-aware choice of the split row (Section 4.1.1 and Appendix A
+ * "Smart-Splitting"; Algorithm 1 finds the offset by profiling because its GEMMs
+ * are closed source, here the GEMM's tile grid is known, so the same sweep is
+ * evaluated analytically). A GEMM over r rows with output width n runs
+ * ceil(r / tile_m) * ceil(n / tile_n) workgroups, i.e. ceil(that / cus) waves on
+ * `cus` compute units. Among the candidates k = tw_split_point(T, multiple) +
+ * j * multiple (j = 0, 1, 2, ..., k < T, offset at most 512 rows as in
+ * Algorithm 1) the one with the fewest total waves over both splits and all
+ * n_gemms output widths wins; ties go to the smallest offset. Returns T ("do not
+ * split") only when tw_split_point already does, i.e. for batches too small to
+ * cut at that multiple. If not NULL, *waves_split receives the winner's wave
+ * total and *waves_unsplit that of the whole batch, so the caller can apply the
+ * paper's criterion (split waves <= unsplit waves) or its own threshold.
+ * Host only. gemm_n_out: host array of n_gemms output widths. Returns -1 on bad
+ * arguments (T < 0, n_gemms < 1, cus < 1, NULL array, a width < 1).
+ */
+int64_t tw_smart_split_point(int64_t T, int64_t multiple, const int64_t *gemm_n_out, int n_gemms,
+                             int cus, int64_t *waves_split, int64_t *waves_unsplit);
+
+/* Rows and columns of the output tile one GEMM workgroup computes. */
+void tw_gemm_tile_shape(int *tile_m, int *tile_n);
+
+/*
  * Measurement aid (not part of the method): a streaming kernel with the same
  * persistent, CU-budgeted launch shape as the fused kernel, used to measure
  * what a given number of compute units can pull from / push to HBM, and as the

@@ -19,6 +19,10 @@ from .binding import (  # noqa: F401
     overlap_launch,
     hbm_probe,
     hbm_probe_mixed,
+    weave_layer,
+    smart_split_point,
+    gemm_tile_shape,
+    LayerArgs,
     FusedArgs,
     GemmArgs,
     STATUS,

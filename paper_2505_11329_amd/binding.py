@@ -36,6 +36,12 @@ class GemmArgs(ctypes.Structure):
                 ("b_layout", ctypes.c_int), ("cu_budget", ctypes.c_int)]
 
 
+class LayerArgs(ctypes.Structure):
+    """struct tw_layer_args"""
+    _fields_ = [("X1", _vp), ("W1", _vp), ("K1", _i64), ("fused", FusedArgs), ("W2", _vp), ("N2", _i64),
+                ("Y", _vp), ("gemm_cu_budget", ctypes.c_int)]
+
+
 class TwError(RuntimeError):
     def __init__(self, status, what):
         self.status = int(status)
@@ -84,6 +90,13 @@ def lib():
         L.tw_overlap_launch.restype = ctypes.c_int
         L.tw_hbm_probe.argtypes = [_vp, _vp, _i64, ctypes.c_int, ctypes.c_int, _vp]
         L.tw_hbm_probe.restype = ctypes.c_int
+        L.tw_weave_layer.argtypes = [ctypes.POINTER(LayerArgs), _i64, _vp, _vp, _vp, ctypes.c_int, ctypes.c_int]
+        L.tw_weave_layer.restype = ctypes.c_int
+        L.tw_smart_split_point.argtypes = [_i64, _i64, ctypes.POINTER(_i64), ctypes.c_int, ctypes.c_int,
+                                           ctypes.POINTER(_i64), ctypes.POINTER(_i64)]
+        L.tw_smart_split_point.restype = _i64
+        L.tw_gemm_tile_shape.argtypes = [ctypes.POINTER(ctypes.c_int), ctypes.POINTER(ctypes.c_int)]
+        L.tw_gemm_tile_shape.restype = None
         L.tw_hbm_probe_mixed.argtypes = [_vp, _vp, _i64, ctypes.c_int, ctypes.c_int, ctypes.c_int, _vp]
         L.tw_hbm_probe_mixed.restype = ctypes.c_int
         L.tw_device_cu_count.argtypes = []
@@ -286,3 +299,38 @@ def hbm_probe_mixed(src, dst, stream_bytes, n_read, n_write, cu_budget=0, stream
     _check(lib().tw_hbm_probe_mixed(_vp(src.data_ptr()) if src is not None else _vp(None), _vp(dst.data_ptr()),
                                     int(stream_bytes), int(n_read), int(n_write), int(cu_budget),
                                     _stream_handle(stream)), "tw_hbm_probe_mixed")
+
+
+def smart_split_point(T, multiple, gemm_n_out, cus):
+    """tw_smart_split_point. Returns (split_row, waves_split, waves_unsplit)."""
+    arr = (_i64 * max(len(gemm_n_out), 1))(*[int(x) for x in gemm_n_out])
+    ws, wu = _i64(0), _i64(0)
+    k = int(lib().tw_smart_split_point(int(T), int(multiple), arr, len(gemm_n_out), int(cus),
+                                       ctypes.byref(ws), ctypes.byref(wu)))
+    return k, int(ws.value), int(wu.value)
+
+
+def gemm_tile_shape():
+    m, n = ctypes.c_int(0), ctypes.c_int(0)
+    lib().tw_gemm_tile_shape(ctypes.byref(m), ctypes.byref(n))
+    return m.value, n.value
+
+
+def weave_layer(X1, W1, partials, residual, weight, eps, W2, split_row, stream_compute, stream_comm,
+                fused_cu_budget=32, gemm_cu_budget=0, out=None, residual_out=None, Y=None, parent=None,
+                use_parent=True, join=True):
+    """tw_weave_layer. partials[0] is overwritten with X1 @ W1.T. Returns (out, residual_out, Y)."""
+    import torch
+    a, keep, out, residual_out = _fused_pack(partials, residual, weight, eps, fused_cu_budget, out, residual_out)
+    T, H = residual.shape
+    K1 = X1.shape[1]
+    N2 = W2.shape[0]
+    if Y is None:
+        Y = torch.empty((T, N2), dtype=torch.bfloat16, device=residual.device)
+    la = LayerArgs(_bf16_ptr(X1, "X1", (T, K1)), _bf16_ptr(W1, "W1", (H, K1)), K1, a,
+                   _bf16_ptr(W2, "W2", (N2, H)), N2, _bf16_ptr(Y, "Y", (T, N2)), int(gemm_cu_budget))
+    _check(lib().tw_weave_layer(ctypes.byref(la), int(split_row), _stream_handle(stream_compute),
+                                _stream_handle(stream_comm),
+                                _stream_handle(parent) if use_parent else _vp(None),
+                                1 if use_parent else 0, 1 if join else 0), "tw_weave_layer")
+    return out, residual_out, Y

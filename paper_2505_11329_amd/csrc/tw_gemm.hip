@@ -35,7 +35,7 @@
 
 namespace tw {
 
-static constexpr int BM = 256, BN = 128, BK = 64;
+static constexpr int BM = kGemmTileM, BN = kGemmTileN, BK = 64;
 static constexpr int kGemmThreads = 512;
 static constexpr int kStageABytes = BM * BK * 2;  // 32 KiB
 static constexpr int kStageBBytes = BN * BK * 2;  // 16 KiB

@@ -179,4 +179,106 @@ tw_status tw_overlap_launch(const tw_fused_args *fused, const tw_gemm_args *gemm
     return TW_OK;
 }
 
+// ---- one woven layer boundary: G1 -> F -> G2 over two token splits ----
+
+static tw_gemm_args rows_of(const tw_gemm_args &g, int64_t r0, int64_t r1)
+{
+    tw_gemm_args s = g;
+    s.A = static_cast<const char *>(g.A) + r0 * g.K * 2;
+    s.C = static_cast<char *>(g.C) + r0 * g.N * 2;
+    s.M = r1 - r0;
+    return s;
+}
+
+tw_status tw_weave_layer(const tw_layer_args *layer, int64_t split_row, void *stream_compute,
+                         void *stream_comm, void *parent, int parent_is_set, int join)
+{
+    if (!layer) return TW_ERR_NULL;
+    const tw_fused_args &f = layer->fused;
+    TW_TRY(validate_fused(f));
+    const int64_t T = f.N;
+    if (split_row < 0 || split_row > T) return TW_ERR_SPLIT;
+    if (stream_compute == stream_comm) return TW_ERR_SPLIT;
+    if (layer->K1 < 0 || layer->N2 < 0) return TW_ERR_SHAPE;
+    if (T == 0) return TW_OK;
+    const tw_gemm_args g1 = {layer->X1, layer->W1, const_cast<void *>(f.partials[0]), T, f.H, layer->K1,
+                             TW_B_NK, layer->gemm_cu_budget};
+    const tw_gemm_args g2 = {f.out, layer->W2, layer->Y, T, layer->N2, f.H, TW_B_NK, layer->gemm_cu_budget};
+    TW_TRY(validate_gemm(g1));
+    TW_TRY(validate_gemm(g2));
+
+    hipStream_t sx = static_cast<hipStream_t>(stream_compute), sc = static_cast<hipStream_t>(stream_comm);
+    hipStream_t sp = static_cast<hipStream_t>(parent);
+    if (parent_is_set) {
+        hipEvent_t fork;
+        TW_TRY(borrow_event(&fork));
+        TW_HIP(hipEventRecord(fork, sp));
+        if (sx != sp) TW_HIP(hipStreamWaitEvent(sx, fork, 0));
+        if (sc != sp) TW_HIP(hipStreamWaitEvent(sc, fork, 0));
+    }
+    const int64_t cuts[3] = {0, (split_row == 0 || split_row == T) ? T : split_row, T};
+    const int n_splits = cuts[1] == T ? 1 : 2;
+    // compute stream: every G1 first, so the second split's projection is what
+    // runs next to the first split's fused kernel
+    hipEvent_t g1_done[2], f_done[2];
+    for (int s = 0; s < n_splits; ++s) {
+        TW_TRY(launch_gemm(rows_of(g1, cuts[s], cuts[s + 1]), sx));
+        TW_TRY(borrow_event(&g1_done[s]));
+        TW_HIP(hipEventRecord(g1_done[s], sx));
+    }
+    for (int s = 0; s < n_splits; ++s) {
+        TW_HIP(hipStreamWaitEvent(sc, g1_done[s], 0));
+        TW_TRY(launch_fused(f, cuts[s], cuts[s + 1], nullptr, 0, sc));
+        TW_TRY(borrow_event(&f_done[s]));
+        TW_HIP(hipEventRecord(f_done[s], sc));
+        TW_HIP(hipStreamWaitEvent(sx, f_done[s], 0));
+        TW_TRY(launch_gemm(rows_of(g2, cuts[s], cuts[s + 1]), sx));
+    }
+    if (parent_is_set && join) {
+        if (sx != sp) TW_TRY(stream_wait_stream(sp, sx));
+        if (sc != sp) TW_TRY(stream_wait_stream(sp, sc));
+    }
+    return TW_OK;
+}
+
+void tw_gemm_tile_shape(int *tile_m, int *tile_n)
+{
+    if (tile_m) *tile_m = kGemmTileM;
+    if (tile_n) *tile_n = kGemmTileN;
+}
+
+static int64_t gemm_waves(int64_t rows, int64_t n_out, int64_t cus)
+{
+    if (rows <= 0) return 0;
+    const int64_t wgs = ((rows + kGemmTileM - 1) / kGemmTileM) * ((n_out + kGemmTileN - 1) / kGemmTileN);
+    return (wgs + cus - 1) / cus;
+}
+
+int64_t tw_smart_split_point(int64_t T, int64_t multiple, const int64_t *gemm_n_out, int n_gemms, int cus,
+                             int64_t *waves_split, int64_t *waves_unsplit)
+{
+    if (T < 0 || n_gemms < 1 || cus < 1 || !gemm_n_out) return -1;
+    for (int i = 0; i < n_gemms; ++i)
+        if (gemm_n_out[i] < 1) return -1;
+    if (multiple <= 0) multiple = 1;
+    int64_t unsplit = 0;
+    for (int i = 0; i < n_gemms; ++i) unsplit += gemm_waves(T, gemm_n_out[i], cus);
+    if (waves_unsplit) *waves_unsplit = unsplit;
+    if (waves_split) *waves_split = unsplit;
+    const int64_t base = tw_split_point(T, multiple);
+    if (base >= T) return T;
+    int64_t best_k = T, best_cost = INT64_MAX;
+    for (int64_t k = base; k < T && k - base <= 512; k += multiple) {
+        int64_t cost = 0;
+        for (int i = 0; i < n_gemms; ++i)
+            cost += gemm_waves(k, gemm_n_out[i], cus) + gemm_waves(T - k, gemm_n_out[i], cus);
+        if (cost < best_cost) {
+            best_cost = cost;
+            best_k = k;
+        }
+    }
+    if (waves_split) *waves_split = best_cost;
+    return best_k;
+}
+
 }  // extern "C"

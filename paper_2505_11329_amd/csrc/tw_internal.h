@@ -77,6 +77,7 @@ tw_status launch_fused(const tw_fused_args &a, int64_t row_begin, int64_t row_en
 // ---- GEMM stand-in (tw_gemm.hip) ----
 tw_status validate_gemm(const tw_gemm_args &g);
 tw_status launch_gemm(const tw_gemm_args &g, hipStream_t stream);
+static constexpr int kGemmTileM = 256, kGemmTileN = 128;
 
 // ---- fork/join events (tw_host.hip) ----
 // A small per-device pool of timing-disabled events used to order streams.

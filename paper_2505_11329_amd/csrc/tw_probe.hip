@@ -62,25 +62,24 @@ __global__ __launch_bounds__(kProbeThreads) void probe_kernel(const u32x4 *src, 
 }
 
 // The fused kernel's traffic shape without its arithmetic: per 16 KiB "row" a
-// workgroup reads n_read streams and writes n_write streams at the same offset.
+// workgroup reads NR streams and writes n_write streams at the same offset.
 // What this reaches is the ceiling for any kernel with that mix of loads and
-// stores at the given budget.
+// stores at the given budget. NR is a template parameter so that exactly NR
+// loads are issued per row (a run-time count would issue dead ones).
+template <int NR>
 __global__ __launch_bounds__(kProbeThreads) void probe_mixed_kernel(const char *src, char *dst,
-                                                                    unsigned stream_bytes, int n_read,
-                                                                    int n_write)
+                                                                    unsigned stream_bytes, int n_write)
 {
     const unsigned rows = stream_bytes / (kProbeThreads * 16u);
     u32x4 acc = {1u, 2u, 3u, 4u};
     for (unsigned row = blockIdx.x; row < rows; row += gridDim.x) {
         const unsigned off = row * (kProbeThreads * 16u) + threadIdx.x * 16u;
-        u32x4 v[TW_MAX_P + 1];
+        u32x4 v[NR > 0 ? NR : 1];
 #pragma unroll
-        for (int r = 0; r <= TW_MAX_P; ++r) {
-            // dead streams (uniform condition) get an empty descriptor and read as zero
-            const bool live = r < n_read;
+        for (int r = 0; r < NR; ++r) {
             __amdgpu_buffer_rsrc_t rs = __builtin_amdgcn_make_buffer_rsrc(
-                const_cast<char *>(src) + static_cast<size_t>(live ? r : 0) * stream_bytes, 0,
-                live ? static_cast<int>(stream_bytes) : 0, 0x00020000);
+                const_cast<char *>(src) + static_cast<size_t>(r) * stream_bytes, 0,
+                static_cast<int>(stream_bytes), 0x00020000);
             v[r] = __builtin_amdgcn_raw_buffer_load_b128(rs, off, 0, 2);
         }
         for (int wst = 0; wst < n_write; ++wst) {
@@ -89,10 +88,37 @@ __global__ __launch_bounds__(kProbeThreads) void probe_mixed_kernel(const char *
             __builtin_amdgcn_raw_buffer_store_b128(acc, rs, off, 0, 2);
         }
 #pragma unroll
-        for (int r = 0; r <= TW_MAX_P; ++r) acc ^= v[r];
+        for (int r = 0; r < NR; ++r) acc ^= v[r];
     }
     if (n_write == 0 && acc.x == 0x12345u && acc.y == 0x777u)
         reinterpret_cast<u32x4 *>(dst)[threadIdx.x] = acc;
+}
+
+template <int NR>
+static tw_status launch_mixed(const void *src, void *dst, int64_t stream_bytes, int n_write, unsigned grid,
+                              hipStream_t stream)
+{
+    auto kern = probe_mixed_kernel<NR>;
+    static std::atomic<int> allowed{0};
+    if (!allowed.load(std::memory_order_acquire)) {
+        TW_HIP(hipFuncSetAttribute(reinterpret_cast<const void *>(kern),
+                                   hipFuncAttributeMaxDynamicSharedMemorySize,
+                                   static_cast<int>(kProbePadBytes)));
+        allowed.store(1, std::memory_order_release);
+    }
+    TW_HIP(launch_kernel(kern, dim3(grid), dim3(kProbeThreads), kProbePadBytes, stream,
+                         static_cast<const char *>(src), static_cast<char *>(dst),
+                         static_cast<unsigned>(stream_bytes), n_write));
+    return TW_OK;
+}
+
+template <int NR>
+static tw_status dispatch_mixed(int n_read, const void *src, void *dst, int64_t stream_bytes, int n_write,
+                                unsigned grid, hipStream_t stream)
+{
+    if (n_read == NR) return launch_mixed<NR>(src, dst, stream_bytes, n_write, grid, stream);
+    if constexpr (NR > 0) return dispatch_mixed<NR - 1>(n_read, src, dst, stream_bytes, n_write, grid, stream);
+    return TW_ERR_SHAPE;
 }
 
 template <int MODE>
@@ -154,15 +180,6 @@ extern "C" tw_status tw_hbm_probe_mixed(const void *src, void *dst, int64_t stre
     int cus = 0;
     TW_TRY(current_cu_count(&cus));
     const unsigned grid = static_cast<unsigned>(resolve_budget(cu_budget, cus));
-    static std::atomic<int> allowed{0};
-    if (!allowed.load(std::memory_order_acquire)) {
-        TW_HIP(hipFuncSetAttribute(reinterpret_cast<const void *>(probe_mixed_kernel),
-                                   hipFuncAttributeMaxDynamicSharedMemorySize,
-                                   static_cast<int>(kProbePadBytes)));
-        allowed.store(1, std::memory_order_release);
-    }
-    TW_HIP(launch_kernel(probe_mixed_kernel, dim3(grid), dim3(kProbeThreads), kProbePadBytes,
-                         static_cast<hipStream_t>(stream), static_cast<const char *>(src),
-                         static_cast<char *>(dst), static_cast<unsigned>(stream_bytes), n_read, n_write));
-    return TW_OK;
+    return dispatch_mixed<TW_MAX_P + 1>(n_read, src, dst, stream_bytes, n_write, grid,
+                                        static_cast<hipStream_t>(stream));
 }

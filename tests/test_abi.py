@@ -216,3 +216,69 @@ def test_mixed_probe_argument_checks():
     assert L.tw_hbm_probe_mixed(VP(addr(0) + 8), VP(addr(2000)), sb, 9, 2, 8, VP(None)) == E_ALIGN
     assert L.tw_hbm_probe_mixed(VP(addr(0)), VP(addr(0) + 8 * sb), sb, 9, 2, 8, VP(None)) == E_ALIAS
     assert L.tw_hbm_probe_mixed(VP(addr(0)), VP(addr(2000)), 0, 9, 2, 8, VP(None)) == OK
+
+
+def test_smart_split_point_matches_its_definition():
+    """Independent statement of the criterion: among k = base + j*multiple (k < T,
+    offset <= 512) take the fewest total GEMM waves, ties to the smallest k."""
+    tm, tn = tw.gemm_tile_shape()
+    assert (tm, tn) == (256, 128)
+
+    def waves(rows, n, cus):
+        if rows <= 0:
+            return 0
+        return -(-(-(-rows // tm) * -(-n // tn)) // cus)
+
+    for T in (0, 1, 64, 100, 255, 256, 257, 1000, 1024, 2048, 3000, 4096, 8192, 16384, 20000):
+        for mult in (64, 128):
+            for widths in ([8192], [8192, 3584], [4096, 14336, 1024]):
+                for cus in (224, 256, 132, 8):
+                    k, ws, wu = tw.smart_split_point(T, mult, widths, cus)
+                    base = tw.split_point(T, mult)
+                    want_u = sum(waves(T, n, cus) for n in widths)
+                    assert wu == want_u
+                    if base >= T:
+                        assert k == T and ws == wu
+                        continue
+                    cands = [c for c in range(base, T, mult) if c - base <= 512]
+                    cost = {c: sum(waves(c, n, cus) + waves(T - c, n, cus) for n in widths) for c in cands}
+                    best = min(cands, key=lambda c: (cost[c], c))
+                    assert (k, ws) == (best, cost[best]), (T, mult, widths, cus)
+    # the situation of the paper's example (Section 4.1.1): 300 workgroups (10 row
+    # tiles x 30 column tiles) on 132 units are 3 waves; the even cut (150 + 150)
+    # needs 2 + 2 = 4, moving one row tile to the prefix (180 + 120) needs 2 + 1 = 3
+    k, ws, wu = tw.smart_split_point(10 * 256, 256, [30 * 128], 132)
+    assert (k, ws, wu) == (6 * 256, 3, 3)
+    assert tw.smart_split_point(-1, 64, [8], 8)[0] == -1
+    assert tw.smart_split_point(64, 64, [], 8)[0] == -1
+    assert tw.smart_split_point(64, 64, [0], 8)[0] == -1
+    assert tw.smart_split_point(64, 64, [8], 0)[0] == -1
+
+
+def test_weave_layer_argument_checks():
+    from paper_2505_11329_amd.binding import LayerArgs
+    L = tw.lib()
+    assert L.tw_weave_layer(None, 0, VP(1), VP(2), VP(None), 0, 0) == E_NULL
+    arr = (VP * P)(addr(0), addr(1))
+    f = FusedArgs(ctypes.cast(arr, ctypes.POINTER(VP)), addr(4), addr(5), 1e-5, N, H, P, 8, addr(6), addr(7))
+    la = LayerArgs(addr(10), addr(11), 64, f, addr(12), 64, addr(13), 0)
+    assert L.tw_weave_layer(ctypes.byref(la), -1, VP(1), VP(2), VP(None), 0, 0) == E_SPLIT
+    assert L.tw_weave_layer(ctypes.byref(la), N + 1, VP(1), VP(2), VP(None), 0, 0) == E_SPLIT
+    assert L.tw_weave_layer(ctypes.byref(la), 2, VP(3), VP(3), VP(None), 0, 0) == E_SPLIT
+    la.K1 = 12
+    assert L.tw_weave_layer(ctypes.byref(la), 2, VP(1), VP(2), VP(None), 0, 0) == E_UNSUP
+    la.K1 = 64
+    la.N2 = 12
+    assert L.tw_weave_layer(ctypes.byref(la), 2, VP(1), VP(2), VP(None), 0, 0) == E_UNSUP
+    la.N2 = 64
+    la.X1 = None
+    assert L.tw_weave_layer(ctypes.byref(la), 2, VP(1), VP(2), VP(None), 0, 0) == E_NULL
+    la.X1 = addr(10)
+    la.Y = addr(6)          # Y on top of the fused output it is computed from
+    assert L.tw_weave_layer(ctypes.byref(la), 2, VP(1), VP(2), VP(None), 0, 0) == E_ALIAS
+    la.Y = addr(13)
+    la.fused.H = 60
+    assert L.tw_weave_layer(ctypes.byref(la), 2, VP(1), VP(2), VP(None), 0, 0) == E_UNSUP
+    la.fused.H = H
+    la.fused.N = 0
+    assert L.tw_weave_layer(ctypes.byref(la), 0, VP(1), VP(2), VP(None), 0, 0) == OK

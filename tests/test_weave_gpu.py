@@ -1,0 +1,90 @@
+"""tw_weave_layer: the chain G1 -> fused -> G2 over two token splits on two
+streams (TokenWeave Fig. 7b). Each stage is checked against the fp64 oracle fed
+with the bits the previous GPU stage produced, and every split row must give the
+same bits as the unsplit chain."""
+import numpy as np
+import pytest
+
+import oracle
+import tw_workloads as W
+from helpers import assert_parity, to_bits, to_gpu
+
+pytestmark = pytest.mark.gpu
+
+T, K1, H, P, N2 = 640, 512, 1024, 4, 768
+STD = 0.15
+
+
+@pytest.fixture(scope="module")
+def torch_cuda():
+    import torch
+    assert torch.cuda.is_available()
+    return torch
+
+
+def gemm_tol_check(got, ref, K, sa, sb, what):
+    tol = 1e-2 * np.abs(ref) + 1e-3 * np.sqrt(K) * sa * sb
+    bad = np.abs(got - ref) > tol
+    assert not bad.any(), "%s: %d of %d out of tolerance" % (what, bad.sum(), bad.size)
+
+
+def make_inputs():
+    g1 = W.make_gemm_inputs(T, K1, H, STD, seed=3, b_layout="nk")
+    cfg = dict(N=T, H=H, P=P, partial_std=0.5, residual_std=1.0, outlier_frac=0.01, outlier_scale=20.0,
+               eps=1e-5, seed=5)
+    f = W.make_fused_inputs(cfg)
+    W2 = W.normal_bf16((N2, H), 0.05, 9, W.STREAM_GEMM_B)
+    return g1, f, W2
+
+
+def run_layer(tw, torch, g1, f, W2, split_row, streams, parent=None):
+    X1, W1 = to_gpu(g1["A"]), to_gpu(g1["B"])
+    parts = [torch.zeros((T, H), dtype=torch.bfloat16, device="cuda:0")] + [to_gpu(p) for p in f["partials"][1:]]
+    out, res, Y = tw.weave_layer(X1, W1, parts, to_gpu(f["residual"]), to_gpu(f["weight"]), f["eps"], to_gpu(W2),
+                                 split_row, streams[0], streams[1], fused_cu_budget=32, gemm_cu_budget=224,
+                                 parent=parent, use_parent=True, join=True)
+    torch.cuda.synchronize()
+    return to_bits(parts[0]), to_bits(out), to_bits(res), to_bits(Y)
+
+
+def test_weave_layer_stagewise_parity_and_split_invariance(tw, torch_cuda):
+    torch = torch_cuda
+    g1, f, W2 = make_inputs()
+    streams = (torch.cuda.Stream(), torch.cuda.Stream())
+    C0, out0, res0, Y0 = run_layer(tw, torch, g1, f, W2, 0, streams)
+
+    # G1 against the textbook product
+    gemm_tol_check(oracle.bf16_to_f64(C0), oracle.gemm(g1["A"], g1["B"], "nk"), K1, STD, STD, "G1")
+    # F against the fused oracle on the bits G1 produced
+    ref_out, ref_res = oracle.fused([C0] + f["partials"][1:], f["residual"], f["weight"], f["eps"])
+    assert_parity(oracle.bf16_to_f64(res0), ref_res, "weave residual_out")
+    assert_parity(oracle.bf16_to_f64(out0), ref_out, "weave out")
+    # G2 against the textbook product on the bits F produced (|out| ~ 1)
+    gemm_tol_check(oracle.bf16_to_f64(Y0), oracle.gemm(out0, W2, "nk"), H, 1.5, 0.05, "G2")
+
+    for k in (T, 256, 512, 384, 1, T - 1, 320):
+        C, out, res, Y = run_layer(tw, torch, g1, f, W2, k, streams)
+        assert np.array_equal(C, C0) and np.array_equal(out, out0), k
+        assert np.array_equal(res, res0) and np.array_equal(Y, Y0), k
+
+
+def test_weave_layer_orders_itself_after_the_parent_stream(tw, torch_cuda):
+    torch = torch_cuda
+    g1, f, W2 = make_inputs()
+    streams = (torch.cuda.Stream(), torch.cuda.Stream())
+    want = run_layer(tw, torch, g1, f, W2, 0, streams)
+    parent = torch.cuda.Stream()
+    X1_src, W1 = to_gpu(g1["A"]), to_gpu(g1["B"])
+    X1 = torch.zeros_like(X1_src)
+    parts = [torch.zeros((T, H), dtype=torch.bfloat16, device="cuda:0")] + [to_gpu(p) for p in f["partials"][1:]]
+    resid, weight, W2g = to_gpu(f["residual"]), to_gpu(f["weight"]), to_gpu(W2)
+    torch.cuda.synchronize()
+    for _ in range(3):
+        with torch.cuda.stream(parent):
+            X1.zero_()
+            X1.copy_(X1_src)             # the input is produced on the parent right before the launch
+            out, res, Y = tw.weave_layer(X1, W1, parts, resid, weight, f["eps"], W2g, 384, streams[0], streams[1],
+                                         fused_cu_budget=32, gemm_cu_budget=224, parent=parent)
+            yc, oc = Y.clone(), out.clone()   # and consumed on it right after
+        parent.synchronize()
+        assert np.array_equal(to_bits(yc), want[3]) and np.array_equal(to_bits(oc), want[1])
