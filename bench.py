@@ -261,6 +261,7 @@ def extras(result, tw, W, torch, np, stream, sets, fused_sets, algo_bytes, event
     C = torch.empty((gc["M"], gc["N"]), dtype=torch.bfloat16, device="cuda:0")
     flops = 2.0 * gc["M"] * gc["K"] * gc["N"]
     comm, comp = torch.cuda.Stream(), torch.cuda.Stream()
+    cus_total = tw.device_cu_count()
     tf = event_times(fused_fns(s5, 32), 30, 5, stream)
     tg = event_times([lambda: tw.gemm_bf16(A, B, C=C, cu_budget=0, stream=stream)], 30, 5, stream)
 
@@ -271,44 +272,129 @@ def extras(result, tw, W, torch, np, stream, sets, fused_sets, algo_bytes, event
             tw.gemm_bf16(A, B, C=C, cu_budget=0, stream=stream)
         return f
 
-    def overlap_fn(s, gemm_budget):
+    def overlap_fn(s, fused_budget, gemm_budget):
+        # the caller's stream is the compute stream (as in the paper: a compute stream and a
+        # communication stream), so only the comm stream is forked from and joined into it
         def f():
             with torch.cuda.stream(stream):
                 tw.overlap_launch(dict(partials=s["partials"], residual=s["residual"], weight=s["weight"],
-                                       eps=s["eps"], cu_budget=32, out=s["out"], residual_out=s["res_out"]),
-                                  dict(A=A, B=B, C=C, cu_budget=gemm_budget), comm, comp, parent=stream,
+                                       eps=s["eps"], cu_budget=fused_budget, out=s["out"],
+                                       residual_out=s["res_out"]),
+                                  dict(A=A, B=B, C=C, cu_budget=gemm_budget), comm, stream, parent=stream,
                                   use_parent=True, join=True)
         return f
-    # interleave serial and overlapped trials
-    ts, to = [], []
+    # the best schedule without overlap on one GPU: no partition, each kernel gets every CU in turn
+    def serial_whole_fn(s):
+        def f():
+            tw.reduce_add_rmsnorm(s["partials"], s["residual"], s["weight"], s["eps"], cu_budget=0,
+                                  out=s["out"], residual_out=s["res_out"], stream=stream)
+            tw.gemm_bf16(A, B, C=C, cu_budget=0, stream=stream)
+        return f
+    # interleave the four schedules
+    ts, to, tsh, tww = [], [], [], []
     for rep in range(6):
         ts.append(event_times([serial_fn(s) for s in s5], 10, 2, stream))
-        to.append(event_times([overlap_fn(s, 0) for s in s5], 10, 2, stream))
-    ts, to = np.concatenate(ts), np.concatenate(to)
-    # fused duration inside the overlapped run: event pair on the comm stream
-    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-    cont = []
-    for rep in range(20):
-        s = s5[rep % 2]
-        stream.synchronize()
-        tw.gemm_bf16(A, B, C=C, cu_budget=0, stream=comp)      # GEMM already running on the other stream
-        e0.record(comm)
-        tw.reduce_add_rmsnorm(s["partials"], s["residual"], s["weight"], s["eps"], cu_budget=32, out=s["out"],
-                              residual_out=s["res_out"], stream=comm)
-        e1.record(comm)
-        torch.cuda.synchronize()
-        cont.append(e0.elapsed_time(e1) * 1e3)
+        tww.append(event_times([serial_whole_fn(s) for s in s5], 10, 2, stream))
+        to.append(event_times([overlap_fn(s, 32, cus_total - 32) for s in s5], 10, 2, stream))
+        tsh.append(event_times([overlap_fn(s, tw.CU_SHARED, 0) for s in s5], 10, 2, stream))
+    ts, to, tsh, tw_ = np.concatenate(ts), np.concatenate(to), np.concatenate(tsh), np.concatenate(tww)
+
+    # each kernel's own duration while the other runs: event pairs on the two streams
+    def contended(fused_budget, gemm_budget, gemm_first):
+        f_us, g_us = [], []
+        ev = [torch.cuda.Event(enable_timing=True) for _ in range(4)]
+        for rep in range(16):
+            s = s5[rep % 2]
+            torch.cuda.synchronize()
+
+            def launch_gemm():
+                ev[0].record(comp)
+                tw.gemm_bf16(A, B, C=C, cu_budget=gemm_budget, stream=comp)
+                ev[1].record(comp)
+
+            def launch_fused():
+                ev[2].record(comm)
+                tw.reduce_add_rmsnorm(s["partials"], s["residual"], s["weight"], s["eps"], cu_budget=fused_budget,
+                                      out=s["out"], residual_out=s["res_out"], stream=comm)
+                ev[3].record(comm)
+            if gemm_first:
+                launch_gemm()
+                launch_fused()
+            else:
+                launch_fused()
+                launch_gemm()
+            torch.cuda.synchronize()
+            if rep >= 2:
+                g_us.append(ev[0].elapsed_time(ev[1]) * 1e3)
+                f_us.append(ev[2].elapsed_time(ev[3]) * 1e3)
+        return float(np.median(f_us)), float(np.median(g_us))
+    cont_f32, cont_g32 = contended(32, cus_total - 32, False)
+    cont_fsh, cont_gsh = contended(tw.CU_SHARED, 0, True)
     result["overlap"] = {
         "workload": "c5_overlap_tp8: fused N=2048,H=8192,P=8 @32 CUs || GEMM [2048x8192]x[8192x3584] bf16",
         "fused_alone_us": round(float(np.median(tf)), 1), "gemm_alone_us": round(float(np.median(tg)), 1),
         "gemm_alone_TFLOPs": round(flops / np.median(tg) / 1e6, 1),
         "gemm_frac_mfma_peak": round(flops / np.median(tg) / 1e6 / MFMA_BF16_PEAK_TFLOPS, 4),
-        "serial_us": round(float(np.median(ts)), 1), "overlapped_us": round(float(np.median(to)), 1),
-        "gain": round(float(np.median(ts) / np.median(to)), 3),
-        "fused_under_contention_us": round(float(np.median(cont)), 1),
-        "fused_under_contention_GBps": round(nb5 / np.median(cont) / 1e3, 1),
-        "note": "serial = both on one stream; overlapped = tw_overlap_launch on two streams with fork/join; "
-                "trials interleaved",
+        "serial_budget32_us": round(float(np.median(ts)), 1),
+        "serial_whole_device_us": round(float(np.median(tw_)), 1),
+        "overlapped_budget32_us": round(float(np.median(to)), 1),
+        "overlapped_shared_us": round(float(np.median(tsh)), 1),
+        "gain_budget32_vs_serial_budget32": round(float(np.median(ts) / np.median(to)), 3),
+        "gain_budget32_vs_serial_whole_device": round(float(np.median(tw_) / np.median(to)), 3),
+        "gain_shared_vs_serial_whole_device": round(float(np.median(tw_) / np.median(tsh)), 3),
+        "under_contention_budget32": {"fused_us": round(cont_f32, 1), "fused_GBps": round(nb5 / cont_f32 / 1e3, 1),
+                                      "gemm_us": round(cont_g32, 1)},
+        "under_contention_shared": {"fused_us": round(cont_fsh, 1), "fused_GBps": round(nb5 / cont_fsh / 1e3, 1),
+                                    "gemm_us": round(cont_gsh, 1)},
+        "note": "serial_budget32 = fused at 32 CUs then GEMM on one stream; serial_whole_device = fused on all CUs "
+                "then GEMM on all CUs (the best schedule without overlap); overlapped_budget32 = tw_overlap_launch, "
+                "fused confined to 32 CUs, GEMM on the other 224; overlapped_shared = tw_overlap_launch with "
+                "cu_budget=TW_CU_SHARED: small fused workgroups co-resident with the GEMM's on every CU. The "
+                "caller's stream is the compute stream; trials interleaved; makespans include fork and join",
+    }
+    del s5
+    torch.cuda.empty_cache()
+
+    # one woven layer boundary (G1 -> fused -> G2), T = 4096 tokens, attention-side shapes of a 70B-class
+    # TP=8 model: G1 [T x 1024] x [1024 x 8192], fused H=8192 P=8, G2 [T x 8192] x [8192 x 3584]
+    T, K1, H, P, N2 = 4096, 1024, 8192, 8, 3584
+    d = W.make_fused_inputs("c5_overlap_tp8", N=T)
+    g1 = W.make_gemm_inputs(T, K1, H, 0.02, 1, "nk")
+    X1, W1 = gpu(g1["A"]), gpu(g1["B"])
+    W2 = gpu(W.normal_bf16((N2, H), 0.02, 2, W.STREAM_GEMM_B))
+    parts = [torch.empty((T, H), dtype=torch.bfloat16, device="cuda:0")] + [gpu(p) for p in d["partials"][1:]]
+    resid, weight = gpu(d["residual"]), gpu(d["weight"])
+    out, res_out = torch.empty_like(resid), torch.empty_like(resid)
+    Y = torch.empty((T, N2), dtype=torch.bfloat16, device="cuda:0")
+    cus = tw.device_cu_count()
+
+    def layer_fn(split_row, fb, gb):
+        def f():
+            with torch.cuda.stream(stream):
+                tw.weave_layer(X1, W1, parts, resid, weight, d["eps"], W2, split_row, stream, comm,
+                               fused_cu_budget=fb, gemm_cu_budget=gb, out=out, residual_out=res_out, Y=Y,
+                               parent=stream, use_parent=True, join=True)
+        return f
+    weave = {}
+    t_un = event_times([layer_fn(0, 0, 0)], 20, 3, stream)
+    weave["unsplit_whole_device_us"] = round(float(np.median(t_un)), 1)
+    for fb in (32, 64, 96):
+        k, ws, wu = tw.smart_split_point(T, 128, [H, N2], cus - fb)
+        t_w = event_times([layer_fn(k, fb, cus - fb)], 20, 3, stream)
+        t_s = event_times([layer_fn(0, fb, cus - fb)], 20, 3, stream)
+        weave["fused_budget_%d" % fb] = {"split_row": k, "gemm_waves_split": ws, "gemm_waves_unsplit": wu,
+                                         "woven_us": round(float(np.median(t_w)), 1),
+                                         "unsplit_same_budgets_us": round(float(np.median(t_s)), 1)}
+    k, ws, wu = tw.smart_split_point(T, 128, [H, N2], cus)
+    t_w = event_times([layer_fn(k, tw.CU_SHARED, 0)], 20, 3, stream)
+    weave["fused_shared"] = {"split_row": k, "gemm_waves_split": ws, "gemm_waves_unsplit": wu,
+                             "woven_us": round(float(np.median(t_w)), 1)}
+    result["weave_layer"] = {
+        "workload": "T=4096: G1 [Tx1024]x[1024x8192] -> fused H=8192 P=8 -> G2 [Tx8192]x[8192x3584], bf16",
+        "cases": weave,
+        "note": "woven = tw_weave_layer at the wave-aware split row, fused kernel confined to its budget and the "
+                "GEMMs to the other CUs; unsplit_same_budgets = same budgets, no split; unsplit_whole_device = "
+                "each kernel on all CUs in turn",
     }
 
 

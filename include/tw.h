@@ -55,6 +55,7 @@ typedef enum tw_status {
 } tw_status;
 
 #define TW_MAX_P 16          /* most partial buffers one call can sum              */
+#define TW_CU_SHARED (-1)    /* cu_budget value: co-resident ("shared") launch mode */
 #define TW_MAX_H 65536       /* largest hidden size the fused kernel handles       */
 
 /*
@@ -81,8 +82,13 @@ typedef enum tw_status {
  *   P             1 <= P <= TW_MAX_P
  *   cu_budget     number of compute units the kernel may occupy: the launch is
  *                 a persistent grid of that many workgroups, each sized so that
- *                 no two share a compute unit. <= 0, or >= the device's CU
- *                 count, means the whole device.
+ *                 no two share a compute unit. 0, or >= the device's CU count,
+ *                 means the whole device. TW_CU_SHARED (-1) selects the shared
+ *                 mode instead: many small workgroups (256 threads, <= 96
+ *                 VGPRs, 16 KiB LDS) spread over every compute unit, sized to
+ *                 run NEXT TO a tw_gemm_bf16 workgroup on the same compute unit
+ *                 rather than in place of one; for H > 8192 it falls back to
+ *                 the whole device. Other negative values mean the whole device.
  *   out           device bf16 [N x H]
  *   residual_out  device bf16 [N x H]
  *
@@ -195,9 +201,11 @@ tw_status tw_gemm_bf16(const void *A, const void *B, void *C, int64_t M, int64_t
 /*
  * One step of the weave (Fig. 7b, Section 4.1.2): the fused kernel of one split
  * on stream_comm next to the GEMM of the other split on stream_compute. If
- * parent_is_set, both first wait for the work already enqueued on `parent`;
- * the fused kernel is enqueued first so that its few workgroups are placed
- * before the GEMM fills the remaining compute units. If join is non-zero,
+ * parent_is_set, both first wait for the work already enqueued on `parent`.
+ * With a CU budget the fused kernel is enqueued first so that its few
+ * workgroups are placed before the GEMM fills the remaining compute units; with
+ * fused->cu_budget == TW_CU_SHARED the GEMM is enqueued first and the small
+ * fused workgroups settle beside its workgroups. If join is non-zero,
  * `parent` then waits for both. The two streams must differ.
  * `fused` describes the rows of the split being normalised (its own pointers
  * and N); `gemm` the other split's product. Either may be NULL to leave that

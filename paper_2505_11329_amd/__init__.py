@@ -27,5 +27,5 @@ from .binding import (  # noqa: F401
     GemmArgs,
     STATUS,
     PROBE_READ, PROBE_COPY, PROBE_WRITE,
-    B_NK, B_KN,
+    B_NK, B_KN, CU_SHARED,
 )

@@ -17,6 +17,7 @@ STATUS = {0: "TW_OK", 1: "TW_ERR_NULL", 2: "TW_ERR_SHAPE", 3: "TW_ERR_ALIGN", 4:
           5: "TW_ERR_UNSUPPORTED", 6: "TW_ERR_SPLIT", 7: "TW_ERR_HIP"}
 PROBE_READ, PROBE_COPY, PROBE_WRITE = 0, 1, 2
 B_NK, B_KN = 0, 1
+CU_SHARED = -1
 MAX_P = 16
 
 _vp = ctypes.c_void_p

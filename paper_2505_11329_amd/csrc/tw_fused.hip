@@ -327,6 +327,155 @@ __global__ __launch_bounds__(kThreads) void fused_kernel(const FusedParams prm)
 }
 
 // ---------------------------------------------------------------------------
+// The same arithmetic in workgroups small enough to sit NEXT TO a GEMM workgroup
+// on the same compute unit (256 threads, at most 96 VGPRs, 16 KiB of LDS): the
+// "shared" launch mode. Instead of taking a few compute units away from the
+// GEMM, the fused kernel is spread thinly over all of them and uses the HBM
+// bandwidth the matrix-core-bound GEMM leaves idle.
+//
+// Bits are identical to fused_kernel's: a thread here plays Q = TPR/256 of the
+// wide kernel's threads (columns tid, tid+256, ...), keeps one sum of squares
+// per played thread, and the reduction runs the very same tree (64-lane
+// butterfly per played wave, then the 16-lane butterfly over the row's wave
+// sums in LDS). Only rows of at most 1024 vectors (H <= 8192) are handled.
+// Weights live in LDS; one chunk of loads is in flight per thread.
+// ---------------------------------------------------------------------------
+static constexpr int kThinThreads = 256;
+
+template <int PT, int Q, bool TRACE>
+__global__ __launch_bounds__(kThinThreads) __attribute__((amdgpu_waves_per_eu(5)))
+void fused_thin_kernel(const FusedParams prm, const uint32_t groups_per_wg)
+{
+    __shared__ float s_wave_sum[2][kWaves];
+    __shared__ __attribute__((aligned(16))) u32x4 s_weight[1024];
+
+    const int tid = threadIdx.x;
+    const int lane = tid & 63;
+    const int wave = tid >> 6;
+    const int tpr_log2 = prm.tpr_log2;
+    const int tpr = 1 << tpr_log2;
+    const int hv = prm.hv;
+    // Q > 1: the whole workgroup covers one row, thread plays columns tid + 256 q.
+    // Q == 1: rows of at most 256 vectors, 256 / tpr of them per workgroup.
+    const int row_in_iter = (Q > 1) ? 0 : (tid >> tpr_log2);
+    const int col0 = (Q > 1) ? tid : (tid & (tpr - 1));
+
+    if (TRACE && tid == 0) {
+        prm.hw_ids[2 * blockIdx.x] = __builtin_amdgcn_s_getreg(4 | (0 << 6) | (31 << 11));
+        prm.hw_ids[2 * blockIdx.x + 1] = __builtin_amdgcn_s_getreg(20 | (0 << 6) | (31 << 11));
+    }
+
+    {
+        const __amdgpu_buffer_rsrc_t r_w = make_rsrc(prm.weight, static_cast<uint32_t>(hv) * 16u);
+        for (int v = tid; v < hv; v += kThinThreads)
+            s_weight[v] = __builtin_amdgcn_raw_buffer_load_b128(r_w, v * 16u, 0, 0);
+    }
+
+    __amdgpu_buffer_rsrc_t r_part[PT > 0 ? PT : 1];
+    if constexpr (PT > 0) {
+#pragma unroll
+        for (int p = 0; p < PT; ++p) r_part[p] = make_rsrc(prm.partials[p], prm.n_bytes);
+    }
+    const __amdgpu_buffer_rsrc_t r_res = make_rsrc(prm.residual, prm.n_bytes);
+    const __amdgpu_buffer_rsrc_t r_out = make_rsrc(prm.out, prm.n_bytes);
+    const __amdgpu_buffer_rsrc_t r_res_out = make_rsrc(prm.residual_out, prm.n_bytes);
+
+    uint32_t lane_off[Q];
+    bool cvalid[Q];
+#pragma unroll
+    for (int q = 0; q < Q; ++q) {
+        const int v = col0 + q * kThinThreads;
+        cvalid[q] = v < hv;
+        lane_off[q] = static_cast<uint32_t>(row_in_iter * hv + v) * 16u;
+    }
+    __syncthreads();  // weights are in LDS
+
+    const uint32_t group_bytes = prm.group_bytes;
+    auto chunk_off = [&](uint32_t group, int q) -> uint32_t {
+        return cvalid[q] ? lane_off[q] + group * group_bytes : kOutOfRange;
+    };
+    auto issue = [&](Chunk<PT> &c, uint32_t off) {
+        if constexpr (PT > 0) {
+            __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+            for (int p = 0; p < PT; ++p) c.v[p] = ld(r_part[p], off);
+            c.v[PT] = ld(r_res, off);
+            __builtin_amdgcn_sched_barrier(0);
+        }
+    };
+    auto reduce_chunk = [&](const Chunk<PT> &c, uint32_t off, float (&x)[8]) {
+        if constexpr (PT > 0) {
+            unpack8(c.v[0], x);
+#pragma unroll
+            for (int p = 1; p < PT; ++p) add8(c.v[p], x);
+            add8(c.v[PT], x);
+        } else {
+            const u32x4 r = ld(r_res, off);
+            for (int p0 = 0; p0 < prm.P; p0 += 4) {
+                u32x4 t[4];
+#pragma unroll
+                for (int i = 0; i < 4; ++i) {
+                    const bool live = p0 + i < prm.P;
+                    t[i] = ld(make_rsrc(prm.partials[live ? p0 + i : 0], live ? prm.n_bytes : 0u), off);
+                }
+                if (p0 == 0) unpack8(t[0], x); else add8(t[0], x);
+#pragma unroll
+                for (int i = 1; i < 4; ++i) add8(t[i], x);
+            }
+            add8(r, x);
+        }
+    };
+
+    // This workgroup's row groups: [first, first + groups_per_wg), cut at n_groups.
+    const uint32_t first = blockIdx.x * groups_per_wg;
+    const uint32_t last = min(first + groups_per_wg, prm.n_groups);
+    Chunk<PT> buf;
+    issue(buf, chunk_off(first, 0));
+    int parity = 0;
+    for (uint32_t group = first; group < last; ++group) {
+        float x[Q][8];
+        float ss[Q];
+#pragma unroll
+        for (int q = 0; q < Q; ++q) {
+            const uint32_t off = chunk_off(group, q);
+            reduce_chunk(buf, off, x[q]);
+            // next chunk: the next played thread of this row, or this workgroup's
+            // next row; after its last row nothing is fetched
+            issue(buf, (q + 1 < Q) ? chunk_off(group, q + 1)
+                                   : (group + 1 < last ? chunk_off(group + 1, 0) : kOutOfRange));
+            st(r_res_out, off, pack8(x[q]));
+            float acc = 0.0f;
+#pragma unroll
+            for (int e = 0; e < 8; ++e) acc = __builtin_fmaf(x[q][e], x[q][e], acc);
+            ss[q] = group_sum(acc, tpr_log2 < 6 ? tpr_log2 : 6);
+        }
+        float total = ss[0];
+        if (tpr_log2 > 6) {
+            if (lane == 0) {
+#pragma unroll
+                for (int q = 0; q < Q; ++q) s_wave_sum[parity][wave + q * (kThinThreads / 64)] = ss[q];
+            }
+            __syncthreads();
+            const int waves_per_row = tpr >> 6;
+            const int k = lane & 15;
+            const float part = k < waves_per_row ? s_wave_sum[parity][row_in_iter * waves_per_row + k] : 0.0f;
+            total = group_sum(part, 4);
+            parity ^= 1;
+        }
+        const float s = rsqrtf(total * prm.inv_h + prm.eps);
+#pragma unroll
+        for (int q = 0; q < Q; ++q) {
+            float w[8], y[8];
+            const int v = col0 + q * kThinThreads;
+            unpack8(s_weight[cvalid[q] ? v : 0], w);
+#pragma unroll
+            for (int e = 0; e < 8; ++e) y[e] = (x[q][e] * s) * w[e];
+            st(r_out, chunk_off(group, q), pack8(y));
+        }
+    }
+}
+
+// ---------------------------------------------------------------------------
 // host side
 // ---------------------------------------------------------------------------
 
@@ -405,6 +554,52 @@ static tw_status launch_t(const FusedParams &prm, bool trace, int64_t grid, hipS
     return TW_OK;
 }
 
+template <int PT, int Q>
+static tw_status launch_thin_t(const FusedParams &prm, bool trace, int64_t grid, uint32_t groups_per_wg,
+                               hipStream_t stream)
+{
+    auto kern = trace ? fused_thin_kernel<PT, Q, true> : fused_thin_kernel<PT, Q, false>;
+    TW_HIP(launch_kernel(kern, dim3(static_cast<unsigned>(grid)), dim3(kThinThreads), 0u, stream, prm,
+                         groups_per_wg));
+    return TW_OK;
+}
+
+template <int PT>
+static tw_status launch_thin(const FusedParams &prm, int q, bool trace, int64_t grid, uint32_t groups_per_wg,
+                             hipStream_t s)
+{
+    switch (q) {
+    case 1: return launch_thin_t<PT, 1>(prm, trace, grid, groups_per_wg, s);
+    case 2: return launch_thin_t<PT, 2>(prm, trace, grid, groups_per_wg, s);
+    case 4: return launch_thin_t<PT, 4>(prm, trace, grid, groups_per_wg, s);
+    }
+    return TW_ERR_UNSUPPORTED;
+}
+
+// Geometry of the shared (co-resident) mode: 256-thread workgroups, each doing
+// groups_per_wg consecutive row groups; enough workgroups that the hardware
+// dispatcher balances them over compute units that are busy to different degrees.
+struct ThinGeometry {
+    int q;              // wide-kernel threads played by one thread (1, 2 or 4)
+    int rows_per_iter;  // rows per row group
+};
+static ThinGeometry thin_geometry(const FusedGeometry &g)
+{
+    ThinGeometry t;
+    const int tpr = 1 << g.tpr_log2;
+    t.q = tpr > kThinThreads ? tpr / kThinThreads : 1;
+    t.rows_per_iter = tpr >= kThinThreads ? 1 : kThinThreads / tpr;
+    return t;
+}
+static void thin_grid(int64_t n_rows, const ThinGeometry &t, int cus, int64_t *grid, uint32_t *groups_per_wg)
+{
+    const int64_t n_groups = (n_rows + t.rows_per_iter - 1) / t.rows_per_iter;
+    int64_t gpw = n_groups / (int64_t(8) * cus);
+    gpw = gpw < 1 ? 1 : gpw > 8 ? 8 : gpw;
+    *groups_per_wg = static_cast<uint32_t>(gpw);
+    *grid = (n_groups + gpw - 1) / gpw;
+}
+
 template <int PT>
 static tw_status launch_vpt(const FusedParams &prm, int vpt, bool trace, int64_t grid, hipStream_t s)
 {
@@ -433,11 +628,22 @@ tw_status launch_fused(const tw_fused_args &a, int64_t row_begin, int64_t row_en
     int64_t rows_per_launch = kMaxLaunchBytes / row_bytes;
     rows_per_launch -= rows_per_launch % g.rows_per_iter;
     if (trace && row_end - row_begin > rows_per_launch) return TW_ERR_UNSUPPORTED;
+    // Shared mode has a kernel for rows of up to 1024 vectors; wider rows run on
+    // the wide kernel over the whole device.
+    const bool thin = a.cu_budget == TW_CU_SHARED && g.vpt == 1;
+    const ThinGeometry tg = thin_geometry(g);
+    const int rows_per_group = thin ? tg.rows_per_iter : g.rows_per_iter;
 
     for (int64_t r0 = row_begin; r0 < row_end; r0 += rows_per_launch) {
         const int64_t n_rows = (row_end - r0 < rows_per_launch) ? row_end - r0 : rows_per_launch;
-        const int64_t grid = fused_grid_size(n_rows, g, budget);
-        if (grid > 1024) return TW_ERR_UNSUPPORTED;  // offset arithmetic in the kernel assumes this
+        int64_t grid = 0;
+        uint32_t groups_per_wg = 1;
+        if (thin) {
+            thin_grid(n_rows, tg, cus, &grid, &groups_per_wg);
+        } else {
+            grid = fused_grid_size(n_rows, g, budget);
+            if (grid > 1024) return TW_ERR_UNSUPPORTED;  // offset arithmetic in the kernel assumes this
+        }
         if (trace && hw_ids_len < grid) return TW_ERR_SHAPE;
 
         FusedParams prm;
@@ -450,14 +656,24 @@ tw_status launch_fused(const tw_fused_args &a, int64_t row_begin, int64_t row_en
         prm.residual_out = static_cast<char *>(a.residual_out) + off;
         prm.hw_ids = hw_ids;
         prm.n_bytes = static_cast<uint32_t>(n_rows * row_bytes);
-        prm.group_bytes = static_cast<uint32_t>(g.rows_per_iter * row_bytes);
-        prm.n_groups = static_cast<uint32_t>((n_rows + g.rows_per_iter - 1) / g.rows_per_iter);
+        prm.group_bytes = static_cast<uint32_t>(rows_per_group * row_bytes);
+        prm.n_groups = static_cast<uint32_t>((n_rows + rows_per_group - 1) / rows_per_group);
         prm.hv = g.hv;
         prm.P = a.P;
         prm.tpr_log2 = g.tpr_log2;
         prm.eps = a.eps;
         prm.inv_h = 1.0f / static_cast<float>(a.H);
 
+        if (thin) {
+            switch (a.P) {
+            case 1: TW_TRY((launch_thin<1>(prm, tg.q, trace, grid, groups_per_wg, stream))); break;
+            case 2: TW_TRY((launch_thin<2>(prm, tg.q, trace, grid, groups_per_wg, stream))); break;
+            case 4: TW_TRY((launch_thin<4>(prm, tg.q, trace, grid, groups_per_wg, stream))); break;
+            case 8: TW_TRY((launch_thin<8>(prm, tg.q, trace, grid, groups_per_wg, stream))); break;
+            default: TW_TRY((launch_thin<0>(prm, tg.q, trace, grid, groups_per_wg, stream))); break;
+            }
+            continue;
+        }
         switch (a.P) {
         case 1: TW_TRY((launch_vpt<1>(prm, g.vpt, trace, grid, stream))); break;
         case 2: TW_TRY((launch_vpt<2>(prm, g.vpt, trace, grid, stream))); break;
@@ -502,7 +718,14 @@ int64_t tw_fused_grid(int64_t N, int64_t H, int cu_budget)
     if (N == 0) return 0;
     int cus = 0;
     if (current_cu_count(&cus) != TW_OK) return -1;
-    return fused_grid_size(N, fused_geometry(H), resolve_budget(cu_budget, cus));
+    const FusedGeometry g = fused_geometry(H);
+    if (cu_budget == TW_CU_SHARED && g.vpt == 1 && N * H * 2 <= kMaxLaunchBytes) {
+        int64_t grid = 0;
+        uint32_t gpw = 1;
+        thin_grid(N, thin_geometry(g), cus, &grid, &gpw);
+        return grid;
+    }
+    return fused_grid_size(N, g, resolve_budget(cu_budget, cus));
 }
 
 }  // extern "C"

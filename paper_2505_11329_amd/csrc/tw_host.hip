@@ -168,10 +168,15 @@ tw_status tw_overlap_launch(const tw_fused_args *fused, const tw_gemm_args *gemm
         if (fused && sc != sp) TW_HIP(hipStreamWaitEvent(sc, fork, 0));
         if (gemm && sx != sp) TW_HIP(hipStreamWaitEvent(sx, fork, 0));
     }
-    // The few workgroups of the fused kernel go first: they take their compute
-    // units, and the GEMM's workgroups are placed on what is left.
+    // Budgeted mode: the few workgroups of the fused kernel go first, they take
+    // their compute units and the GEMM's workgroups are placed on what is left.
+    // Shared mode: the GEMM goes first and takes one slot on every compute unit;
+    // the small fused workgroups then fill in beside it (launched first, they
+    // would pile up five to a compute unit and keep the GEMM out until done).
+    const bool gemm_first = fused && gemm && fused->cu_budget == TW_CU_SHARED;
+    if (gemm && gemm_first) TW_TRY(launch_gemm(*gemm, sx));
     if (fused && fused->N > 0) TW_TRY(launch_fused(*fused, 0, fused->N, nullptr, 0, sc));
-    if (gemm) TW_TRY(launch_gemm(*gemm, sx));
+    if (gemm && !gemm_first) TW_TRY(launch_gemm(*gemm, sx));
     if (parent_is_set && join) {
         if (fused && sc != sp) TW_TRY(stream_wait_stream(sp, sc));
         if (gemm && sx != sp) TW_TRY(stream_wait_stream(sp, sx));

@@ -277,3 +277,42 @@ def test_traced_launch_reports_distinct_compute_units(tw, torch_cuda):
         places = set(zip(xcc.tolist(), se.tolist(), sh.tolist(), cu.tolist()))
         assert len(places) == budget, "workgroups shared a compute unit: %d places for %d workgroups" % (
             len(places), budget)
+
+
+# ---- shared (co-resident) launch mode: same bits as the budgeted kernel --------
+
+SHARED_SHAPES = [(1, 8, 1), (3, 24, 3), (1000, 64, 7), (130, 512, 16), (17, 520, 5), (33, 1024, 4),
+                 (300, 2048, 2), (19, 4096, 8), (77, 4096, 2), (7, 8008, 2), (65, 8192, 1), (1025, 8192, 8),
+                 (9, 8200, 2), (5, 16384, 4)]
+
+
+@pytest.mark.parametrize("N,H,P", SHARED_SHAPES)
+def test_shared_mode_same_bits_as_budgeted(tw, torch_cuda, N, H, P):
+    d = small(N, H, P, seed=7 * N + H + P)
+    g = upload(d)
+    want = run(tw, torch_cuda, g, cu_budget=16)
+    got = run(tw, torch_cuda, g, cu_budget=tw.CU_SHARED)
+    assert np.array_equal(got[0], want[0]) and np.array_equal(got[1], want[1])
+    if N * H <= 1 << 20:
+        check_against_oracle(d, got[0], got[1], "shared N=%d H=%d P=%d" % (N, H, P))
+
+
+@pytest.mark.parametrize("name,N", [("c2_8b_tp2", None), ("c3_70b_shard_tp8", None), ("c4_split_sweep_tp4", 4096)])
+def test_shared_mode_on_configs_and_split(tw, torch_cuda, name, N):
+    torch = torch_cuda
+    d = W.make_fused_inputs(name, N=N)
+    g = upload(d)
+    want = run(tw, torch, g, cu_budget=32)
+    got = run(tw, torch, g, cu_budget=tw.CU_SHARED)
+    assert np.array_equal(got[0], want[0]) and np.array_equal(got[1], want[1])
+    sa, sb = torch.cuda.Stream(), torch.cuda.Stream()
+    k = tw.split_point(d["N"], 128)
+    o, r = tw.split_launch(g["partials"], g["residual"], g["weight"], g["eps"], k, sa, sb, cu_budget=tw.CU_SHARED)
+    torch.cuda.synchronize()
+    assert np.array_equal(to_bits(o), want[0]) and np.array_equal(to_bits(r), want[1])
+    # in place, as the paper's kernel updates the residual stream
+    g2 = upload(d)
+    o, r = tw.reduce_add_rmsnorm(g2["partials"], g2["residual"], g2["weight"], g2["eps"], cu_budget=tw.CU_SHARED,
+                                 out=g2["partials"][0], residual_out=g2["residual"])
+    torch.cuda.synchronize()
+    assert np.array_equal(to_bits(o), want[0]) and np.array_equal(to_bits(r), want[1])
