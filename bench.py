@@ -43,6 +43,10 @@ def main():
     ap.add_argument("--budget", type=int, default=HEADLINE_BUDGET, help="CU budget of the timed steps")
     ap.add_argument("--no-extras", action="store_true", help="only the timed region (for profilers)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--sweep", action="store_true",
+                    help="instead of the benchmark line: token sweep 32..64K of the fused kernel at H=8192 (P=8, "
+                         "P=4) and H=4096 (P=2), whole device / shared / 32 CUs, one JSON object (the analogue of "
+                         "the paper's Tables 1-2)")
     ap.add_argument("--counters-run", choices=("fused", "gemm"), default=None,
                     help="for rocprofv3 --pmc. fused: a few fused launches plus plain copy launches of known "
                          "size (tw_hbm_probe, 192 MiB read + 192 MiB written each) to scale the byte counters "
@@ -93,6 +97,43 @@ def main():
         on_stream.synchronize()
         return np.array([a.elapsed_time(b) for a, b in evs]) * 1e3
 
+    if args.sweep:
+        rows = []
+        for (H, P, cfgname) in ((8192, 8, "c3_70b_shard_tp8"), (8192, 4, "c4_split_sweep_tp4"), (4096, 2, "c2_8b_tp2")):
+            for N in (32, 64, 128, 256, 512, 1024, 2048, 4096, 8192, 16384, 32768, 65536):
+                per_set = (P + 3) * 2 * H * N
+                nsets = max(2, min(6, int((600 << 20) // per_set) + 1))
+                if nsets * per_set > (12 << 30):
+                    nsets = 2
+                ss = []
+                for k in range(nsets):
+                    # large batches are drawn on the GPU (same distributions): the host generator is slow
+                    gen = torch.Generator(device=dev)
+                    gen.manual_seed(1000 * k + N)
+                    cfg = W.CONFIGS[cfgname]
+                    parts = [torch.empty((N, H), dtype=torch.bfloat16, device=dev).normal_(0.0, cfg["partial_std"],
+                                                                                            generator=gen)
+                             for _ in range(P)]
+                    resid = torch.empty((N, H), dtype=torch.bfloat16, device=dev).normal_(0.0, 1.0, generator=gen)
+                    s_ = dict(partials=parts, residual=resid, weight=gpu(W.uniform_bf16((H,), 0.5, 1.5, 0,
+                                                                                       W.STREAM_WEIGHT)),
+                              eps=cfg["eps"], N=N, H=H, P=P, out=torch.empty_like(resid),
+                              res_out=torch.empty_like(resid))
+                    ss.append(s_)
+                row = {"H": H, "P": P, "N": N, "algorithmic_MB": round(per_set / 1e6, 2)}
+                for label, b in (("whole_device", 0), ("shared", tw.CU_SHARED), ("budget32", 32)):
+                    fns = [tw.prepare_reduce_add_rmsnorm(x["partials"], x["residual"], x["weight"], x["eps"],
+                                                         cu_budget=b, out=x["out"], residual_out=x["res_out"],
+                                                         stream=stream)[0] for x in ss]
+                    iters = 40 if N <= 8192 else 12
+                    t = event_times(fns, iters, 4, stream)
+                    row[label + "_us"] = round(float(np.median(t)), 2)
+                    row[label + "_GBps"] = round(per_set / np.median(t) / 1e3, 1)
+                rows.append(row)
+                del ss
+                torch.cuda.empty_cache()
+        print(json.dumps({"sweep": rows, "note": "median of HIP-event timed launches, rotating buffer sets, bf16"}))
+        return
     if args.counters_run == "gemm":
         gc = W.CONFIGS["c5_overlap_tp8"]["gemm"]
         g = W.make_gemm_inputs(gc["M"], gc["K"], gc["N"], gc["std"], 0, "nk")
@@ -203,6 +244,10 @@ def extras(result, tw, W, torch, np, stream, sets, fused_sets, algo_bytes, event
         row["probe_mix_9r2w_GBps"] = round(11 * sb / np.median(tp) / 1e3, 1)
         row["frac_of_mix_probe"] = round(row["GBps"] / row["probe_mix_9r2w_GBps"], 3)
         budgets[str(b)] = row
+    t = event_times(fused_fns(sets, tw.CU_SHARED), 60, 8, stream)
+    budgets["shared"] = {"us": round(float(np.median(t)), 1), "GBps": round(nbytes / np.median(t) / 1e3, 1),
+                         "frac_hbm_peak": round(nbytes / np.median(t) / 1e3 / HBM_PEAK_GBS, 4),
+                         "note": "cu_budget=TW_CU_SHARED run alone: 256-thread workgroups on every CU"}
     result["budgets"] = {"workload": WORKLOAD, "per_budget": budgets,
                          "note": "probe_read = one stream read; probe_mix_9r2w = 9 streams read + 2 written with "
                                  "the fused kernel's launch shape and access pattern but no arithmetic: the "

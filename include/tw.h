@@ -275,6 +275,18 @@ tw_status tw_weave_layer(const tw_layer_args *layer, int64_t split_row, void *st
 int64_t tw_smart_split_point(int64_t T, int64_t multiple, const int64_t *gemm_n_out, int n_gemms,
                              int cus, int64_t *waves_split, int64_t *waves_unsplit);
 
+/*
+ * Selective enabling (Fig. 3 and Appendix A "Selective Enabling of Splitting and
+ * Overlap"): split and overlap only when the batch has at least `threshold`
+ * tokens, otherwise run the fused kernel unsplit. threshold <= 0 takes the
+ * built-in default for MI355X, TW_DEFAULT_SPLIT_THRESHOLD, found by profiling
+ * tw_weave_layer against the unsplit chain on a 70B-class layer boundary (the
+ * paper's own thresholds, 1K and 4K tokens, are for its 8xH100 system). Returns
+ * 1 to split, 0 not to. Host only.
+ */
+#define TW_DEFAULT_SPLIT_THRESHOLD 4096
+int tw_should_split(int64_t num_tokens, int64_t threshold);
+
 /* Rows and columns of the output tile one GEMM workgroup computes. */
 void tw_gemm_tile_shape(int *tile_m, int *tile_n);
 

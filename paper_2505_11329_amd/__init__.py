@@ -22,6 +22,7 @@ from .binding import (  # noqa: F401
     weave_layer,
     smart_split_point,
     gemm_tile_shape,
+    should_split,
     LayerArgs,
     FusedArgs,
     GemmArgs,

@@ -96,6 +96,8 @@ def lib():
         L.tw_smart_split_point.argtypes = [_i64, _i64, ctypes.POINTER(_i64), ctypes.c_int, ctypes.c_int,
                                            ctypes.POINTER(_i64), ctypes.POINTER(_i64)]
         L.tw_smart_split_point.restype = _i64
+        L.tw_should_split.argtypes = [_i64, _i64]
+        L.tw_should_split.restype = ctypes.c_int
         L.tw_gemm_tile_shape.argtypes = [ctypes.POINTER(ctypes.c_int), ctypes.POINTER(ctypes.c_int)]
         L.tw_gemm_tile_shape.restype = None
         L.tw_hbm_probe_mixed.argtypes = [_vp, _vp, _i64, ctypes.c_int, ctypes.c_int, ctypes.c_int, _vp]
@@ -335,3 +337,8 @@ def weave_layer(X1, W1, partials, residual, weight, eps, W2, split_row, stream_c
                                 _stream_handle(parent) if use_parent else _vp(None),
                                 1 if use_parent else 0, 1 if join else 0), "tw_weave_layer")
     return out, residual_out, Y
+
+
+def should_split(num_tokens, threshold=0):
+    """tw_should_split."""
+    return bool(lib().tw_should_split(int(num_tokens), int(threshold)))

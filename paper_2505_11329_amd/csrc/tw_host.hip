@@ -246,6 +246,12 @@ tw_status tw_weave_layer(const tw_layer_args *layer, int64_t split_row, void *st
     return TW_OK;
 }
 
+int tw_should_split(int64_t num_tokens, int64_t threshold)
+{
+    if (threshold <= 0) threshold = TW_DEFAULT_SPLIT_THRESHOLD;
+    return num_tokens >= threshold ? 1 : 0;
+}
+
 void tw_gemm_tile_shape(int *tile_m, int *tile_n)
 {
     if (tile_m) *tile_m = kGemmTileM;

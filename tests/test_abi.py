@@ -282,3 +282,10 @@ def test_weave_layer_argument_checks():
     la.fused.H = H
     la.fused.N = 0
     assert L.tw_weave_layer(ctypes.byref(la), 0, VP(1), VP(2), VP(None), 0, 0) == OK
+
+
+def test_should_split_threshold():
+    assert not tw.should_split(0) and not tw.should_split(4095)
+    assert tw.should_split(4096) and tw.should_split(10 ** 6)
+    assert tw.should_split(1024, 1024) and not tw.should_split(1023, 1024)
+    assert tw.should_split(4096, -5) and not tw.should_split(100, 0)
