@@ -328,7 +328,7 @@ __global__ __launch_bounds__(kThreads) void fused_kernel(const FusedParams prm)
 
 // ---------------------------------------------------------------------------
 // The same arithmetic in workgroups small enough to sit NEXT TO a GEMM workgroup
-// on the same compute unit (256 threads, at most 96 VGPRs, 16 KiB of LDS): the
+// on the same compute unit (256 threads, at most 96 VGPRs, 128 bytes of LDS): the
 // "shared" launch mode. Instead of taking a few compute units away from the
 // GEMM, the fused kernel is spread thinly over all of them and uses the HBM
 // bandwidth the matrix-core-bound GEMM leaves idle.
@@ -338,7 +338,7 @@ __global__ __launch_bounds__(kThreads) void fused_kernel(const FusedParams prm)
 // per played thread, and the reduction runs the very same tree (64-lane
 // butterfly per played wave, then the 16-lane butterfly over the row's wave
 // sums in LDS). Only rows of at most 1024 vectors (H <= 8192) are handled.
-// Weights live in LDS; one chunk of loads is in flight per thread.
+// One chunk of loads is in flight per thread.
 // ---------------------------------------------------------------------------
 static constexpr int kThinThreads = 256;
 
@@ -347,7 +347,6 @@ __global__ __launch_bounds__(kThinThreads) __attribute__((amdgpu_waves_per_eu(5)
 void fused_thin_kernel(const FusedParams prm, const uint32_t groups_per_wg)
 {
     __shared__ float s_wave_sum[2][kWaves];
-    __shared__ __attribute__((aligned(16))) u32x4 s_weight[1024];
 
     const int tid = threadIdx.x;
     const int lane = tid & 63;
@@ -365,11 +364,11 @@ void fused_thin_kernel(const FusedParams prm, const uint32_t groups_per_wg)
         prm.hw_ids[2 * blockIdx.x + 1] = __builtin_amdgcn_s_getreg(20 | (0 << 6) | (31 << 11));
     }
 
-    {
-        const __amdgpu_buffer_rsrc_t r_w = make_rsrc(prm.weight, static_cast<uint32_t>(hv) * 16u);
-        for (int v = tid; v < hv; v += kThinThreads)
-            s_weight[v] = __builtin_amdgcn_raw_buffer_load_b128(r_w, v * 16u, 0, 0);
-    }
+    // The weights are re-read for every row with ordinary (cached) loads: the
+    // streamed tensors are loaded "nt" and do not displace them from the L1, and
+    // neither registers nor LDS are spent on them, which is what lets this
+    // workgroup fit beside a GEMM workgroup that uses 144 KiB of LDS.
+    const __amdgpu_buffer_rsrc_t r_w = make_rsrc(prm.weight, static_cast<uint32_t>(hv) * 16u);
 
     __amdgpu_buffer_rsrc_t r_part[PT > 0 ? PT : 1];
     if constexpr (PT > 0) {
@@ -388,8 +387,6 @@ void fused_thin_kernel(const FusedParams prm, const uint32_t groups_per_wg)
         cvalid[q] = v < hv;
         lane_off[q] = static_cast<uint32_t>(row_in_iter * hv + v) * 16u;
     }
-    __syncthreads();  // weights are in LDS
-
     const uint32_t group_bytes = prm.group_bytes;
     auto chunk_off = [&](uint32_t group, int q) -> uint32_t {
         return cvalid[q] ? lane_off[q] + group * group_bytes : kOutOfRange;
@@ -467,7 +464,7 @@ void fused_thin_kernel(const FusedParams prm, const uint32_t groups_per_wg)
         for (int q = 0; q < Q; ++q) {
             float w[8], y[8];
             const int v = col0 + q * kThinThreads;
-            unpack8(s_weight[cvalid[q] ? v : 0], w);
+            unpack8(__builtin_amdgcn_raw_buffer_load_b128(r_w, cvalid[q] ? v * 16u : kOutOfRange, 0, 0), w);
 #pragma unroll
             for (int e = 0; e < 8; ++e) y[e] = (x[q][e] * s) * w[e];
             st(r_out, chunk_off(group, q), pack8(y));

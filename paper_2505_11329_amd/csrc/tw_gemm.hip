@@ -239,8 +239,203 @@ __global__ __launch_bounds__(kGemmThreads) void gemm_bf16_nk_kernel(const GemmPa
 }
 
 // ---------------------------------------------------------------------------
+// Variant with direct global -> LDS loads (gfx950's 16-byte buffer_load ... lds):
+// no register staging and no ds_write, three LDS stages so that a load has two
+// full K steps to land. The loads write 64 consecutive 16-byte LDS slots per
+// wave instruction, so the xor swizzle is applied on the global side: the lane
+// that fills slot s of line l fetches piece (s & 7) ^ (l & 7) of row 2l + (s >> 3).
+//
+// The compiler cannot tell which LDS stage an asynchronous load targets and
+// would wait for ALL outstanding loads before any LDS read it can see; operand
+// fragments are therefore read with inline ds_read_b128 and the waits (vmcnt for
+// landed stages, lgkmcnt for fragments) are placed by hand. Dynamic LDS is the
+// kernel's only LDS object, so its byte offsets are LDS addresses.
+// ---------------------------------------------------------------------------
+static constexpr int kDmaStages = 3;
+static constexpr int kGemmDmaLdsBytes = kDmaStages * kStageBytes;  // 144 KiB
+
+typedef __attribute__((address_space(3))) void *lds_ptr_t;
+
+__device__ __forceinline__ bf16x8 lds_read16(uint32_t addr)
+{
+    bf16x8 v;
+    asm volatile("ds_read_b128 %0, %1" : "=v"(v) : "v"(addr) : "memory");
+    return v;
+}
+// Wait until at most N of this wave's LDS reads are outstanding. The fragments
+// are passed through so that no MFMA that uses them can be moved above the wait.
+#define TW_WAIT_LGKM(N, f)                                                                   \
+    asm volatile("s_waitcnt lgkmcnt(" #N ")"                                                 \
+                 : "+v"((f).a[0]), "+v"((f).a[1]), "+v"((f).b[0]), "+v"((f).b[1])::"memory")
+
+__global__ __launch_bounds__(kGemmThreads) void gemm_bf16_nk_dma_kernel(const GemmParams prm)
+{
+    extern __shared__ __attribute__((aligned(16))) char lds[];
+
+    const int tid = threadIdx.x;
+    const int lane = tid & 63;
+    const int wave = tid >> 6;
+    const int wave_m = wave >> 1;
+    const int wave_n = wave & 1;
+    const int l31 = lane & 31;
+    const int lhi = lane >> 5;
+
+    const long long row_bytes = prm.K * 2;
+    const int k_tiles = static_cast<int>((prm.K + BK - 1) / BK);
+    const int total_tiles = prm.tiles_m * prm.tiles_n;
+
+    // global -> LDS duty: wave instruction i of this wave fills slots
+    // [(i * 8 + wave) * 64, +64); this lane's slot inside a line and the row and
+    // piece that belong there (the same for every instruction up to a row offset)
+    const int line_in_instr = lane >> 4;            // 0..3
+    const int slot = lane & 15;
+    // line = (i * 8 + wave) * 4 + line_in_instr; (line & 7) = ((wave & 1) * 4 + line_in_instr)
+    const int piece = (slot & 7) ^ (((wave & 1) << 2) | line_in_instr);
+    const int row_lo = 2 * (wave * 4 + line_in_instr) + (slot >> 3);  // + 64 * i
+
+    // fragment read addresses inside a stage (A area at 0, B area after it)
+    uint32_t fa_addr[4][2], fb_addr[4][2];
+#pragma unroll
+    for (int kk = 0; kk < 4; ++kk)
+#pragma unroll
+        for (int i = 0; i < 2; ++i) {
+            fa_addr[kk][i] = lds_piece(wave_m * 64 + i * 32 + l31, kk * 2 + lhi);
+            fb_addr[kk][i] = kStageABytes + lds_piece(wave_n * 64 + i * 32 + l31, kk * 2 + lhi);
+        }
+
+    struct Frags {
+        bf16x8 a[2], b[2];
+    };
+
+    for (int w = blockIdx.x; w < prm.tiles_per_xcd * kXcds; w += gridDim.x) {
+        const int slot_w = w / kXcds;
+        const int lin = (w % kXcds) * prm.tiles_per_xcd + slot_w;
+        if (lin >= total_tiles) continue;
+        const int per_group = prm.group_m * prm.tiles_n;
+        const int grp = lin / per_group;
+        const int first_tm = grp * prm.group_m;
+        const int gsz = min(prm.group_m, prm.tiles_m - first_tm);
+        const int in_grp = lin - grp * per_group;
+        const int tm = first_tm + in_grp % gsz;
+        const int tn = in_grp / gsz;
+
+        const long long m0 = static_cast<long long>(tm) * BM;
+        const long long n0 = static_cast<long long>(tn) * BN;
+        const int rows_a = static_cast<int>(min(static_cast<long long>(BM), prm.M - m0));
+        const int rows_b = static_cast<int>(min(static_cast<long long>(BN), prm.N - n0));
+        const __amdgpu_buffer_rsrc_t ra = gemm_rsrc(prm.A + m0 * row_bytes, static_cast<uint32_t>(rows_a * row_bytes));
+        const __amdgpu_buffer_rsrc_t rb = gemm_rsrc(prm.B + n0 * row_bytes, static_cast<uint32_t>(rows_b * row_bytes));
+
+        f32x16 acc[2][2];
+#pragma unroll
+        for (int i = 0; i < 2; ++i)
+#pragma unroll
+            for (int j = 0; j < 2; ++j)
+#pragma unroll
+                for (int e = 0; e < 16; ++e) acc[i][j][e] = 0.0f;
+
+        // six asynchronous 16-byte loads per lane fill one stage with K step kt
+        auto fetch = [&](int kt, int stage) {
+            const long long k = static_cast<long long>(kt) * BK + piece * 8;
+            const bool kin = k < prm.K;
+            const uint32_t kb = static_cast<uint32_t>(k * 2);
+            char *sa = lds + stage * kStageBytes;
+#pragma unroll
+            for (int i = 0; i < 4; ++i) {
+                const uint32_t off = static_cast<uint32_t>((row_lo + 64 * i) * row_bytes) + kb;
+                __builtin_amdgcn_raw_ptr_buffer_load_lds(ra, (lds_ptr_t)(sa + (i * 8 + wave) * 1024), 16,
+                                                         kin ? off : kOob, 0, 0, 0);
+            }
+#pragma unroll
+            for (int i = 0; i < 2; ++i) {
+                const uint32_t off = static_cast<uint32_t>((row_lo + 64 * i) * row_bytes) + kb;
+                __builtin_amdgcn_raw_ptr_buffer_load_lds(rb, (lds_ptr_t)(sa + kStageABytes + (i * 8 + wave) * 1024),
+                                                         16, kin ? off : kOob, 0, 0, 0);
+            }
+        };
+        auto load_frags = [&](Frags &f, uint32_t stage_base, int kk) {
+#pragma unroll
+            for (int i = 0; i < 2; ++i) {
+                f.a[i] = lds_read16(stage_base + fa_addr[kk][i]);
+                f.b[i] = lds_read16(stage_base + fb_addr[kk][i]);
+            }
+        };
+        auto mfma_step = [&](const Frags &f) {
+#pragma unroll
+            for (int nb = 0; nb < 2; ++nb)
+#pragma unroll
+                for (int mb = 0; mb < 2; ++mb)
+                    acc[nb][mb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(f.b[nb], f.a[mb], acc[nb][mb], 0, 0, 0);
+        };
+
+        // All waves are done with the previous tile's LDS reads before it is refilled.
+        __builtin_amdgcn_s_waitcnt(0xC07F);  // lgkmcnt(0)
+        __builtin_amdgcn_s_barrier();
+        fetch(0, 0);
+        fetch(1, 1);
+
+        int stage = 0;
+        for (int kt = 0; kt < k_tiles; ++kt) {
+            // K step kt has landed once at most the six loads of step kt + 1 are
+            // outstanding (loads past the end are issued too, out of range, so
+            // the count is the same in every trip)
+            __builtin_amdgcn_s_waitcnt(0x0F76);  // vmcnt(6)
+            __builtin_amdgcn_s_barrier();
+            int next_stage = stage + 2;
+            next_stage = next_stage >= kDmaStages ? next_stage - kDmaStages : next_stage;
+            fetch(kt + 2, next_stage);
+            __builtin_amdgcn_sched_barrier(0);
+
+            const uint32_t base = static_cast<uint32_t>(stage * kStageBytes);
+            Frags f0, f1;
+            load_frags(f0, base, 0);
+            load_frags(f1, base, 1);
+            TW_WAIT_LGKM(4, f0);
+            mfma_step(f0);
+            __builtin_amdgcn_sched_barrier(0);
+            load_frags(f0, base, 2);
+            TW_WAIT_LGKM(4, f1);
+            mfma_step(f1);
+            __builtin_amdgcn_sched_barrier(0);
+            load_frags(f1, base, 3);
+            TW_WAIT_LGKM(4, f0);
+            mfma_step(f0);
+            __builtin_amdgcn_sched_barrier(0);
+            TW_WAIT_LGKM(0, f1);
+            mfma_step(f1);
+            __builtin_amdgcn_sched_barrier(0);
+            stage = stage + 1 >= kDmaStages ? 0 : stage + 1;
+        }
+        // the two prefetches past the end are still in flight and target LDS
+        __builtin_amdgcn_s_waitcnt(0x0F70);  // vmcnt(0)
+
+        const long long c_row_bytes = prm.N * 2;
+        const __amdgpu_buffer_rsrc_t rc = gemm_rsrc(prm.C + m0 * c_row_bytes, static_cast<uint32_t>(rows_a * c_row_bytes));
+#pragma unroll
+        for (int mb = 0; mb < 2; ++mb) {
+            const int m = wave_m * 64 + mb * 32 + l31;
+#pragma unroll
+            for (int nb = 0; nb < 2; ++nb) {
+#pragma unroll
+                for (int q = 0; q < 4; ++q) {
+                    const long long n = n0 + wave_n * 64 + nb * 32 + q * 8 + lhi * 4;
+                    u32x2 v;
+                    v.x = pack_bf16x2(acc[nb][mb][q * 4 + 0], acc[nb][mb][q * 4 + 1]);
+                    v.y = pack_bf16x2(acc[nb][mb][q * 4 + 2], acc[nb][mb][q * 4 + 3]);
+                    const uint32_t off = static_cast<uint32_t>(m * c_row_bytes + n * 2);
+                    __builtin_amdgcn_raw_buffer_store_b64(v, rc, n < prm.N ? off : kOob, 0, 0);
+                }
+            }
+        }
+    }
+}
+
+// ---------------------------------------------------------------------------
 // host side
 // ---------------------------------------------------------------------------
+
+// 0: register-staged kernel, 1: direct-to-LDS kernel
+static std::atomic<int> g_gemm_variant{1};
 
 tw_status validate_gemm(const tw_gemm_args &g)
 {
@@ -303,9 +498,14 @@ tw_status launch_gemm(const tw_gemm_args &g, hipStream_t stream)
     if (!allowed.load(std::memory_order_acquire)) {
         TW_HIP(hipFuncSetAttribute(reinterpret_cast<const void *>(gemm_bf16_nk_kernel),
                                    hipFuncAttributeMaxDynamicSharedMemorySize, kGemmLdsBytes));
+        TW_HIP(hipFuncSetAttribute(reinterpret_cast<const void *>(gemm_bf16_nk_dma_kernel),
+                                   hipFuncAttributeMaxDynamicSharedMemorySize, kGemmDmaLdsBytes));
         allowed.store(1, std::memory_order_release);
     }
-    TW_HIP(launch_kernel(gemm_bf16_nk_kernel, dim3(grid), dim3(kGemmThreads), kGemmLdsBytes, stream, prm));
+    if (g_gemm_variant.load(std::memory_order_relaxed) == 1)
+        TW_HIP(launch_kernel(gemm_bf16_nk_dma_kernel, dim3(grid), dim3(kGemmThreads), kGemmDmaLdsBytes, stream, prm));
+    else
+        TW_HIP(launch_kernel(gemm_bf16_nk_kernel, dim3(grid), dim3(kGemmThreads), kGemmLdsBytes, stream, prm));
     return TW_OK;
 }
 
@@ -320,3 +520,6 @@ extern "C" tw_status tw_gemm_bf16(const void *A, const void *B, void *C, int64_t
     TW_TRY(validate_gemm(g));
     return launch_gemm(g, static_cast<hipStream_t>(stream));
 }
+
+// Lab switch between the two GEMM kernels (not declared in the public header).
+extern "C" void tw_internal_set_gemm_variant(int v) { tw::g_gemm_variant.store(v); }
