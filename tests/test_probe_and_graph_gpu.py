@@ -1,0 +1,98 @@
+"""GPU checks of the measurement probes (they are exported, so they must do what
+the header says) and of HIP-graph capture of the library's multi-stream calls."""
+import numpy as np
+import pytest
+
+import tw_workloads as W
+from helpers import to_bits, to_gpu
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module")
+def torch_cuda():
+    import torch
+    assert torch.cuda.is_available()
+    return torch
+
+
+def test_copy_and_write_probes_move_the_bytes_they_claim(tw, torch_cuda):
+    torch = torch_cuda
+    n = (3 << 20) + 4096 + 16          # not a multiple of the grid stride: exercises the tail loop
+    src = torch.randint(0, 256, (n,), dtype=torch.uint8, device="cuda:0")
+    for budget in (1, 8, 0):
+        dst = torch.zeros(n + 64, dtype=torch.uint8, device="cuda:0")
+        tw.hbm_probe(src, dst, n, tw.PROBE_COPY, cu_budget=budget)
+        torch.cuda.synchronize()
+        assert torch.equal(dst[:n], src) and int(dst[n:].sum()) == 0
+    dst = torch.zeros(n + 64, dtype=torch.uint8, device="cuda:0")
+    tw.hbm_probe(None, dst, n, tw.PROBE_WRITE, cu_budget=8)
+    torch.cuda.synchronize()
+    pat = dst[:n].view(torch.int32)
+    assert bool((pat == 0x3F803F80).all()) and int(dst[n:].sum()) == 0
+    sink = torch.zeros(256 * tw.device_cu_count(), dtype=torch.uint8, device="cuda:0")
+    tw.hbm_probe(src, sink, n, tw.PROBE_READ, cu_budget=8)
+    torch.cuda.synchronize()
+
+
+def test_mixed_probe_writes_only_its_write_streams(tw, torch_cuda):
+    torch = torch_cuda
+    sb = 1 << 20
+    src = torch.randint(0, 256, (9 * sb,), dtype=torch.uint8, device="cuda:0")
+    dst = torch.zeros(2 * sb + 4096, dtype=torch.uint8, device="cuda:0")
+    for n_read in (0, 1, 5, 9, 17):
+        if n_read > 9:
+            src17 = torch.randint(0, 256, (17 * sb,), dtype=torch.uint8, device="cuda:0")
+            tw.hbm_probe_mixed(src17, dst, sb, n_read, 2, cu_budget=4)
+        else:
+            tw.hbm_probe_mixed(src, dst, sb, n_read, 2, cu_budget=4)
+        torch.cuda.synchronize()
+        assert int(dst[2 * sb:].sum()) == 0          # nothing past the two streams
+    before = src.clone()
+    tw.hbm_probe_mixed(src, dst, sb, 9, 0, cu_budget=4)
+    torch.cuda.synchronize()
+    assert torch.equal(src, before)
+
+
+def test_weave_layer_can_be_captured_in_a_hip_graph(tw, torch_cuda):
+    """tw_weave_layer forks and joins a second stream with events; captured on the
+    caller's stream it becomes one graph. Every replay (with eager work and
+    synchronisations in between) must reproduce the eager result bit for bit."""
+    torch = torch_cuda
+    T, K1, H, P, N2 = 512, 256, 2048, 4, 640
+    g1 = W.make_gemm_inputs(T, K1, H, 0.1, seed=3, b_layout="nk")
+    cfg = dict(N=T, H=H, P=P, partial_std=0.5, residual_std=1.0, outlier_frac=0.0, outlier_scale=1.0,
+               eps=1e-5, seed=5)
+    f = W.make_fused_inputs(cfg)
+    X1, W1 = to_gpu(g1["A"]), to_gpu(g1["B"])
+    W2 = to_gpu(W.normal_bf16((N2, H), 0.05, 9, W.STREAM_GEMM_B))
+    parts = [torch.zeros((T, H), dtype=torch.bfloat16, device="cuda:0")] + [to_gpu(p) for p in f["partials"][1:]]
+    resid, weight = to_gpu(f["residual"]), to_gpu(f["weight"])
+    out, res, Y = (torch.empty_like(resid), torch.empty_like(resid),
+                   torch.empty((T, N2), dtype=torch.bfloat16, device="cuda:0"))
+    main, comm = torch.cuda.Stream(), torch.cuda.Stream()
+
+    def layer():
+        tw.weave_layer(X1, W1, parts, resid, weight, f["eps"], W2, 256, main, comm,
+                       fused_cu_budget=tw.CU_SHARED, gemm_cu_budget=0, out=out, residual_out=res, Y=Y,
+                       parent=main, use_parent=True, join=True)
+    with torch.cuda.stream(main):
+        layer()                                   # eager: also the warm-up that capture needs
+    torch.cuda.synchronize()
+    want = (to_bits(out).copy(), to_bits(res).copy(), to_bits(Y).copy())
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph, stream=main):
+        layer()
+    for rep in range(4):
+        with torch.cuda.stream(main):
+            out.zero_()
+            res.zero_()
+            Y.zero_()
+            parts[0].zero_()
+            graph.replay()
+        main.synchronize()
+        assert np.array_equal(to_bits(out), want[0]) and np.array_equal(to_bits(res), want[1])
+        assert np.array_equal(to_bits(Y), want[2])
+        with torch.cuda.stream(main):            # eager work between replays
+            tw.reduce_add_rmsnorm(parts, resid, weight, f["eps"], cu_budget=8)
+        torch.cuda.synchronize()
