@@ -174,6 +174,7 @@ int64_t tw_split_point(int64_t N, int64_t multiple);
  *             TW_B_NK: [N x K] row-major, i.e. B(k,n) at B[n*K + k] -- the way a
  *                      linear layer's weight [out_features x in_features] is kept;
  *             TW_B_KN: [K x N] row-major, B(k,n) at B[k*N + n].
+ *             Both layouts give bit-identical C.
  *   C         device bf16 [M x N], row-major; must not overlap A or B
  *   M, N, K   >= 0 (any zero: TW_OK, C untouched unless K == 0 and M*N > 0, in
  *             which case C is zero-filled); K must be a multiple of 8 and N a

@@ -538,14 +538,9 @@ template <int PT, int VPT>
 static tw_status launch_t(const FusedParams &prm, bool trace, int64_t grid, hipStream_t stream)
 {
     auto kern = trace ? fused_kernel<PT, VPT, true> : fused_kernel<PT, VPT, false>;
-    // More than 64 KiB of dynamic LDS has to be allowed per kernel, once.
-    static std::atomic<int> allowed[2] = {0, 0};
-    if (!allowed[trace].load(std::memory_order_acquire)) {
-        TW_HIP(hipFuncSetAttribute(reinterpret_cast<const void *>(kern),
-                                   hipFuncAttributeMaxDynamicSharedMemorySize,
-                                   static_cast<int>(kOccupancyPadBytes)));
-        allowed[trace].store(1, std::memory_order_release);
-    }
+    static std::atomic<int> allowed[2][kMaxDevices];
+    TW_TRY(allow_dynamic_lds(reinterpret_cast<const void *>(kern), static_cast<int>(kOccupancyPadBytes),
+                             allowed[trace]));
     TW_HIP(launch_kernel(kern, dim3(static_cast<unsigned>(grid)), dim3(kThreads), kOccupancyPadBytes,
                          stream, prm));
     return TW_OK;

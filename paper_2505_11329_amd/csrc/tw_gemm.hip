@@ -30,6 +30,7 @@
 //     compact blocks: the tiles an XCD works on share rows of A and columns of
 //     B in that XCD's L2.
 #include <atomic>
+#include <type_traits>
 
 #include "tw_internal.h"
 
@@ -262,13 +263,40 @@ __device__ __forceinline__ bf16x8 lds_read16(uint32_t addr)
     asm volatile("ds_read_b128 %0, %1" : "=v"(v) : "v"(addr) : "memory");
     return v;
 }
+// gfx950's transposing LDS read. Within each group of 16 lanes, lane 4a+b
+// receives, for j = 0..3, the b-th 16-bit element of the 8-byte chunk that lane
+// a + 4j points at (lane mapping established with a probe kernel). With lane
+// a + 4j pointing at row k0+j, columns 4a..4a+3 of a [k][n] tile, lane d = 4a+b
+// ends up with column d of rows k0..k0+3: four consecutive k of one n, which is
+// what an MFMA operand register pair holds.
+template <int OFF>
+__device__ __forceinline__ u32x2 lds_read_tr8(uint32_t addr)
+{
+    u32x2 v;
+    asm volatile("ds_read_b64_tr_b16 %0, %1 offset:%2" : "=v"(v) : "v"(addr), "n"(OFF) : "memory");
+    return v;
+}
+
+// Operand fragments of one K sub-step. With B stored [K x N] a B fragment
+// arrives as two register pairs (k 0..3 and k 4..7 of the lane's column).
+template <bool B_KN>
+struct DmaFrags {
+    bf16x8 a[2];
+    bf16x8 b[2];
+    u32x2 blo[2], bhi[2];
+};
 // Wait until at most N of this wave's LDS reads are outstanding. The fragments
-// are passed through so that no MFMA that uses them can be moved above the wait.
-#define TW_WAIT_LGKM(N, f)                                                                   \
+// are passed through so that no use of them can be moved above the wait.
+#define TW_WAIT_LGKM_NK(N, f)                                                                \
     asm volatile("s_waitcnt lgkmcnt(" #N ")"                                                 \
                  : "+v"((f).a[0]), "+v"((f).a[1]), "+v"((f).b[0]), "+v"((f).b[1])::"memory")
+#define TW_WAIT_LGKM_KN(N, f)                                                                \
+    asm volatile("s_waitcnt lgkmcnt(" #N ")"                                                 \
+                 : "+v"((f).a[0]), "+v"((f).a[1]), "+v"((f).blo[0]), "+v"((f).bhi[0]),       \
+                   "+v"((f).blo[1]), "+v"((f).bhi[1])::"memory")
 
-__global__ __launch_bounds__(kGemmThreads) void gemm_bf16_nk_dma_kernel(const GemmParams prm)
+template <bool B_KN>
+__global__ __launch_bounds__(kGemmThreads) void gemm_bf16_dma_kernel(const GemmParams prm)
 {
     extern __shared__ __attribute__((aligned(16))) char lds[];
 
@@ -280,7 +308,8 @@ __global__ __launch_bounds__(kGemmThreads) void gemm_bf16_nk_dma_kernel(const Ge
     const int l31 = lane & 31;
     const int lhi = lane >> 5;
 
-    const long long row_bytes = prm.K * 2;
+    const long long row_bytes = prm.K * 2;      // of A, and of B when it is stored [N x K]
+    const long long bkn_row_bytes = prm.N * 2;  // of B when it is stored [K x N]
     const int k_tiles = static_cast<int>((prm.K + BK - 1) / BK);
     const int total_tiles = prm.tiles_m * prm.tiles_n;
 
@@ -292,9 +321,15 @@ __global__ __launch_bounds__(kGemmThreads) void gemm_bf16_nk_dma_kernel(const Ge
     // line = (i * 8 + wave) * 4 + line_in_instr; (line & 7) = ((wave & 1) * 4 + line_in_instr)
     const int piece = (slot & 7) ^ (((wave & 1) << 2) | line_in_instr);
     const int row_lo = 2 * (wave * 4 + line_in_instr) + (slot >> 3);  // + 64 * i
+    // B stored [K x N]: its LDS area holds 64 k-rows of 256 bytes (128 n); a wave
+    // instruction fills four rows; row r keeps 16-byte piece s at slot
+    // s ^ ((r & 3) << 1), so that the four rows one transposing read touches
+    // fall into different banks.
+    const int bkn_row_lo = wave * 4 + line_in_instr;                  // + 32 * i
+    const int bkn_piece = slot ^ (line_in_instr << 1);
 
     // fragment read addresses inside a stage (A area at 0, B area after it)
-    uint32_t fa_addr[4][2], fb_addr[4][2];
+    uint32_t fa_addr[4][2], fb_addr[4][2], fbkn_addr[2];
 #pragma unroll
     for (int kk = 0; kk < 4; ++kk)
 #pragma unroll
@@ -302,10 +337,19 @@ __global__ __launch_bounds__(kGemmThreads) void gemm_bf16_nk_dma_kernel(const Ge
             fa_addr[kk][i] = lds_piece(wave_m * 64 + i * 32 + l31, kk * 2 + lhi);
             fb_addr[kk][i] = kStageABytes + lds_piece(wave_n * 64 + i * 32 + l31, kk * 2 + lhi);
         }
+    {
+        // lane = 16 g + s: group g covers columns (g & 1) * 16 .. +15 of the 32-wide
+        // block and k group g >> 1; s = a + 4 j points at row j, columns 4a..4a+3
+        const int g = lane >> 4, sl = lane & 15, a4 = sl & 3, j = sl >> 2;
+#pragma unroll
+        for (int i = 0; i < 2; ++i) {
+            const int col = wave_n * 64 + i * 32 + (g & 1) * 16 + 4 * a4;
+            const int row = (g >> 1) * 8 + j;  // + 16 kk + 4 half, added as an immediate
+            fbkn_addr[i] = kStageABytes + row * 256 + ((((col >> 3) ^ (j << 1))) << 4) + (col & 7) * 2;
+        }
+    }
 
-    struct Frags {
-        bf16x8 a[2], b[2];
-    };
+    using Frags = DmaFrags<B_KN>;
 
     for (int w = blockIdx.x; w < prm.tiles_per_xcd * kXcds; w += gridDim.x) {
         const int slot_w = w / kXcds;
@@ -346,27 +390,72 @@ __global__ __launch_bounds__(kGemmThreads) void gemm_bf16_nk_dma_kernel(const Ge
                 __builtin_amdgcn_raw_ptr_buffer_load_lds(ra, (lds_ptr_t)(sa + (i * 8 + wave) * 1024), 16,
                                                          kin ? off : kOob, 0, 0, 0);
             }
+            if constexpr (!B_KN) {
 #pragma unroll
-            for (int i = 0; i < 2; ++i) {
-                const uint32_t off = static_cast<uint32_t>((row_lo + 64 * i) * row_bytes) + kb;
-                __builtin_amdgcn_raw_ptr_buffer_load_lds(rb, (lds_ptr_t)(sa + kStageABytes + (i * 8 + wave) * 1024),
-                                                         16, kin ? off : kOob, 0, 0, 0);
+                for (int i = 0; i < 2; ++i) {
+                    const uint32_t off = static_cast<uint32_t>((row_lo + 64 * i) * row_bytes) + kb;
+                    __builtin_amdgcn_raw_ptr_buffer_load_lds(rb, (lds_ptr_t)(sa + kStageABytes + (i * 8 + wave) * 1024),
+                                                             16, kin ? off : kOob, 0, 0, 0);
+                }
+            } else {
+                // rows k0 .. k0+63 of B through a descriptor of their own: rows past K
+                // fall outside it, columns past N are redirected out of range
+                const long long k0 = static_cast<long long>(kt) * BK;
+                const long long k_left = prm.K - k0;
+                const int rows_k = static_cast<int>(k_left < 0 ? 0 : (k_left > BK ? BK : k_left));
+                const __amdgpu_buffer_rsrc_t rk = gemm_rsrc(prm.B + (k_left > 0 ? k0 : 0) * bkn_row_bytes,
+                                                            static_cast<uint32_t>(rows_k * bkn_row_bytes));
+                const long long n = n0 + bkn_piece * 8;
+#pragma unroll
+                for (int i = 0; i < 2; ++i) {
+                    const uint32_t off = static_cast<uint32_t>((bkn_row_lo + 32 * i) * bkn_row_bytes + n * 2);
+                    __builtin_amdgcn_raw_ptr_buffer_load_lds(rk, (lds_ptr_t)(sa + kStageABytes + (i * 8 + wave) * 1024),
+                                                             16, n < prm.N ? off : kOob, 0, 0, 0);
+                }
             }
         };
-        auto load_frags = [&](Frags &f, uint32_t stage_base, int kk) {
+        auto load_frags = [&](Frags &f, uint32_t stage_base, auto kk_tag) {
+            constexpr int kk = decltype(kk_tag)::value;
 #pragma unroll
-            for (int i = 0; i < 2; ++i) {
-                f.a[i] = lds_read16(stage_base + fa_addr[kk][i]);
-                f.b[i] = lds_read16(stage_base + fb_addr[kk][i]);
+            for (int i = 0; i < 2; ++i) f.a[i] = lds_read16(stage_base + fa_addr[kk][i]);
+            if constexpr (!B_KN) {
+#pragma unroll
+                for (int i = 0; i < 2; ++i) f.b[i] = lds_read16(stage_base + fb_addr[kk][i]);
+            } else {
+#pragma unroll
+                for (int i = 0; i < 2; ++i) {
+                    f.blo[i] = lds_read_tr8<kk * 4096>(stage_base + fbkn_addr[i]);
+                    f.bhi[i] = lds_read_tr8<kk * 4096 + 1024>(stage_base + fbkn_addr[i]);
+                }
             }
         };
         auto mfma_step = [&](const Frags &f) {
 #pragma unroll
-            for (int nb = 0; nb < 2; ++nb)
+            for (int nb = 0; nb < 2; ++nb) {
+                bf16x8 b;
+                if constexpr (B_KN) {
+                    const u32x4 t = {f.blo[nb].x, f.blo[nb].y, f.bhi[nb].x, f.bhi[nb].y};
+                    b = __builtin_bit_cast(bf16x8, t);
+                } else {
+                    b = f.b[nb];
+                }
 #pragma unroll
                 for (int mb = 0; mb < 2; ++mb)
-                    acc[nb][mb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(f.b[nb], f.a[mb], acc[nb][mb], 0, 0, 0);
+                    acc[nb][mb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(b, f.a[mb], acc[nb][mb], 0, 0, 0);
+            }
         };
+        // wait until only the LDS reads of the NEXT sub-step (4, or 6 with the
+        // transposing reads) may still be outstanding / until none is
+        auto wait_prev = [&](Frags &f) {
+            if constexpr (B_KN) TW_WAIT_LGKM_KN(6, f); else TW_WAIT_LGKM_NK(4, f);
+        };
+        auto wait_all = [&](Frags &f) {
+            if constexpr (B_KN) TW_WAIT_LGKM_KN(0, f); else TW_WAIT_LGKM_NK(0, f);
+        };
+        using K0 = std::integral_constant<int, 0>;
+        using K1 = std::integral_constant<int, 1>;
+        using K2 = std::integral_constant<int, 2>;
+        using K3 = std::integral_constant<int, 3>;
 
         // All waves are done with the previous tile's LDS reads before it is refilled.
         __builtin_amdgcn_s_waitcnt(0xC07F);  // lgkmcnt(0)
@@ -388,20 +477,20 @@ __global__ __launch_bounds__(kGemmThreads) void gemm_bf16_nk_dma_kernel(const Ge
 
             const uint32_t base = static_cast<uint32_t>(stage * kStageBytes);
             Frags f0, f1;
-            load_frags(f0, base, 0);
-            load_frags(f1, base, 1);
-            TW_WAIT_LGKM(4, f0);
+            load_frags(f0, base, K0{});
+            load_frags(f1, base, K1{});
+            wait_prev(f0);
             mfma_step(f0);
             __builtin_amdgcn_sched_barrier(0);
-            load_frags(f0, base, 2);
-            TW_WAIT_LGKM(4, f1);
+            load_frags(f0, base, K2{});
+            wait_prev(f1);
             mfma_step(f1);
             __builtin_amdgcn_sched_barrier(0);
-            load_frags(f1, base, 3);
-            TW_WAIT_LGKM(4, f0);
+            load_frags(f1, base, K3{});
+            wait_prev(f0);
             mfma_step(f0);
             __builtin_amdgcn_sched_barrier(0);
-            TW_WAIT_LGKM(0, f1);
+            wait_all(f1);
             mfma_step(f1);
             __builtin_amdgcn_sched_barrier(0);
             stage = stage + 1 >= kDmaStages ? 0 : stage + 1;
@@ -447,7 +536,6 @@ tw_status validate_gemm(const tw_gemm_args &g)
     if (g.K % 8 != 0 || g.N % 8 != 0) return TW_ERR_UNSUPPORTED;
     // a tile's rows are addressed with 32-bit byte offsets
     if (g.K > (int64_t(1) << 22) || g.N > (int64_t(1) << 22) || g.M > (int64_t(1) << 40)) return TW_ERR_UNSUPPORTED;
-    if (g.b_layout == TW_B_KN) return TW_ERR_UNSUPPORTED;
     if (!aligned16(g.A) || !aligned16(g.B) || !aligned16(g.C)) return TW_ERR_ALIGN;
     const uint64_t a_bytes = uint64_t(g.M) * uint64_t(g.K) * 2, b_bytes = uint64_t(g.N) * uint64_t(g.K) * 2;
     const uint64_t c_bytes = uint64_t(g.M) * uint64_t(g.N) * 2;
@@ -494,16 +582,14 @@ tw_status launch_gemm(const tw_gemm_args &g, hipStream_t stream)
     const int64_t slots = int64_t(prm.tiles_per_xcd) * kXcds;
     const unsigned grid = static_cast<unsigned>(slots < budget ? slots : budget);
 
-    static std::atomic<int> allowed{0};
-    if (!allowed.load(std::memory_order_acquire)) {
-        TW_HIP(hipFuncSetAttribute(reinterpret_cast<const void *>(gemm_bf16_nk_kernel),
-                                   hipFuncAttributeMaxDynamicSharedMemorySize, kGemmLdsBytes));
-        TW_HIP(hipFuncSetAttribute(reinterpret_cast<const void *>(gemm_bf16_nk_dma_kernel),
-                                   hipFuncAttributeMaxDynamicSharedMemorySize, kGemmDmaLdsBytes));
-        allowed.store(1, std::memory_order_release);
-    }
-    if (g_gemm_variant.load(std::memory_order_relaxed) == 1)
-        TW_HIP(launch_kernel(gemm_bf16_nk_dma_kernel, dim3(grid), dim3(kGemmThreads), kGemmDmaLdsBytes, stream, prm));
+    static std::atomic<int> allowed[3][kMaxDevices];
+    TW_TRY(allow_dynamic_lds(reinterpret_cast<const void *>(gemm_bf16_nk_kernel), kGemmLdsBytes, allowed[0]));
+    TW_TRY(allow_dynamic_lds(reinterpret_cast<const void *>(gemm_bf16_dma_kernel<false>), kGemmDmaLdsBytes, allowed[1]));
+    TW_TRY(allow_dynamic_lds(reinterpret_cast<const void *>(gemm_bf16_dma_kernel<true>), kGemmDmaLdsBytes, allowed[2]));
+    if (g.b_layout == TW_B_KN)
+        TW_HIP(launch_kernel(gemm_bf16_dma_kernel<true>, dim3(grid), dim3(kGemmThreads), kGemmDmaLdsBytes, stream, prm));
+    else if (g_gemm_variant.load(std::memory_order_relaxed) == 1)
+        TW_HIP(launch_kernel(gemm_bf16_dma_kernel<false>, dim3(grid), dim3(kGemmThreads), kGemmDmaLdsBytes, stream, prm));
     else
         TW_HIP(launch_kernel(gemm_bf16_nk_kernel, dim3(grid), dim3(kGemmThreads), kGemmLdsBytes, stream, prm));
     return TW_OK;

@@ -17,7 +17,6 @@ tw_status hip_fail(hipError_t e, const char *where)
     return TW_ERR_HIP;
 }
 
-static constexpr int kMaxDevices = 64;
 static std::mutex g_mu;
 static int g_cu_count[kMaxDevices];  // 0 = not queried yet
 
@@ -39,6 +38,17 @@ tw_status current_cu_count(int *cu_count)
     std::lock_guard<std::mutex> lk(g_mu);
     g_cu_count[dev] = n;
     *cu_count = n;
+    return TW_OK;
+}
+
+tw_status allow_dynamic_lds(const void *kernel, int bytes, std::atomic<int> *done)
+{
+    int dev = 0;
+    TW_HIP(hipGetDevice(&dev));
+    if (dev < 0 || dev >= kMaxDevices) return hip_fail(hipErrorInvalidDevice, "tw_host.hip: device id out of range");
+    if (done[dev].load(std::memory_order_acquire)) return TW_OK;
+    TW_HIP(hipFuncSetAttribute(kernel, hipFuncAttributeMaxDynamicSharedMemorySize, bytes));
+    done[dev].store(1, std::memory_order_release);
     return TW_OK;
 }
 
@@ -211,6 +221,22 @@ tw_status tw_weave_layer(const tw_layer_args *layer, int64_t split_row, void *st
     const tw_gemm_args g2 = {f.out, layer->W2, layer->Y, T, layer->N2, f.H, TW_B_NK, layer->gemm_cu_budget};
     TW_TRY(validate_gemm(g1));
     TW_TRY(validate_gemm(g2));
+    {   // Y is written while the other split's fused kernel may still be running:
+        // it must not touch anything that kernel reads or writes, nor G1's operands
+        const uint64_t y_bytes = uint64_t(T) * uint64_t(layer->N2) * 2, t_bytes = uint64_t(T) * uint64_t(f.H) * 2;
+        if (ranges_overlap(layer->Y, y_bytes, f.residual, t_bytes) ||
+            ranges_overlap(layer->Y, y_bytes, f.residual_out, t_bytes) ||
+            ranges_overlap(layer->Y, y_bytes, f.weight, uint64_t(f.H) * 2) ||
+            ranges_overlap(layer->Y, y_bytes, layer->X1, uint64_t(T) * uint64_t(layer->K1) * 2) ||
+            ranges_overlap(layer->Y, y_bytes, layer->W1, uint64_t(f.H) * uint64_t(layer->K1) * 2))
+            return TW_ERR_ALIAS;
+        for (int p = 0; p < f.P; ++p)
+            if (ranges_overlap(layer->Y, y_bytes, f.partials[p], t_bytes)) return TW_ERR_ALIAS;
+        // G1 writes partials[0] before the fused kernel runs: it must not be one of
+        // G1's own inputs (checked above) nor the weights of either GEMM
+        if (ranges_overlap(f.partials[0], t_bytes, layer->W2, uint64_t(layer->N2) * uint64_t(f.H) * 2))
+            return TW_ERR_ALIAS;
+    }
 
     hipStream_t sx = static_cast<hipStream_t>(stream_compute), sc = static_cast<hipStream_t>(stream_comm);
     hipStream_t sp = static_cast<hipStream_t>(parent);

@@ -4,6 +4,8 @@
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 
+#include <atomic>
+
 #include "tw.h"
 
 namespace tw {
@@ -31,6 +33,11 @@ inline hipError_t launch_kernel(void (*kern)(Params...), dim3 grid, dim3 block, 
     void *argv[] = {const_cast<void *>(static_cast<const void *>(&args))...};
     return hipLaunchKernel(reinterpret_cast<const void *>(kern), grid, block, argv, lds_bytes, stream);
 }
+
+// Kernels that ask for more than 64 KiB of dynamic LDS have to be allowed to,
+// once per device. `done` is a per-kernel array of kMaxDevices flags.
+static constexpr int kMaxDevices = 64;
+tw_status allow_dynamic_lds(const void *kernel, int bytes, std::atomic<int> *done);
 
 #define TW_TRY(expr)                                  \
     do {                                              \

@@ -99,13 +99,8 @@ static tw_status launch_mixed(const void *src, void *dst, int64_t stream_bytes, 
                               hipStream_t stream)
 {
     auto kern = probe_mixed_kernel<NR>;
-    static std::atomic<int> allowed{0};
-    if (!allowed.load(std::memory_order_acquire)) {
-        TW_HIP(hipFuncSetAttribute(reinterpret_cast<const void *>(kern),
-                                   hipFuncAttributeMaxDynamicSharedMemorySize,
-                                   static_cast<int>(kProbePadBytes)));
-        allowed.store(1, std::memory_order_release);
-    }
+    static std::atomic<int> allowed[kMaxDevices];
+    TW_TRY(allow_dynamic_lds(reinterpret_cast<const void *>(kern), static_cast<int>(kProbePadBytes), allowed));
     TW_HIP(launch_kernel(kern, dim3(grid), dim3(kProbeThreads), kProbePadBytes, stream,
                          static_cast<const char *>(src), static_cast<char *>(dst),
                          static_cast<unsigned>(stream_bytes), n_write));
@@ -125,13 +120,8 @@ template <int MODE>
 static tw_status launch_probe(const void *src, void *dst, int64_t bytes, unsigned grid, hipStream_t stream)
 {
     auto kern = probe_kernel<MODE>;
-    static std::atomic<int> allowed{0};
-    if (!allowed.load(std::memory_order_acquire)) {
-        TW_HIP(hipFuncSetAttribute(reinterpret_cast<const void *>(kern),
-                                   hipFuncAttributeMaxDynamicSharedMemorySize,
-                                   static_cast<int>(kProbePadBytes)));
-        allowed.store(1, std::memory_order_release);
-    }
+    static std::atomic<int> allowed[kMaxDevices];
+    TW_TRY(allow_dynamic_lds(reinterpret_cast<const void *>(kern), static_cast<int>(kProbePadBytes), allowed));
     TW_HIP(launch_kernel(kern, dim3(grid), dim3(kProbeThreads), kProbePadBytes, stream,
                          static_cast<const u32x4 *>(src), static_cast<u32x4 *>(dst),
                          static_cast<long long>(bytes / 16)));

@@ -34,17 +34,30 @@ SHAPES = [(256, 128, 64), (64, 64, 64), (300, 200, 136), (1, 8, 8), (257, 136, 7
           (33, 1000, 264), (700, 24, 4096)]
 
 
+@pytest.mark.parametrize("layout", ["nk", "kn"])
 @pytest.mark.parametrize("M,N,K", SHAPES)
-def test_gemm_small_shapes_full_compare(tw, torch_cuda, M, N, K):
-    g = W.make_gemm_inputs(M, K, N, 0.5, seed=M + N + K, b_layout="nk")
-    C = tw.gemm_bf16(to_gpu(g["A"]), to_gpu(g["B"]), b_layout=tw.B_NK)
+def test_gemm_small_shapes_full_compare(tw, torch_cuda, M, N, K, layout):
+    g = W.make_gemm_inputs(M, K, N, 0.5, seed=M + N + K, b_layout=layout)
+    code = tw.B_NK if layout == "nk" else tw.B_KN
+    C = tw.gemm_bf16(to_gpu(g["A"]), to_gpu(g["B"]), b_layout=code)
     torch_cuda.cuda.synchronize()
-    ref = oracle.gemm(g["A"], g["B"], "nk")
-    gemm_check(oracle.bf16_to_f64(to_bits(C)), ref, K, 0.5, "gemm %dx%dx%d" % (M, N, K))
+    ref = oracle.gemm(g["A"], g["B"], layout)
+    gemm_check(oracle.bf16_to_f64(to_bits(C)), ref, K, 0.5, "gemm %s %dx%dx%d" % (layout, M, N, K))
     # a budgeted (persistent) launch walks the same tiles: same bits
-    C2 = tw.gemm_bf16(to_gpu(g["A"]), to_gpu(g["B"]), b_layout=tw.B_NK, cu_budget=3)
+    C2 = tw.gemm_bf16(to_gpu(g["A"]), to_gpu(g["B"]), b_layout=code, cu_budget=3)
     torch_cuda.cuda.synchronize()
     assert np.array_equal(to_bits(C), to_bits(C2))
+
+
+def test_gemm_both_layouts_give_the_same_bits(tw, torch_cuda):
+    """B(k, n) is the same matrix whichever way it is stored, and both kernels
+    multiply and add in the same order."""
+    a = W.make_gemm_inputs(520, 1000, 392, 0.3, seed=11, b_layout="nk")
+    b = W.make_gemm_inputs(520, 1000, 392, 0.3, seed=11, b_layout="kn")
+    C1 = tw.gemm_bf16(to_gpu(a["A"]), to_gpu(a["B"]), b_layout=tw.B_NK)
+    C2 = tw.gemm_bf16(to_gpu(b["A"]), to_gpu(b["B"]), b_layout=tw.B_KN)
+    torch_cuda.cuda.synchronize()
+    assert np.array_equal(to_bits(C1), to_bits(C2))
 
 
 def test_gemm_k_zero_gives_zeros(tw, torch_cuda):
@@ -57,18 +70,19 @@ def test_gemm_k_zero_gives_zeros(tw, torch_cuda):
     assert (to_bits(C) == 0).all()
 
 
-def test_gemm_demo_shape_sampled(tw, torch_cuda):
+@pytest.mark.parametrize("layout", ["nk", "kn"])
+def test_gemm_demo_shape_sampled(tw, torch_cuda, layout):
     """[2048 x 8192] x [8192 x 3584], N(0, 0.02^2): 4096 sampled outputs, one by one."""
     gc = W.CONFIGS["c5_overlap_tp8"]["gemm"]
-    g = W.make_gemm_inputs(gc["M"], gc["K"], gc["N"], gc["std"], seed=0, b_layout="nk")
-    C = tw.gemm_bf16(to_gpu(g["A"]), to_gpu(g["B"]))
+    g = W.make_gemm_inputs(gc["M"], gc["K"], gc["N"], gc["std"], seed=0, b_layout=layout)
+    C = tw.gemm_bf16(to_gpu(g["A"]), to_gpu(g["B"]), b_layout=tw.B_NK if layout == "nk" else tw.B_KN)
     torch_cuda.cuda.synchronize()
     Cb = to_bits(C)
     rng = np.random.default_rng(0)
     ms = np.concatenate([rng.integers(0, gc["M"], 4088), [0, 0, gc["M"] - 1, gc["M"] - 1, 255, 256, 1023, 1024]])
     ns = np.concatenate([rng.integers(0, gc["N"], 4088), [0, gc["N"] - 1, 0, gc["N"] - 1, 127, 128, 3583, 1792]])
-    ref = oracle.gemm_samples(g["A"], g["B"], "nk", ms, ns)
-    gemm_check(oracle.bf16_to_f64(Cb[ms, ns]), ref, gc["K"], gc["std"], "demo gemm")
+    ref = oracle.gemm_samples(g["A"], g["B"], layout, ms, ns)
+    gemm_check(oracle.bf16_to_f64(Cb[ms, ns]), ref, gc["K"], gc["std"], "demo gemm " + layout)
     assert np.count_nonzero(Cb) > 0.99 * Cb.size
 
 
