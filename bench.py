@@ -47,6 +47,10 @@ def main():
                     help="instead of the benchmark line: token sweep 32..64K of the fused kernel at H=8192 (P=8, "
                          "P=4) and H=4096 (P=2), whole device / shared / 32 CUs, one JSON object (the analogue of "
                          "the paper's Tables 1-2)")
+    ap.add_argument("--split-sweep", action="store_true",
+                    help="instead of the benchmark line: for a range of token counts, the woven layer boundary "
+                         "timed at the equal split and at the offsets {0,64,128,192,256,512} past it (the sweep "
+                         "of Algorithm 1), next to the row tw_smart_split_point picks without timing anything")
     ap.add_argument("--counters-run", choices=("fused", "gemm"), default=None,
                     help="for rocprofv3 --pmc. fused: a few fused launches plus plain copy launches of known "
                          "size (tw_hbm_probe, 192 MiB read + 192 MiB written each) to scale the byte counters "
@@ -133,6 +137,60 @@ def main():
                 del ss
                 torch.cuda.empty_cache()
         print(json.dumps({"sweep": rows, "note": "median of HIP-event timed launches, rotating buffer sets, bf16"}))
+        return
+    if args.split_sweep:
+        K1, H, P, N2 = 1024, 8192, 8, 3584
+        comm = torch.cuda.Stream()
+        cus = tw.device_cu_count()
+        gen = torch.Generator(device=dev)
+        gen.manual_seed(7)
+
+        def rnd(shape, std):
+            return torch.empty(shape, dtype=torch.bfloat16, device=dev).normal_(0.0, std, generator=gen)
+        W1, W2 = rnd((H, K1), 0.02), rnd((N2, H), 0.02)
+        weight = gpu(W.uniform_bf16((H,), 0.5, 1.5, 0, W.STREAM_WEIGHT))
+        rows = []
+        for T in range(4096, 8192 + 1, 256):
+            X1, resid = rnd((T, K1), 0.02), rnd((T, H), 1.0)
+            parts = [rnd((T, H), 0.25) for _ in range(P)]
+            out, res_out = torch.empty_like(resid), torch.empty_like(resid)
+            Y = torch.empty((T, N2), dtype=torch.bfloat16, device=dev)
+
+            def layer_fn(split_row):
+                def f():
+                    with torch.cuda.stream(stream):
+                        tw.weave_layer(X1, W1, parts, resid, weight, 1e-5, W2, split_row, stream, comm,
+                                       fused_cu_budget=tw.CU_SHARED, gemm_cu_budget=0, out=out,
+                                       residual_out=res_out, Y=Y, parent=stream, use_parent=True, join=True)
+                return f
+            half = (T // 2 + 63) // 64 * 64
+            timed = {}
+            for off in (0, 64, 128, 192, 256, 512):
+                k = half + off
+                if k < T:
+                    timed[k] = round(float(np.median(event_times([layer_fn(k)], 24, 4, stream))), 1)
+            k_smart, ws, wu = tw.smart_split_point(T, 64, [H, N2], cus, gemm_k=[K1, H])
+            if k_smart not in timed:
+                timed[k_smart] = round(float(np.median(event_times([layer_fn(k_smart)], 24, 4, stream))), 1)
+            k_best = min(timed, key=timed.get)
+            rows.append({"T": T, "equal_split_row": half, "equal_us": timed[half],
+                         "measured_best_row": k_best, "measured_best_us": timed[k_best],
+                         "smart_row": k_smart, "smart_us": timed[k_smart],
+                         "model_cost_split": ws, "model_cost_unsplit": wu,
+                         "unsplit_us": round(float(np.median(event_times([layer_fn(0)], 24, 4, stream))), 1),
+                         "all_us": {str(k): v for k, v in sorted(timed.items())}})
+            del X1, resid, parts, out, res_out, Y
+            torch.cuda.empty_cache()
+
+        def spread(key):
+            rate = np.array([r["T"] / r[key] for r in rows])
+            return round(float(rate.std() / rate.mean()), 4)
+        print(json.dumps({"split_sweep": rows,
+                          "tokens_per_us_relative_spread": {"equal": spread("equal_us"), "smart": spread("smart_us"),
+                                                            "measured_best": spread("measured_best_us")},
+                          "note": "layer boundary [Tx1024]x[1024x8192] -> fused H=8192 P=8 (shared mode) -> "
+                                  "[Tx8192]x[8192x3584]; medians of HIP-event timed calls of tw_weave_layer; "
+                                  "smart_row comes from tile counts alone"}))
         return
     if args.counters_run == "gemm":
         gc = W.CONFIGS["c5_overlap_tp8"]["gemm"]
@@ -429,15 +487,15 @@ def extras(result, tw, W, torch, np, stream, sets, fused_sets, algo_bytes, event
     t_un = event_times([layer_fn(0, 0, 0)], 20, 3, stream)
     weave["unsplit_whole_device_us"] = round(float(np.median(t_un)), 1)
     for fb in (32, 64, 96):
-        k, ws, wu = tw.smart_split_point(T, 128, [H, N2], cus - fb)
+        k, ws, wu = tw.smart_split_point(T, 128, [H, N2], cus - fb, gemm_k=[K1, H])
         t_w = event_times([layer_fn(k, fb, cus - fb)], 20, 3, stream)
         t_s = event_times([layer_fn(0, fb, cus - fb)], 20, 3, stream)
-        weave["fused_budget_%d" % fb] = {"split_row": k, "gemm_waves_split": ws, "gemm_waves_unsplit": wu,
+        weave["fused_budget_%d" % fb] = {"split_row": k, "model_cost_split": ws, "model_cost_unsplit": wu,
                                          "woven_us": round(float(np.median(t_w)), 1),
                                          "unsplit_same_budgets_us": round(float(np.median(t_s)), 1)}
-    k, ws, wu = tw.smart_split_point(T, 128, [H, N2], cus)
+    k, ws, wu = tw.smart_split_point(T, 128, [H, N2], cus, gemm_k=[K1, H])
     t_w = event_times([layer_fn(k, tw.CU_SHARED, 0)], 20, 3, stream)
-    weave["fused_shared"] = {"split_row": k, "gemm_waves_split": ws, "gemm_waves_unsplit": wu,
+    weave["fused_shared"] = {"split_row": k, "model_cost_split": ws, "model_cost_unsplit": wu,
                              "woven_us": round(float(np.median(t_w)), 1)}
     result["weave_layer"] = {
         "workload": "T=4096: G1 [Tx1024]x[1024x8192] -> fused H=8192 P=8 -> G2 [Tx8192]x[8192x3584], bf16",

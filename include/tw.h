@@ -262,19 +262,21 @@ tw_status tw_weave_layer(const tw_layer_args *layer, int64_t split_row, void *st
  * are closed source, here the GEMM's tile grid is known, so the same sweep is
  * evaluated analytically). A GEMM over r rows with output width n runs
  * ceil(r / tile_m) * ceil(n / tile_n) workgroups, i.e. ceil(that / cus) waves on
- * `cus` compute units. Among the candidates k = tw_split_point(T, multiple) +
- * j * multiple (j = 0, 1, 2, ..., k < T, offset at most 512 rows as in
- * Algorithm 1) the one with the fewest total waves over both splits and all
- * n_gemms output widths wins; ties go to the smallest offset. Returns T ("do not
- * split") only when tw_split_point already does, i.e. for batches too small to
- * cut at that multiple. If not NULL, *waves_split receives the winner's wave
- * total and *waves_unsplit that of the whole batch, so the caller can apply the
- * paper's criterion (split waves <= unsplit waves) or its own threshold.
- * Host only. gemm_n_out: host array of n_gemms output widths. Returns -1 on bad
- * arguments (T < 0, n_gemms < 1, cus < 1, NULL array, a width < 1).
+ * `cus` compute units, and a wave lasts in proportion to the GEMM's depth k. The
+ * cost of a cut is the sum over both splits and all n_gemms GEMMs of waves * k
+ * (gemm_k == NULL: every GEMM weighs 1, the cost is the plain wave count). Among
+ * the candidates k = tw_split_point(T, multiple) + j * multiple (j = 0, 1, 2,
+ * ..., k < T, offset at most 512 rows as in Algorithm 1) the cheapest wins; ties
+ * go to the smallest offset. Returns T ("do not split") only when tw_split_point
+ * already does, i.e. for batches too small to cut at that multiple. If not NULL,
+ * *cost_split receives the winner's cost and *cost_unsplit that of the whole
+ * batch, so the caller can apply the paper's criterion (split waves <= unsplit
+ * waves) or its own threshold. Host only. gemm_n_out, gemm_k: host arrays of
+ * n_gemms output widths and depths. Returns -1 on bad arguments (T < 0,
+ * n_gemms < 1, cus < 1, NULL widths, a width or depth < 1).
  */
-int64_t tw_smart_split_point(int64_t T, int64_t multiple, const int64_t *gemm_n_out, int n_gemms,
-                             int cus, int64_t *waves_split, int64_t *waves_unsplit);
+int64_t tw_smart_split_point(int64_t T, int64_t multiple, const int64_t *gemm_n_out, const int64_t *gemm_k,
+                             int n_gemms, int cus, int64_t *cost_split, int64_t *cost_unsplit);
 
 /*
  * Selective enabling (Fig. 3 and Appendix A "Selective Enabling of Splitting and

@@ -93,7 +93,8 @@ def lib():
         L.tw_hbm_probe.restype = ctypes.c_int
         L.tw_weave_layer.argtypes = [ctypes.POINTER(LayerArgs), _i64, _vp, _vp, _vp, ctypes.c_int, ctypes.c_int]
         L.tw_weave_layer.restype = ctypes.c_int
-        L.tw_smart_split_point.argtypes = [_i64, _i64, ctypes.POINTER(_i64), ctypes.c_int, ctypes.c_int,
+        L.tw_smart_split_point.argtypes = [_i64, _i64, ctypes.POINTER(_i64), ctypes.POINTER(_i64), ctypes.c_int,
+                                           ctypes.c_int,
                                            ctypes.POINTER(_i64), ctypes.POINTER(_i64)]
         L.tw_smart_split_point.restype = _i64
         L.tw_should_split.argtypes = [_i64, _i64]
@@ -304,11 +305,17 @@ def hbm_probe_mixed(src, dst, stream_bytes, n_read, n_write, cu_budget=0, stream
                                     _stream_handle(stream)), "tw_hbm_probe_mixed")
 
 
-def smart_split_point(T, multiple, gemm_n_out, cus):
-    """tw_smart_split_point. Returns (split_row, waves_split, waves_unsplit)."""
+def smart_split_point(T, multiple, gemm_n_out, cus, gemm_k=None):
+    """tw_smart_split_point. Returns (split_row, cost_split, cost_unsplit); without gemm_k the costs are
+    wave counts."""
     arr = (_i64 * max(len(gemm_n_out), 1))(*[int(x) for x in gemm_n_out])
+    karr = None
+    if gemm_k is not None:
+        if len(gemm_k) != len(gemm_n_out):
+            raise ValueError("gemm_k needs one depth per GEMM")
+        karr = (_i64 * max(len(gemm_k), 1))(*[int(x) for x in gemm_k])
     ws, wu = _i64(0), _i64(0)
-    k = int(lib().tw_smart_split_point(int(T), int(multiple), arr, len(gemm_n_out), int(cus),
+    k = int(lib().tw_smart_split_point(int(T), int(multiple), arr, karr, len(gemm_n_out), int(cus),
                                        ctypes.byref(ws), ctypes.byref(wu)))
     return k, int(ws.value), int(wu.value)
 

@@ -291,30 +291,32 @@ static int64_t gemm_waves(int64_t rows, int64_t n_out, int64_t cus)
     return (wgs + cus - 1) / cus;
 }
 
-int64_t tw_smart_split_point(int64_t T, int64_t multiple, const int64_t *gemm_n_out, int n_gemms, int cus,
-                             int64_t *waves_split, int64_t *waves_unsplit)
+int64_t tw_smart_split_point(int64_t T, int64_t multiple, const int64_t *gemm_n_out, const int64_t *gemm_k,
+                             int n_gemms, int cus, int64_t *cost_split, int64_t *cost_unsplit)
 {
     if (T < 0 || n_gemms < 1 || cus < 1 || !gemm_n_out) return -1;
     for (int i = 0; i < n_gemms; ++i)
-        if (gemm_n_out[i] < 1) return -1;
+        if (gemm_n_out[i] < 1 || (gemm_k && gemm_k[i] < 1)) return -1;
     if (multiple <= 0) multiple = 1;
-    int64_t unsplit = 0;
-    for (int i = 0; i < n_gemms; ++i) unsplit += gemm_waves(T, gemm_n_out[i], cus);
-    if (waves_unsplit) *waves_unsplit = unsplit;
-    if (waves_split) *waves_split = unsplit;
+    auto cost_of = [&](int64_t rows) {
+        int64_t c = 0;
+        for (int i = 0; i < n_gemms; ++i) c += gemm_waves(rows, gemm_n_out[i], cus) * (gemm_k ? gemm_k[i] : 1);
+        return c;
+    };
+    const int64_t unsplit = cost_of(T);
+    if (cost_unsplit) *cost_unsplit = unsplit;
+    if (cost_split) *cost_split = unsplit;
     const int64_t base = tw_split_point(T, multiple);
     if (base >= T) return T;
     int64_t best_k = T, best_cost = INT64_MAX;
     for (int64_t k = base; k < T && k - base <= 512; k += multiple) {
-        int64_t cost = 0;
-        for (int i = 0; i < n_gemms; ++i)
-            cost += gemm_waves(k, gemm_n_out[i], cus) + gemm_waves(T - k, gemm_n_out[i], cus);
+        const int64_t cost = cost_of(k) + cost_of(T - k);
         if (cost < best_cost) {
             best_cost = cost;
             best_k = k;
         }
     }
-    if (waves_split) *waves_split = best_cost;
+    if (cost_split) *cost_split = best_cost;
     return best_k;
 }
 

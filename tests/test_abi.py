@@ -244,6 +244,14 @@ def test_smart_split_point_matches_its_definition():
                     cost = {c: sum(waves(c, n, cus) + waves(T - c, n, cus) for n in widths) for c in cands}
                     best = min(cands, key=lambda c: (cost[c], c))
                     assert (k, ws) == (best, cost[best]), (T, mult, widths, cus)
+                    # with depths, a wave of GEMM i weighs depths[i]
+                    depths = [1024, 8192, 512][:len(widths)]
+                    k, ws, wu = tw.smart_split_point(T, mult, widths, cus, gemm_k=depths)
+                    cost = {c: sum((waves(c, n, cus) + waves(T - c, n, cus)) * d for n, d in zip(widths, depths))
+                            for c in cands}
+                    best = min(cands, key=lambda c: (cost[c], c))
+                    assert (k, ws) == (best, cost[best]), (T, mult, widths, cus)
+                    assert wu == sum(waves(T, n, cus) * d for n, d in zip(widths, depths))
     # the situation of the paper's example (Section 4.1.1): 300 workgroups (10 row
     # tiles x 30 column tiles) on 132 units are 3 waves; the even cut (150 + 150)
     # needs 2 + 2 = 4, moving one row tile to the prefix (180 + 120) needs 2 + 1 = 3
@@ -253,6 +261,13 @@ def test_smart_split_point_matches_its_definition():
     assert tw.smart_split_point(64, 64, [], 8)[0] == -1
     assert tw.smart_split_point(64, 64, [0], 8)[0] == -1
     assert tw.smart_split_point(64, 64, [8], 0)[0] == -1
+    assert tw.smart_split_point(64, 64, [8], 8, gemm_k=[0])[0] == -1
+    # a cut that saves one long wave at the price of one short wave is taken only
+    # when the depths say so: T=5632 over widths 8192 (depth 1024) and 3584 (depth
+    # 8192) on 256 units -- 2816+2816 and 3328+2304 both make 10 waves, but the
+    # second has one deep wave fewer
+    assert tw.smart_split_point(5632, 64, [8192, 3584], 256)[0] == 2816
+    assert tw.smart_split_point(5632, 64, [8192, 3584], 256, gemm_k=[1024, 8192])[0] == 3328
 
 
 def test_weave_layer_argument_checks():
