@@ -85,10 +85,13 @@ typedef enum tw_status {
  *                 no two share a compute unit. 0, or >= the device's CU count,
  *                 means the whole device. TW_CU_SHARED (-1) selects the shared
  *                 mode instead: many small workgroups (256 threads, <= 96
- *                 VGPRs, 16 KiB LDS) spread over every compute unit, sized to
- *                 run NEXT TO a tw_gemm_bf16 workgroup on the same compute unit
- *                 rather than in place of one; for H > 8192 it falls back to
- *                 the whole device. Other negative values mean the whole device.
+ *                 VGPRs, under 1 KiB LDS) spread over every compute unit, sized
+ *                 to run NEXT TO a tw_gemm_bf16 workgroup on the same compute
+ *                 unit rather than in place of one; for H > 8192 it falls back
+ *                 to the whole device. Other negative values mean the whole
+ *                 device. A whole-device launch of at most two rows per compute
+ *                 unit (H <= 8192) is sent as those small workgroups too: same
+ *                 bits, lower latency.
  *   out           device bf16 [N x H]
  *   residual_out  device bf16 [N x H]
  *

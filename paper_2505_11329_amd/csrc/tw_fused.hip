@@ -604,6 +604,19 @@ static tw_status launch_vpt(const FusedParams &prm, int vpt, bool trace, int64_t
     return TW_ERR_UNSUPPORTED;
 }
 
+// Which kernel a launch takes. Shared mode has a kernel for rows of up to 1024
+// vectors; wider rows run on the wide kernel over the whole device. A
+// whole-device launch of at most two rows per compute unit also takes the small
+// workgroups: they are placed faster and put every row in flight at once
+// (measured 5-20 % faster up to that size, slower well beyond it). Both kernels
+// give the same bits.
+static bool takes_thin_kernel(int cu_budget, int cus, const FusedGeometry &g, int64_t n_rows)
+{
+    if (g.vpt != 1) return false;
+    if (cu_budget == TW_CU_SHARED) return true;
+    return resolve_budget(cu_budget, cus) == cus && n_rows <= 2 * static_cast<int64_t>(cus);
+}
+
 tw_status launch_fused(const tw_fused_args &a, int64_t row_begin, int64_t row_end, uint32_t *hw_ids,
                        int64_t hw_ids_len, hipStream_t stream)
 {
@@ -620,9 +633,7 @@ tw_status launch_fused(const tw_fused_args &a, int64_t row_begin, int64_t row_en
     int64_t rows_per_launch = kMaxLaunchBytes / row_bytes;
     rows_per_launch -= rows_per_launch % g.rows_per_iter;
     if (trace && row_end - row_begin > rows_per_launch) return TW_ERR_UNSUPPORTED;
-    // Shared mode has a kernel for rows of up to 1024 vectors; wider rows run on
-    // the wide kernel over the whole device.
-    const bool thin = a.cu_budget == TW_CU_SHARED && g.vpt == 1;
+    const bool thin = takes_thin_kernel(a.cu_budget, cus, g, row_end - row_begin);
     const ThinGeometry tg = thin_geometry(g);
     const int rows_per_group = thin ? tg.rows_per_iter : g.rows_per_iter;
 
@@ -711,7 +722,7 @@ int64_t tw_fused_grid(int64_t N, int64_t H, int cu_budget)
     int cus = 0;
     if (current_cu_count(&cus) != TW_OK) return -1;
     const FusedGeometry g = fused_geometry(H);
-    if (cu_budget == TW_CU_SHARED && g.vpt == 1 && N * H * 2 <= kMaxLaunchBytes) {
+    if (takes_thin_kernel(cu_budget, cus, g, N) && N * H * 2 <= kMaxLaunchBytes) {
         int64_t grid = 0;
         uint32_t gpw = 1;
         thin_grid(N, thin_geometry(g), cus, &grid, &gpw);
