@@ -9,6 +9,7 @@ from .oracle import (  # noqa: F401
     build,
     fused,
     fused_rounded_x,
+    unfused,
     fused_mt,
     gemm,
     gemm_samples,

@@ -43,7 +43,7 @@ def _load():
         lib = ctypes.CDLL(_LIB)
         fused_args = [ctypes.POINTER(_u16p), _u16p, _u16p, ctypes.c_float,
                       ctypes.c_int64, ctypes.c_int64, ctypes.c_int, _f64p, _f64p]
-        for name in ("tw_oracle_fused", "tw_oracle_fused_rounded_x"):
+        for name in ("tw_oracle_fused", "tw_oracle_fused_rounded_x", "tw_oracle_unfused"):
             fn = getattr(lib, name)
             fn.argtypes = fused_args
             fn.restype = ctypes.c_int
@@ -108,6 +108,12 @@ def fused(partials, residual, weight, eps):
 def fused_rounded_x(partials, residual, weight, eps):
     """Alternative reading: the bf16-rounded sum feeds the norm."""
     return _fused_call("tw_oracle_fused_rounded_x", partials, residual, weight, eps)
+
+
+def unfused(partials, residual, weight, eps):
+    """The three-pass pipeline (all-reduce to bf16, residual add + sum of squares, scale from the stored
+    bf16 residual stream). Returns (ref_out, ref_res) like fused()."""
+    return _fused_call("tw_oracle_unfused", partials, residual, weight, eps)
 
 
 def fused_mt(partials, residual, weight, eps, nthreads):

@@ -156,6 +156,46 @@ int tw_oracle_fused_rounded_x(const uint16_t *const *partials,
                       ref_out, ref_res);
 }
 
+/* ---- the unfused pipeline the paper measures its kernel against (Section 4.2,
+ * Table 1: all-reduce, then residual add + RMSNorm; Section 4.3 describes the
+ * standard RMSNorm as two reads of the tensor and one write). Three stages,
+ * each a pass over memory with bf16 tensors in between:
+ *   1. t = bf16(p_0 + ... + p_{P-1}), the all-reduce's bf16 output. Which bf16
+ *      neighbour t lands on is a decision, so it is taken in the precision the
+ *      device path takes it in: a binary32 sum in the order p = 0 .. P-1, then
+ *      one rounding to nearest even;
+ *   2. x = t + residual (exact in binary64); the new residual stream is x
+ *      (ref_res, unrounded; what is stored is bf16(x)); the sum of squares is
+ *      taken over the unrounded x;
+ *   3. the stored residual stream is read back: out = bf16(x) * s * w.
+ * ref_out is the unrounded result of stage 3. ---- */
+int tw_oracle_unfused(const uint16_t *const *partials, const uint16_t *residual,
+                      const uint16_t *weight, float eps, int64_t N, int64_t H,
+                      int P, double *ref_out, double *ref_res)
+{
+    if (N < 0 || H <= 0 || P < 1)
+        return -1;
+    for (int64_t r = 0; r < N; ++r) {
+        const int64_t base = r * H;
+        double sumsq = 0.0;
+        for (int64_t c = 0; c < H; ++c) {
+            volatile float acc = 0.0f; /* volatile: no excess precision, no contraction */
+            for (int p = 0; p < P; ++p)
+                acc = acc + (float)bf16_to_f64(partials[p][base + c]);
+            const double t = bf16_to_f64(tw_oracle_f64_to_bf16((double)acc));
+            const double x = t + bf16_to_f64(residual[base + c]);
+            ref_res[base + c] = x;
+            sumsq += x * x;
+        }
+        const double s = 1.0 / sqrt(sumsq / (double)H + (double)eps);
+        for (int64_t c = 0; c < H; ++c) {
+            const double stored = bf16_to_f64(tw_oracle_f64_to_bf16(ref_res[base + c]));
+            ref_out[base + c] = stored * s * bf16_to_f64(weight[c]);
+        }
+    }
+    return 0;
+}
+
 /* ---- row-parallel wrapper: same per-row code, rows dealt out in contiguous
  * blocks to nthreads POSIX threads. Only used to time the oracle on all host
  * cores; results are identical to the single-threaded call because rows are

@@ -414,3 +414,76 @@ def test_gemm_layouts_describe_the_same_matrix():
     b = W.make_gemm_inputs(8, 16, 24, 0.5, seed=1, b_layout="nk")
     assert np.array_equal(a["B"], b["B"].T)
     assert np.array_equal(oracle.gemm(a["A"], a["B"], "kn"), oracle.gemm(b["A"], b["B"], "nk"))
+
+
+# ---- the unfused three-pass pipeline (ablation oracle) --------------------------
+
+def _read_golden(name):
+    vals = {}
+    with open(os.path.join(os.path.dirname(__file__), "golden", name)) as f:
+        for line in f:
+            line = line.strip()
+            if not line or line.startswith("#"):
+                continue
+            k, *rest = line.split()
+            vals[k] = rest
+    return vals
+
+
+def test_unfused_worked_example():
+    g = _read_golden("unfused_example_h2.txt")
+    H, P = int(g["H"][0]), int(g["P"][0])
+    enc = lambda k: W.f32_to_bf16_bits(np.array([float(v) for v in g[k]], dtype=np.float32)).reshape(1, H)
+    parts = [enc("partial%d" % p) for p in range(P)]
+    for p in range(P):      # the inputs of the example are exact in bf16
+        assert np.array_equal(oracle.bf16_to_f64(parts[p])[0], [float(v) for v in g["partial%d" % p]])
+    out, res = oracle.unfused(parts, enc("residual"), enc("weight").reshape(H), float(g["eps"][0]))
+    assert np.array_equal(res[0], [float(v) for v in g["expect_res"]])
+    assert np.allclose(out[0], [float(v) for v in g["expect_out"]], rtol=1e-15, atol=0)
+    # and the one-pass definition differs on it, as the file says
+    _, res_f = oracle.fused(parts, enc("residual"), enc("weight").reshape(H), float(g["eps"][0]))
+    assert np.array_equal(res_f[0], [float(v) for v in g["fused_res"]])
+
+
+def test_unfused_equals_fused_when_no_rounding_happens():
+    """Small integers: every sum is an integer below 256, exact in bf16, so both
+    intermediate roundings are no-ops and the two definitions coincide."""
+    rng = np.random.default_rng(5)
+    N, H, P = 6, 40, 4
+    ints = lambda lo, hi, shape: W.f32_to_bf16_bits(rng.integers(lo, hi + 1, shape).astype(np.float32))
+    parts = [ints(-20, 20, (N, H)) for _ in range(P)]
+    resid = ints(-40, 40, (N, H))
+    w = W.f32_to_bf16_bits(rng.choice([0.5, 1.0, 2.0], H).astype(np.float32))
+    a = oracle.unfused(parts, resid, w, 1e-5)
+    b = oracle.fused(parts, resid, w, 1e-5)
+    assert np.array_equal(a[0], b[0]) and np.array_equal(a[1], b[1])
+
+
+def test_unfused_single_partial_isolates_the_stage_three_rounding():
+    """P = 1: the all-reduce has nothing to round, x equals the fused x, the
+    sum of squares is the same, and the output differs exactly by the factor
+    bf16(x)/x that re-reading the stored residual stream introduces."""
+    d = W.make_fused_inputs("c1_tiny", N=16, seed=3, P=1)
+    a_out, a_res = oracle.unfused(d["partials"], d["residual"], d["weight"], d["eps"])
+    b_out, b_res = oracle.fused(d["partials"], d["residual"], d["weight"], d["eps"])
+    assert np.array_equal(a_res, b_res)
+    stored = oracle.bf16_to_f64(oracle.f64_to_bf16(b_res))
+    nz = b_res != 0
+    assert np.allclose(a_out[nz], b_out[nz] * (stored[nz] / b_res[nz]), rtol=1e-14, atol=0)
+    assert np.all(a_out[~nz] == 0)
+
+
+@pytest.mark.parametrize("name", ["c1_tiny", "c3_70b_shard_tp8"])
+def test_unfused_stays_within_one_rounding_of_the_partial_sum(name):
+    """x differs from the one-pass x by the single rounding of the partial sum:
+    at most half a bf16 ulp, i.e. at most 2^-8 relative to that sum (an ulp is
+    2^-7 of the binade's lower end), plus the binary32 summation error (2^-23
+    per addition)."""
+    d = W.make_fused_inputs(name, N=32)
+    _, a_res = oracle.unfused(d["partials"], d["residual"], d["weight"], d["eps"])
+    _, b_res = oracle.fused(d["partials"], d["residual"], d["weight"], d["eps"])
+    psum = sum(oracle.bf16_to_f64(p) for p in d["partials"])
+    pabs = sum(np.abs(oracle.bf16_to_f64(p)) for p in d["partials"])
+    bound = 2.0 ** -8 * np.abs(psum) + len(d["partials"]) * 2.0 ** -23 * pabs + 1e-300
+    assert np.all(np.abs(a_res - b_res) <= bound)
+    assert np.any(a_res != b_res)       # and the rounding does happen on real data
