@@ -326,6 +326,27 @@ def extras(result, tw, W, torch, np, stream, sets, fused_sets, algo_bytes, event
         t = event_times(fused_fns(s2, b), 60, 8, stream)
         c2[str(b)] = {"us": round(float(np.median(t)), 1), "GBps": round(nb2 / np.median(t) / 1e3, 1)}
     result["config2_8b_tp2"] = c2
+
+    # what the single pass saves: the same step as "all-reduce to bf16, then residual add + RMSNorm
+    # re-reading what it stored" (two launches, three passes), both on the whole device
+    abl = {}
+    for name, ss in ((WORKLOAD.split(":")[0], sets), ("c2_8b_tp2", s2)):
+        scr = [torch.empty_like(x["residual"]) for x in ss]
+        unf = [(lambda x=x, sc=sc: tw.reduce_add_rmsnorm_unfused(x["partials"], x["residual"], x["weight"], x["eps"],
+                                                                 out=x["out"], residual_out=x["res_out"],
+                                                                 sum_scratch=sc, stream=stream))
+               for x, sc in zip(ss, scr)]
+        t_u = float(np.median(event_times(unf, 60, 8, stream)))
+        t_f = float(np.median(event_times(fused_fns(ss, 0), 60, 8, stream)))
+        P_, H_, N_ = ss[0]["P"], ss[0]["H"], ss[0]["N"]
+        abl[name] = {"fused_us": round(t_f, 1), "unfused_us": round(t_u, 1), "speedup": round(t_u / t_f, 3),
+                     "bytes_ratio_unfused_over_fused": round((P_ + 6) / (P_ + 3), 3),
+                     "unfused_GBps_of_its_own_bytes": round((P_ + 6) * 2 * H_ * N_ / t_u / 1e3, 1)}
+        del scr, unf
+    result["ablation_unfused"] = {
+        "per_config": abl,
+        "note": "tw_reduce_add_rmsnorm_unfused: (P+6)*2H bytes per row in two launches against the fused "
+                "kernel's (P+3)*2H in one; whole device, rotating buffer sets"}
     del s2
     torch.cuda.empty_cache()
 

@@ -134,6 +134,23 @@ tw_status tw_reduce_add_rmsnorm_traced(const void *const *partials, const void *
                                        int P, int cu_budget, void *out, void *residual_out,
                                        uint32_t *hw_ids, int64_t hw_ids_len, void *stream);
 
+/*
+ * Ablation: the pipeline the fused kernel replaces (Section 4.2 and Table 1:
+ * all-reduce, then residual add + RMSNorm; Section 4.3: a stand-alone RMSNorm
+ * reads the tensor twice and writes it once). Two launches on `stream`:
+ *   t = bf16(p_0 + ... + p_{P-1}) into sum_scratch;
+ *   x = t + residual, residual_out = bf16(x), s = rsqrt(mean(x^2) + eps), then
+ *   out = bf16((bf16(x) * s) * weight) with bf16(x) read back from residual_out.
+ * That moves (P + 6) * 2H bytes per row where tw_reduce_add_rmsnorm moves
+ * (P + 3) * 2H, and rounds twice more, so its outputs are close to, not equal
+ * to, the fused kernel's. Same arguments and rules as tw_reduce_add_rmsnorm,
+ * except: args->cu_budget is ignored (both launches use the whole device);
+ * H <= 8192 (else TW_ERR_UNSUPPORTED); sum_scratch is device bf16 [N x H],
+ * 16-byte aligned, owned by the caller, overwritten, and must not overlap any
+ * other tensor of the call (TW_ERR_ALIAS).
+ */
+tw_status tw_reduce_add_rmsnorm_unfused(const tw_fused_args *args, void *sum_scratch, void *stream);
+
 /* Number of workgroups the fused kernel is launched with for these sizes on the
  * current device (0 if N == 0; -1 if the arguments are invalid or no device). */
 int64_t tw_fused_grid(int64_t N, int64_t H, int cu_budget);

@@ -14,6 +14,7 @@ from .binding import (  # noqa: F401
     reduce_add_rmsnorm,
     prepare_reduce_add_rmsnorm,
     reduce_add_rmsnorm_traced,
+    reduce_add_rmsnorm_unfused,
     split_launch,
     gemm_bf16,
     overlap_launch,

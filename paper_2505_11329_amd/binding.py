@@ -80,6 +80,8 @@ def lib():
         L.tw_reduce_add_rmsnorm_traced.restype = ctypes.c_int
         L.tw_fused_grid.argtypes = [_i64, _i64, ctypes.c_int]
         L.tw_fused_grid.restype = _i64
+        L.tw_reduce_add_rmsnorm_unfused.argtypes = [ctypes.POINTER(FusedArgs), _vp, _vp]
+        L.tw_reduce_add_rmsnorm_unfused.restype = ctypes.c_int
         L.tw_split_launch.argtypes = [ctypes.POINTER(FusedArgs), _i64, _vp, _vp, _vp, ctypes.c_int, ctypes.c_int]
         L.tw_split_launch.restype = ctypes.c_int
         L.tw_split_point.argtypes = [_i64, _i64]
@@ -226,6 +228,19 @@ def reduce_add_rmsnorm_traced(partials, residual, weight, eps, cu_budget=0, out=
                                               grid, _stream_handle(stream)),
            "tw_reduce_add_rmsnorm_traced")
     return out, residual_out, hw
+
+
+def reduce_add_rmsnorm_unfused(partials, residual, weight, eps, out=None, residual_out=None, sum_scratch=None,
+                               stream=None):
+    """tw_reduce_add_rmsnorm_unfused (the three-pass ablation). Returns (out, residual_out)."""
+    import torch
+    a, keep, out, residual_out = _fused_pack(partials, residual, weight, eps, 0, out, residual_out)
+    if sum_scratch is None:
+        sum_scratch = torch.empty_like(residual)
+    T, H = residual.shape
+    _check(lib().tw_reduce_add_rmsnorm_unfused(ctypes.byref(a), _bf16_ptr(sum_scratch, "sum_scratch", (T, H)),
+                                               _stream_handle(stream)), "tw_reduce_add_rmsnorm_unfused")
+    return out, residual_out
 
 
 def split_launch(partials, residual, weight, eps, split_row, stream_a, stream_b, cu_budget=0,

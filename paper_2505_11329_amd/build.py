@@ -7,7 +7,7 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 ROOT = os.path.dirname(HERE)
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libtw.so")
-SOURCES = ["tw_host.hip", "tw_fused.hip", "tw_gemm.hip", "tw_probe.hip"]
+SOURCES = ["tw_host.hip", "tw_fused.hip", "tw_unfused.hip", "tw_gemm.hip", "tw_probe.hip"]
 
 # Packed fp32 VALU instructions are switched off for every kernel (the compiler
 # would otherwise form them from plain float code).

@@ -38,9 +38,6 @@ static constexpr int kWaves = kThreads / 64;
 // Dynamic LDS each workgroup requests so that only one fits on a compute unit
 // (gfx950 has 160 KiB per CU).
 static constexpr unsigned kOccupancyPadBytes = 96 * 1024;
-// One launch addresses its tensors with 32-bit byte offsets; longer batches are
-// cut into several launches on the host (rows are independent).
-static constexpr int64_t kMaxLaunchBytes = int64_t(1) << 31;
 
 struct FusedParams {
     const void *partials[TW_MAX_P];

@@ -64,6 +64,10 @@ inline bool ranges_overlap(const void *a, uint64_t alen, const void *b, uint64_t
     return pa < pb + blen && pb < pa + alen;
 }
 
+// One launch addresses its tensors with 32-bit byte offsets; longer batches are
+// cut into several launches on the host (rows are independent).
+static constexpr int64_t kMaxLaunchBytes = int64_t(1) << 31;
+
 // ---- fused reduce + residual add + RMSNorm (tw_fused.hip) ----
 // Host-only argument checks; no HIP call.
 tw_status validate_fused(const tw_fused_args &a);

@@ -142,6 +142,27 @@ def test_split_launch_argument_checks():
     assert split_call(0, n=0) == OK                    # nothing to do
 
 
+def unfused_call(scratch=addr(8), n=N, **kw):
+    arr = (VP * P)(addr(0), addr(1))
+    a = FusedArgs(ctypes.cast(arr, ctypes.POINTER(VP)), addr(4), addr(5), 1e-5, n, H, P, 8, addr(6), addr(7))
+    for k, v in kw.items():
+        setattr(a, k, v)
+    return tw.lib().tw_reduce_add_rmsnorm_unfused(ctypes.byref(a), VP(scratch), VP(None))
+
+
+def test_unfused_argument_checks():
+    assert tw.lib().tw_reduce_add_rmsnorm_unfused(None, VP(addr(8)), VP(None)) == E_NULL
+    assert unfused_call(scratch=None) == E_NULL
+    assert unfused_call(scratch=addr(8) + 2) == E_ALIGN
+    assert unfused_call(H=60) == E_UNSUP               # fused validation comes first
+    assert unfused_call(H=8200, n=1) == E_UNSUP        # wider than its kernels cover
+    assert unfused_call(n=0) == OK
+    assert unfused_call(n=0, scratch=None) == OK       # nothing to do, nothing to check
+    for other in (0, 1, 4, 5, 6, 7):                   # a partial, residual, weight, out, residual_out
+        assert unfused_call(scratch=addr(other)) == E_ALIAS
+    assert unfused_call(scratch=addr(6) + TENSOR - 16) == E_ALIAS
+
+
 def test_split_point_matches_its_definition():
     # independent statement: the smallest multiple of m that is >= N/2, capped at N
     for n in list(range(0, 70)) + [127, 128, 129, 255, 256, 1000, 1024, 4096, 16384, 10 ** 12 + 7]:

@@ -316,3 +316,42 @@ def test_shared_mode_on_configs_and_split(tw, torch_cuda, name, N):
                                  out=g2["partials"][0], residual_out=g2["residual"])
     torch.cuda.synchronize()
     assert np.array_equal(to_bits(o), want[0]) and np.array_equal(to_bits(r), want[1])
+
+
+# ---- the unfused three-pass pipeline (ablation) against its own oracle ----------
+
+UNFUSED_SHAPES = [(1, 8, 1), (3, 24, 3), (64, 512, 2), (130, 520, 5), (33, 2048, 4), (77, 4096, 2),
+                  (19, 6152, 7), (65, 8192, 8), (300, 8192, 16)]
+
+
+@pytest.mark.parametrize("N,H,P", UNFUSED_SHAPES)
+def test_unfused_pipeline_matches_its_oracle(tw, torch_cuda, N, H, P):
+    d = small(N, H, P, seed=N + H + P)
+    g = upload(d)
+    scratch = torch_cuda.full((N, H), float("nan"), dtype=torch_cuda.bfloat16, device="cuda:0")
+    out, res = tw.reduce_add_rmsnorm_unfused(g["partials"], g["residual"], g["weight"], g["eps"],
+                                             sum_scratch=scratch)
+    torch_cuda.cuda.synchronize()
+    ref_out, ref_res = oracle.unfused(d["partials"], d["residual"], d["weight"], d["eps"])
+    assert_parity(oracle.bf16_to_f64(to_bits(out)), ref_out, "unfused out N=%d H=%d P=%d" % (N, H, P))
+    assert_parity(oracle.bf16_to_f64(to_bits(res)), ref_res, "unfused residual N=%d H=%d P=%d" % (N, H, P))
+    # the all-reduce stage rounds exactly as the oracle does (binary32 sum in order, one rounding), so
+    # the stored residual stream is the oracle's x rounded once: bit-exact
+    assert np.array_equal(to_bits(res), oracle.f64_to_bf16(ref_res))
+
+
+def test_unfused_pipeline_on_the_headline_config_and_in_place(tw, torch_cuda):
+    torch = torch_cuda
+    d = W.make_fused_inputs("c3_70b_shard_tp8")
+    g = upload(d)
+    ref_out, ref_res = oracle.unfused(d["partials"], d["residual"], d["weight"], d["eps"])
+    out, res = tw.reduce_add_rmsnorm_unfused(g["partials"], g["residual"], g["weight"], g["eps"])
+    torch.cuda.synchronize()
+    assert_parity(oracle.bf16_to_f64(to_bits(out)), ref_out, "unfused c3 out")
+    assert np.array_equal(to_bits(res), oracle.f64_to_bf16(ref_res))
+    # paper's in-place form: residual updated in place, result written over a partial
+    want_out, want_res = to_bits(out), to_bits(res)
+    out2, res2 = tw.reduce_add_rmsnorm_unfused(g["partials"], g["residual"], g["weight"], g["eps"],
+                                               out=g["partials"][0], residual_out=g["residual"])
+    torch.cuda.synchronize()
+    assert np.array_equal(to_bits(out2), want_out) and np.array_equal(to_bits(res2), want_res)
