@@ -74,7 +74,8 @@ __global__ __launch_bounds__(kThreads) void fused_kernel(const FusedParams prm)
 {
     __shared__ float s_wave_sum[2][kWaves];
     constexpr int NB = buffers_in_flight<PT, VPT>();
-    constexpr bool KEEP_W = VPT <= 2;  // weights unpacked to fp32 once, else kept packed
+    constexpr bool KEEP_W = VPT <= 2;     // weights unpacked to fp32 once, else kept packed,
+    constexpr bool RELOAD_W = VPT >= 8;  // or (no registers left) re-read through the cache per row
 
     const int tid = threadIdx.x;
     const int lane = tid & 63;
@@ -104,18 +105,19 @@ __global__ __launch_bounds__(kThreads) void fused_kernel(const FusedParams prm)
     // end of the row are pushed out of range for good.
     uint32_t lane_off[VPT];
     bool cvalid[VPT];
-    u32x4 wv[VPT];
+    u32x4 wv[RELOAD_W ? 1 : VPT];
     float wf[KEEP_W ? VPT : 1][8];
-    {
-        const __amdgpu_buffer_rsrc_t r_w = make_rsrc(prm.weight, static_cast<uint32_t>(hv) * 16u);
+    const __amdgpu_buffer_rsrc_t r_w = make_rsrc(prm.weight, static_cast<uint32_t>(hv) * 16u);
+    auto load_w = [&](int j) {
+        return __builtin_amdgcn_raw_buffer_load_b128(r_w, cvalid[j] ? (col0 + j * tpr) * 16u : kOutOfRange, 0, 0);
+    };
 #pragma unroll
-        for (int j = 0; j < VPT; ++j) {
-            const int v = col0 + j * tpr;
-            cvalid[j] = v < hv;
-            lane_off[j] = static_cast<uint32_t>(row_in_iter * hv + v) * 16u;
-            wv[j] = __builtin_amdgcn_raw_buffer_load_b128(r_w, cvalid[j] ? v * 16u : kOutOfRange, 0, 0);
-            if constexpr (KEEP_W) unpack8(wv[j], wf[j]);
-        }
+    for (int j = 0; j < VPT; ++j) {
+        const int v = col0 + j * tpr;
+        cvalid[j] = v < hv;
+        lane_off[j] = static_cast<uint32_t>(row_in_iter * hv + v) * 16u;
+        if constexpr (!RELOAD_W) wv[j] = load_w(j);
+        if constexpr (KEEP_W) unpack8(wv[j], wf[j]);
     }
 
     const uint32_t stride = gridDim.x;
@@ -225,7 +227,8 @@ __global__ __launch_bounds__(kThreads) void fused_kernel(const FusedParams prm)
                     for (int e = 0; e < 8; ++e) y[e] = (x[j][e] * s) * wf[j][e];
                 } else {
                     float w[8];
-                    unpack8(wv[j], w);
+                    if constexpr (RELOAD_W) unpack8(load_w(j), w);
+                    else unpack8(wv[j], w);
 #pragma unroll
                     for (int e = 0; e < 8; ++e) y[e] = (x[j][e] * s) * w[e];
                 }
@@ -508,7 +511,9 @@ static tw_status launch_vpt(const FusedParams &prm, int vpt, bool trace, int64_t
     case 1: return launch_t<PT, 1>(prm, trace, grid, s);
     case 2: return launch_t<PT, 2>(prm, trace, grid, s);
     case 4: return launch_t<PT, 4>(prm, trace, grid, s);
-    case 8: return launch_t<PT, 8>(prm, trace, grid, s);
+    case 8:
+        if constexpr (PT != 8) return launch_t<PT, 8>(prm, trace, grid, s);  // P = 8 goes to the any-P kernel
+        break;
     }
     return TW_ERR_UNSUPPORTED;
 }
@@ -586,7 +591,11 @@ tw_status launch_fused(const tw_fused_args &a, int64_t row_begin, int64_t row_en
             }
             continue;
         }
-        switch (a.P) {
+        // Rows of 8 vectors per thread with all 8 partials in flight would not fit
+        // the 128 registers; the any-P kernel (4 loads at a time, same order of
+        // additions) does.
+        const int p_case = (a.P == 8 && g.vpt == 8) ? 0 : a.P;
+        switch (p_case) {
         case 1: TW_TRY((launch_vpt<1>(prm, g.vpt, trace, grid, stream))); break;
         case 2: TW_TRY((launch_vpt<2>(prm, g.vpt, trace, grid, stream))); break;
         case 4: TW_TRY((launch_vpt<4>(prm, g.vpt, trace, grid, stream))); break;
