@@ -7,15 +7,24 @@
 //   - Workgroup tile 256 (M) x 128 (N), K step 64, 512 threads = 8 wave64 laid
 //     out 4 x 2, each wave owning a 64 x 64 sub-tile as 2 x 2 blocks of
 //     v_mfma_f32_32x32x16_bf16 (64 accumulator registers per lane).
-//   - Operand tiles go global -> registers -> LDS. LDS is double-buffered and the
-//     global loads run two K steps ahead in two register sets, so a load has
-//     almost two K steps to arrive; one barrier per K step. 2 x (32 + 16) KiB of
-//     LDS, so one workgroup per compute unit.
+//   - Operand tiles go from global memory straight into LDS (gfx950's 16-byte
+//     buffer_load ... lds): no register staging and no ds_write. Three LDS
+//     stages of 32 + 16 KiB, so a load has two full K steps to land; one
+//     workgroup per compute unit.
 //   - LDS rows are 128 bytes (64 bf16 of K); two rows make a 256-byte line over
 //     all 64 banks and the 16-byte pieces are xor-swizzled with the line number,
-//     which makes both the 16-byte writes and the MFMA operand reads free of
-//     bank conflicts without padding (measured: 178 B/clk/CU against 128 for a
-//     swizzle that assumes 32 banks, 32 unswizzled).
+//     which makes the MFMA operand reads free of bank conflicts without padding
+//     (measured: 178 B/clk/CU against 128 for a swizzle that assumes 32 banks,
+//     32 unswizzled). An LDS-direct load writes 64 consecutive 16-byte slots per
+//     wave instruction, so the swizzle is applied on the global side: the lane
+//     that fills slot s of line l fetches piece (s & 7) ^ (l & 7) of row
+//     2l + (s >> 3).
+//   - The compiler cannot tell which LDS stage an asynchronous load targets and
+//     would wait for ALL outstanding loads before any LDS read it can see;
+//     operand fragments are therefore read with inline ds_read and the waits
+//     (vmcnt for landed stages, lgkmcnt for fragments) are placed by hand.
+//     Dynamic LDS is the kernel's only LDS object, so its byte offsets are LDS
+//     addresses.
 //   - Each MFMA gets the B fragment as its first operand and the A fragment as
 //     its second, so the 32x32 result block is held transposed: a lane owns one
 //     row m of C and, per group of four accumulator registers, four consecutive
@@ -29,9 +38,13 @@
 //     workgroup w takes tile (w mod 8) * ceil(T/8) + w / 8 of a list ordered in
 //     compact blocks: the tiles an XCD works on share rows of A and columns of
 //     B in that XCD's L2.
+//   - B stored [K x N] (B_KN): the B tile lands as 64 k-rows of 256 bytes and the
+//     MFMA operand (8 consecutive k of one column n) is gathered with the
+//     transposing LDS read ds_read_b64_tr_b16.
 #include <atomic>
 #include <type_traits>
 
+#include "tw_device.h"
 #include "tw_internal.h"
 
 namespace tw {
@@ -41,13 +54,10 @@ static constexpr int kGemmThreads = 512;
 static constexpr int kStageABytes = BM * BK * 2;  // 32 KiB
 static constexpr int kStageBBytes = BN * BK * 2;  // 16 KiB
 static constexpr int kStageBytes = kStageABytes + kStageBBytes;
-static constexpr int kGemmLdsBytes = 2 * kStageBytes;  // 96 KiB
 static constexpr int kXcds = 8;
 
-typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
 typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
 typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
-typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
 typedef float f32x16 __attribute__((ext_vector_type(16)));
 
 struct GemmParams {
@@ -60,12 +70,6 @@ struct GemmParams {
     int tiles_per_xcd;  // ceil(tiles / 8)
 };
 
-__device__ __forceinline__ __amdgpu_buffer_rsrc_t gemm_rsrc(const void *p, uint32_t bytes)
-{
-    return __builtin_amdgcn_make_buffer_rsrc(const_cast<void *>(p), 0, static_cast<int>(bytes), 0x00020000);
-}
-static constexpr uint32_t kOob = 0xFFFFFFF0u;
-
 // Byte offset inside a stage's A (or B) area of the 16-byte piece c of row r.
 // Two consecutive rows form one 256-byte line that spans all 64 LDS banks; the
 // piece index is xor-ed with the low bits of the line number. Sixteen lanes that
@@ -77,183 +81,8 @@ __device__ __forceinline__ uint32_t lds_piece(int r, int c)
     return (r >> 1) * 256 + ((((r & 1) << 3) | (c ^ ((r >> 1) & 7))) << 4);
 }
 
-__device__ __forceinline__ uint32_t pack_bf16x2(float lo, float hi)
-{
-    bf16x2 v;
-    v.x = static_cast<__bf16>(lo);
-    v.y = static_cast<__bf16>(hi);
-    return __builtin_bit_cast(uint32_t, v);
-}
-
-__global__ __launch_bounds__(kGemmThreads) void gemm_bf16_nk_kernel(const GemmParams prm)
-{
-    extern __shared__ __attribute__((aligned(16))) char lds[];
-
-    const int tid = threadIdx.x;
-    const int lane = tid & 63;
-    const int wave = tid >> 6;
-    const int wave_m = wave >> 1;  // 0..3 : 64-row band of the tile
-    const int wave_n = wave & 1;   // 0..1 : 64-column band
-    const int l31 = lane & 31;
-    const int lhi = lane >> 5;
-
-    // global -> LDS duty of this thread: piece ld_c of rows ld_r + 64 * i
-    const int ld_r = tid >> 3;  // 0..63
-    const int ld_c = tid & 7;
-    const long long row_bytes = prm.K * 2;  // of A and of B (stored [N x K])
-    const int k_tiles = static_cast<int>((prm.K + BK - 1) / BK);
-    const int total_tiles = prm.tiles_m * prm.tiles_n;
-
-    for (int w = blockIdx.x; w < prm.tiles_per_xcd * kXcds; w += gridDim.x) {
-        const int slot = w / kXcds;
-        const int lin = (w % kXcds) * prm.tiles_per_xcd + slot;
-        if (lin >= total_tiles) continue;  // uniform over the workgroup
-        const int per_group = prm.group_m * prm.tiles_n;
-        const int grp = lin / per_group;
-        const int first_tm = grp * prm.group_m;
-        const int gsz = min(prm.group_m, prm.tiles_m - first_tm);
-        const int in_grp = lin - grp * per_group;
-        const int tm = first_tm + in_grp % gsz;
-        const int tn = in_grp / gsz;
-
-        const long long m0 = static_cast<long long>(tm) * BM;
-        const long long n0 = static_cast<long long>(tn) * BN;
-        const int rows_a = static_cast<int>(min(static_cast<long long>(BM), prm.M - m0));
-        const int rows_b = static_cast<int>(min(static_cast<long long>(BN), prm.N - n0));
-        const __amdgpu_buffer_rsrc_t ra = gemm_rsrc(prm.A + m0 * row_bytes, static_cast<uint32_t>(rows_a * row_bytes));
-        const __amdgpu_buffer_rsrc_t rb = gemm_rsrc(prm.B + n0 * row_bytes, static_cast<uint32_t>(rows_b * row_bytes));
-
-        f32x16 acc[2][2];  // [n block][m block]
-#pragma unroll
-        for (int i = 0; i < 2; ++i)
-#pragma unroll
-            for (int j = 0; j < 2; ++j)
-#pragma unroll
-                for (int e = 0; e < 16; ++e) acc[i][j][e] = 0.0f;
-
-        // Two register sets stage the global loads: while K step t is multiplied
-        // out of LDS, step t+1 is on its way in one set (issued one step earlier)
-        // and step t+2 is issued into the other, so a load has almost two K steps
-        // to arrive before it is written to LDS.
-        u32x4 ga[2][4], gb[2][2];
-        auto fetch = [&](int kt, u32x4 (&a)[4], u32x4 (&b)[2]) {
-            const long long k = static_cast<long long>(kt) * BK + ld_c * 8;
-            const bool kin = k < prm.K;
-            const uint32_t kb = static_cast<uint32_t>(k * 2);
-#pragma unroll
-            for (int i = 0; i < 4; ++i) {
-                const uint32_t off = static_cast<uint32_t>((ld_r + 64 * i) * row_bytes) + kb;
-                a[i] = __builtin_amdgcn_raw_buffer_load_b128(ra, kin ? off : kOob, 0, 0);
-            }
-#pragma unroll
-            for (int i = 0; i < 2; ++i) {
-                const uint32_t off = static_cast<uint32_t>((ld_r + 64 * i) * row_bytes) + kb;
-                b[i] = __builtin_amdgcn_raw_buffer_load_b128(rb, kin ? off : kOob, 0, 0);
-            }
-        };
-        auto stash = [&](int stage, const u32x4 (&a)[4], const u32x4 (&b)[2]) {
-            char *sa = lds + stage * kStageBytes;
-            char *sb = sa + kStageABytes;
-#pragma unroll
-            for (int i = 0; i < 4; ++i) *reinterpret_cast<u32x4 *>(sa + lds_piece(ld_r + 64 * i, ld_c)) = a[i];
-#pragma unroll
-            for (int i = 0; i < 2; ++i) *reinterpret_cast<u32x4 *>(sb + lds_piece(ld_r + 64 * i, ld_c)) = b[i];
-        };
-        // One K step out of LDS. The operand fragments of sub-step kk + 1 are
-        // requested before the MFMAs of sub-step kk are issued, so LDS latency is
-        // covered by matrix-core time; the copy of the next K step into the other
-        // LDS stage is slipped in after the second sub-step.
-        struct Frags {
-            bf16x8 a[2], b[2];
-        };
-        auto load_frags = [&](Frags &f, const char *sa, const char *sb, int kk) {
-#pragma unroll
-            for (int i = 0; i < 2; ++i) {
-                f.a[i] = *reinterpret_cast<const bf16x8 *>(sa + lds_piece(wave_m * 64 + i * 32 + l31, kk * 2 + lhi));
-                f.b[i] = *reinterpret_cast<const bf16x8 *>(sb + lds_piece(wave_n * 64 + i * 32 + l31, kk * 2 + lhi));
-            }
-        };
-        auto mfma_step = [&](const Frags &f) {
-#pragma unroll
-            for (int nb = 0; nb < 2; ++nb)
-#pragma unroll
-                for (int mb = 0; mb < 2; ++mb)
-                    acc[nb][mb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(f.b[nb], f.a[mb], acc[nb][mb], 0, 0, 0);
-        };
-        auto multiply_and_stash = [&](int stage, const u32x4 (&na)[4], const u32x4 (&nb_)[2]) {
-            const char *sa = lds + stage * kStageBytes;
-            const char *sb = sa + kStageABytes;
-            Frags f[2];
-            load_frags(f[0], sa, sb, 0);
-#pragma unroll
-            for (int kk = 0; kk < BK / 16; ++kk) {
-                if (kk + 1 < BK / 16) load_frags(f[(kk + 1) & 1], sa, sb, kk + 1);
-                __builtin_amdgcn_sched_barrier(0);
-                mfma_step(f[kk & 1]);
-                __builtin_amdgcn_sched_barrier(0);
-                if (kk == 1) stash(stage ^ 1, na, nb_);
-            }
-        };
-
-        // The previous tile's last reads of LDS must be over before it is refilled.
-        __syncthreads();
-        fetch(0, ga[0], gb[0]);
-        fetch(1, ga[1], gb[1]);
-        stash(0, ga[0], gb[0]);
-        __syncthreads();
-
-        // K step t is multiplied from LDS stage t & 1; register set (t + 1) & 1
-        // holds step t + 1, set t & 1 is free for step t + 2. Nothing in the body
-        // is conditional: K steps past the end fetch out of range, i.e. zeros, and
-        // an odd number of steps is rounded up with one all-zero step.
-        for (int kt = 0; kt < k_tiles; kt += 2) {
-#pragma unroll
-            for (int h = 0; h < 2; ++h) {
-                fetch(kt + h + 2, ga[h], gb[h]);
-                __builtin_amdgcn_sched_barrier(0);  // keep the loads at the top of the step
-                multiply_and_stash(h, ga[h ^ 1], gb[h ^ 1]);
-                __syncthreads();
-            }
-        }
-
-        // Store: lane owns row m = l31 of each block and 4 consecutive n per
-        // register quad: n = 8 * quad + 4 * lhi + (0..3) inside the 32-wide block.
-        const long long c_row_bytes = prm.N * 2;
-        const __amdgpu_buffer_rsrc_t rc = gemm_rsrc(prm.C + m0 * c_row_bytes, static_cast<uint32_t>(rows_a * c_row_bytes));
-#pragma unroll
-        for (int mb = 0; mb < 2; ++mb) {
-            const int m = wave_m * 64 + mb * 32 + l31;
-#pragma unroll
-            for (int nb = 0; nb < 2; ++nb) {
-#pragma unroll
-                for (int q = 0; q < 4; ++q) {
-                    const long long n = n0 + wave_n * 64 + nb * 32 + q * 8 + lhi * 4;
-                    u32x2 v;
-                    v.x = pack_bf16x2(acc[nb][mb][q * 4 + 0], acc[nb][mb][q * 4 + 1]);
-                    v.y = pack_bf16x2(acc[nb][mb][q * 4 + 2], acc[nb][mb][q * 4 + 3]);
-                    const uint32_t off = static_cast<uint32_t>(m * c_row_bytes + n * 2);
-                    __builtin_amdgcn_raw_buffer_store_b64(v, rc, n < prm.N ? off : kOob, 0, 0);
-                }
-            }
-        }
-    }
-}
-
-// ---------------------------------------------------------------------------
-// Variant with direct global -> LDS loads (gfx950's 16-byte buffer_load ... lds):
-// no register staging and no ds_write, three LDS stages so that a load has two
-// full K steps to land. The loads write 64 consecutive 16-byte LDS slots per
-// wave instruction, so the xor swizzle is applied on the global side: the lane
-// that fills slot s of line l fetches piece (s & 7) ^ (l & 7) of row 2l + (s >> 3).
-//
-// The compiler cannot tell which LDS stage an asynchronous load targets and
-// would wait for ALL outstanding loads before any LDS read it can see; operand
-// fragments are therefore read with inline ds_read_b128 and the waits (vmcnt for
-// landed stages, lgkmcnt for fragments) are placed by hand. Dynamic LDS is the
-// kernel's only LDS object, so its byte offsets are LDS addresses.
-// ---------------------------------------------------------------------------
-static constexpr int kDmaStages = 3;
-static constexpr int kGemmDmaLdsBytes = kDmaStages * kStageBytes;  // 144 KiB
+static constexpr int kStages = 3;
+static constexpr int kGemmLdsBytes = kStages * kStageBytes;  // 144 KiB
 
 typedef __attribute__((address_space(3))) void *lds_ptr_t;
 
@@ -296,7 +125,7 @@ struct DmaFrags {
                    "+v"((f).blo[1]), "+v"((f).bhi[1])::"memory")
 
 template <bool B_KN>
-__global__ __launch_bounds__(kGemmThreads) void gemm_bf16_dma_kernel(const GemmParams prm)
+__global__ __launch_bounds__(kGemmThreads) void gemm_bf16_kernel(const GemmParams prm)
 {
     extern __shared__ __attribute__((aligned(16))) char lds[];
 
@@ -367,8 +196,8 @@ __global__ __launch_bounds__(kGemmThreads) void gemm_bf16_dma_kernel(const GemmP
         const long long n0 = static_cast<long long>(tn) * BN;
         const int rows_a = static_cast<int>(min(static_cast<long long>(BM), prm.M - m0));
         const int rows_b = static_cast<int>(min(static_cast<long long>(BN), prm.N - n0));
-        const __amdgpu_buffer_rsrc_t ra = gemm_rsrc(prm.A + m0 * row_bytes, static_cast<uint32_t>(rows_a * row_bytes));
-        const __amdgpu_buffer_rsrc_t rb = gemm_rsrc(prm.B + n0 * row_bytes, static_cast<uint32_t>(rows_b * row_bytes));
+        const __amdgpu_buffer_rsrc_t ra = make_rsrc(prm.A + m0 * row_bytes, static_cast<uint32_t>(rows_a * row_bytes));
+        const __amdgpu_buffer_rsrc_t rb = make_rsrc(prm.B + n0 * row_bytes, static_cast<uint32_t>(rows_b * row_bytes));
 
         f32x16 acc[2][2];
 #pragma unroll
@@ -388,14 +217,14 @@ __global__ __launch_bounds__(kGemmThreads) void gemm_bf16_dma_kernel(const GemmP
             for (int i = 0; i < 4; ++i) {
                 const uint32_t off = static_cast<uint32_t>((row_lo + 64 * i) * row_bytes) + kb;
                 __builtin_amdgcn_raw_ptr_buffer_load_lds(ra, (lds_ptr_t)(sa + (i * 8 + wave) * 1024), 16,
-                                                         kin ? off : kOob, 0, 0, 0);
+                                                         kin ? off : kOutOfRange, 0, 0, 0);
             }
             if constexpr (!B_KN) {
 #pragma unroll
                 for (int i = 0; i < 2; ++i) {
                     const uint32_t off = static_cast<uint32_t>((row_lo + 64 * i) * row_bytes) + kb;
                     __builtin_amdgcn_raw_ptr_buffer_load_lds(rb, (lds_ptr_t)(sa + kStageABytes + (i * 8 + wave) * 1024),
-                                                             16, kin ? off : kOob, 0, 0, 0);
+                                                             16, kin ? off : kOutOfRange, 0, 0, 0);
                 }
             } else {
                 // rows k0 .. k0+63 of B through a descriptor of their own: rows past K
@@ -403,14 +232,14 @@ __global__ __launch_bounds__(kGemmThreads) void gemm_bf16_dma_kernel(const GemmP
                 const long long k0 = static_cast<long long>(kt) * BK;
                 const long long k_left = prm.K - k0;
                 const int rows_k = static_cast<int>(k_left < 0 ? 0 : (k_left > BK ? BK : k_left));
-                const __amdgpu_buffer_rsrc_t rk = gemm_rsrc(prm.B + (k_left > 0 ? k0 : 0) * bkn_row_bytes,
+                const __amdgpu_buffer_rsrc_t rk = make_rsrc(prm.B + (k_left > 0 ? k0 : 0) * bkn_row_bytes,
                                                             static_cast<uint32_t>(rows_k * bkn_row_bytes));
                 const long long n = n0 + bkn_piece * 8;
 #pragma unroll
                 for (int i = 0; i < 2; ++i) {
                     const uint32_t off = static_cast<uint32_t>((bkn_row_lo + 32 * i) * bkn_row_bytes + n * 2);
                     __builtin_amdgcn_raw_ptr_buffer_load_lds(rk, (lds_ptr_t)(sa + kStageABytes + (i * 8 + wave) * 1024),
-                                                             16, n < prm.N ? off : kOob, 0, 0, 0);
+                                                             16, n < prm.N ? off : kOutOfRange, 0, 0, 0);
                 }
             }
         };
@@ -471,7 +300,7 @@ __global__ __launch_bounds__(kGemmThreads) void gemm_bf16_dma_kernel(const GemmP
             __builtin_amdgcn_s_waitcnt(0x0F76);  // vmcnt(6)
             __builtin_amdgcn_s_barrier();
             int next_stage = stage + 2;
-            next_stage = next_stage >= kDmaStages ? next_stage - kDmaStages : next_stage;
+            next_stage = next_stage >= kStages ? next_stage - kStages : next_stage;
             fetch(kt + 2, next_stage);
             __builtin_amdgcn_sched_barrier(0);
 
@@ -493,13 +322,13 @@ __global__ __launch_bounds__(kGemmThreads) void gemm_bf16_dma_kernel(const GemmP
             wait_all(f1);
             mfma_step(f1);
             __builtin_amdgcn_sched_barrier(0);
-            stage = stage + 1 >= kDmaStages ? 0 : stage + 1;
+            stage = stage + 1 >= kStages ? 0 : stage + 1;
         }
         // the two prefetches past the end are still in flight and target LDS
         __builtin_amdgcn_s_waitcnt(0x0F70);  // vmcnt(0)
 
         const long long c_row_bytes = prm.N * 2;
-        const __amdgpu_buffer_rsrc_t rc = gemm_rsrc(prm.C + m0 * c_row_bytes, static_cast<uint32_t>(rows_a * c_row_bytes));
+        const __amdgpu_buffer_rsrc_t rc = make_rsrc(prm.C + m0 * c_row_bytes, static_cast<uint32_t>(rows_a * c_row_bytes));
 #pragma unroll
         for (int mb = 0; mb < 2; ++mb) {
             const int m = wave_m * 64 + mb * 32 + l31;
@@ -512,7 +341,7 @@ __global__ __launch_bounds__(kGemmThreads) void gemm_bf16_dma_kernel(const GemmP
                     v.x = pack_bf16x2(acc[nb][mb][q * 4 + 0], acc[nb][mb][q * 4 + 1]);
                     v.y = pack_bf16x2(acc[nb][mb][q * 4 + 2], acc[nb][mb][q * 4 + 3]);
                     const uint32_t off = static_cast<uint32_t>(m * c_row_bytes + n * 2);
-                    __builtin_amdgcn_raw_buffer_store_b64(v, rc, n < prm.N ? off : kOob, 0, 0);
+                    __builtin_amdgcn_raw_buffer_store_b64(v, rc, n < prm.N ? off : kOutOfRange, 0, 0);
                 }
             }
         }
@@ -522,9 +351,6 @@ __global__ __launch_bounds__(kGemmThreads) void gemm_bf16_dma_kernel(const GemmP
 // ---------------------------------------------------------------------------
 // host side
 // ---------------------------------------------------------------------------
-
-// 0: register-staged kernel, 1: direct-to-LDS kernel
-static std::atomic<int> g_gemm_variant{1};
 
 tw_status validate_gemm(const tw_gemm_args &g)
 {
@@ -582,16 +408,14 @@ tw_status launch_gemm(const tw_gemm_args &g, hipStream_t stream)
     const int64_t slots = int64_t(prm.tiles_per_xcd) * kXcds;
     const unsigned grid = static_cast<unsigned>(slots < budget ? slots : budget);
 
-    static std::atomic<int> allowed[3][kMaxDevices];
-    TW_TRY(allow_dynamic_lds(reinterpret_cast<const void *>(gemm_bf16_nk_kernel), kGemmLdsBytes, allowed[0]));
-    TW_TRY(allow_dynamic_lds(reinterpret_cast<const void *>(gemm_bf16_dma_kernel<false>), kGemmDmaLdsBytes, allowed[1]));
-    TW_TRY(allow_dynamic_lds(reinterpret_cast<const void *>(gemm_bf16_dma_kernel<true>), kGemmDmaLdsBytes, allowed[2]));
-    if (g.b_layout == TW_B_KN)
-        TW_HIP(launch_kernel(gemm_bf16_dma_kernel<true>, dim3(grid), dim3(kGemmThreads), kGemmDmaLdsBytes, stream, prm));
-    else if (g_gemm_variant.load(std::memory_order_relaxed) == 1)
-        TW_HIP(launch_kernel(gemm_bf16_dma_kernel<false>, dim3(grid), dim3(kGemmThreads), kGemmDmaLdsBytes, stream, prm));
-    else
-        TW_HIP(launch_kernel(gemm_bf16_nk_kernel, dim3(grid), dim3(kGemmThreads), kGemmLdsBytes, stream, prm));
+    static std::atomic<int> allowed[2][kMaxDevices];
+    if (g.b_layout == TW_B_KN) {
+        TW_TRY(allow_dynamic_lds(reinterpret_cast<const void *>(gemm_bf16_kernel<true>), kGemmLdsBytes, allowed[1]));
+        TW_HIP(launch_kernel(gemm_bf16_kernel<true>, dim3(grid), dim3(kGemmThreads), kGemmLdsBytes, stream, prm));
+    } else {
+        TW_TRY(allow_dynamic_lds(reinterpret_cast<const void *>(gemm_bf16_kernel<false>), kGemmLdsBytes, allowed[0]));
+        TW_HIP(launch_kernel(gemm_bf16_kernel<false>, dim3(grid), dim3(kGemmThreads), kGemmLdsBytes, stream, prm));
+    }
     return TW_OK;
 }
 
@@ -606,6 +430,3 @@ extern "C" tw_status tw_gemm_bf16(const void *A, const void *B, void *C, int64_t
     TW_TRY(validate_gemm(g));
     return launch_gemm(g, static_cast<hipStream_t>(stream));
 }
-
-// Lab switch between the two GEMM kernels (not declared in the public header).
-extern "C" void tw_internal_set_gemm_variant(int v) { tw::g_gemm_variant.store(v); }
