@@ -43,6 +43,7 @@
 //     transposing LDS read ds_read_b64_tr_b16.
 #include <atomic>
 #include <type_traits>
+#include <utility>
 
 #include "tw_device.h"
 #include "tw_internal.h"
@@ -50,7 +51,6 @@
 namespace tw {
 
 static constexpr int BM = kGemmTileM, BN = kGemmTileN, BK = 64;
-static constexpr int kGemmThreads = 512;
 static constexpr int kStageABytes = BM * BK * 2;  // 32 KiB
 static constexpr int kStageBBytes = BN * BK * 2;  // 16 KiB
 static constexpr int kStageBytes = kStageABytes + kStageBBytes;
@@ -85,11 +85,13 @@ static constexpr int kStages = 3;
 static constexpr int kGemmLdsBytes = kStages * kStageBytes;  // 144 KiB
 
 typedef __attribute__((address_space(3))) void *lds_ptr_t;
+typedef __attribute__((address_space(3))) char *lds_char_ptr_t;
 
+template <int OFF>
 __device__ __forceinline__ bf16x8 lds_read16(uint32_t addr)
 {
     bf16x8 v;
-    asm volatile("ds_read_b128 %0, %1" : "=v"(v) : "v"(addr) : "memory");
+    asm volatile("ds_read_b128 %0, %1 offset:%2" : "=v"(v) : "v"(addr), "n"(OFF) : "memory");
     return v;
 }
 // gfx950's transposing LDS read. Within each group of 16 lanes, lane 4a+b
@@ -106,32 +108,66 @@ __device__ __forceinline__ u32x2 lds_read_tr8(uint32_t addr)
     return v;
 }
 
-// Operand fragments of one K sub-step. With B stored [K x N] a B fragment
-// arrives as two register pairs (k 0..3 and k 4..7 of the lane's column).
-template <bool B_KN>
-struct DmaFrags {
-    bf16x8 a[2];
+// Operand fragments of one K sub-step for a wave that owns WM x 2 blocks of
+// 32 x 32. With B stored [K x N] a B fragment arrives as two register pairs
+// (k 0..3 and k 4..7 of the lane's column).
+template <bool B_KN, int WM>
+struct Frags {
+    bf16x8 a[WM];
     bf16x8 b[2];
     u32x2 blo[2], bhi[2];
 };
 // Wait until at most N of this wave's LDS reads are outstanding. The fragments
 // are passed through so that no use of them can be moved above the wait.
-#define TW_WAIT_LGKM_NK(N, f)                                                                \
-    asm volatile("s_waitcnt lgkmcnt(" #N ")"                                                 \
-                 : "+v"((f).a[0]), "+v"((f).a[1]), "+v"((f).b[0]), "+v"((f).b[1])::"memory")
-#define TW_WAIT_LGKM_KN(N, f)                                                                \
-    asm volatile("s_waitcnt lgkmcnt(" #N ")"                                                 \
-                 : "+v"((f).a[0]), "+v"((f).a[1]), "+v"((f).blo[0]), "+v"((f).bhi[0]),       \
-                   "+v"((f).blo[1]), "+v"((f).bhi[1])::"memory")
+#define TW_FRAG_A2(f) "+v"((f).a[0]), "+v"((f).a[1])
+#define TW_FRAG_A4(f) TW_FRAG_A2(f), "+v"((f).a[2]), "+v"((f).a[3])
+#define TW_FRAG_B_NK(f) "+v"((f).b[0]), "+v"((f).b[1])
+#define TW_FRAG_B_KN(f) "+v"((f).blo[0]), "+v"((f).bhi[0]), "+v"((f).blo[1]), "+v"((f).bhi[1])
+#define TW_WAIT_LGKM(N, A_OPS, B_OPS) \
+    asm volatile("s_waitcnt lgkmcnt(%[cnt])" : A_OPS, B_OPS : [cnt] "n"(N) : "memory")
 
-template <bool B_KN>
-__global__ __launch_bounds__(kGemmThreads) void gemm_bf16_kernel(const GemmParams prm)
+// f(integral_constant<int, 0>) ... f(integral_constant<int, N - 1>), unrolled
+template <int... I, typename Fn>
+__device__ __forceinline__ void static_for_impl(std::integer_sequence<int, I...>, Fn &&f)
 {
+    (f(std::integral_constant<int, I>{}), ...);
+}
+template <int N, typename Fn>
+__device__ __forceinline__ void static_for(Fn &&f)
+{
+    static_for_impl(std::make_integer_sequence<int, N>{}, f);
+}
+
+template <int N, bool B_KN, int WM>
+__device__ __forceinline__ void wait_lgkm(Frags<B_KN, WM> &f)
+{
+    if constexpr (WM == 2 && !B_KN) TW_WAIT_LGKM(N, TW_FRAG_A2(f), TW_FRAG_B_NK(f));
+    if constexpr (WM == 2 && B_KN) TW_WAIT_LGKM(N, TW_FRAG_A2(f), TW_FRAG_B_KN(f));
+    if constexpr (WM == 4 && !B_KN) TW_WAIT_LGKM(N, TW_FRAG_A4(f), TW_FRAG_B_NK(f));
+    if constexpr (WM == 4 && B_KN) TW_WAIT_LGKM(N, TW_FRAG_A4(f), TW_FRAG_B_KN(f));
+}
+
+// WM = 32-row blocks per wave: 2 -> eight waves laid out 4 x 2, each 64 x 64;
+// 4 -> four waves laid out 2 x 2, each 128 x 64 (one wave per SIMD, fewer LDS
+// bytes read per MFMA).
+template <bool B_KN, int WM>
+__global__ __launch_bounds__(64 * (16 / WM)) void gemm_bf16_kernel(const GemmParams prm)
+{
+    // The body is for the device pass only: the host pass needs the launch stub,
+    // and silently drops it when it cannot make sense of the target-specific
+    // builtins and inline assembly below.
+#if defined(__HIP_DEVICE_COMPILE__)
     extern __shared__ __attribute__((aligned(16))) char lds[];
+    constexpr int NW = 16 / WM;          // waves per workgroup
+    constexpr int A_LOADS = 32 / NW;     // wave instructions (1 KiB each) per wave that fill a stage's A area
+    constexpr int B_LOADS = 16 / NW;     // ... and its B area
+    constexpr int kLoads = A_LOADS + B_LOADS;      // loads of one K step per lane
+    static_assert(kLoads == 6 || kLoads == 12, "wait encodings below");
+    constexpr int kFragReads = WM + (B_KN ? 4 : 2);  // LDS reads of one sub-step
 
     const int tid = threadIdx.x;
     const int lane = tid & 63;
-    const int wave = tid >> 6;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);  // uniform: keeps LDS targets in scalar registers
     const int wave_m = wave >> 1;
     const int wave_n = wave & 1;
     const int l31 = lane & 31;
@@ -143,29 +179,29 @@ __global__ __launch_bounds__(kGemmThreads) void gemm_bf16_kernel(const GemmParam
     const int total_tiles = prm.tiles_m * prm.tiles_n;
 
     // global -> LDS duty: wave instruction i of this wave fills slots
-    // [(i * 8 + wave) * 64, +64); this lane's slot inside a line and the row and
+    // [(i * NW + wave) * 64, +64); this lane's slot inside a line and the row and
     // piece that belong there (the same for every instruction up to a row offset)
     const int line_in_instr = lane >> 4;            // 0..3
     const int slot = lane & 15;
-    // line = (i * 8 + wave) * 4 + line_in_instr; (line & 7) = ((wave & 1) * 4 + line_in_instr)
+    // line = (i * NW + wave) * 4 + line_in_instr; (line & 7) = ((wave & 1) * 4 + line_in_instr)
     const int piece = (slot & 7) ^ (((wave & 1) << 2) | line_in_instr);
-    const int row_lo = 2 * (wave * 4 + line_in_instr) + (slot >> 3);  // + 64 * i
+    const int row_lo = 2 * (wave * 4 + line_in_instr) + (slot >> 3);  // + 8 * NW * i
     // B stored [K x N]: its LDS area holds 64 k-rows of 256 bytes (128 n); a wave
     // instruction fills four rows; row r keeps 16-byte piece s at slot
     // s ^ ((r & 3) << 1), so that the four rows one transposing read touches
     // fall into different banks.
-    const int bkn_row_lo = wave * 4 + line_in_instr;                  // + 32 * i
+    const int bkn_row_lo = wave * 4 + line_in_instr;                  // + 4 * NW * i
     const int bkn_piece = slot ^ (line_in_instr << 1);
 
-    // fragment read addresses inside a stage (A area at 0, B area after it)
-    uint32_t fa_addr[4][2], fb_addr[4][2], fbkn_addr[2];
+    // fragment read addresses inside a stage (A area at 0, B area after it) for
+    // the wave's first 32-row block; block i lies 32 rows = 4096 bytes further
+    // (the swizzle repeats every 16 rows), which goes into the read's offset field
+    uint32_t fa_addr[4], fb_addr[4], fbkn_addr[2];
 #pragma unroll
-    for (int kk = 0; kk < 4; ++kk)
-#pragma unroll
-        for (int i = 0; i < 2; ++i) {
-            fa_addr[kk][i] = lds_piece(wave_m * 64 + i * 32 + l31, kk * 2 + lhi);
-            fb_addr[kk][i] = kStageABytes + lds_piece(wave_n * 64 + i * 32 + l31, kk * 2 + lhi);
-        }
+    for (int kk = 0; kk < 4; ++kk) {
+        fa_addr[kk] = lds_piece(wave_m * (32 * WM) + l31, kk * 2 + lhi);
+        fb_addr[kk] = kStageABytes + lds_piece(wave_n * 64 + l31, kk * 2 + lhi);
+    }
     {
         // lane = 16 g + s: group g covers columns (g & 1) * 16 .. +15 of the 32-wide
         // block and k group g >> 1; s = a + 4 j points at row j, columns 4a..4a+3
@@ -178,7 +214,7 @@ __global__ __launch_bounds__(kGemmThreads) void gemm_bf16_kernel(const GemmParam
         }
     }
 
-    using Frags = DmaFrags<B_KN>;
+    using F = Frags<B_KN, WM>;
 
     for (int w = blockIdx.x; w < prm.tiles_per_xcd * kXcds; w += gridDim.x) {
         const int slot_w = w / kXcds;
@@ -199,130 +235,167 @@ __global__ __launch_bounds__(kGemmThreads) void gemm_bf16_kernel(const GemmParam
         const __amdgpu_buffer_rsrc_t ra = make_rsrc(prm.A + m0 * row_bytes, static_cast<uint32_t>(rows_a * row_bytes));
         const __amdgpu_buffer_rsrc_t rb = make_rsrc(prm.B + n0 * row_bytes, static_cast<uint32_t>(rows_b * row_bytes));
 
-        f32x16 acc[2][2];
+        f32x16 acc[2][WM];
 #pragma unroll
         for (int i = 0; i < 2; ++i)
 #pragma unroll
-            for (int j = 0; j < 2; ++j)
+            for (int j = 0; j < WM; ++j)
 #pragma unroll
                 for (int e = 0; e < 16; ++e) acc[i][j][e] = 0.0f;
 
-        // six asynchronous 16-byte loads per lane fill one stage with K step kt
-        auto fetch = [&](int kt, int stage) {
+        // A_LOADS + B_LOADS asynchronous 16-byte loads per lane fill one stage with
+        // a K step; load `idx` of them is issued by fetch_one
+        struct FetchCtx {
+            uint32_t kb;       // byte offset of this lane's piece inside a row
+            uint32_t oob;      // 0 if the piece lies inside K, else or-ing it pushes an offset out of range
+            lds_char_ptr_t sa; // the stage in LDS
+            long long bk_off;  // [K x N] only: byte offset of row k0 of B, and how many
+            uint32_t bk_len;   // bytes of B the rows k0 .. k0+63 that exist take
+        };
+        auto fetch_ctx = [&](int kt, int stage) {
+            FetchCtx c;
             const long long k = static_cast<long long>(kt) * BK + piece * 8;
-            const bool kin = k < prm.K;
-            const uint32_t kb = static_cast<uint32_t>(k * 2);
-            char *sa = lds + stage * kStageBytes;
-#pragma unroll
-            for (int i = 0; i < 4; ++i) {
-                const uint32_t off = static_cast<uint32_t>((row_lo + 64 * i) * row_bytes) + kb;
-                __builtin_amdgcn_raw_ptr_buffer_load_lds(ra, (lds_ptr_t)(sa + (i * 8 + wave) * 1024), 16,
-                                                         kin ? off : kOutOfRange, 0, 0, 0);
-            }
-            if constexpr (!B_KN) {
-#pragma unroll
-                for (int i = 0; i < 2; ++i) {
-                    const uint32_t off = static_cast<uint32_t>((row_lo + 64 * i) * row_bytes) + kb;
-                    __builtin_amdgcn_raw_ptr_buffer_load_lds(rb, (lds_ptr_t)(sa + kStageABytes + (i * 8 + wave) * 1024),
-                                                             16, kin ? off : kOutOfRange, 0, 0, 0);
-                }
+            c.oob = k < prm.K ? 0u : kOutOfRange;
+            c.kb = static_cast<uint32_t>(k * 2);
+            c.sa = (lds_char_ptr_t)(lds + stage * kStageBytes);
+            const long long k0 = static_cast<long long>(kt) * BK;
+            const long long k_left = prm.K - k0;
+            const int rows_k = static_cast<int>(k_left < 0 ? 0 : (k_left > BK ? BK : k_left));
+            c.bk_off = (k_left > 0 ? k0 : 0) * bkn_row_bytes;
+            c.bk_len = static_cast<uint32_t>(rows_k * bkn_row_bytes);
+            return c;
+        };
+        // (not a generic lambda: idx is a constant at every call site and folds
+        // after inlining)
+        auto fetch_one = [&](const FetchCtx &c, const int idx) {
+            if (idx < A_LOADS) {
+                const int i = idx;
+                const uint32_t off = static_cast<uint32_t>((row_lo + 8 * NW * i) * row_bytes) + c.kb;
+                __builtin_amdgcn_raw_ptr_buffer_load_lds(ra, (lds_ptr_t)(c.sa + (i * NW + wave) * 1024), 16,
+                                                         off | c.oob, 0, 0, 0);
+            } else if constexpr (!B_KN) {
+                const int i = idx - A_LOADS;
+                const uint32_t off = static_cast<uint32_t>((row_lo + 8 * NW * i) * row_bytes) + c.kb;
+                __builtin_amdgcn_raw_ptr_buffer_load_lds(
+                    rb, (lds_ptr_t)(c.sa + kStageABytes + (i * NW + wave) * 1024), 16,
+                    off | c.oob, 0, 0, 0);
             } else {
                 // rows k0 .. k0+63 of B through a descriptor of their own: rows past K
                 // fall outside it, columns past N are redirected out of range
-                const long long k0 = static_cast<long long>(kt) * BK;
-                const long long k_left = prm.K - k0;
-                const int rows_k = static_cast<int>(k_left < 0 ? 0 : (k_left > BK ? BK : k_left));
-                const __amdgpu_buffer_rsrc_t rk = make_rsrc(prm.B + (k_left > 0 ? k0 : 0) * bkn_row_bytes,
-                                                            static_cast<uint32_t>(rows_k * bkn_row_bytes));
+                const int i = idx - A_LOADS;
+                const __amdgpu_buffer_rsrc_t rbk = make_rsrc(prm.B + c.bk_off, c.bk_len);
                 const long long n = n0 + bkn_piece * 8;
-#pragma unroll
-                for (int i = 0; i < 2; ++i) {
-                    const uint32_t off = static_cast<uint32_t>((bkn_row_lo + 32 * i) * bkn_row_bytes + n * 2);
-                    __builtin_amdgcn_raw_ptr_buffer_load_lds(rk, (lds_ptr_t)(sa + kStageABytes + (i * 8 + wave) * 1024),
-                                                             16, n < prm.N ? off : kOutOfRange, 0, 0, 0);
-                }
+                const uint32_t off = static_cast<uint32_t>((bkn_row_lo + 4 * NW * i) * bkn_row_bytes + n * 2);
+                __builtin_amdgcn_raw_ptr_buffer_load_lds(
+                    rbk, (lds_ptr_t)(c.sa + kStageABytes + (i * NW + wave) * 1024), 16,
+                    n < prm.N ? off : kOutOfRange, 0, 0, 0);
             }
         };
-        auto load_frags = [&](Frags &f, uint32_t stage_base, auto kk_tag) {
+        auto fetch = [&](int kt, int stage) {
+            const FetchCtx c = fetch_ctx(kt, stage);
+            static_for<kLoads>([&](auto i) { fetch_one(c, decltype(i)::value); });
+        };
+        // LDS read `j` of the kFragReads that make up the fragments of sub-step kk
+        auto read_one = [&](F &f, uint32_t stage_base, auto kk_tag, auto j_tag) {
             constexpr int kk = decltype(kk_tag)::value;
-#pragma unroll
-            for (int i = 0; i < 2; ++i) f.a[i] = lds_read16(stage_base + fa_addr[kk][i]);
-            if constexpr (!B_KN) {
-#pragma unroll
-                for (int i = 0; i < 2; ++i) f.b[i] = lds_read16(stage_base + fb_addr[kk][i]);
+            constexpr int j = decltype(j_tag)::value;
+            if constexpr (j < WM) {
+                f.a[j] = lds_read16<4096 * j>(stage_base + fa_addr[kk]);
+            } else if constexpr (!B_KN) {
+                f.b[j - WM] = lds_read16<4096 * (j - WM)>(stage_base + fb_addr[kk]);
             } else {
-#pragma unroll
-                for (int i = 0; i < 2; ++i) {
-                    f.blo[i] = lds_read_tr8<kk * 4096>(stage_base + fbkn_addr[i]);
-                    f.bhi[i] = lds_read_tr8<kk * 4096 + 1024>(stage_base + fbkn_addr[i]);
-                }
+                constexpr int i = (j - WM) >> 1;
+                if constexpr (((j - WM) & 1) == 0) f.blo[i] = lds_read_tr8<kk * 4096>(stage_base + fbkn_addr[i]);
+                else f.bhi[i] = lds_read_tr8<kk * 4096 + 1024>(stage_base + fbkn_addr[i]);
             }
         };
-        auto mfma_step = [&](const Frags &f) {
-#pragma unroll
-            for (int nb = 0; nb < 2; ++nb) {
-                bf16x8 b;
+        auto load_frags = [&](F &f, uint32_t stage_base, auto kk_tag) {
+            static_for<kFragReads>([&](auto j) { read_one(f, stage_base, kk_tag, j); });
+        };
+        // One K sub-step: the 2 * WM MFMAs on `cur`, and between them the LDS
+        // reads of the next sub-step's fragments into `nxt` and LOADS_HERE of
+        // the global loads of K step kt + 2, spread evenly: the memory pipes are
+        // fed while the matrix core works and nothing is issued in a burst.
+        auto sub_step = [&](F &cur, F &nxt, uint32_t nxt_base, auto kk_next, const FetchCtx &fc, auto first_load,
+                            auto n_loads) {
+            constexpr int kFirst = decltype(first_load)::value;
+            constexpr int kHere = decltype(n_loads)::value;
+            constexpr int kSlots = 2 * WM;
+            constexpr int kItems = kFragReads + kHere;
+            static_for<kSlots>([&](auto m_tag) {
+                constexpr int m = decltype(m_tag)::value;
+                constexpr int nb = m / WM, mb = m % WM;
+                bf16x8 bfrag;
                 if constexpr (B_KN) {
-                    const u32x4 t = {f.blo[nb].x, f.blo[nb].y, f.bhi[nb].x, f.bhi[nb].y};
-                    b = __builtin_bit_cast(bf16x8, t);
+                    const u32x4 t = {cur.blo[nb].x, cur.blo[nb].y, cur.bhi[nb].x, cur.bhi[nb].y};
+                    bfrag = __builtin_bit_cast(bf16x8, t);
                 } else {
-                    b = f.b[nb];
+                    bfrag = cur.b[nb];
                 }
-#pragma unroll
-                for (int mb = 0; mb < 2; ++mb)
-                    acc[nb][mb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(b, f.a[mb], acc[nb][mb], 0, 0, 0);
-            }
-        };
-        // wait until only the LDS reads of the NEXT sub-step (4, or 6 with the
-        // transposing reads) may still be outstanding / until none is
-        auto wait_prev = [&](Frags &f) {
-            if constexpr (B_KN) TW_WAIT_LGKM_KN(6, f); else TW_WAIT_LGKM_NK(4, f);
-        };
-        auto wait_all = [&](Frags &f) {
-            if constexpr (B_KN) TW_WAIT_LGKM_KN(0, f); else TW_WAIT_LGKM_NK(0, f);
+                acc[nb][mb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(bfrag, cur.a[mb], acc[nb][mb], 0, 0, 0);
+                __builtin_amdgcn_sched_barrier(0);
+                // items [m * kItems / kSlots, (m + 1) * kItems / kSlots) follow MFMA m
+                static_for<kItems>([&](auto t_tag) {
+                    constexpr int t = decltype(t_tag)::value;
+                    if constexpr (t >= m * kItems / kSlots && t < (m + 1) * kItems / kSlots) {
+                        if constexpr (t < kFragReads) read_one(nxt, nxt_base, kk_next, t_tag);
+                        else fetch_one(fc, kFirst + t - kFragReads);
+                    }
+                });
+                __builtin_amdgcn_sched_barrier(0);
+            });
         };
         using K0 = std::integral_constant<int, 0>;
         using K1 = std::integral_constant<int, 1>;
         using K2 = std::integral_constant<int, 2>;
         using K3 = std::integral_constant<int, 3>;
+        constexpr int kPerSub = kLoads / 3;  // the loads of a K step go out during its first three sub-steps
+        using L0 = std::integral_constant<int, 0>;
+        using L1 = std::integral_constant<int, kPerSub>;
+        using L2 = std::integral_constant<int, 2 * kPerSub>;
+        using LN = std::integral_constant<int, kPerSub>;
+        using LZ = std::integral_constant<int, 0>;
 
         // All waves are done with the previous tile's LDS reads before it is refilled.
         __builtin_amdgcn_s_waitcnt(0xC07F);  // lgkmcnt(0)
         __builtin_amdgcn_s_barrier();
         fetch(0, 0);
         fetch(1, 1);
+        // A K step has landed once at most the loads of the following one are
+        // outstanding (loads past the end are issued too, out of range, so the
+        // count is the same in every trip); the barrier extends that to the
+        // loads of the other waves.
+        auto wait_landed = [&]() {
+            if constexpr (kLoads == 6) __builtin_amdgcn_s_waitcnt(0x0F76);  // vmcnt(6)
+            else __builtin_amdgcn_s_waitcnt(0x0F7C);                        // vmcnt(12)
+            __builtin_amdgcn_s_barrier();
+        };
+        wait_landed();
 
+        F f0, f1;
+        load_frags(f0, 0, K0{});
         int stage = 0;
         for (int kt = 0; kt < k_tiles; ++kt) {
-            // K step kt has landed once at most the six loads of step kt + 1 are
-            // outstanding (loads past the end are issued too, out of range, so
-            // the count is the same in every trip)
-            __builtin_amdgcn_s_waitcnt(0x0F76);  // vmcnt(6)
-            __builtin_amdgcn_s_barrier();
-            int next_stage = stage + 2;
-            next_stage = next_stage >= kStages ? next_stage - kStages : next_stage;
-            fetch(kt + 2, next_stage);
-            __builtin_amdgcn_sched_barrier(0);
-
             const uint32_t base = static_cast<uint32_t>(stage * kStageBytes);
-            Frags f0, f1;
-            load_frags(f0, base, K0{});
-            load_frags(f1, base, K1{});
-            wait_prev(f0);
-            mfma_step(f0);
-            __builtin_amdgcn_sched_barrier(0);
-            load_frags(f0, base, K2{});
-            wait_prev(f1);
-            mfma_step(f1);
-            __builtin_amdgcn_sched_barrier(0);
-            load_frags(f1, base, K3{});
-            wait_prev(f0);
-            mfma_step(f0);
-            __builtin_amdgcn_sched_barrier(0);
-            wait_all(f1);
-            mfma_step(f1);
-            __builtin_amdgcn_sched_barrier(0);
-            stage = stage + 1 >= kStages ? 0 : stage + 1;
+            int fetch_stage = stage + 2;
+            fetch_stage = fetch_stage >= kStages ? fetch_stage - kStages : fetch_stage;
+            const int next_stage = stage + 1 >= kStages ? 0 : stage + 1;
+            const FetchCtx fc = fetch_ctx(kt + 2, fetch_stage);
+
+            wait_lgkm<0>(f0);
+            sub_step(f0, f1, base, K1{}, fc, L0{}, LN{});
+            wait_lgkm<0>(f1);
+            sub_step(f1, f0, base, K2{}, fc, L1{}, LN{});
+            wait_lgkm<0>(f0);
+            sub_step(f0, f1, base, K3{}, fc, L2{}, LN{});
+            // the last fragments of this stage have arrived: this wave is done
+            // reading it. Has K step kt + 1 landed (for every wave)? After the
+            // barrier every wave is also done reading this stage, so the loads the
+            // next trip issues may overwrite the stage before it.
+            wait_lgkm<0>(f1);
+            wait_landed();
+            sub_step(f1, f0, static_cast<uint32_t>(next_stage * kStageBytes), K0{}, fc, LZ{}, LZ{});
+            stage = next_stage;
         }
         // the two prefetches past the end are still in flight and target LDS
         __builtin_amdgcn_s_waitcnt(0x0F70);  // vmcnt(0)
@@ -330,8 +403,8 @@ __global__ __launch_bounds__(kGemmThreads) void gemm_bf16_kernel(const GemmParam
         const long long c_row_bytes = prm.N * 2;
         const __amdgpu_buffer_rsrc_t rc = make_rsrc(prm.C + m0 * c_row_bytes, static_cast<uint32_t>(rows_a * c_row_bytes));
 #pragma unroll
-        for (int mb = 0; mb < 2; ++mb) {
-            const int m = wave_m * 64 + mb * 32 + l31;
+        for (int mb = 0; mb < WM; ++mb) {
+            const int m = wave_m * (32 * WM) + mb * 32 + l31;
 #pragma unroll
             for (int nb = 0; nb < 2; ++nb) {
 #pragma unroll
@@ -346,6 +419,9 @@ __global__ __launch_bounds__(kGemmThreads) void gemm_bf16_kernel(const GemmParam
             }
         }
     }
+#else
+    (void)prm;
+#endif
 }
 
 // ---------------------------------------------------------------------------
@@ -408,13 +484,21 @@ tw_status launch_gemm(const tw_gemm_args &g, hipStream_t stream)
     const int64_t slots = int64_t(prm.tiles_per_xcd) * kXcds;
     const unsigned grid = static_cast<unsigned>(slots < budget ? slots : budget);
 
+    // Eight waves of 64 x 64 (WM = 2). Four waves of 128 x 64 (WM = 4) read a
+    // quarter less from LDS per MFMA and measured the same speed; the smaller
+    // register footprint of WM = 2 leaves room for a co-resident fused workgroup.
+    constexpr int kWM = 2;
     static std::atomic<int> allowed[2][kMaxDevices];
     if (g.b_layout == TW_B_KN) {
-        TW_TRY(allow_dynamic_lds(reinterpret_cast<const void *>(gemm_bf16_kernel<true>), kGemmLdsBytes, allowed[1]));
-        TW_HIP(launch_kernel(gemm_bf16_kernel<true>, dim3(grid), dim3(kGemmThreads), kGemmLdsBytes, stream, prm));
+        TW_TRY(allow_dynamic_lds(reinterpret_cast<const void *>(gemm_bf16_kernel<true, kWM>), kGemmLdsBytes,
+                                 allowed[1]));
+        TW_HIP(launch_kernel(gemm_bf16_kernel<true, kWM>, dim3(grid), dim3(64 * (16 / kWM)), kGemmLdsBytes, stream,
+                             prm));
     } else {
-        TW_TRY(allow_dynamic_lds(reinterpret_cast<const void *>(gemm_bf16_kernel<false>), kGemmLdsBytes, allowed[0]));
-        TW_HIP(launch_kernel(gemm_bf16_kernel<false>, dim3(grid), dim3(kGemmThreads), kGemmLdsBytes, stream, prm));
+        TW_TRY(allow_dynamic_lds(reinterpret_cast<const void *>(gemm_bf16_kernel<false, kWM>), kGemmLdsBytes,
+                                 allowed[0]));
+        TW_HIP(launch_kernel(gemm_bf16_kernel<false, kWM>, dim3(grid), dim3(64 * (16 / kWM)), kGemmLdsBytes, stream,
+                             prm));
     }
     return TW_OK;
 }
