@@ -182,10 +182,46 @@ def main():
             del X1, resid, parts, out, res_out, Y
             torch.cuda.empty_cache()
 
+        # where splitting starts to pay: the plain chain (three launches on one stream, no events)
+        # against the woven layer in shared mode and with a 32-CU budget, over batch sizes
+        thr = []
+        for T in (256, 512, 1024, 2048, 4096, 8192, 16384):
+            X1, resid = rnd((T, K1), 0.02), rnd((T, H), 1.0)
+            parts = [rnd((T, H), 0.25) for _ in range(P)]
+            out, res_out = torch.empty_like(resid), torch.empty_like(resid)
+            Y = torch.empty((T, N2), dtype=torch.bfloat16, device=dev)
+
+            def plain():
+                tw.gemm_bf16(X1, W1, C=parts[0], stream=stream)
+                tw.reduce_add_rmsnorm(parts, resid, weight, 1e-5, cu_budget=0, out=out, residual_out=res_out,
+                                      stream=stream)
+                tw.gemm_bf16(out, W2, C=Y, stream=stream)
+
+            def woven(split_row, fb, gb):
+                def f():
+                    with torch.cuda.stream(stream):
+                        tw.weave_layer(X1, W1, parts, resid, weight, 1e-5, W2, split_row, stream, comm,
+                                       fused_cu_budget=fb, gemm_cu_budget=gb, out=out, residual_out=res_out, Y=Y,
+                                       parent=stream, use_parent=True, join=True)
+                return f
+            row = {"T": T, "plain_us": round(float(np.median(event_times([plain], 24, 4, stream))), 1)}
+            k, _, _ = tw.smart_split_point(T, 64, [H, N2], cus, gemm_k=[K1, H])
+            if k < T:
+                row["split_row"] = k
+                row["woven_shared_us"] = round(float(np.median(event_times([woven(k, tw.CU_SHARED, 0)], 24, 4,
+                                                                           stream))), 1)
+            k32, _, _ = tw.smart_split_point(T, 64, [H, N2], cus - 32, gemm_k=[K1, H])
+            if k32 < T:
+                row["woven_budget32_us"] = round(float(np.median(event_times([woven(k32, 32, cus - 32)], 24, 4,
+                                                                             stream))), 1)
+            thr.append(row)
+            del X1, resid, parts, out, res_out, Y
+            torch.cuda.empty_cache()
+
         def spread(key):
             rate = np.array([r["T"] / r[key] for r in rows])
             return round(float(rate.std() / rate.mean()), 4)
-        print(json.dumps({"split_sweep": rows,
+        print(json.dumps({"split_sweep": rows, "threshold_sweep": thr,
                           "tokens_per_us_relative_spread": {"equal": spread("equal_us"), "smart": spread("smart_us"),
                                                             "measured_best": spread("measured_best_us")},
                           "note": "layer boundary [Tx1024]x[1024x8192] -> fused H=8192 P=8 (shared mode) -> "

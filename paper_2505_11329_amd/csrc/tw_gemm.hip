@@ -50,11 +50,23 @@
 
 namespace tw {
 
-static constexpr int BM = kGemmTileM, BN = kGemmTileN, BK = 64;
-static constexpr int kStageABytes = BM * BK * 2;  // 32 KiB
-static constexpr int kStageBBytes = BN * BK * 2;  // 16 KiB
-static constexpr int kStageBytes = kStageABytes + kStageBBytes;
+static constexpr int BM = kGemmTileM;
 static constexpr int kXcds = 8;
+
+// A tile configuration: WM x WN blocks of 32 x 32 per wave, 16 / WM waves laid
+// out (8 / WM) x 2, hence a 256 x (64 * WN) workgroup tile; K steps of BK_;
+// STAGES LDS stages. The library builds <2, 2, 3, 64>: eight waves of 64 x 64,
+// tile 256 x 128, 3 x 48 KiB of LDS.
+template <int WM, int WN, int STAGES, int BK_>
+struct TileCfg {
+    static constexpr int kWaves = 16 / WM;
+    static constexpr int kThreads = 64 * kWaves;
+    static constexpr int kBN = 64 * WN;
+    static constexpr int kStageABytes = BM * BK_ * 2;
+    static constexpr int kStageBBytes = kBN * BK_ * 2;
+    static constexpr int kStageBytes = kStageABytes + kStageBBytes;
+    static constexpr int kLdsBytes = STAGES * kStageBytes;
+};
 
 typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
 typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
@@ -70,19 +82,20 @@ struct GemmParams {
     int tiles_per_xcd;  // ceil(tiles / 8)
 };
 
-// Byte offset inside a stage's A (or B) area of the 16-byte piece c of row r.
-// Two consecutive rows form one 256-byte line that spans all 64 LDS banks; the
-// piece index is xor-ed with the low bits of the line number. Sixteen lanes that
-// read the same piece of sixteen consecutive rows (an MFMA operand fetch), and
-// sixteen lanes that write the sixteen pieces of one line (the global->LDS
-// copy), each touch every bank exactly once.
+// Byte offset inside a stage's A (or B) area of the 16-byte piece c of row r,
+// rows of BK_ bf16. 256 / (2 BK_) consecutive rows form one 256-byte line that
+// spans all 64 LDS banks; the piece index is xor-ed with the low bits of the
+// line number. Sixteen lanes that read the same piece of sixteen consecutive
+// rows (an MFMA operand fetch), and sixteen lanes that write the sixteen pieces
+// of one line (the global->LDS copy), each touch every bank exactly once.
+template <int BK_>
 __device__ __forceinline__ uint32_t lds_piece(int r, int c)
 {
-    return (r >> 1) * 256 + ((((r & 1) << 3) | (c ^ ((r >> 1) & 7))) << 4);
+    constexpr int kRowsPerLine = 128 / BK_;  // 2 or 4
+    constexpr int kPieces = BK_ / 8;         // 8 or 4 per row
+    const int line = r / kRowsPerLine;
+    return line * 256 + (((r % kRowsPerLine) * kPieces + (c ^ (line & (kPieces - 1)))) << 4);
 }
-
-static constexpr int kStages = 3;
-static constexpr int kGemmLdsBytes = kStages * kStageBytes;  // 144 KiB
 
 typedef __attribute__((address_space(3))) void *lds_ptr_t;
 typedef __attribute__((address_space(3))) char *lds_char_ptr_t;
@@ -108,20 +121,21 @@ __device__ __forceinline__ u32x2 lds_read_tr8(uint32_t addr)
     return v;
 }
 
-// Operand fragments of one K sub-step for a wave that owns WM x 2 blocks of
-// 32 x 32. With B stored [K x N] a B fragment arrives as two register pairs
-// (k 0..3 and k 4..7 of the lane's column).
-template <bool B_KN, int WM>
+// Operand fragments of one K sub-step for a wave that owns WM x WN blocks of
+// 32 x 32. With B stored [K x N] (WN = 2 only) a B fragment arrives as two
+// register pairs (k 0..3 and k 4..7 of the lane's column).
+template <bool B_KN, int WM, int WN>
 struct Frags {
     bf16x8 a[WM];
-    bf16x8 b[2];
+    bf16x8 b[WN];
     u32x2 blo[2], bhi[2];
 };
 // Wait until at most N of this wave's LDS reads are outstanding. The fragments
 // are passed through so that no use of them can be moved above the wait.
 #define TW_FRAG_A2(f) "+v"((f).a[0]), "+v"((f).a[1])
 #define TW_FRAG_A4(f) TW_FRAG_A2(f), "+v"((f).a[2]), "+v"((f).a[3])
-#define TW_FRAG_B_NK(f) "+v"((f).b[0]), "+v"((f).b[1])
+#define TW_FRAG_B2(f) "+v"((f).b[0]), "+v"((f).b[1])
+#define TW_FRAG_B4(f) TW_FRAG_B2(f), "+v"((f).b[2]), "+v"((f).b[3])
 #define TW_FRAG_B_KN(f) "+v"((f).blo[0]), "+v"((f).bhi[0]), "+v"((f).blo[1]), "+v"((f).bhi[1])
 #define TW_WAIT_LGKM(N, A_OPS, B_OPS) \
     asm volatile("s_waitcnt lgkmcnt(%[cnt])" : A_OPS, B_OPS : [cnt] "n"(N) : "memory")
@@ -138,19 +152,20 @@ __device__ __forceinline__ void static_for(Fn &&f)
     static_for_impl(std::make_integer_sequence<int, N>{}, f);
 }
 
-template <int N, bool B_KN, int WM>
-__device__ __forceinline__ void wait_lgkm(Frags<B_KN, WM> &f)
+template <int N, bool B_KN, int WM, int WN>
+__device__ __forceinline__ void wait_lgkm(Frags<B_KN, WM, WN> &f)
 {
-    if constexpr (WM == 2 && !B_KN) TW_WAIT_LGKM(N, TW_FRAG_A2(f), TW_FRAG_B_NK(f));
+    static_assert(WM == 2 || WM == 4, "fragment operand lists below");
+    static_assert(B_KN ? WN == 2 : (WN == 2 || WN == 4), "fragment operand lists below");
     if constexpr (WM == 2 && B_KN) TW_WAIT_LGKM(N, TW_FRAG_A2(f), TW_FRAG_B_KN(f));
-    if constexpr (WM == 4 && !B_KN) TW_WAIT_LGKM(N, TW_FRAG_A4(f), TW_FRAG_B_NK(f));
     if constexpr (WM == 4 && B_KN) TW_WAIT_LGKM(N, TW_FRAG_A4(f), TW_FRAG_B_KN(f));
+    if constexpr (WM == 2 && !B_KN && WN == 2) TW_WAIT_LGKM(N, TW_FRAG_A2(f), TW_FRAG_B2(f));
+    if constexpr (WM == 4 && !B_KN && WN == 2) TW_WAIT_LGKM(N, TW_FRAG_A4(f), TW_FRAG_B2(f));
+    if constexpr (WM == 2 && !B_KN && WN == 4) TW_WAIT_LGKM(N, TW_FRAG_A2(f), TW_FRAG_B4(f));
+    if constexpr (WM == 4 && !B_KN && WN == 4) TW_WAIT_LGKM(N, TW_FRAG_A4(f), TW_FRAG_B4(f));
 }
 
-// WM = 32-row blocks per wave: 2 -> eight waves laid out 4 x 2, each 64 x 64;
-// 4 -> four waves laid out 2 x 2, each 128 x 64 (one wave per SIMD, fewer LDS
-// bytes read per MFMA).
-template <bool B_KN, int WM>
+template <bool B_KN, int WM, int WN, int STAGES, int BK>
 __global__ __launch_bounds__(64 * (16 / WM)) void gemm_bf16_kernel(const GemmParams prm)
 {
     // The body is for the device pass only: the host pass needs the launch stub,
@@ -158,12 +173,21 @@ __global__ __launch_bounds__(64 * (16 / WM)) void gemm_bf16_kernel(const GemmPar
     // builtins and inline assembly below.
 #if defined(__HIP_DEVICE_COMPILE__)
     extern __shared__ __attribute__((aligned(16))) char lds[];
-    constexpr int NW = 16 / WM;          // waves per workgroup
-    constexpr int A_LOADS = 32 / NW;     // wave instructions (1 KiB each) per wave that fill a stage's A area
-    constexpr int B_LOADS = 16 / NW;     // ... and its B area
-    constexpr int kLoads = A_LOADS + B_LOADS;      // loads of one K step per lane
-    static_assert(kLoads == 6 || kLoads == 12, "wait encodings below");
-    constexpr int kFragReads = WM + (B_KN ? 4 : 2);  // LDS reads of one sub-step
+    using Cfg = TileCfg<WM, WN, STAGES, BK>;
+    constexpr int NW = Cfg::kWaves;
+    constexpr int BN = Cfg::kBN;
+    constexpr int kStageABytes = Cfg::kStageABytes;
+    constexpr int kStageBytes = Cfg::kStageBytes;
+    constexpr int kStages = STAGES;
+    constexpr int kSubs = BK / 16;                           // K sub-steps (one MFMA deep) per K step
+    constexpr int kBlockBytes = 32 * BK * 2;                 // LDS distance between 32-row blocks
+    constexpr int A_LOADS = kStageABytes / 1024 / NW;        // wave instructions (1 KiB each) per wave that
+    constexpr int B_LOADS = Cfg::kStageBBytes / 1024 / NW;   // fill a stage's A area, and its B area
+    constexpr int kLoads = A_LOADS + B_LOADS;                // loads of one K step per lane
+    static_assert(BK == 64 || BK == 32, "LDS layouts below");
+    static_assert(STAGES >= 2 && (STAGES - 2) * kLoads < 64, "vmcnt field");
+    static_assert(!B_KN || (WN == 2 && BK == 64), "[K x N] operands: 256 x 128 x 64 tiles only");
+    constexpr int kFragReads = WM + (B_KN ? 4 : WN);  // LDS reads of one sub-step
 
     const int tid = threadIdx.x;
     const int lane = tid & 63;
@@ -183,9 +207,12 @@ __global__ __launch_bounds__(64 * (16 / WM)) void gemm_bf16_kernel(const GemmPar
     // piece that belong there (the same for every instruction up to a row offset)
     const int line_in_instr = lane >> 4;            // 0..3
     const int slot = lane & 15;
-    // line = (i * NW + wave) * 4 + line_in_instr; (line & 7) = ((wave & 1) * 4 + line_in_instr)
-    const int piece = (slot & 7) ^ (((wave & 1) << 2) | line_in_instr);
-    const int row_lo = 2 * (wave * 4 + line_in_instr) + (slot >> 3);  // + 8 * NW * i
+    constexpr int kRowsPerLine = 128 / BK, kPieces = BK / 8;
+    // line = (i * NW + wave) * 4 + line_in_instr, of which the swizzle uses the low bits
+    const int line_low = ((wave * 4) | line_in_instr) & (kPieces - 1);
+    const int piece = (slot % kPieces) ^ line_low;
+    const int row_lo = kRowsPerLine * (wave * 4 + line_in_instr) + slot / kPieces;  // + 4 * kRowsPerLine * NW * i
+    constexpr int kRowsPerInstr = 4 * kRowsPerLine * NW;  // rows all waves' instruction i cover
     // B stored [K x N]: its LDS area holds 64 k-rows of 256 bytes (128 n); a wave
     // instruction fills four rows; row r keeps 16-byte piece s at slot
     // s ^ ((r & 3) << 1), so that the four rows one transposing read touches
@@ -194,13 +221,13 @@ __global__ __launch_bounds__(64 * (16 / WM)) void gemm_bf16_kernel(const GemmPar
     const int bkn_piece = slot ^ (line_in_instr << 1);
 
     // fragment read addresses inside a stage (A area at 0, B area after it) for
-    // the wave's first 32-row block; block i lies 32 rows = 4096 bytes further
-    // (the swizzle repeats every 16 rows), which goes into the read's offset field
-    uint32_t fa_addr[4], fb_addr[4], fbkn_addr[2];
+    // the wave's first 32-row block; block i lies 32 rows = kBlockBytes further
+    // (the swizzle repeats within that), which goes into the read's offset field
+    uint32_t fa_addr[kSubs], fb_addr[kSubs], fbkn_addr[2];
 #pragma unroll
-    for (int kk = 0; kk < 4; ++kk) {
-        fa_addr[kk] = lds_piece(wave_m * (32 * WM) + l31, kk * 2 + lhi);
-        fb_addr[kk] = kStageABytes + lds_piece(wave_n * 64 + l31, kk * 2 + lhi);
+    for (int kk = 0; kk < kSubs; ++kk) {
+        fa_addr[kk] = lds_piece<BK>(wave_m * (32 * WM) + l31, kk * 2 + lhi);
+        fb_addr[kk] = kStageABytes + lds_piece<BK>(wave_n * (32 * WN) + l31, kk * 2 + lhi);
     }
     {
         // lane = 16 g + s: group g covers columns (g & 1) * 16 .. +15 of the 32-wide
@@ -214,7 +241,7 @@ __global__ __launch_bounds__(64 * (16 / WM)) void gemm_bf16_kernel(const GemmPar
         }
     }
 
-    using F = Frags<B_KN, WM>;
+    using F = Frags<B_KN, WM, WN>;
 
     for (int w = blockIdx.x; w < prm.tiles_per_xcd * kXcds; w += gridDim.x) {
         const int slot_w = w / kXcds;
@@ -235,9 +262,9 @@ __global__ __launch_bounds__(64 * (16 / WM)) void gemm_bf16_kernel(const GemmPar
         const __amdgpu_buffer_rsrc_t ra = make_rsrc(prm.A + m0 * row_bytes, static_cast<uint32_t>(rows_a * row_bytes));
         const __amdgpu_buffer_rsrc_t rb = make_rsrc(prm.B + n0 * row_bytes, static_cast<uint32_t>(rows_b * row_bytes));
 
-        f32x16 acc[2][WM];
+        f32x16 acc[WN][WM];
 #pragma unroll
-        for (int i = 0; i < 2; ++i)
+        for (int i = 0; i < WN; ++i)
 #pragma unroll
             for (int j = 0; j < WM; ++j)
 #pragma unroll
@@ -270,12 +297,12 @@ __global__ __launch_bounds__(64 * (16 / WM)) void gemm_bf16_kernel(const GemmPar
         auto fetch_one = [&](const FetchCtx &c, const int idx) {
             if (idx < A_LOADS) {
                 const int i = idx;
-                const uint32_t off = static_cast<uint32_t>((row_lo + 8 * NW * i) * row_bytes) + c.kb;
+                const uint32_t off = static_cast<uint32_t>((row_lo + kRowsPerInstr * i) * row_bytes) + c.kb;
                 __builtin_amdgcn_raw_ptr_buffer_load_lds(ra, (lds_ptr_t)(c.sa + (i * NW + wave) * 1024), 16,
                                                          off | c.oob, 0, 0, 0);
             } else if constexpr (!B_KN) {
                 const int i = idx - A_LOADS;
-                const uint32_t off = static_cast<uint32_t>((row_lo + 8 * NW * i) * row_bytes) + c.kb;
+                const uint32_t off = static_cast<uint32_t>((row_lo + kRowsPerInstr * i) * row_bytes) + c.kb;
                 __builtin_amdgcn_raw_ptr_buffer_load_lds(
                     rb, (lds_ptr_t)(c.sa + kStageABytes + (i * NW + wave) * 1024), 16,
                     off | c.oob, 0, 0, 0);
@@ -300,9 +327,9 @@ __global__ __launch_bounds__(64 * (16 / WM)) void gemm_bf16_kernel(const GemmPar
             constexpr int kk = decltype(kk_tag)::value;
             constexpr int j = decltype(j_tag)::value;
             if constexpr (j < WM) {
-                f.a[j] = lds_read16<4096 * j>(stage_base + fa_addr[kk]);
+                f.a[j] = lds_read16<kBlockBytes * j>(stage_base + fa_addr[kk]);
             } else if constexpr (!B_KN) {
-                f.b[j - WM] = lds_read16<4096 * (j - WM)>(stage_base + fb_addr[kk]);
+                f.b[j - WM] = lds_read16<kBlockBytes * (j - WM)>(stage_base + fb_addr[kk]);
             } else {
                 constexpr int i = (j - WM) >> 1;
                 if constexpr (((j - WM) & 1) == 0) f.blo[i] = lds_read_tr8<kk * 4096>(stage_base + fbkn_addr[i]);
@@ -320,8 +347,7 @@ __global__ __launch_bounds__(64 * (16 / WM)) void gemm_bf16_kernel(const GemmPar
                             auto n_loads) {
             constexpr int kFirst = decltype(first_load)::value;
             constexpr int kHere = decltype(n_loads)::value;
-            constexpr int kSlots = 2 * WM;
-            constexpr int kItems = kFragReads + kHere;
+            constexpr int kSlots = WN * WM;
             static_for<kSlots>([&](auto m_tag) {
                 constexpr int m = decltype(m_tag)::value;
                 constexpr int nb = m / WM, mb = m % WM;
@@ -334,40 +360,34 @@ __global__ __launch_bounds__(64 * (16 / WM)) void gemm_bf16_kernel(const GemmPar
                 }
                 acc[nb][mb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(bfrag, cur.a[mb], acc[nb][mb], 0, 0, 0);
                 __builtin_amdgcn_sched_barrier(0);
-                // items [m * kItems / kSlots, (m + 1) * kItems / kSlots) follow MFMA m
-                static_for<kItems>([&](auto t_tag) {
+                // What follows MFMA m: the fragment reads go out during the first
+                // half of the sub-step (they are waited for at its end and need the
+                // second half to arrive), the global loads are spread over all of it.
+                constexpr int kReadSlots = kSlots / 2;
+                static_for<kFragReads>([&](auto t_tag) {
                     constexpr int t = decltype(t_tag)::value;
-                    if constexpr (t >= m * kItems / kSlots && t < (m + 1) * kItems / kSlots) {
-                        if constexpr (t < kFragReads) read_one(nxt, nxt_base, kk_next, t_tag);
-                        else fetch_one(fc, kFirst + t - kFragReads);
-                    }
+                    if constexpr (t * kReadSlots / kFragReads == m) read_one(nxt, nxt_base, kk_next, t_tag);
+                });
+                static_for<(kHere > 0 ? kHere : 1)>([&](auto t_tag) {
+                    constexpr int t = decltype(t_tag)::value;
+                    if constexpr (t < kHere && t * kSlots / (kHere > 0 ? kHere : 1) == m) fetch_one(fc, kFirst + t);
                 });
                 __builtin_amdgcn_sched_barrier(0);
             });
         };
         using K0 = std::integral_constant<int, 0>;
-        using K1 = std::integral_constant<int, 1>;
-        using K2 = std::integral_constant<int, 2>;
-        using K3 = std::integral_constant<int, 3>;
-        constexpr int kPerSub = kLoads / 3;  // the loads of a K step go out during its first three sub-steps
-        using L0 = std::integral_constant<int, 0>;
-        using L1 = std::integral_constant<int, kPerSub>;
-        using L2 = std::integral_constant<int, 2 * kPerSub>;
-        using LN = std::integral_constant<int, kPerSub>;
-        using LZ = std::integral_constant<int, 0>;
 
         // All waves are done with the previous tile's LDS reads before it is refilled.
         __builtin_amdgcn_s_waitcnt(0xC07F);  // lgkmcnt(0)
         __builtin_amdgcn_s_barrier();
-        fetch(0, 0);
-        fetch(1, 1);
-        // A K step has landed once at most the loads of the following one are
-        // outstanding (loads past the end are issued too, out of range, so the
-        // count is the same in every trip); the barrier extends that to the
+        static_for<kStages - 1>([&](auto st) { fetch(decltype(st)::value, decltype(st)::value); });
+        // K step kt + 1 has landed once at most the loads of the kStages - 2 later
+        // K steps are outstanding (loads past the end are issued too, out of range,
+        // so the count is the same in every trip); the barrier extends that to the
         // loads of the other waves.
         auto wait_landed = [&]() {
-            if constexpr (kLoads == 6) __builtin_amdgcn_s_waitcnt(0x0F76);  // vmcnt(6)
-            else __builtin_amdgcn_s_waitcnt(0x0F7C);                        // vmcnt(12)
+            constexpr int n = (kStages - 2) * kLoads;
+            __builtin_amdgcn_s_waitcnt(((n >> 4) << 14) | 0x0F70 | (n & 15));  // vmcnt(n)
             __builtin_amdgcn_s_barrier();
         };
         wait_landed();
@@ -377,27 +397,36 @@ __global__ __launch_bounds__(64 * (16 / WM)) void gemm_bf16_kernel(const GemmPar
         int stage = 0;
         for (int kt = 0; kt < k_tiles; ++kt) {
             const uint32_t base = static_cast<uint32_t>(stage * kStageBytes);
-            int fetch_stage = stage + 2;
-            fetch_stage = fetch_stage >= kStages ? fetch_stage - kStages : fetch_stage;
             const int next_stage = stage + 1 >= kStages ? 0 : stage + 1;
-            const FetchCtx fc = fetch_ctx(kt + 2, fetch_stage);
+            // the stage that was read during the previous trip is free
+            const int fetch_stage = stage == 0 ? kStages - 1 : stage - 1;
+            const FetchCtx fc = fetch_ctx(kt + kStages - 1, fetch_stage);
 
-            wait_lgkm<0>(f0);
-            sub_step(f0, f1, base, K1{}, fc, L0{}, LN{});
-            wait_lgkm<0>(f1);
-            sub_step(f1, f0, base, K2{}, fc, L1{}, LN{});
-            wait_lgkm<0>(f0);
-            sub_step(f0, f1, base, K3{}, fc, L2{}, LN{});
-            // the last fragments of this stage have arrived: this wave is done
-            // reading it. Has K step kt + 1 landed (for every wave)? After the
-            // barrier every wave is also done reading this stage, so the loads the
-            // next trip issues may overwrite the stage before it.
-            wait_lgkm<0>(f1);
-            wait_landed();
-            sub_step(f1, f0, static_cast<uint32_t>(next_stage * kStageBytes), K0{}, fc, LZ{}, LZ{});
+            // sub-steps alternate between the two fragment sets; the global loads go
+            // out during all but the last one
+            static_for<kSubs>([&](auto sub_tag) {
+                constexpr int sub = decltype(sub_tag)::value;
+                F &cur = (sub & 1) ? f1 : f0;
+                F &nxt = (sub & 1) ? f0 : f1;
+                wait_lgkm<0>(cur);
+                if constexpr (sub < kSubs - 1) {
+                    constexpr int first = sub * kLoads / (kSubs - 1);
+                    constexpr int count = (sub + 1) * kLoads / (kSubs - 1) - first;
+                    sub_step(cur, nxt, base, std::integral_constant<int, sub + 1>{}, fc,
+                             std::integral_constant<int, first>{}, std::integral_constant<int, count>{});
+                } else {
+                    // the last fragments of this stage have arrived: this wave is done
+                    // reading it. Has K step kt + 1 landed (for every wave)? After the
+                    // barrier every wave is also done reading this stage, so the loads
+                    // the next trip issues may overwrite the stage before it.
+                    wait_landed();
+                    sub_step(cur, nxt, static_cast<uint32_t>(next_stage * kStageBytes), K0{}, fc,
+                             std::integral_constant<int, 0>{}, std::integral_constant<int, 0>{});
+                }
+            });
             stage = next_stage;
         }
-        // the two prefetches past the end are still in flight and target LDS
+        // the prefetches past the end are still in flight and target LDS
         __builtin_amdgcn_s_waitcnt(0x0F70);  // vmcnt(0)
 
         const long long c_row_bytes = prm.N * 2;
@@ -406,16 +435,17 @@ __global__ __launch_bounds__(64 * (16 / WM)) void gemm_bf16_kernel(const GemmPar
         for (int mb = 0; mb < WM; ++mb) {
             const int m = wave_m * (32 * WM) + mb * 32 + l31;
 #pragma unroll
-            for (int nb = 0; nb < 2; ++nb) {
+            for (int nb = 0; nb < WN; ++nb) {
 #pragma unroll
                 for (int q = 0; q < 4; ++q) {
-                    const long long n = n0 + wave_n * 64 + nb * 32 + q * 8 + lhi * 4;
+                    const long long n = n0 + wave_n * (32 * WN) + nb * 32 + q * 8 + lhi * 4;
                     u32x2 v;
                     v.x = pack_bf16x2(acc[nb][mb][q * 4 + 0], acc[nb][mb][q * 4 + 1]);
                     v.y = pack_bf16x2(acc[nb][mb][q * 4 + 2], acc[nb][mb][q * 4 + 3]);
                     const uint32_t off = static_cast<uint32_t>(m * c_row_bytes + n * 2);
                     __builtin_amdgcn_raw_buffer_store_b64(v, rc, n < prm.N ? off : kOutOfRange, 0, 0);
                 }
+                __builtin_amdgcn_sched_barrier(0);  // one block's accumulators at a time
             }
         }
     }
@@ -446,13 +476,11 @@ tw_status validate_gemm(const tw_gemm_args &g)
     return TW_OK;
 }
 
-tw_status launch_gemm(const tw_gemm_args &g, hipStream_t stream)
+template <bool B_KN, int WM, int WN, int STAGES, int BK>
+static tw_status launch_cfg(const tw_gemm_args &g, int budget, hipStream_t stream)
 {
-    if (g.M == 0 || g.N == 0) return TW_OK;
-    int cus = 0;
-    TW_TRY(current_cu_count(&cus));
-    const int budget = resolve_budget(g.cu_budget, cus);
-
+    using Cfg = TileCfg<WM, WN, STAGES, BK>;
+    constexpr int BN = Cfg::kBN;
     GemmParams prm;
     prm.A = static_cast<const char *>(g.A);
     prm.B = static_cast<const char *>(g.B);
@@ -484,23 +512,28 @@ tw_status launch_gemm(const tw_gemm_args &g, hipStream_t stream)
     const int64_t slots = int64_t(prm.tiles_per_xcd) * kXcds;
     const unsigned grid = static_cast<unsigned>(slots < budget ? slots : budget);
 
-    // Eight waves of 64 x 64 (WM = 2). Four waves of 128 x 64 (WM = 4) read a
-    // quarter less from LDS per MFMA and measured the same speed; the smaller
-    // register footprint of WM = 2 leaves room for a co-resident fused workgroup.
-    constexpr int kWM = 2;
-    static std::atomic<int> allowed[2][kMaxDevices];
-    if (g.b_layout == TW_B_KN) {
-        TW_TRY(allow_dynamic_lds(reinterpret_cast<const void *>(gemm_bf16_kernel<true, kWM>), kGemmLdsBytes,
-                                 allowed[1]));
-        TW_HIP(launch_kernel(gemm_bf16_kernel<true, kWM>, dim3(grid), dim3(64 * (16 / kWM)), kGemmLdsBytes, stream,
-                             prm));
-    } else {
-        TW_TRY(allow_dynamic_lds(reinterpret_cast<const void *>(gemm_bf16_kernel<false, kWM>), kGemmLdsBytes,
-                                 allowed[0]));
-        TW_HIP(launch_kernel(gemm_bf16_kernel<false, kWM>, dim3(grid), dim3(64 * (16 / kWM)), kGemmLdsBytes, stream,
-                             prm));
-    }
+    static std::atomic<int> allowed[kMaxDevices];
+    TW_TRY(allow_dynamic_lds(reinterpret_cast<const void *>(gemm_bf16_kernel<B_KN, WM, WN, STAGES, BK>), Cfg::kLdsBytes,
+                             allowed));
+    TW_HIP(launch_kernel(gemm_bf16_kernel<B_KN, WM, WN, STAGES, BK>, dim3(grid), dim3(Cfg::kThreads), Cfg::kLdsBytes,
+                         stream, prm));
     return TW_OK;
+}
+
+tw_status launch_gemm(const tw_gemm_args &g, hipStream_t stream)
+{
+    if (g.M == 0 || g.N == 0) return TW_OK;
+    int cus = 0;
+    TW_TRY(current_cu_count(&cus));
+    const int budget = resolve_budget(g.cu_budget, cus);
+    // Eight waves of 64 x 64, tile 256 x 128 x 64, three LDS stages. Measured
+    // alternatives that were no faster and are not built: four waves of 128 x 64
+    // (a quarter fewer LDS bytes per MFMA), and 256 x 256 tiles with four waves of
+    // 128 x 128 over four stages of K = 32 (two thirds of the bytes fetched per
+    // flop). With operand fetch the shader clock sits near 1.5 GHz whatever the
+    // tile; without it the same loops run at 2.1 GHz and 2.0 PFLOP/s.
+    if (g.b_layout == TW_B_KN) return launch_cfg<true, 2, 2, 3, 64>(g, budget, stream);
+    return launch_cfg<false, 2, 2, 3, 64>(g, budget, stream);
 }
 
 }  // namespace tw

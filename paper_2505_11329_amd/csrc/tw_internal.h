@@ -90,6 +90,7 @@ tw_status validate_gemm(const tw_gemm_args &g);
 tw_status launch_gemm(const tw_gemm_args &g, hipStream_t stream);
 static constexpr int kGemmTileM = 256, kGemmTileN = 128;
 
+
 // ---- fork/join events (tw_host.hip) ----
 // A small per-device pool of timing-disabled events used to order streams.
 tw_status borrow_event(hipEvent_t *ev);
