@@ -25,6 +25,13 @@
 //     (vmcnt for landed stages, lgkmcnt for fragments) are placed by hand.
 //     Dynamic LDS is the kernel's only LDS object, so its byte offsets are LDS
 //     addresses.
+//   - The K loop is software-pipelined by hand, instruction by instruction:
+//     between the MFMAs of one K sub-step (k = 16) a wave issues the LDS reads
+//     of the next sub-step's fragments (during the first half, so that they
+//     have the second half to arrive) and its share of the global loads of
+//     K step kt + 2; the "next stage has landed" check (vmcnt + workgroup
+//     barrier) sits before the last MFMA group of a K step, when every wave
+//     still has matrix work queued.
 //   - Each MFMA gets the B fragment as its first operand and the A fragment as
 //     its second, so the 32x32 result block is held transposed: a lane owns one
 //     row m of C and, per group of four accumulator registers, four consecutive
