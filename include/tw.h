@@ -90,8 +90,8 @@ typedef enum tw_status {
  *                 unit rather than in place of one; for H > 8192 it falls back
  *                 to the whole device. Other negative values mean the whole
  *                 device. A whole-device launch of at most two rows per compute
- *                 unit (H <= 8192) is sent as those small workgroups too: same
- *                 bits, lower latency.
+ *                 unit (eight when P >= 8; H <= 8192) is sent as those small
+ *                 workgroups too: same bits, lower latency.
  *   out           device bf16 [N x H]
  *   residual_out  device bf16 [N x H]
  *
@@ -153,7 +153,7 @@ tw_status tw_reduce_add_rmsnorm_unfused(const tw_fused_args *args, void *sum_scr
 
 /* Number of workgroups the fused kernel is launched with for these sizes on the
  * current device (0 if N == 0; -1 if the arguments are invalid or no device). */
-int64_t tw_fused_grid(int64_t N, int64_t H, int cu_budget);
+int64_t tw_fused_grid(int64_t N, int64_t H, int P, int cu_budget);
 
 /*
  * Two-way token split (Section 4: prefix split T_a, suffix split T_b; every

@@ -78,7 +78,7 @@ def lib():
         L.tw_reduce_add_rmsnorm.restype = ctypes.c_int
         L.tw_reduce_add_rmsnorm_traced.argtypes = fused_sig + [_vp, _i64, _vp]
         L.tw_reduce_add_rmsnorm_traced.restype = ctypes.c_int
-        L.tw_fused_grid.argtypes = [_i64, _i64, ctypes.c_int]
+        L.tw_fused_grid.argtypes = [_i64, _i64, ctypes.c_int, ctypes.c_int]
         L.tw_fused_grid.restype = _i64
         L.tw_reduce_add_rmsnorm_unfused.argtypes = [ctypes.POINTER(FusedArgs), _vp, _vp]
         L.tw_reduce_add_rmsnorm_unfused.restype = ctypes.c_int
@@ -140,8 +140,8 @@ def split_point(N, multiple):
     return int(lib().tw_split_point(int(N), int(multiple)))
 
 
-def fused_grid(N, H, cu_budget=0):
-    return int(lib().tw_fused_grid(int(N), int(H), int(cu_budget)))
+def fused_grid(N, H, P, cu_budget=0):
+    return int(lib().tw_fused_grid(int(N), int(H), int(P), int(cu_budget)))
 
 
 # ---- marshalling helpers -------------------------------------------------
@@ -221,7 +221,7 @@ def reduce_add_rmsnorm_traced(partials, residual, weight, eps, cu_budget=0, out=
     """tw_reduce_add_rmsnorm_traced. Returns (out, residual_out, hw_ids int32 [grid, 2])."""
     import torch
     a, keep, out, residual_out = _fused_pack(partials, residual, weight, eps, cu_budget, out, residual_out)
-    grid = max(fused_grid(a.N, a.H, cu_budget), 1)
+    grid = max(fused_grid(a.N, a.H, a.P, cu_budget), 1)
     hw = torch.zeros((grid, 2), dtype=torch.int32, device=residual.device)
     _check(lib().tw_reduce_add_rmsnorm_traced(a.partials, a.residual, a.weight, a.eps, a.N, a.H, a.P,
                                               a.cu_budget, a.out, a.residual_out, _vp(hw.data_ptr()),

@@ -519,16 +519,19 @@ static tw_status launch_vpt(const FusedParams &prm, int vpt, bool trace, int64_t
 }
 
 // Which kernel a launch takes. Shared mode has a kernel for rows of up to 1024
-// vectors; wider rows run on the wide kernel over the whole device. A
-// whole-device launch of at most two rows per compute unit also takes the small
-// workgroups: they are placed faster and put every row in flight at once
-// (measured 5-20 % faster up to that size, slower well beyond it). Both kernels
-// give the same bits.
-static bool takes_thin_kernel(int cu_budget, int cus, const FusedGeometry &g, int64_t n_rows)
+// vectors; wider rows run on the wide kernel over the whole device. A small
+// whole-device launch also takes the small workgroups: they are placed faster
+// and put every row in flight at once, where the wide kernel's software pipeline
+// has only a few rows per workgroup to run over. Measured on MI355X: faster up
+// to two rows per compute unit for any P (5-20 %), and up to eight rows per
+// compute unit when P >= 8 (2-8 %); slower well beyond that. Both kernels give
+// the same bits.
+static bool takes_thin_kernel(int cu_budget, int cus, const FusedGeometry &g, int64_t n_rows, int P)
 {
     if (g.vpt != 1) return false;
     if (cu_budget == TW_CU_SHARED) return true;
-    return resolve_budget(cu_budget, cus) == cus && n_rows <= 2 * static_cast<int64_t>(cus);
+    const int64_t rows_per_cu = P >= 8 ? 8 : 2;
+    return resolve_budget(cu_budget, cus) == cus && n_rows <= rows_per_cu * cus;
 }
 
 tw_status launch_fused(const tw_fused_args &a, int64_t row_begin, int64_t row_end, uint32_t *hw_ids,
@@ -547,7 +550,7 @@ tw_status launch_fused(const tw_fused_args &a, int64_t row_begin, int64_t row_en
     int64_t rows_per_launch = kMaxLaunchBytes / row_bytes;
     rows_per_launch -= rows_per_launch % g.rows_per_iter;
     if (trace && row_end - row_begin > rows_per_launch) return TW_ERR_UNSUPPORTED;
-    const bool thin = takes_thin_kernel(a.cu_budget, cus, g, row_end - row_begin);
+    const bool thin = takes_thin_kernel(a.cu_budget, cus, g, row_end - row_begin, a.P);
     const ThinGeometry tg = thin_geometry(g);
     const int rows_per_group = thin ? tg.rows_per_iter : g.rows_per_iter;
 
@@ -633,14 +636,14 @@ tw_status tw_reduce_add_rmsnorm_traced(const void *const *partials, const void *
     return launch_fused(a, 0, N, hw_ids, hw_ids_len, static_cast<hipStream_t>(stream));
 }
 
-int64_t tw_fused_grid(int64_t N, int64_t H, int cu_budget)
+int64_t tw_fused_grid(int64_t N, int64_t H, int P, int cu_budget)
 {
-    if (N < 0 || H <= 0 || H % 8 != 0 || H > TW_MAX_H) return -1;
+    if (N < 0 || H <= 0 || H % 8 != 0 || H > TW_MAX_H || P < 1 || P > TW_MAX_P) return -1;
     if (N == 0) return 0;
     int cus = 0;
     if (current_cu_count(&cus) != TW_OK) return -1;
     const FusedGeometry g = fused_geometry(H);
-    if (takes_thin_kernel(cu_budget, cus, g, N) && N * H * 2 <= kMaxLaunchBytes) {
+    if (takes_thin_kernel(cu_budget, cus, g, N, P) && N * H * 2 <= kMaxLaunchBytes) {
         int64_t grid = 0;
         uint32_t gpw = 1;
         thin_grid(N, thin_geometry(g), cus, &grid, &gpw);

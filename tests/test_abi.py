@@ -113,7 +113,7 @@ def test_valid_calls_without_a_gpu_return_hip_error_and_allowed_aliasing_passes_
     assert tw.lib().tw_last_hip_error() != 0
     assert fused_call(res_out=addr(4)) == E_HIP   # in-place residual is allowed
     assert fused_call(out=addr(1)) == E_HIP       # out over a partial is allowed
-    assert tw.fused_grid(4, 64, 8) == -1
+    assert tw.fused_grid(4, 64, 2, 8) == -1
 
 
 def test_empty_batch_is_ok_everywhere():
@@ -121,8 +121,9 @@ def test_empty_batch_is_ok_everywhere():
     assert fused_call(n=0, residual=None, out=None, res_out=None, partials=[None, None]) == OK
     assert fused_call(n=0, weight=None) == E_NULL
     assert fused_call(n=0, h=60) == E_UNSUP
-    assert tw.fused_grid(0, 64, 8) == 0
-    assert tw.fused_grid(4, 60, 8) == -1
+    assert tw.fused_grid(0, 64, 2, 8) == 0
+    assert tw.fused_grid(4, 60, 2, 8) == -1
+    assert tw.fused_grid(4, 64, 0, 8) == -1 and tw.fused_grid(4, 64, 17, 8) == -1
 
 
 def split_call(split_row, sa=1, sb=2, n=N, **kw):
