@@ -248,7 +248,8 @@ tw_status tw_overlap_launch(const tw_fused_args *fused, const tw_gemm_args *gemm
  * go to stream_compute in the order G1(a) G1(b) G2(a) G2(b), fused kernels to
  * stream_comm in the order F(a) F(b); events make F(s) wait for G1(s) and G2(s)
  * wait for F(s), so F(a) runs next to G1(b) and F(b) next to G2(a). With
- * split_row == 0 or == T the chain G1, F, G2 runs unsplit (nothing overlaps).
+ * split_row == 0 or == T the chain G1, F, G2 runs unsplit on stream_compute alone
+ * (nothing overlaps, no events).
  * Results are bit-identical for every split_row.
  *
  *   X1, W1, K1   device bf16 [T x K1] and [H x K1] (TW_B_NK), K1 a multiple of 8

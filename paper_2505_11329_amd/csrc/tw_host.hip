@@ -34,7 +34,7 @@ tw_status current_cu_count(int *cu_count)
     }
     int n = 0;
     TW_HIP(hipDeviceGetAttribute(&n, hipDeviceAttributeMultiprocessorCount, dev));
-    if (n <= 0) return hip_fail(hipErrorInvalidDevice, "tw_host.hip: device id out of range");
+    if (n <= 0) return hip_fail(hipErrorInvalidDevice, "tw_host.hip: the device reports no compute units");
     std::lock_guard<std::mutex> lk(g_mu);
     g_cu_count[dev] = n;
     *cu_count = n;
@@ -249,6 +249,14 @@ tw_status tw_weave_layer(const tw_layer_args *layer, int64_t split_row, void *st
     }
     const int64_t cuts[3] = {0, (split_row == 0 || split_row == T) ? T : split_row, T};
     const int n_splits = cuts[1] == T ? 1 : 2;
+    if (n_splits == 1) {
+        // nothing to weave: the chain runs on the compute stream, with no events
+        TW_TRY(launch_gemm(g1, sx));
+        TW_TRY(launch_fused(f, 0, T, nullptr, 0, sx));
+        TW_TRY(launch_gemm(g2, sx));
+        if (parent_is_set && join && sx != sp) TW_TRY(stream_wait_stream(sp, sx));
+        return TW_OK;
+    }
     // compute stream: every G1 first, so the second split's projection is what
     // runs next to the first split's fused kernel
     hipEvent_t g1_done[2], f_done[2];
