@@ -342,6 +342,16 @@ def extras(result, tw, W, torch, np, stream, sets, fused_sets, algo_bytes, event
         tp = event_times(fns, 20, 4, stream)
         row["probe_mix_9r2w_GBps"] = round(11 * sb / np.median(tp) / 1e3, 1)
         row["frac_of_mix_probe"] = round(row["GBps"] / row["probe_mix_9r2w_GBps"], 3)
+        # where the workgroups ran: distinct (XCC, SE, SH, CU) places decoded from the hardware id registers
+        x = sets[0]
+        _, _, hw = tw.reduce_add_rmsnorm_traced(x["partials"], x["residual"], x["weight"], x["eps"], cu_budget=b,
+                                                out=x["out"], residual_out=x["res_out"], stream=stream)
+        stream.synchronize()
+        hw = hw.cpu().numpy().astype(np.int64) & 0xFFFFFFFF
+        places = set(zip((hw[:, 1] & 0xF).tolist(), ((hw[:, 0] >> 13) & 0x7).tolist(),
+                         ((hw[:, 0] >> 12) & 0x1).tolist(), ((hw[:, 0] >> 8) & 0xF).tolist()))
+        row["workgroups"] = int(hw.shape[0])
+        row["cus_occupied"] = len(places)
         budgets[str(b)] = row
     # context only: the same launch when its inputs are still in the 256 MB Infinity Cache (as they
     # would be right after the kernels that produce them); one buffer set, no rotation
