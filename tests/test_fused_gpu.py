@@ -355,3 +355,30 @@ def test_unfused_pipeline_on_the_headline_config_and_in_place(tw, torch_cuda):
                                                out=g["partials"][0], residual_out=g["residual"])
     torch.cuda.synchronize()
     assert np.array_equal(to_bits(out2), want_out) and np.array_equal(to_bits(res2), want_res)
+
+
+# ---- randomized shapes: every launch mode against the oracle and each other ------
+
+def test_random_shapes_all_modes_agree(tw, torch_cuda):
+    """Seeded random (N, H, P): whole device, a small budget, the shared mode and a
+    two-stream split must give the same bits, and those bits must match the oracle."""
+    torch = torch_cuda
+    rng = np.random.default_rng(20250511)
+    sa, sb = torch.cuda.Stream(), torch.cuda.Stream()
+    for case in range(40):
+        H = 8 * int(rng.integers(1, 1200)) if case % 4 else 8 * int(rng.integers(1, 64))
+        N = int(rng.integers(1, 400)) if H <= 4096 else int(rng.integers(1, 60))
+        P = int(rng.integers(1, 17))
+        d = small(N, H, P, seed=1000 + case, eps=float(rng.choice([0.0, 1e-6, 1e-5, 1e-2])))
+        g = upload(d)
+        what = "case %d: N=%d H=%d P=%d" % (case, N, H, P)
+        want = run(tw, torch, g, cu_budget=0)
+        check_against_oracle(d, want[0], want[1], what)
+        for budget in (int(rng.integers(1, 9)), tw.CU_SHARED):
+            got = run(tw, torch, g, cu_budget=budget)
+            assert np.array_equal(got[0], want[0]) and np.array_equal(got[1], want[1]), (what, budget)
+        k = int(rng.integers(0, N + 1))
+        o2, r2 = tw.split_launch(g["partials"], g["residual"], g["weight"], g["eps"], k, sa, sb,
+                                 cu_budget=int(rng.integers(1, 9)))
+        torch.cuda.synchronize()
+        assert np.array_equal(to_bits(o2), want[0]) and np.array_equal(to_bits(r2), want[1]), (what, "split", k)
