@@ -134,3 +134,23 @@ def test_overlap_launch_shared_mode_equals_the_two_calls(tw, torch_cuda):
         assert np.array_equal(to_bits(oc), to_bits(out0))
         assert np.array_equal(to_bits(rc), to_bits(res0))
         assert np.array_equal(to_bits(cc), to_bits(C0))
+
+
+def test_gemm_random_shapes_both_layouts(tw, torch_cuda):
+    """Seeded random M, N, K (N and K multiples of 8): both operand layouts and a
+    budgeted launch give the same bits, and those match the oracle."""
+    rng = np.random.default_rng(7)
+    for case in range(16):
+        M = int(rng.integers(1, 600))
+        N = 8 * int(rng.integers(1, 60))
+        K = 8 * int(rng.integers(1, 90))
+        a = W.make_gemm_inputs(M, K, N, 0.3, seed=100 + case, b_layout="nk")
+        b = W.make_gemm_inputs(M, K, N, 0.3, seed=100 + case, b_layout="kn")
+        C1 = tw.gemm_bf16(to_gpu(a["A"]), to_gpu(a["B"]), b_layout=tw.B_NK)
+        C2 = tw.gemm_bf16(to_gpu(b["A"]), to_gpu(b["B"]), b_layout=tw.B_KN)
+        C3 = tw.gemm_bf16(to_gpu(a["A"]), to_gpu(a["B"]), b_layout=tw.B_NK, cu_budget=int(rng.integers(1, 9)))
+        torch_cuda.cuda.synchronize()
+        what = "case %d: %dx%dx%d" % (case, M, N, K)
+        assert np.array_equal(to_bits(C1), to_bits(C2)), what
+        assert np.array_equal(to_bits(C1), to_bits(C3)), what
+        gemm_check(oracle.bf16_to_f64(to_bits(C1)), oracle.gemm(a["A"], a["B"], "nk"), K, 0.3, what)
