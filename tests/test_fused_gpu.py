@@ -253,6 +253,17 @@ def test_batch_longer_than_one_launch_can_address(tw, torch_cuda):
     idx = torch.from_numpy(rows).to("cuda:0")
     d = dict(partials=[to_bits(part[idx])], residual=to_bits(resid[idx]), weight=to_bits(w), eps=1e-5)
     check_against_oracle(d, to_bits(out[idx]), to_bits(res[idx]), "multi-launch batch")
+    # the same batch through the unfused pipeline (also cut into several launches) and through the
+    # shared mode, on the same sampled rows
+    o3, r3 = tw.reduce_add_rmsnorm([part], resid, w, 1e-5, cu_budget=tw.CU_SHARED)
+    torch.cuda.synchronize()
+    assert torch.equal(o3[idx], out[idx]) and torch.equal(r3[idx], res[idx])
+    del o3, r3
+    o2, r2 = tw.reduce_add_rmsnorm_unfused([part], resid, w, 1e-5)
+    torch.cuda.synchronize()
+    ref_out, ref_res = oracle.unfused(d["partials"], d["residual"], d["weight"], d["eps"])
+    assert_parity(oracle.bf16_to_f64(to_bits(o2[idx])), ref_out, "multi-launch unfused out")
+    assert np.array_equal(to_bits(r2[idx]), oracle.f64_to_bf16(ref_res))
 
 
 def test_traced_launch_reports_distinct_compute_units(tw, torch_cuda):
