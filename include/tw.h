@@ -89,9 +89,10 @@ typedef enum tw_status {
  *                 to run NEXT TO a tw_gemm_bf16 workgroup on the same compute
  *                 unit rather than in place of one; for H > 8192 it falls back
  *                 to the whole device. Other negative values mean the whole
- *                 device. A whole-device launch of at most two rows per compute
- *                 unit (eight when P >= 8; H <= 8192) is sent as those small
- *                 workgroups too: same bits, lower latency.
+ *                 device. A whole-device launch with P = 2 or 4 and at most two
+ *                 rows per compute unit, or P = 8 and at most eight (H <= 8192),
+ *                 is sent as those small workgroups too: same bits, lower
+ *                 latency.
  *   out           device bf16 [N x H]
  *   residual_out  device bf16 [N x H]
  *

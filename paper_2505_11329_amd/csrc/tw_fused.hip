@@ -520,18 +520,21 @@ static tw_status launch_vpt(const FusedParams &prm, int vpt, bool trace, int64_t
 
 // Which kernel a launch takes. Shared mode has a kernel for rows of up to 1024
 // vectors; wider rows run on the wide kernel over the whole device. A small
-// whole-device launch also takes the small workgroups: they are placed faster
-// and put every row in flight at once, where the wide kernel's software pipeline
-// has only a few rows per workgroup to run over. Measured on MI355X: faster up
-// to two rows per compute unit for any P (5-20 %), and up to eight rows per
-// compute unit when P >= 8 (2-8 %); slower well beyond that. Both kernels give
-// the same bits.
+// whole-device launch with P = 2, 4 or 8 also takes the small workgroups: they
+// are placed faster and put every row in flight at once, where the wide kernel's
+// software pipeline has only a few rows per workgroup to run over. Measured on
+// MI355X (H = 4096 and 8192, 32 ... 4096 rows, launch shapes without a ragged
+// last trip): P = 8 up to eight rows per compute unit (2-15 % faster), P = 2 and
+// 4 up to two rows per compute unit (0-11 %). Elsewhere the wide kernel is as
+// fast or faster; for P without a specialised kernel, whose loads go out four
+// at a time, by up to 40 % on small batches. Both kernels give the same bits.
 static bool takes_thin_kernel(int cu_budget, int cus, const FusedGeometry &g, int64_t n_rows, int P)
 {
     if (g.vpt != 1) return false;
     if (cu_budget == TW_CU_SHARED) return true;
-    const int64_t rows_per_cu = P >= 8 ? 8 : 2;
-    return resolve_budget(cu_budget, cus) == cus && n_rows <= rows_per_cu * cus;
+    if (resolve_budget(cu_budget, cus) != cus) return false;
+    const int64_t rows_per_cu = P == 8 ? 8 : (P == 2 || P == 4) ? 2 : 0;
+    return n_rows <= rows_per_cu * cus;
 }
 
 tw_status launch_fused(const tw_fused_args &a, int64_t row_begin, int64_t row_end, uint32_t *hw_ids,
