@@ -6,6 +6,7 @@
 // hardware byte counters are scaled against.
 #include <atomic>
 
+#include "tw_device.h"
 #include "tw_internal.h"
 
 namespace tw {
@@ -13,8 +14,6 @@ namespace tw {
 static constexpr int kProbeThreads = 1024;
 static constexpr unsigned kProbePadBytes = 96 * 1024;  // one workgroup per compute unit
 static constexpr int kInFlight = 8;
-
-typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
 
 template <int MODE>
 __global__ __launch_bounds__(kProbeThreads) void probe_kernel(const u32x4 *src, u32x4 *dst, long long n_vec)
@@ -63,8 +62,9 @@ __global__ __launch_bounds__(kProbeThreads) void probe_kernel(const u32x4 *src, 
 
 // The fused kernel's traffic shape without its arithmetic: per 16 KiB "row" a
 // workgroup reads NR streams and writes n_write streams at the same offset.
-// What this reaches is the ceiling for any kernel with that mix of loads and
-// stores at the given budget. NR is a template parameter so that exactly NR
+// Loads and stores carry the fused kernel's cache policies. What this reaches is
+// the ceiling for any kernel with that mix of loads and stores at the given
+// budget. NR is a template parameter so that exactly NR
 // loads are issued per row (a run-time count would issue dead ones).
 template <int NR>
 __global__ __launch_bounds__(kProbeThreads) void probe_mixed_kernel(const char *src, char *dst,
@@ -80,12 +80,12 @@ __global__ __launch_bounds__(kProbeThreads) void probe_mixed_kernel(const char *
             __amdgpu_buffer_rsrc_t rs = __builtin_amdgcn_make_buffer_rsrc(
                 const_cast<char *>(src) + static_cast<size_t>(r) * stream_bytes, 0,
                 static_cast<int>(stream_bytes), 0x00020000);
-            v[r] = __builtin_amdgcn_raw_buffer_load_b128(rs, off, 0, 2);
+            v[r] = __builtin_amdgcn_raw_buffer_load_b128(rs, off, 0, kStreamPolicy);
         }
         for (int wst = 0; wst < n_write; ++wst) {
             __amdgpu_buffer_rsrc_t rs = __builtin_amdgcn_make_buffer_rsrc(
                 dst + static_cast<size_t>(wst) * stream_bytes, 0, static_cast<int>(stream_bytes), 0x00020000);
-            __builtin_amdgcn_raw_buffer_store_b128(acc, rs, off, 0, 2);
+            __builtin_amdgcn_raw_buffer_store_b128(acc, rs, off, 0, kStorePolicy);
         }
 #pragma unroll
         for (int r = 0; r < NR; ++r) acc ^= v[r];
