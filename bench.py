@@ -102,12 +102,18 @@ def main():
         return np.array([a.elapsed_time(b) for a, b in evs]) * 1e3
 
     def interleaved_medians(cands, rounds=4, iters=8, warm=2):
-        """Median launch time (µs) of each candidate {key: fn}; the candidates take turns in short bursts so
-        that clock and temperature drift hits all of them alike (the GEMMs are power-limited)."""
-        acc = {k: [] for k in cands}
-        for _ in range(rounds):
-            for k, fn in cands.items():
-                acc[k].append(event_times([fn], iters, warm, stream))
+        """Median launch time (µs) of each candidate {key: fn or list of fns}. The candidates take turns in
+        short bursts so that clock and temperature drift hits all of them alike (the GEMMs are power-limited),
+        and the order rotates from round to round: what ran just before a burst moves its times by a few
+        percent, so no candidate keeps the same predecessor."""
+        keys = list(cands)
+        acc = {k: [] for k in keys}
+        step = max(1, len(keys) // rounds)
+        for r in range(rounds):
+            shift = (r * step) % len(keys)
+            for k in keys[shift:] + keys[:shift]:
+                fns = cands[k] if isinstance(cands[k], (list, tuple)) else [cands[k]]
+                acc[k].append(event_times(fns, iters, warm, stream))
         return {k: round(float(np.median(np.concatenate(v))), 1) for k, v in acc.items()}
 
     if args.sweep:
@@ -305,7 +311,7 @@ def main():
     }
 
     if not args.no_extras:
-        extras(result, tw, W, torch, np, stream, sets, fused_sets, algo_bytes, event_times, gpu)
+        extras(result, tw, W, torch, np, stream, sets, fused_sets, algo_bytes, event_times, interleaved_medians, gpu)
     del sets, launches
     torch.cuda.empty_cache()
     if not args.no_cpu_baseline:
@@ -313,7 +319,7 @@ def main():
     print(json.dumps(result))
 
 
-def extras(result, tw, W, torch, np, stream, sets, fused_sets, algo_bytes, event_times, gpu):
+def extras(result, tw, W, torch, np, stream, sets, fused_sets, algo_bytes, event_times, interleaved_medians, gpu):
     """Per-budget table, probe ceilings, split sweep, overlap demo. All outside the timed region."""
     nbytes = algo_bytes(sets[0])
 
@@ -470,14 +476,11 @@ def extras(result, tw, W, torch, np, stream, sets, fused_sets, algo_bytes, event
                                   out=s["out"], residual_out=s["res_out"], stream=stream)
             tw.gemm_bf16(A, B, C=C, cu_budget=0, stream=stream)
         return f
-    # interleave the four schedules
-    ts, to, tsh, tww = [], [], [], []
-    for rep in range(6):
-        ts.append(event_times([serial_fn(s) for s in s5], 10, 2, stream))
-        tww.append(event_times([serial_whole_fn(s) for s in s5], 10, 2, stream))
-        to.append(event_times([overlap_fn(s, 32, cus_total - 32) for s in s5], 10, 2, stream))
-        tsh.append(event_times([overlap_fn(s, tw.CU_SHARED, 0) for s in s5], 10, 2, stream))
-    ts, to, tsh, tw_ = np.concatenate(ts), np.concatenate(to), np.concatenate(tsh), np.concatenate(tww)
+    # the schedules take turns, in rotating order
+    ov = interleaved_medians({
+        "serial32": [serial_fn(s) for s in s5], "serial_whole": [serial_whole_fn(s) for s in s5],
+        "budget32": [overlap_fn(s, 32, cus_total - 32) for s in s5],
+        "shared": [overlap_fn(s, tw.CU_SHARED, 0) for s in s5]}, rounds=8, iters=10, warm=2)
 
     # each kernel's own duration while the other runs: event pairs on the two streams
     def contended(fused_budget, gemm_budget, gemm_first):
@@ -515,13 +518,13 @@ def extras(result, tw, W, torch, np, stream, sets, fused_sets, algo_bytes, event
         "fused_alone_us": round(float(np.median(tf)), 1), "gemm_alone_us": round(float(np.median(tg)), 1),
         "gemm_alone_TFLOPs": round(flops / np.median(tg) / 1e6, 1),
         "gemm_frac_mfma_peak": round(flops / np.median(tg) / 1e6 / MFMA_BF16_PEAK_TFLOPS, 4),
-        "serial_budget32_us": round(float(np.median(ts)), 1),
-        "serial_whole_device_us": round(float(np.median(tw_)), 1),
-        "overlapped_budget32_us": round(float(np.median(to)), 1),
-        "overlapped_shared_us": round(float(np.median(tsh)), 1),
-        "gain_budget32_vs_serial_budget32": round(float(np.median(ts) / np.median(to)), 3),
-        "gain_budget32_vs_serial_whole_device": round(float(np.median(tw_) / np.median(to)), 3),
-        "gain_shared_vs_serial_whole_device": round(float(np.median(tw_) / np.median(tsh)), 3),
+        "serial_budget32_us": ov["serial32"],
+        "serial_whole_device_us": ov["serial_whole"],
+        "overlapped_budget32_us": ov["budget32"],
+        "overlapped_shared_us": ov["shared"],
+        "gain_budget32_vs_serial_budget32": round(ov["serial32"] / ov["budget32"], 3),
+        "gain_budget32_vs_serial_whole_device": round(ov["serial_whole"] / ov["budget32"], 3),
+        "gain_shared_vs_serial_whole_device": round(ov["serial_whole"] / ov["shared"], 3),
         "under_contention_budget32": {"fused_us": round(cont_f32, 1), "fused_GBps": round(nb5 / cont_f32 / 1e3, 1),
                                       "gemm_us": round(cont_g32, 1)},
         "under_contention_shared": {"fused_us": round(cont_fsh, 1), "fused_GBps": round(nb5 / cont_fsh / 1e3, 1),
@@ -530,7 +533,7 @@ def extras(result, tw, W, torch, np, stream, sets, fused_sets, algo_bytes, event
                 "then GEMM on all CUs (the best schedule without overlap); overlapped_budget32 = tw_overlap_launch, "
                 "fused confined to 32 CUs, GEMM on the other 224; overlapped_shared = tw_overlap_launch with "
                 "cu_budget=TW_CU_SHARED: small fused workgroups co-resident with the GEMM's on every CU. The "
-                "caller's stream is the compute stream; trials interleaved; makespans include fork and join",
+                "caller's stream is the compute stream; the schedules take turns in bursts, in rotating order; makespans include fork and join",
     }
     del s5
     torch.cuda.empty_cache()
@@ -555,7 +558,7 @@ def extras(result, tw, W, torch, np, stream, sets, fused_sets, algo_bytes, event
                                fused_cu_budget=fb, gemm_cu_budget=gb, out=out, residual_out=res_out, Y=Y,
                                parent=stream, use_parent=True, join=True)
         return f
-    # the schedules take turns in bursts of 8 calls (the GEMMs are power-limited: drift hits all alike)
+    # the schedules take turns in bursts of 8 calls, in rotating order
     cands = {"unsplit": layer_fn(0, 0, 0)}
     plan = {}
     for fb in (32, 64, 96):
@@ -566,11 +569,7 @@ def extras(result, tw, W, torch, np, stream, sets, fused_sets, algo_bytes, event
     k, ws, wu = tw.smart_split_point(T, 128, [H, N2], cus, gemm_k=[K1, H])
     plan["shared"] = (k, ws, wu)
     cands["woven_shared"] = layer_fn(k, tw.CU_SHARED, 0)
-    acc = {c: [] for c in cands}
-    for _ in range(4):
-        for c, fn in cands.items():
-            acc[c].append(event_times([fn], 8, 2, stream))
-    med = {c: round(float(np.median(np.concatenate(v))), 1) for c, v in acc.items()}
+    med = interleaved_medians(cands, rounds=5, iters=8, warm=2)
     weave = {"unsplit_whole_device_us": med["unsplit"]}
     for fb in (32, 64, 96):
         k, ws, wu = plan[fb]
