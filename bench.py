@@ -171,23 +171,29 @@ def main():
             out, res_out = torch.empty_like(resid), torch.empty_like(resid)
             Y = torch.empty((T, N2), dtype=torch.bfloat16, device=dev)
 
-            def layer_fn(split_row):
+            def layer_fn(split_row, schedule=tw.WEAVE_AUTO):
                 def f():
                     with torch.cuda.stream(stream):
                         tw.weave_layer(X1, W1, parts, resid, weight, 1e-5, W2, split_row, stream, comm,
                                        fused_cu_budget=tw.CU_SHARED, gemm_cu_budget=0, out=out,
-                                       residual_out=res_out, Y=Y, parent=stream, use_parent=True, join=True)
+                                       residual_out=res_out, Y=Y, parent=stream, use_parent=True, join=True,
+                                       schedule=schedule)
                 return f
             half = (T // 2 + 63) // 64 * 64
             k_smart, ws, wu = tw.smart_split_point(T, 64, [H, N2], cus, gemm_k=[K1, H])
             ks = sorted({half + off for off in (0, 64, 128, 192, 256, 512) if half + off < T} | {k_smart})
-            timed = interleaved_medians({k: layer_fn(k) for k in [0] + ks})
+            cands = {k: layer_fn(k) for k in [0] + ks}
+            for k in sorted({half, k_smart}):      # the same two cuts under the other schedule
+                cands["ordered_%d" % k] = layer_fn(k, tw.WEAVE_ORDERED)
+            timed = interleaved_medians(cands)
             unsplit_us = timed.pop(0)
+            ordered = {int(k[8:]): timed.pop(k) for k in list(timed) if isinstance(k, str)}
             k_best = min(timed, key=timed.get)
             rows.append({"T": T, "equal_split_row": half, "equal_us": timed[half],
                          "measured_best_row": k_best, "measured_best_us": timed[k_best],
                          "smart_row": k_smart, "smart_us": timed[k_smart],
                          "model_cost_split": ws, "model_cost_unsplit": wu, "unsplit_us": unsplit_us,
+                         "ordered_equal_us": ordered[half], "ordered_smart_us": ordered[k_smart],
                          "all_us": {str(k): v for k, v in sorted(timed.items())}})
             del X1, resid, parts, out, res_out, Y
             torch.cuda.empty_cache()
@@ -207,12 +213,12 @@ def main():
                                       stream=stream)
                 tw.gemm_bf16(out, W2, C=Y, stream=stream)
 
-            def woven(split_row, fb, gb):
+            def woven(split_row, fb, gb, schedule=tw.WEAVE_AUTO):
                 def f():
                     with torch.cuda.stream(stream):
                         tw.weave_layer(X1, W1, parts, resid, weight, 1e-5, W2, split_row, stream, comm,
                                        fused_cu_budget=fb, gemm_cu_budget=gb, out=out, residual_out=res_out, Y=Y,
-                                       parent=stream, use_parent=True, join=True)
+                                       parent=stream, use_parent=True, join=True, schedule=schedule)
                 return f
             cands = {"plain_us": plain}
             row = {"T": T}
@@ -220,6 +226,8 @@ def main():
             if k < T:
                 row["split_row"] = k
                 cands["woven_shared_us"] = woven(k, tw.CU_SHARED, 0)
+                cands["woven_shared_ordered_us"] = woven(k, tw.CU_SHARED, 0, tw.WEAVE_ORDERED)
+                cands["woven_shared_chains_us"] = woven(k, tw.CU_SHARED, 0, tw.WEAVE_CHAINS)
             k32, _, _ = tw.smart_split_point(T, 64, [H, N2], cus - 32, gemm_k=[K1, H])
             if k32 < T:
                 cands["woven_budget32_us"] = woven(k32, 32, cus - 32)
@@ -233,11 +241,14 @@ def main():
             return round(float(rate.std() / rate.mean()), 4)
         print(json.dumps({"split_sweep": rows, "threshold_sweep": thr,
                           "tokens_per_us_relative_spread": {"equal": spread("equal_us"), "smart": spread("smart_us"),
-                                                            "measured_best": spread("measured_best_us")},
+                                                            "measured_best": spread("measured_best_us"),
+                                                            "ordered_equal": spread("ordered_equal_us"),
+                                                            "ordered_smart": spread("ordered_smart_us")},
                           "note": "layer boundary [Tx1024]x[1024x8192] -> fused H=8192 P=8 (shared mode) -> "
                                   "[Tx8192]x[8192x3584]; medians of HIP-event timed calls of tw_weave_layer, the "
                                   "candidates of one T taking turns in bursts of 8; smart_row comes from tile "
-                                  "counts alone"}))
+                                  "counts alone; the schedule is the library's choice (TW_WEAVE_AUTO) except "
+                                  "in the threshold sweep's _ordered and _chains columns"}))
         return
     if args.counters_run == "gemm":
         gc = W.CONFIGS["c5_overlap_tp8"]["gemm"]
@@ -551,12 +562,12 @@ def extras(result, tw, W, torch, np, stream, sets, fused_sets, algo_bytes, event
     Y = torch.empty((T, N2), dtype=torch.bfloat16, device="cuda:0")
     cus = tw.device_cu_count()
 
-    def layer_fn(split_row, fb, gb):
+    def layer_fn(split_row, fb, gb, schedule=tw.WEAVE_AUTO):
         def f():
             with torch.cuda.stream(stream):
                 tw.weave_layer(X1, W1, parts, resid, weight, d["eps"], W2, split_row, stream, comm,
                                fused_cu_budget=fb, gemm_cu_budget=gb, out=out, residual_out=res_out, Y=Y,
-                               parent=stream, use_parent=True, join=True)
+                               parent=stream, use_parent=True, join=True, schedule=schedule)
         return f
     # the schedules take turns in bursts of 8 calls, in rotating order
     cands = {"unsplit": layer_fn(0, 0, 0)}
@@ -569,6 +580,8 @@ def extras(result, tw, W, torch, np, stream, sets, fused_sets, algo_bytes, event
     k, ws, wu = tw.smart_split_point(T, 128, [H, N2], cus, gemm_k=[K1, H])
     plan["shared"] = (k, ws, wu)
     cands["woven_shared"] = layer_fn(k, tw.CU_SHARED, 0)
+    cands["woven_shared_ordered"] = layer_fn(k, tw.CU_SHARED, 0, tw.WEAVE_ORDERED)
+    cands["woven_shared_chains"] = layer_fn(k, tw.CU_SHARED, 0, tw.WEAVE_CHAINS)
     med = interleaved_medians(cands, rounds=5, iters=8, warm=2)
     weave = {"unsplit_whole_device_us": med["unsplit"]}
     for fb in (32, 64, 96):
@@ -578,12 +591,14 @@ def extras(result, tw, W, torch, np, stream, sets, fused_sets, algo_bytes, event
                                          "unsplit_same_budgets_us": med["unsplit_%d" % fb]}
     k, ws, wu = plan["shared"]
     weave["fused_shared"] = {"split_row": k, "model_cost_split": ws, "model_cost_unsplit": wu,
-                             "woven_us": med["woven_shared"]}
+                             "woven_us": med["woven_shared"], "woven_ordered_us": med["woven_shared_ordered"],
+                             "woven_chains_us": med["woven_shared_chains"]}
     result["weave_layer"] = {
         "workload": "T=4096: G1 [Tx1024]x[1024x8192] -> fused H=8192 P=8 -> G2 [Tx8192]x[8192x3584], bf16",
         "cases": weave,
         "note": "woven = tw_weave_layer at the wave-aware split row, fused kernel confined to its budget and the "
-                "GEMMs to the other CUs; unsplit_same_budgets = same budgets, no split; unsplit_whole_device = "
+                "GEMMs to the other CUs (fused_shared: co-resident; woven_us with the schedule the library "
+                "picks, then each schedule forced); unsplit_same_budgets = same budgets, no split; unsplit_whole_device = "
                 "each kernel on all CUs in turn, one stream, no events; the schedules take turns in bursts",
     }
 

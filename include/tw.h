@@ -245,13 +245,25 @@ tw_status tw_overlap_launch(const tw_fused_args *fused, const tw_gemm_args *gemm
  *   F : the fused step of tw_fused_args over all P partials and the residual
  *   G2: Y = out * W2^T            [T x H] x [N2 x H]^T   the next projection
  *
- * run for the two token splits a = [0, split_row) and b = [split_row, T). GEMMs
- * go to stream_compute in the order G1(a) G1(b) G2(a) G2(b), fused kernels to
- * stream_comm in the order F(a) F(b); events make F(s) wait for G1(s) and G2(s)
- * wait for F(s), so F(a) runs next to G1(b) and F(b) next to G2(a). With
- * split_row == 0 or == T the chain G1, F, G2 runs unsplit on stream_compute alone
- * (nothing overlaps, no events).
- * Results are bit-identical for every split_row.
+ * run for the two token splits a = [0, split_row) and b = [split_row, T), in one
+ * of two schedules:
+ *   TW_WEAVE_ORDERED  GEMMs go to stream_compute in the order G1(a) G1(b) G2(a)
+ *       G2(b), fused kernels to stream_comm in the order F(a) F(b); events make
+ *       F(s) wait for G1(s) and G2(s) wait for F(s), so F(a) runs next to G1(b)
+ *       and F(b) next to G2(a). No two GEMMs ever compete, but three waits on
+ *       another stream (15-20 us each on MI355X) lie on the critical path.
+ *   TW_WEAVE_CHAINS   each split is a chain of its own: G1(a) F(a) G2(a) on
+ *       stream_compute, G1(b) F(b) G2(b) on stream_comm, the second chain held
+ *       back until G1(a) is done so that the two stay out of step. One wait on
+ *       another stream, off the critical path; what overlaps with what is left
+ *       to the hardware.
+ *   TW_WEAVE_AUTO     chains when the fused kernel is not confined to a CU budget
+ *       (shared mode or whole device) and the unsplit chain is estimated to take
+ *       under 700 us, where the waits of the ordered schedule cost more than its
+ *       stricter order gains; ordered otherwise.
+ * With split_row == 0 or == T the chain G1, F, G2 runs unsplit on stream_compute
+ * alone (nothing overlaps, no events).
+ * Results are bit-identical for every split_row and schedule.
  *
  *   X1, W1, K1   device bf16 [T x K1] and [H x K1] (TW_B_NK), K1 a multiple of 8
  *   fused        as for tw_reduce_add_rmsnorm with N = T; fused.partials[0] is
@@ -264,6 +276,10 @@ tw_status tw_overlap_launch(const tw_fused_args *fused, const tw_gemm_args *gemm
  * The two streams must differ. Buffers must satisfy the aliasing rules of the
  * three operations they take part in.
  */
+#define TW_WEAVE_AUTO 0
+#define TW_WEAVE_ORDERED 1
+#define TW_WEAVE_CHAINS 2
+
 typedef struct tw_layer_args {
     const void *X1;
     const void *W1;
@@ -273,6 +289,7 @@ typedef struct tw_layer_args {
     int64_t N2;
     void *Y;
     int gemm_cu_budget;
+    int schedule; /* TW_WEAVE_AUTO, TW_WEAVE_ORDERED or TW_WEAVE_CHAINS; others: TW_ERR_UNSUPPORTED */
 } tw_layer_args;
 
 tw_status tw_weave_layer(const tw_layer_args *layer, int64_t split_row, void *stream_compute,

@@ -29,5 +29,5 @@ from .binding import (  # noqa: F401
     GemmArgs,
     STATUS,
     PROBE_READ, PROBE_COPY, PROBE_WRITE,
-    B_NK, B_KN, CU_SHARED,
+    B_NK, B_KN, CU_SHARED, WEAVE_AUTO, WEAVE_ORDERED, WEAVE_CHAINS,
 )

@@ -18,6 +18,7 @@ STATUS = {0: "TW_OK", 1: "TW_ERR_NULL", 2: "TW_ERR_SHAPE", 3: "TW_ERR_ALIGN", 4:
 PROBE_READ, PROBE_COPY, PROBE_WRITE = 0, 1, 2
 B_NK, B_KN = 0, 1
 CU_SHARED = -1
+WEAVE_AUTO, WEAVE_ORDERED, WEAVE_CHAINS = 0, 1, 2
 MAX_P = 16
 
 _vp = ctypes.c_void_p
@@ -40,7 +41,7 @@ class GemmArgs(ctypes.Structure):
 class LayerArgs(ctypes.Structure):
     """struct tw_layer_args"""
     _fields_ = [("X1", _vp), ("W1", _vp), ("K1", _i64), ("fused", FusedArgs), ("W2", _vp), ("N2", _i64),
-                ("Y", _vp), ("gemm_cu_budget", ctypes.c_int)]
+                ("Y", _vp), ("gemm_cu_budget", ctypes.c_int), ("schedule", ctypes.c_int)]
 
 
 class TwError(RuntimeError):
@@ -343,7 +344,7 @@ def gemm_tile_shape():
 
 def weave_layer(X1, W1, partials, residual, weight, eps, W2, split_row, stream_compute, stream_comm,
                 fused_cu_budget=32, gemm_cu_budget=0, out=None, residual_out=None, Y=None, parent=None,
-                use_parent=True, join=True):
+                use_parent=True, join=True, schedule=WEAVE_AUTO):
     """tw_weave_layer. partials[0] is overwritten with X1 @ W1.T. Returns (out, residual_out, Y)."""
     import torch
     a, keep, out, residual_out = _fused_pack(partials, residual, weight, eps, fused_cu_budget, out, residual_out)
@@ -353,7 +354,7 @@ def weave_layer(X1, W1, partials, residual, weight, eps, W2, split_row, stream_c
     if Y is None:
         Y = torch.empty((T, N2), dtype=torch.bfloat16, device=residual.device)
     la = LayerArgs(_bf16_ptr(X1, "X1", (T, K1)), _bf16_ptr(W1, "W1", (H, K1)), K1, a,
-                   _bf16_ptr(W2, "W2", (N2, H)), N2, _bf16_ptr(Y, "Y", (T, N2)), int(gemm_cu_budget))
+                   _bf16_ptr(W2, "W2", (N2, H)), N2, _bf16_ptr(Y, "Y", (T, N2)), int(gemm_cu_budget), int(schedule))
     _check(lib().tw_weave_layer(ctypes.byref(la), int(split_row), _stream_handle(stream_compute),
                                 _stream_handle(stream_comm),
                                 _stream_handle(parent) if use_parent else _vp(None),

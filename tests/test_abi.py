@@ -317,8 +317,13 @@ def test_weave_layer_argument_checks():
     la.fused.H = 60
     assert L.tw_weave_layer(ctypes.byref(la), 2, VP(1), VP(2), VP(None), 0, 0) == E_UNSUP
     la.fused.H = H
+    for bad in (-1, 3, 99):
+        la.schedule = bad
+        assert L.tw_weave_layer(ctypes.byref(la), 2, VP(1), VP(2), VP(None), 0, 0) == E_UNSUP
     la.fused.N = 0
-    assert L.tw_weave_layer(ctypes.byref(la), 0, VP(1), VP(2), VP(None), 0, 0) == OK
+    for schedule in (tw.WEAVE_AUTO, tw.WEAVE_ORDERED, tw.WEAVE_CHAINS):
+        la.schedule = schedule
+        assert L.tw_weave_layer(ctypes.byref(la), 0, VP(1), VP(2), VP(None), 0, 0) == OK
 
 
 def test_should_split_threshold():

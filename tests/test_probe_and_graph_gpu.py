@@ -54,7 +54,8 @@ def test_mixed_probe_writes_only_its_write_streams(tw, torch_cuda):
     assert torch.equal(src, before)
 
 
-def test_weave_layer_can_be_captured_in_a_hip_graph(tw, torch_cuda):
+@pytest.mark.parametrize("schedule", [1, 2])   # TW_WEAVE_ORDERED, TW_WEAVE_CHAINS
+def test_weave_layer_can_be_captured_in_a_hip_graph(tw, torch_cuda, schedule):
     """tw_weave_layer forks and joins a second stream with events; captured on the
     caller's stream it becomes one graph. Every replay (with eager work and
     synchronisations in between) must reproduce the eager result bit for bit."""
@@ -75,7 +76,7 @@ def test_weave_layer_can_be_captured_in_a_hip_graph(tw, torch_cuda):
     def layer():
         tw.weave_layer(X1, W1, parts, resid, weight, f["eps"], W2, 256, main, comm,
                        fused_cu_budget=tw.CU_SHARED, gemm_cu_budget=0, out=out, residual_out=res, Y=Y,
-                       parent=main, use_parent=True, join=True)
+                       parent=main, use_parent=True, join=True, schedule=schedule)
     with torch.cuda.stream(main):
         layer()                                   # eager: also the warm-up that capture needs
     torch.cuda.synchronize()

@@ -37,12 +37,13 @@ def make_inputs():
     return g1, f, W2
 
 
-def run_layer(tw, torch, g1, f, W2, split_row, streams, parent=None):
+def run_layer(tw, torch, g1, f, W2, split_row, streams, parent=None, budgets=(32, 224), schedule=1):
     X1, W1 = to_gpu(g1["A"]), to_gpu(g1["B"])
     parts = [torch.zeros((T, H), dtype=torch.bfloat16, device="cuda:0")] + [to_gpu(p) for p in f["partials"][1:]]
     out, res, Y = tw.weave_layer(X1, W1, parts, to_gpu(f["residual"]), to_gpu(f["weight"]), f["eps"], to_gpu(W2),
-                                 split_row, streams[0], streams[1], fused_cu_budget=32, gemm_cu_budget=224,
-                                 parent=parent, use_parent=True, join=True)
+                                 split_row, streams[0], streams[1], fused_cu_budget=budgets[0],
+                                 gemm_cu_budget=budgets[1], parent=parent, use_parent=True, join=True,
+                                 schedule=schedule)
     torch.cuda.synchronize()
     return to_bits(parts[0]), to_bits(out), to_bits(res), to_bits(Y)
 
@@ -66,9 +67,18 @@ def test_weave_layer_stagewise_parity_and_split_invariance(tw, torch_cuda):
         C, out, res, Y = run_layer(tw, torch, g1, f, W2, k, streams)
         assert np.array_equal(C, C0) and np.array_equal(out, out0), k
         assert np.array_equal(res, res0) and np.array_equal(Y, Y0), k
+    # the other schedule (one chain per split) and the library's own choice, with the fused kernel
+    # confined to a budget, co-resident, and on the whole device
+    for schedule in (tw.WEAVE_CHAINS, tw.WEAVE_AUTO):
+        for budgets in ((32, 224), (tw.CU_SHARED, 0), (0, 0)):
+            for k in (256, 100, T - 1):
+                C, out, res, Y = run_layer(tw, torch, g1, f, W2, k, streams, budgets=budgets, schedule=schedule)
+                assert np.array_equal(C, C0) and np.array_equal(out, out0), (schedule, budgets, k)
+                assert np.array_equal(res, res0) and np.array_equal(Y, Y0), (schedule, budgets, k)
 
 
-def test_weave_layer_orders_itself_after_the_parent_stream(tw, torch_cuda):
+@pytest.mark.parametrize("schedule", [1, 2])   # TW_WEAVE_ORDERED, TW_WEAVE_CHAINS
+def test_weave_layer_orders_itself_after_the_parent_stream(tw, torch_cuda, schedule):
     torch = torch_cuda
     g1, f, W2 = make_inputs()
     streams = (torch.cuda.Stream(), torch.cuda.Stream())
@@ -84,7 +94,7 @@ def test_weave_layer_orders_itself_after_the_parent_stream(tw, torch_cuda):
             X1.zero_()
             X1.copy_(X1_src)             # the input is produced on the parent right before the launch
             out, res, Y = tw.weave_layer(X1, W1, parts, resid, weight, f["eps"], W2g, 384, streams[0], streams[1],
-                                         fused_cu_budget=32, gemm_cu_budget=224, parent=parent)
+                                         fused_cu_budget=32, gemm_cu_budget=224, parent=parent, schedule=schedule)
             yc, oc = Y.clone(), out.clone()   # and consumed on it right after
         parent.synchronize()
         assert np.array_equal(to_bits(yc), want[3]) and np.array_equal(to_bits(oc), want[1])
