@@ -51,10 +51,13 @@ def main():
                     help="instead of the benchmark line: for a range of token counts, the woven layer boundary "
                          "timed at the equal split and at the offsets {0,64,128,192,256,512} past it (the sweep "
                          "of Algorithm 1), next to the row tw_smart_split_point picks without timing anything")
-    ap.add_argument("--counters-run", choices=("fused", "gemm"), default=None,
+    ap.add_argument("--counters-run", choices=("fused", "gemm", "weave"), default=None,
                     help="for rocprofv3 --pmc. fused: a few fused launches plus plain copy launches of known "
                          "size (tw_hbm_probe, 192 MiB read + 192 MiB written each) to scale the byte counters "
-                         "by. gemm: a few launches of the bf16 GEMM on the overlap demo's shape")
+                         "by. gemm: a few launches of the bf16 GEMM on the overlap demo's shape. weave (for "
+                         "rocprofv3 --kernel-trace): the T=4096 layer boundary unsplit, then woven in the "
+                         "ordered schedule, then as one chain per split, five calls each with a device "
+                         "synchronisation after every call, so that the trace shows which kernels overlap")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on ONE GPU (no collectives, no sharding); --gpus %d is not "
@@ -249,6 +252,29 @@ def main():
                                   "candidates of one T taking turns in bursts of 8; smart_row comes from tile "
                                   "counts alone; the schedule is the library's choice (TW_WEAVE_AUTO) except "
                                   "in the threshold sweep's _ordered and _chains columns"}))
+        return
+    if args.counters_run == "weave":
+        T, K1, H, P, N2 = 4096, 1024, 8192, 8, 3584
+        gen = torch.Generator(device=dev)
+        gen.manual_seed(0)
+
+        def rnd(shape, std):
+            return torch.empty(shape, dtype=torch.bfloat16, device=dev).normal_(0.0, std, generator=gen)
+        X1, W1, W2 = rnd((T, K1), 0.02), rnd((H, K1), 0.02), rnd((N2, H), 0.02)
+        parts, resid = [rnd((T, H), 0.25) for _ in range(P)], rnd((T, H), 1.0)
+        weight = gpu(W.uniform_bf16((H,), 0.5, 1.5, 0, W.STREAM_WEIGHT))
+        comm = torch.cuda.Stream()
+        k, _, _ = tw.smart_split_point(T, 128, [H, N2], tw.device_cu_count(), gemm_k=[K1, H])
+        order = [("unsplit", 0, tw.WEAVE_ORDERED), ("ordered", k, tw.WEAVE_ORDERED), ("chains", k, tw.WEAVE_CHAINS)]
+        for name, split_row, schedule in order:
+            for i in range(5):
+                with torch.cuda.stream(stream):
+                    tw.weave_layer(X1, W1, parts, resid, weight, 1e-5, W2, split_row, stream, comm,
+                                   fused_cu_budget=tw.CU_SHARED, gemm_cu_budget=0, parent=stream, use_parent=True,
+                                   join=True, schedule=schedule)
+                torch.cuda.synchronize()
+        print(json.dumps({"counters_run": "weave", "T": T, "split_row": k, "calls_per_schedule": 5,
+                          "order": [o[0] for o in order]}))
         return
     if args.counters_run == "gemm":
         gc = W.CONFIGS["c5_overlap_tp8"]["gemm"]
