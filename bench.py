@@ -45,8 +45,9 @@ def main():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--sweep", action="store_true",
                     help="instead of the benchmark line: token sweep 32..64K of the fused kernel at H=8192 (P=8, "
-                         "P=4) and H=4096 (P=2), whole device / shared / 32 CUs, one JSON object (the analogue of "
-                         "the paper's Tables 1-2)")
+                         "P=4) and H=4096 (P=2), whole device / shared / 32 CUs (the analogue of the paper's "
+                         "Tables 1-2), and a sweep over hidden sizes 1024..16384 at a fixed volume, one JSON "
+                         "object")
     ap.add_argument("--split-sweep", action="store_true",
                     help="instead of the benchmark line: for a range of token counts, the woven layer boundary "
                          "timed at the equal split and at the offsets {0,64,128,192,256,512} past it (the sweep "
@@ -120,41 +121,49 @@ def main():
         return {k: round(float(np.median(np.concatenate(v))), 1) for k, v in acc.items()}
 
     if args.sweep:
+        def sweep_point(H, P, N, cfgname):
+            per_set = (P + 3) * 2 * H * N
+            nsets = max(2, min(6, int((600 << 20) // per_set) + 1))
+            if nsets * per_set > (12 << 30):
+                nsets = 2
+            ss = []
+            for k in range(nsets):
+                # large batches are drawn on the GPU (same distributions): the host generator is slow
+                gen = torch.Generator(device=dev)
+                gen.manual_seed(1000 * k + N)
+                cfg = W.CONFIGS[cfgname]
+                parts = [torch.empty((N, H), dtype=torch.bfloat16, device=dev).normal_(0.0, cfg["partial_std"],
+                                                                                        generator=gen)
+                         for _ in range(P)]
+                resid = torch.empty((N, H), dtype=torch.bfloat16, device=dev).normal_(0.0, 1.0, generator=gen)
+                s_ = dict(partials=parts, residual=resid, weight=gpu(W.uniform_bf16((H,), 0.5, 1.5, 0,
+                                                                                   W.STREAM_WEIGHT)),
+                          eps=cfg["eps"], N=N, H=H, P=P, out=torch.empty_like(resid),
+                          res_out=torch.empty_like(resid))
+                ss.append(s_)
+            row = {"H": H, "P": P, "N": N, "algorithmic_MB": round(per_set / 1e6, 2)}
+            for label, b in (("whole_device", 0), ("shared", tw.CU_SHARED), ("budget32", 32)):
+                fns = [tw.prepare_reduce_add_rmsnorm(x["partials"], x["residual"], x["weight"], x["eps"],
+                                                     cu_budget=b, out=x["out"], residual_out=x["res_out"],
+                                                     stream=stream)[0] for x in ss]
+                iters = 40 if N <= 8192 else 12
+                t = event_times(fns, iters, 4, stream)
+                row[label + "_us"] = round(float(np.median(t)), 2)
+                row[label + "_GBps"] = round(per_set / np.median(t) / 1e3, 1)
+            del ss
+            torch.cuda.empty_cache()
+            return row
         rows = []
         for (H, P, cfgname) in ((8192, 8, "c3_70b_shard_tp8"), (8192, 4, "c4_split_sweep_tp4"), (4096, 2, "c2_8b_tp2")):
             for N in (32, 64, 128, 256, 512, 1024, 2048, 4096, 8192, 16384, 32768, 65536):
-                per_set = (P + 3) * 2 * H * N
-                nsets = max(2, min(6, int((600 << 20) // per_set) + 1))
-                if nsets * per_set > (12 << 30):
-                    nsets = 2
-                ss = []
-                for k in range(nsets):
-                    # large batches are drawn on the GPU (same distributions): the host generator is slow
-                    gen = torch.Generator(device=dev)
-                    gen.manual_seed(1000 * k + N)
-                    cfg = W.CONFIGS[cfgname]
-                    parts = [torch.empty((N, H), dtype=torch.bfloat16, device=dev).normal_(0.0, cfg["partial_std"],
-                                                                                            generator=gen)
-                             for _ in range(P)]
-                    resid = torch.empty((N, H), dtype=torch.bfloat16, device=dev).normal_(0.0, 1.0, generator=gen)
-                    s_ = dict(partials=parts, residual=resid, weight=gpu(W.uniform_bf16((H,), 0.5, 1.5, 0,
-                                                                                       W.STREAM_WEIGHT)),
-                              eps=cfg["eps"], N=N, H=H, P=P, out=torch.empty_like(resid),
-                              res_out=torch.empty_like(resid))
-                    ss.append(s_)
-                row = {"H": H, "P": P, "N": N, "algorithmic_MB": round(per_set / 1e6, 2)}
-                for label, b in (("whole_device", 0), ("shared", tw.CU_SHARED), ("budget32", 32)):
-                    fns = [tw.prepare_reduce_add_rmsnorm(x["partials"], x["residual"], x["weight"], x["eps"],
-                                                         cu_budget=b, out=x["out"], residual_out=x["res_out"],
-                                                         stream=stream)[0] for x in ss]
-                    iters = 40 if N <= 8192 else 12
-                    t = event_times(fns, iters, 4, stream)
-                    row[label + "_us"] = round(float(np.median(t)), 2)
-                    row[label + "_GBps"] = round(per_set / np.median(t) / 1e3, 1)
-                rows.append(row)
-                del ss
-                torch.cuda.empty_cache()
-        print(json.dumps({"sweep": rows, "note": "median of HIP-event timed launches, rotating buffer sets, bf16"}))
+                rows.append(sweep_point(H, P, N, cfgname))
+        # hidden sizes between and beyond the paper's two, at ~180 MB of algorithmic bytes each
+        hidden = []
+        for (P, cfgname) in ((8, "c3_70b_shard_tp8"), (2, "c2_8b_tp2")):
+            for H in (1024, 2048, 2560, 3072, 3584, 4096, 5120, 6144, 7168, 8192, 10240, 12288, 16384):
+                hidden.append(sweep_point(H, P, int(180e6 / ((P + 3) * 2 * H)) // 64 * 64, cfgname))
+        print(json.dumps({"sweep": rows, "hidden_size_sweep": hidden,
+                          "note": "median of HIP-event timed launches, rotating buffer sets, bf16"}))
         return
     if args.split_sweep:
         K1, H, P, N2 = 1024, 8192, 8, 3584

@@ -8,16 +8,18 @@
 // every input byte is read once and every output byte written once.
 //
 // Shape of the launch
-//   - One workgroup of 1024 threads (16 wave64) per compute unit, a persistent
+//   - One workgroup of up to 1024 threads (16 wave64) per compute unit, a persistent
 //     grid of `budget` workgroups striding over groups of rows (Listing 1's
 //     "token_id = blockIdx.x + iter * gridDim.x"). Each workgroup asks for more
 //     than half of a compute unit's LDS, so two can never share one: the grid
 //     size IS the number of compute units occupied.
-//   - A row is covered by TPR = min(1024, pow2ceil(H/8)) threads, each owning
-//     VPT 16-byte vector columns (8 bf16); a workgroup handles 1024/TPR rows per
-//     loop trip. The thread->column map and the reduction tree depend on H
-//     only, never on N, the grid or the row's position: the same row gives the
-//     same bits in any launch (split or not, any budget).
+//   - A row wider than a wave is covered by WPR whole waves (2 ... 16), each
+//     thread owning VPT 16-byte vector columns (8 bf16); a workgroup handles
+//     16/WPR rows per loop trip and is launched with just those waves. A narrower
+//     row takes a power-of-two group of lanes. The thread->column map and the
+//     reduction tree depend on H only, never on N, the grid or the row's
+//     position: the same row gives the same bits in any launch (split or not,
+//     any budget).
 //   - Loads are software-pipelined two "chunks" deep (a chunk = the P+1 vectors
 //     that feed one output vector): the loads of chunk q+2 are issued as soon as
 //     chunk q has been summed, before the row's reduction and barrier, so a
@@ -51,7 +53,8 @@ struct FusedParams {
     uint32_t n_groups;     // ceil(rows / rows_per_iter)
     int hv;                // 16-byte vectors per row
     int P;
-    int tpr_log2;
+    int tpr_log2;          // rows of at most 64 vectors (and the thin kernel): 2^tpr_log2 lanes per row
+    int wpr;               // wide kernel, rows wider than a wave: waves per row; else 0
     float eps;
     float inv_h;
 };
@@ -81,9 +84,14 @@ __global__ __launch_bounds__(kThreads) void fused_kernel(const FusedParams prm)
     const int lane = tid & 63;
     const int wave = tid >> 6;
     const int tpr_log2 = prm.tpr_log2;
-    const int tpr = 1 << tpr_log2;
-    const int row_in_iter = tid >> tpr_log2;
-    const int col0 = tid & (tpr - 1);
+    // Rows wider than a wave take wpr whole waves each (any number up to 16: the
+    // workgroup is launched with just the waves that have columns to work on, an
+    // idle wave's out-of-range loads and stores would still cost L1 request
+    // slots); narrower rows take a power-of-two group of lanes.
+    const int wpr = prm.wpr;
+    const int tpr = wpr ? wpr << 6 : 1 << tpr_log2;
+    const int row_in_iter = wpr ? __builtin_amdgcn_readfirstlane(wave / wpr) : tid >> tpr_log2;
+    const int col0 = wpr ? tid - row_in_iter * tpr : tid & (tpr - 1);
     const int hv = prm.hv;
 
     if (TRACE && tid == 0) {
@@ -209,13 +217,13 @@ __global__ __launch_bounds__(kThreads) void fused_kernel(const FusedParams prm)
 
             // Row sum of squares: the row's lanes inside this wave, then (rows
             // wider than a wave) the row's waves through LDS.
-            ss = group_sum(ss, tpr_log2 < 6 ? tpr_log2 : 6);
-            if (tpr_log2 > 6) {
+            ss = group_sum(ss, wpr ? 6 : tpr_log2);
+            if (wpr) {
+                // the row's wave sums, padded with zeros to 16, through a 16-lane butterfly
                 if (lane == 0) s_wave_sum[parity][wave] = ss;
                 __syncthreads();
-                const int waves_per_row = tpr >> 6;  // 2, 4, 8 or 16
                 const int k = lane & 15;
-                const float part = k < waves_per_row ? s_wave_sum[parity][row_in_iter * waves_per_row + k] : 0.0f;
+                const float part = k < wpr ? s_wave_sum[parity][row_in_iter * wpr + k] : 0.0f;
                 ss = group_sum(part, 4);
                 parity ^= 1;
             }
@@ -247,8 +255,9 @@ __global__ __launch_bounds__(kThreads) void fused_kernel(const FusedParams prm)
 // GEMM, the fused kernel is spread thinly over all of them and uses the HBM
 // bandwidth the matrix-core-bound GEMM leaves idle.
 //
-// Bits are identical to fused_kernel's: a thread here plays Q = TPR/256 of the
-// wide kernel's threads (columns tid, tid+256, ...), keeps one sum of squares
+// Bits are identical to fused_kernel's: a thread here plays Q (a row's vectors
+// over 256, rounded up: 1 ... 4) of the wide kernel's threads (columns tid,
+// tid+256, ...), keeps one sum of squares
 // per played thread, and the reduction runs the very same tree (64-lane
 // butterfly per played wave, then the 16-lane butterfly over the row's wave
 // sums in LDS). Only rows of at most 1024 vectors (H <= 8192) are handled.
@@ -371,7 +380,8 @@ void fused_thin_kernel(const FusedParams prm, const uint32_t groups_per_wg)
                 for (int q = 0; q < Q; ++q) s_wave_sum[parity][wave + q * (kThinThreads / 64)] = ss[q];
             }
             __syncthreads();
-            const int waves_per_row = tpr >> 6;
+            // the played waves' sums, padded with zeros to 16, as in the wide kernel
+            const int waves_per_row = (Q > 1) ? Q * (kThinThreads / 64) : tpr >> 6;
             const int k = lane & 15;
             const float part = k < waves_per_row ? s_wave_sum[parity][row_in_iter * waves_per_row + k] : 0.0f;
             total = group_sum(part, 4);
@@ -401,10 +411,18 @@ FusedGeometry fused_geometry(int64_t H)
     int l2 = 0;
     while ((1 << l2) < g.hv && l2 < 10) ++l2;
     g.tpr_log2 = l2;
-    const int tpr = 1 << l2;
-    const int need = (g.hv + tpr - 1) / tpr;  // 1..8
+    if (g.hv <= 64) {  // several rows per wave, or one
+        g.vpt = 1;
+        g.wpr = 0;
+        g.rows_per_iter = kThreads >> l2;
+        g.block = kThreads;
+        return g;
+    }
+    const int need = (g.hv + kThreads - 1) / kThreads;  // 1..8
     g.vpt = need <= 1 ? 1 : need <= 2 ? 2 : need <= 4 ? 4 : 8;
-    g.rows_per_iter = kThreads >> l2;
+    g.wpr = (g.hv + 64 * g.vpt - 1) / (64 * g.vpt);  // 2..16
+    g.rows_per_iter = kWaves / g.wpr;
+    g.block = g.rows_per_iter * g.wpr * 64;
     return g;
 }
 
@@ -453,14 +471,14 @@ tw_status validate_fused(const tw_fused_args &a)
 }
 
 template <int PT, int VPT>
-static tw_status launch_t(const FusedParams &prm, bool trace, int64_t grid, hipStream_t stream)
+static tw_status launch_t(const FusedParams &prm, bool trace, int64_t grid, int block, hipStream_t stream)
 {
     auto kern = trace ? fused_kernel<PT, VPT, true> : fused_kernel<PT, VPT, false>;
     static std::atomic<int> allowed[2][kMaxDevices];
     TW_TRY(allow_dynamic_lds(reinterpret_cast<const void *>(kern), static_cast<int>(kOccupancyPadBytes),
                              allowed[trace]));
-    TW_HIP(launch_kernel(kern, dim3(static_cast<unsigned>(grid)), dim3(kThreads), kOccupancyPadBytes,
-                         stream, prm));
+    TW_HIP(launch_kernel(kern, dim3(static_cast<unsigned>(grid)), dim3(static_cast<unsigned>(block)),
+                         kOccupancyPadBytes, stream, prm));
     return TW_OK;
 }
 
@@ -481,6 +499,7 @@ static tw_status launch_thin(const FusedParams &prm, int q, bool trace, int64_t 
     switch (q) {
     case 1: return launch_thin_t<PT, 1>(prm, trace, grid, groups_per_wg, s);
     case 2: return launch_thin_t<PT, 2>(prm, trace, grid, groups_per_wg, s);
+    case 3: return launch_thin_t<PT, 3>(prm, trace, grid, groups_per_wg, s);
     case 4: return launch_thin_t<PT, 4>(prm, trace, grid, groups_per_wg, s);
     }
     return TW_ERR_UNSUPPORTED;
@@ -490,14 +509,14 @@ static tw_status launch_thin(const FusedParams &prm, int q, bool trace, int64_t 
 // groups_per_wg consecutive row groups; enough workgroups that the hardware
 // dispatcher balances them over compute units that are busy to different degrees.
 struct ThinGeometry {
-    int q;              // wide-kernel threads played by one thread (1, 2 or 4)
+    int q;              // wide-kernel threads played by one thread (1 ... 4)
     int rows_per_iter;  // rows per row group
 };
 static ThinGeometry thin_geometry(const FusedGeometry &g)
 {
     ThinGeometry t;
     const int tpr = 1 << g.tpr_log2;
-    t.q = tpr > kThinThreads ? tpr / kThinThreads : 1;
+    t.q = g.hv > kThinThreads ? (g.hv + kThinThreads - 1) / kThinThreads : 1;
     t.rows_per_iter = tpr >= kThinThreads ? 1 : kThinThreads / tpr;
     return t;
 }
@@ -511,14 +530,15 @@ static void thin_grid(int64_t n_rows, const ThinGeometry &t, int cus, int64_t *g
 }
 
 template <int PT>
-static tw_status launch_vpt(const FusedParams &prm, int vpt, bool trace, int64_t grid, hipStream_t s)
+static tw_status launch_vpt(const FusedParams &prm, const FusedGeometry &g, bool trace, int64_t grid,
+                            hipStream_t s)
 {
-    switch (vpt) {
-    case 1: return launch_t<PT, 1>(prm, trace, grid, s);
-    case 2: return launch_t<PT, 2>(prm, trace, grid, s);
-    case 4: return launch_t<PT, 4>(prm, trace, grid, s);
+    switch (g.vpt) {
+    case 1: return launch_t<PT, 1>(prm, trace, grid, g.block, s);
+    case 2: return launch_t<PT, 2>(prm, trace, grid, g.block, s);
+    case 4: return launch_t<PT, 4>(prm, trace, grid, g.block, s);
     case 8:
-        if constexpr (PT != 8) return launch_t<PT, 8>(prm, trace, grid, s);  // P = 8 goes to the any-P kernel
+        if constexpr (PT != 8) return launch_t<PT, 8>(prm, trace, grid, g.block, s);  // P = 8 goes to the any-P kernel
         break;
     }
     return TW_ERR_UNSUPPORTED;
@@ -590,6 +610,7 @@ tw_status launch_fused(const tw_fused_args &a, int64_t row_begin, int64_t row_en
         prm.hv = g.hv;
         prm.P = a.P;
         prm.tpr_log2 = g.tpr_log2;
+        prm.wpr = g.wpr;
         prm.eps = a.eps;
         prm.inv_h = 1.0f / static_cast<float>(a.H);
 
@@ -608,11 +629,11 @@ tw_status launch_fused(const tw_fused_args &a, int64_t row_begin, int64_t row_en
         // additions) does.
         const int p_case = (a.P == 8 && g.vpt == 8) ? 0 : a.P;
         switch (p_case) {
-        case 1: TW_TRY((launch_vpt<1>(prm, g.vpt, trace, grid, stream))); break;
-        case 2: TW_TRY((launch_vpt<2>(prm, g.vpt, trace, grid, stream))); break;
-        case 4: TW_TRY((launch_vpt<4>(prm, g.vpt, trace, grid, stream))); break;
-        case 8: TW_TRY((launch_vpt<8>(prm, g.vpt, trace, grid, stream))); break;
-        default: TW_TRY((launch_vpt<0>(prm, g.vpt, trace, grid, stream))); break;
+        case 1: TW_TRY((launch_vpt<1>(prm, g, trace, grid, stream))); break;
+        case 2: TW_TRY((launch_vpt<2>(prm, g, trace, grid, stream))); break;
+        case 4: TW_TRY((launch_vpt<4>(prm, g, trace, grid, stream))); break;
+        case 8: TW_TRY((launch_vpt<8>(prm, g, trace, grid, stream))); break;
+        default: TW_TRY((launch_vpt<0>(prm, g, trace, grid, stream))); break;
         }
     }
     return TW_OK;

@@ -75,9 +75,11 @@ tw_status validate_fused(const tw_fused_args &a);
 // thread, rows per workgroup iteration.
 struct FusedGeometry {
     int hv;             // 16-byte vectors per row
-    int tpr_log2;       // log2(threads per row)
+    int tpr_log2;       // log2 of the row's vectors rounded up to a power of two (at most 1024)
     int vpt;            // vector columns per thread (1, 2, 4 or 8)
+    int wpr;            // waves per row (rows wider than a wave), 0: 2^tpr_log2 lanes per row
     int rows_per_iter;  // rows one workgroup handles per loop trip
+    int block;          // threads per workgroup: the waves that have columns to work on
 };
 FusedGeometry fused_geometry(int64_t H);
 int64_t fused_grid_size(int64_t n_rows, const FusedGeometry &g, int budget_wgs);

@@ -109,6 +109,9 @@ SHAPES = [
     (1, 8, 1), (3, 24, 3), (5, 64, 2), (130, 512, 16), (1000, 64, 7), (17, 520, 5), (33, 1024, 4),
     (19, 4096, 8), (7, 8008, 2), (65, 8192, 1), (9, 8200, 2), (33, 16384, 4), (6, 24000, 8),
     (9, 32768, 2), (5, 40000, 3), (3, 65536, 1), (4, 65536, 8), (2049, 256, 2), (1025, 8192, 8),
+    # rows of a whole number of waves that is not a power of two (5, 7, 10, 12, 14 waves; 10 and 12 x 2)
+    (50, 2560, 8), (14, 3584, 2), (37, 5120, 8), (21, 6144, 2), (9, 7168, 4), (5, 10240, 8), (7, 12288, 2),
+    (3, 20480, 4), (40, 1536, 3), (11, 4104, 8),
 ]
 
 
@@ -294,7 +297,8 @@ def test_traced_launch_reports_distinct_compute_units(tw, torch_cuda):
 
 SHARED_SHAPES = [(1, 8, 1), (3, 24, 3), (1000, 64, 7), (130, 512, 16), (17, 520, 5), (33, 1024, 4),
                  (300, 2048, 2), (19, 4096, 8), (77, 4096, 2), (7, 8008, 2), (65, 8192, 1), (1025, 8192, 8),
-                 (9, 8200, 2), (5, 16384, 4)]
+                 (9, 8200, 2), (5, 16384, 4), (50, 2560, 8), (14, 3584, 2), (37, 5120, 8), (21, 6144, 2),
+                 (9, 7168, 4), (300, 6144, 8), (11, 4104, 8), (40, 1536, 3)]
 
 
 @pytest.mark.parametrize("N,H,P", SHARED_SHAPES)
