@@ -157,6 +157,16 @@ tw_status tw_reduce_add_rmsnorm_unfused(const tw_fused_args *args, void *sum_scr
 int64_t tw_fused_grid(int64_t N, int64_t H, int P, int cu_budget);
 
 /*
+ * How the budgeted fused kernel lays a row of H elements over a workgroup (host
+ * arithmetic only, no device needed): waves per row (0: the row is narrower
+ * than a wave and takes a power-of-two group of lanes), 16-byte vectors per
+ * thread, rows per workgroup trip and threads per workgroup. Any pointer may be
+ * NULL. Returns TW_ERR_UNSUPPORTED for an H the kernel does not take.
+ */
+tw_status tw_fused_layout(int64_t H, int *waves_per_row, int *vectors_per_thread, int *rows_per_trip,
+                          int *threads_per_workgroup);
+
+/*
  * Two-way token split (Section 4: prefix split T_a, suffix split T_b; every
  * operation here is token-level, so the split is a pure row-range split).
  * Rows [0, split_row) are enqueued on stream_a and rows [split_row, N) on

@@ -24,6 +24,7 @@ from .binding import (  # noqa: F401
     smart_split_point,
     gemm_tile_shape,
     should_split,
+    fused_layout,
     LayerArgs,
     FusedArgs,
     GemmArgs,

@@ -100,6 +100,8 @@ def lib():
                                            ctypes.c_int,
                                            ctypes.POINTER(_i64), ctypes.POINTER(_i64)]
         L.tw_smart_split_point.restype = _i64
+        L.tw_fused_layout.argtypes = [_i64] + [ctypes.POINTER(ctypes.c_int)] * 4
+        L.tw_fused_layout.restype = ctypes.c_int
         L.tw_should_split.argtypes = [_i64, _i64]
         L.tw_should_split.restype = ctypes.c_int
         L.tw_gemm_tile_shape.argtypes = [ctypes.POINTER(ctypes.c_int), ctypes.POINTER(ctypes.c_int)]
@@ -360,6 +362,13 @@ def weave_layer(X1, W1, partials, residual, weight, eps, W2, split_row, stream_c
                                 _stream_handle(parent) if use_parent else _vp(None),
                                 1 if use_parent else 0, 1 if join else 0), "tw_weave_layer")
     return out, residual_out, Y
+
+
+def fused_layout(H):
+    """tw_fused_layout: (waves_per_row, vectors_per_thread, rows_per_trip, threads_per_workgroup)."""
+    v = [ctypes.c_int(-1) for _ in range(4)]
+    _check(lib().tw_fused_layout(int(H), *[ctypes.byref(x) for x in v]), "tw_fused_layout")
+    return tuple(x.value for x in v)
 
 
 def should_split(num_tokens, threshold=0):

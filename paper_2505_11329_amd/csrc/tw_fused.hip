@@ -666,6 +666,19 @@ tw_status tw_reduce_add_rmsnorm_traced(const void *const *partials, const void *
     return launch_fused(a, 0, N, hw_ids, hw_ids_len, static_cast<hipStream_t>(stream));
 }
 
+tw_status tw_fused_layout(int64_t H, int *waves_per_row, int *vectors_per_thread, int *rows_per_trip,
+                          int *threads_per_workgroup)
+{
+    if (H <= 0) return TW_ERR_SHAPE;
+    if (H % 8 != 0 || H > TW_MAX_H) return TW_ERR_UNSUPPORTED;
+    const FusedGeometry g = fused_geometry(H);
+    if (waves_per_row) *waves_per_row = g.wpr;
+    if (vectors_per_thread) *vectors_per_thread = g.vpt;
+    if (rows_per_trip) *rows_per_trip = g.rows_per_iter;
+    if (threads_per_workgroup) *threads_per_workgroup = g.block;
+    return TW_OK;
+}
+
 int64_t tw_fused_grid(int64_t N, int64_t H, int P, int cu_budget)
 {
     if (N < 0 || H <= 0 || H % 8 != 0 || H > TW_MAX_H || P < 1 || P > TW_MAX_P) return -1;

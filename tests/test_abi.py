@@ -27,7 +27,7 @@ def test_header_declares_the_documented_entry_points():
     names = declared_functions()
     for must in ("tw_reduce_add_rmsnorm", "tw_split_launch", "tw_split_point", "tw_gemm_bf16",
                  "tw_overlap_launch", "tw_hbm_probe", "tw_device_cu_count", "tw_status_str",
-                 "tw_version", "tw_last_hip_error", "tw_fused_grid", "tw_reduce_add_rmsnorm_traced"):
+                 "tw_version", "tw_last_hip_error", "tw_fused_grid", "tw_fused_layout", "tw_reduce_add_rmsnorm_traced"):
         assert must in names
 
 
@@ -324,6 +324,34 @@ def test_weave_layer_argument_checks():
     for schedule in (tw.WEAVE_AUTO, tw.WEAVE_ORDERED, tw.WEAVE_CHAINS):
         la.schedule = schedule
         assert L.tw_weave_layer(ctypes.byref(la), 0, VP(1), VP(2), VP(None), 0, 0) == OK
+
+
+def test_fused_layout_covers_every_row_width_without_idle_waves():
+    """Host arithmetic of the budgeted kernel's launch shape, for every H it takes."""
+    for H in list(range(8, 8192 + 8, 8)) + list(range(8192, 65536 + 1, 264)) + [65536]:
+        H -= H % 8
+        wpr, vpt, rows, block = tw.fused_layout(H)
+        hv = H // 8
+        assert vpt in (1, 2, 4, 8) and 64 <= block <= 1024 and block % 64 == 0, H
+        if hv <= 64:
+            assert wpr == 0 and vpt == 1 and block == 1024, H
+            lanes = 1024 // rows                      # a power of two, the smallest that holds the row
+            assert lanes * rows == 1024 and lanes >= hv and (lanes == 1 or lanes // 2 < hv), H
+            continue
+        assert 2 <= wpr <= 16, H
+        assert wpr * 64 * vpt >= hv, H                # the row's waves cover it
+        assert (wpr - 1) * 64 * vpt < hv, H           # and none of them is idle
+        assert vpt == 1 or hv > 1024 * vpt // 2, H    # no more vectors per thread than the width asks for
+        assert rows == 16 // wpr and block == rows * wpr * 64, H
+    assert tw.fused_layout(8192) == (16, 1, 1, 1024)
+    assert tw.fused_layout(5120) == (10, 1, 1, 640)
+    assert tw.fused_layout(3072) == (6, 1, 2, 768)
+    assert tw.fused_layout(12288) == (12, 2, 1, 768)
+    L = tw.lib()
+    assert L.tw_fused_layout(0, None, None, None, None) == E_SHAPE
+    assert L.tw_fused_layout(12, None, None, None, None) == E_UNSUP
+    assert L.tw_fused_layout(65536 + 8, None, None, None, None) == E_UNSUP
+    assert L.tw_fused_layout(4096, None, None, None, None) == OK
 
 
 def test_should_split_threshold():
