@@ -340,8 +340,9 @@ def main():
         "metric": "fused reduce+add+RMSNorm GB/s & % HBM peak at fixed CU budget; overlap makespan",
         "value": round(value, 1), "unit": "GB/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
         "ms_per_step": round(ms_per_step, 5), "higher_is_better": True, "scaling": "weak",
-        "vs_baseline": None, "dtype": "f32 (bf16 in HBM, fp32 accumulate)", "data": "synthetic",
+        "vs_baseline": None, "dtype": "f32", "data": "synthetic",
         "config": {"workload": "%s: N=1024 rows (1/8 of 8192 tokens), H=8192, P=8" % WORKLOAD,
+                   "storage": "bf16 tensors in HBM, fp32 arithmetic, one rounding per stored value",
                    "cu_budget": args.budget, "eps": sets[0]["eps"],
                    "buffer_sets_rotated": 4, "algorithmic_bytes_per_step": nbytes,
                    "clocks": "not locked (non-root)"},
