@@ -211,47 +211,53 @@ def main():
             torch.cuda.empty_cache()
 
         # where splitting starts to pay: the plain chain (three launches on one stream, no events)
-        # against the woven layer in shared mode and with a 32-CU budget, over batch sizes
-        thr = []
-        for T in (256, 512, 1024, 2048, 4096, 8192, 16384):
-            X1, resid = rnd((T, K1), 0.02), rnd((T, H), 1.0)
-            parts = [rnd((T, H), 0.25) for _ in range(P)]
-            out, res_out = torch.empty_like(resid), torch.empty_like(resid)
-            Y = torch.empty((T, N2), dtype=torch.bfloat16, device=dev)
+        # against the woven layer in shared mode and with a 32-CU budget, over batch sizes, for the
+        # attention-side boundary of the sweep above and for the MLP-side boundary of the same model
+        def threshold_sweep(K1, N2, W1, W2):
+            thr = []
+            for T in (256, 512, 1024, 2048, 4096, 6144, 8192, 16384):
+                X1, resid = rnd((T, K1), 0.02), rnd((T, H), 1.0)
+                parts = [rnd((T, H), 0.25) for _ in range(P)]
+                out, res_out = torch.empty_like(resid), torch.empty_like(resid)
+                Y = torch.empty((T, N2), dtype=torch.bfloat16, device=dev)
 
-            def plain():
-                tw.gemm_bf16(X1, W1, C=parts[0], stream=stream)
-                tw.reduce_add_rmsnorm(parts, resid, weight, 1e-5, cu_budget=0, out=out, residual_out=res_out,
-                                      stream=stream)
-                tw.gemm_bf16(out, W2, C=Y, stream=stream)
+                def plain():
+                    tw.gemm_bf16(X1, W1, C=parts[0], stream=stream)
+                    tw.reduce_add_rmsnorm(parts, resid, weight, 1e-5, cu_budget=0, out=out, residual_out=res_out,
+                                          stream=stream)
+                    tw.gemm_bf16(out, W2, C=Y, stream=stream)
 
-            def woven(split_row, fb, gb, schedule=tw.WEAVE_AUTO):
-                def f():
-                    with torch.cuda.stream(stream):
-                        tw.weave_layer(X1, W1, parts, resid, weight, 1e-5, W2, split_row, stream, comm,
-                                       fused_cu_budget=fb, gemm_cu_budget=gb, out=out, residual_out=res_out, Y=Y,
-                                       parent=stream, use_parent=True, join=True, schedule=schedule)
-                return f
-            cands = {"plain_us": plain}
-            row = {"T": T}
-            k, _, _ = tw.smart_split_point(T, 64, [H, N2], cus, gemm_k=[K1, H])
-            if k < T:
-                row["split_row"] = k
-                cands["woven_shared_us"] = woven(k, tw.CU_SHARED, 0)
-                cands["woven_shared_ordered_us"] = woven(k, tw.CU_SHARED, 0, tw.WEAVE_ORDERED)
-                cands["woven_shared_chains_us"] = woven(k, tw.CU_SHARED, 0, tw.WEAVE_CHAINS)
-            k32, _, _ = tw.smart_split_point(T, 64, [H, N2], cus - 32, gemm_k=[K1, H])
-            if k32 < T:
-                cands["woven_budget32_us"] = woven(k32, 32, cus - 32)
-            row.update(interleaved_medians(cands))
-            thr.append(row)
-            del X1, resid, parts, out, res_out, Y
-            torch.cuda.empty_cache()
+                def woven(split_row, fb, gb, schedule=tw.WEAVE_AUTO):
+                    def f():
+                        with torch.cuda.stream(stream):
+                            tw.weave_layer(X1, W1, parts, resid, weight, 1e-5, W2, split_row, stream, comm,
+                                           fused_cu_budget=fb, gemm_cu_budget=gb, out=out, residual_out=res_out,
+                                           Y=Y, parent=stream, use_parent=True, join=True, schedule=schedule)
+                    return f
+                cands = {"plain_us": plain}
+                row = {"T": T}
+                k, _, _ = tw.smart_split_point(T, 64, [H, N2], cus, gemm_k=[K1, H])
+                if k < T:
+                    row["split_row"] = k
+                    cands["woven_shared_us"] = woven(k, tw.CU_SHARED, 0)
+                    cands["woven_shared_ordered_us"] = woven(k, tw.CU_SHARED, 0, tw.WEAVE_ORDERED)
+                    cands["woven_shared_chains_us"] = woven(k, tw.CU_SHARED, 0, tw.WEAVE_CHAINS)
+                k32, _, _ = tw.smart_split_point(T, 64, [H, N2], cus - 32, gemm_k=[K1, H])
+                if k32 < T:
+                    cands["woven_budget32_us"] = woven(k32, 32, cus - 32)
+                row.update(interleaved_medians(cands))
+                thr.append(row)
+                del X1, resid, parts, out, res_out, Y
+                torch.cuda.empty_cache()
+            return thr
+        thr = threshold_sweep(K1, N2, W1, W2)
+        K1m, N2m = 3584, 1280
+        thr_mlp = threshold_sweep(K1m, N2m, rnd((H, K1m), 0.02), rnd((N2m, H), 0.02))
 
         def spread(key):
             rate = np.array([r["T"] / r[key] for r in rows])
             return round(float(rate.std() / rate.mean()), 4)
-        print(json.dumps({"split_sweep": rows, "threshold_sweep": thr,
+        print(json.dumps({"split_sweep": rows, "threshold_sweep": thr, "threshold_sweep_mlp_side": thr_mlp,
                           "tokens_per_us_relative_spread": {"equal": spread("equal_us"), "smart": spread("smart_us"),
                                                             "measured_best": spread("measured_best_us"),
                                                             "ordered_equal": spread("ordered_equal_us"),
@@ -260,7 +266,8 @@ def main():
                                   "[Tx8192]x[8192x3584]; medians of HIP-event timed calls of tw_weave_layer, the "
                                   "candidates of one T taking turns in bursts of 8; smart_row comes from tile "
                                   "counts alone; the schedule is the library's choice (TW_WEAVE_AUTO) except "
-                                  "in the threshold sweep's _ordered and _chains columns"}))
+                                  "in the threshold sweeps' _ordered and _chains columns; threshold_sweep_mlp_side is the "
+                                  "boundary [Tx3584]x[3584x8192] -> fused -> [Tx8192]x[8192x1280]"}))
         return
     if args.counters_run == "weave":
         T, K1, H, P, N2 = 4096, 1024, 8192, 8, 3584

@@ -332,11 +332,13 @@ int64_t tw_smart_split_point(int64_t T, int64_t multiple, const int64_t *gemm_n_
  * Overlap"): split and overlap only when the batch has at least `threshold`
  * tokens, otherwise run the fused kernel unsplit. threshold <= 0 takes the
  * built-in default for MI355X, TW_DEFAULT_SPLIT_THRESHOLD, found by profiling
- * tw_weave_layer against the unsplit chain on a 70B-class layer boundary (the
- * paper's own thresholds, 1K and 4K tokens, are for its 8xH100 system). Returns
- * 1 to split, 0 not to. Host only.
+ * tw_weave_layer against the unsplit chain on the two block boundaries of a
+ * 70B-class layer: the attention-side boundary breaks even at about 4K tokens,
+ * the MLP-side one at about 7K, the two together at about 6K (the paper's own
+ * thresholds, 1K and 4K tokens, are for its 8xH100 system). Returns 1 to split,
+ * 0 not to. Host only.
  */
-#define TW_DEFAULT_SPLIT_THRESHOLD 4096
+#define TW_DEFAULT_SPLIT_THRESHOLD 6144
 int tw_should_split(int64_t num_tokens, int64_t threshold);
 
 /* Rows and columns of the output tile one GEMM workgroup computes. */

@@ -355,7 +355,7 @@ def test_fused_layout_covers_every_row_width_without_idle_waves():
 
 
 def test_should_split_threshold():
-    assert not tw.should_split(0) and not tw.should_split(4095)
-    assert tw.should_split(4096) and tw.should_split(10 ** 6)
+    assert not tw.should_split(0) and not tw.should_split(6143)
+    assert tw.should_split(6144) and tw.should_split(10 ** 6)
     assert tw.should_split(1024, 1024) and not tw.should_split(1023, 1024)
-    assert tw.should_split(4096, -5) and not tw.should_split(100, 0)
+    assert tw.should_split(6144, -5) and not tw.should_split(100, 0)
