@@ -341,7 +341,9 @@ int64_t tw_smart_split_point(int64_t T, int64_t multiple, const int64_t *gemm_n_
 #define TW_DEFAULT_SPLIT_THRESHOLD 6144
 int tw_should_split(int64_t num_tokens, int64_t threshold);
 
-/* Rows and columns of the output tile one GEMM workgroup computes. */
+/* Rows and columns of the output tile one GEMM workgroup computes (a product
+ * whose tiles would fill at most half of its compute units is cut into tiles of
+ * half this width instead; tw_smart_split_point counts in tiles of this shape). */
 void tw_gemm_tile_shape(int *tile_m, int *tile_n);
 
 /*

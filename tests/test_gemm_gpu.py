@@ -111,29 +111,37 @@ def test_overlap_launch_equals_the_two_calls(tw, torch_cuda):
         assert np.array_equal(to_bits(cc), to_bits(C0))
 
 
-def test_overlap_launch_shared_mode_equals_the_two_calls(tw, torch_cuda):
+@pytest.mark.parametrize("M,K,N", [(1024, 2048, 1536), (512, 1024, 4096), (2048, 8192, 1280), (2048, 2048, 4096)])
+def test_overlap_launch_shared_mode_equals_the_two_calls(tw, torch_cuda, M, K, N):
     """The co-resident mode: small fused workgroups on every compute unit next to
-    the GEMM's. Same bits as the plain calls, every replay."""
+    the GEMM's. Same bits as the plain calls, on every one of many launches: next
+    to the fused kernel the GEMM's LDS reads and loads take longer, which is when
+    a missing wait shows (C starts as NaNs, so a store that went astray is seen).
+    The shapes cover the narrow tiles (at most half of the compute units filled by
+    wide ones) and the wide tiles."""
     torch = torch_cuda
     cfg = W.CONFIGS["c5_overlap_tp8"]
     d = W.make_fused_inputs(cfg, N=1024)
     g = dict(partials=[to_gpu(p) for p in d["partials"]], residual=to_gpu(d["residual"]),
              weight=to_gpu(d["weight"]), eps=d["eps"])
-    gm = W.make_gemm_inputs(1024, 2048, 1536, 0.02, seed=0, b_layout="nk")
+    gm = W.make_gemm_inputs(M, K, N, 0.02, seed=0, b_layout="nk")
     A, B = to_gpu(gm["A"]), to_gpu(gm["B"])
     out0, res0 = tw.reduce_add_rmsnorm(g["partials"], g["residual"], g["weight"], g["eps"], cu_budget=32)
-    C0 = tw.gemm_bf16(A, B)
+    C0 = tw.gemm_bf16(A, B, cu_budget=16)      # alone, wide tiles
     torch.cuda.synchronize()
+    assert np.array_equal(to_bits(tw.gemm_bf16(A, B)), to_bits(C0))
     comm, comp, parent = torch.cuda.Stream(), torch.cuda.Stream(), torch.cuda.Stream()
-    for _ in range(3):
+    C = torch.empty((M, N), dtype=torch.bfloat16, device="cuda:0")
+    for it in range(30):
         with torch.cuda.stream(parent):
-            out, res, C = tw.overlap_launch(dict(g, cu_budget=tw.CU_SHARED), dict(A=A, B=B, cu_budget=0), comm, comp,
-                                            parent=parent, use_parent=True, join=True)
-            oc, rc, cc = out.clone(), res.clone(), C.clone()
+            C.fill_(float("nan"))
+            out, res, C_ = tw.overlap_launch(dict(g, cu_budget=tw.CU_SHARED), dict(A=A, B=B, C=C, cu_budget=0), comm,
+                                             comp, parent=parent, use_parent=True, join=True)
+            oc, rc, cc = out.clone(), res.clone(), C_.clone()
         parent.synchronize()
-        assert np.array_equal(to_bits(oc), to_bits(out0))
-        assert np.array_equal(to_bits(rc), to_bits(res0))
-        assert np.array_equal(to_bits(cc), to_bits(C0))
+        assert np.array_equal(to_bits(oc), to_bits(out0)), it
+        assert np.array_equal(to_bits(rc), to_bits(res0)), it
+        assert np.array_equal(to_bits(cc), to_bits(C0)), (it, int((to_bits(cc) != to_bits(C0)).sum()))
 
 
 def test_gemm_random_shapes_both_layouts(tw, torch_cuda):
