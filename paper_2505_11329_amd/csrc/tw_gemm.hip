@@ -537,7 +537,7 @@ static tw_status launch_cfg(const tw_gemm_args &g, int budget, hipStream_t strea
     return TW_OK;
 }
 
-tw_status launch_gemm(const tw_gemm_args &g, hipStream_t stream)
+tw_status launch_gemm(const tw_gemm_args &g, hipStream_t stream, bool beside_other_kernels)
 {
     if (g.M == 0 || g.N == 0) return TW_OK;
     int cus = 0;
@@ -556,9 +556,12 @@ tw_status launch_gemm(const tw_gemm_args &g, hipStream_t stream)
     // fetches 5/3 of the operand bytes per flop and takes ~0.77 of the wide tile's
     // time, so it only pays while it brings idle compute units in: 14-23 % faster
     // on 40 ... 128 wide tiles ([2048 x 8192] x [8192 x 1280]: 80 -> 62 us), 25-40 %
-    // slower once the wide tiles already fill more than half. Same bits.
+    // slower once the wide tiles already fill more than half. Same bits. Not next
+    // to other kernels: there the compute units are not idle, the extra operand
+    // traffic competes for the same L1 request slots, and a woven layer measured
+    // level to 3 % slower with the narrow tiles.
     const int64_t wide_tiles = ((g.M + BM - 1) / BM) * ((g.N + kGemmTileN - 1) / kGemmTileN);
-    if (2 * wide_tiles <= budget) return launch_cfg<false, 2, 1, 3, 64>(g, budget, stream);
+    if (!beside_other_kernels && 2 * wide_tiles <= budget) return launch_cfg<false, 2, 1, 3, 64>(g, budget, stream);
     return launch_cfg<false, 2, 2, 3, 64>(g, budget, stream);
 }
 

@@ -184,9 +184,9 @@ tw_status tw_overlap_launch(const tw_fused_args *fused, const tw_gemm_args *gemm
     // the small fused workgroups then fill in beside it (launched first, they
     // would pile up five to a compute unit and keep the GEMM out until done).
     const bool gemm_first = fused && gemm && fused->cu_budget == TW_CU_SHARED;
-    if (gemm && gemm_first) TW_TRY(launch_gemm(*gemm, sx));
+    if (gemm && gemm_first) TW_TRY(launch_gemm(*gemm, sx, fused != nullptr));
     if (fused && fused->N > 0) TW_TRY(launch_fused(*fused, 0, fused->N, nullptr, 0, sc));
-    if (gemm && !gemm_first) TW_TRY(launch_gemm(*gemm, sx));
+    if (gemm && !gemm_first) TW_TRY(launch_gemm(*gemm, sx, fused != nullptr));
     if (parent_is_set && join) {
         if (fused && sc != sp) TW_TRY(stream_wait_stream(sp, sc));
         if (gemm && sx != sp) TW_TRY(stream_wait_stream(sp, sx));
@@ -287,15 +287,15 @@ tw_status tw_weave_layer(const tw_layer_args *layer, int64_t split_row, void *st
     if (takes_chains(*layer, g1, g2, cus)) {
         // one chain per split; the second starts when the first split's G1 is done
         hipEvent_t g1a_done;
-        TW_TRY(launch_gemm(rows_of(g1, cuts[0], cuts[1]), sx));
+        TW_TRY(launch_gemm(rows_of(g1, cuts[0], cuts[1]), sx, true));
         TW_TRY(borrow_event(&g1a_done));
         TW_HIP(hipEventRecord(g1a_done, sx));
         TW_HIP(hipStreamWaitEvent(sc, g1a_done, 0));
         TW_TRY(launch_fused(f, cuts[0], cuts[1], nullptr, 0, sx));
-        TW_TRY(launch_gemm(rows_of(g2, cuts[0], cuts[1]), sx));
-        TW_TRY(launch_gemm(rows_of(g1, cuts[1], cuts[2]), sc));
+        TW_TRY(launch_gemm(rows_of(g2, cuts[0], cuts[1]), sx, true));
+        TW_TRY(launch_gemm(rows_of(g1, cuts[1], cuts[2]), sc, true));
         TW_TRY(launch_fused(f, cuts[1], cuts[2], nullptr, 0, sc));
-        TW_TRY(launch_gemm(rows_of(g2, cuts[1], cuts[2]), sc));
+        TW_TRY(launch_gemm(rows_of(g2, cuts[1], cuts[2]), sc, true));
         if (parent_is_set && join) {
             if (sx != sp) TW_TRY(stream_wait_stream(sp, sx));
             if (sc != sp) TW_TRY(stream_wait_stream(sp, sc));
@@ -306,7 +306,7 @@ tw_status tw_weave_layer(const tw_layer_args *layer, int64_t split_row, void *st
     // runs next to the first split's fused kernel
     hipEvent_t g1_done[2], f_done[2];
     for (int s = 0; s < n_splits; ++s) {
-        TW_TRY(launch_gemm(rows_of(g1, cuts[s], cuts[s + 1]), sx));
+        TW_TRY(launch_gemm(rows_of(g1, cuts[s], cuts[s + 1]), sx, true));
         TW_TRY(borrow_event(&g1_done[s]));
         TW_HIP(hipEventRecord(g1_done[s], sx));
     }
@@ -316,7 +316,7 @@ tw_status tw_weave_layer(const tw_layer_args *layer, int64_t split_row, void *st
         TW_TRY(borrow_event(&f_done[s]));
         TW_HIP(hipEventRecord(f_done[s], sc));
         TW_HIP(hipStreamWaitEvent(sx, f_done[s], 0));
-        TW_TRY(launch_gemm(rows_of(g2, cuts[s], cuts[s + 1]), sx));
+        TW_TRY(launch_gemm(rows_of(g2, cuts[s], cuts[s + 1]), sx, true));
     }
     if (parent_is_set && join) {
         if (sx != sp) TW_TRY(stream_wait_stream(sp, sx));

@@ -89,7 +89,10 @@ tw_status launch_fused(const tw_fused_args &a, int64_t row_begin, int64_t row_en
 
 // ---- GEMM stand-in (tw_gemm.hip) ----
 tw_status validate_gemm(const tw_gemm_args &g);
-tw_status launch_gemm(const tw_gemm_args &g, hipStream_t stream);
+// `beside_other_kernels`: the launch is meant to overlap with another kernel (the
+// fused step, a second GEMM): then the wide tiles are kept even where few of them
+// fill the device.
+tw_status launch_gemm(const tw_gemm_args &g, hipStream_t stream, bool beside_other_kernels = false);
 static constexpr int kGemmTileM = 256, kGemmTileN = 128;
 
 

@@ -132,12 +132,25 @@ def test_overlap_launch_shared_mode_equals_the_two_calls(tw, torch_cuda, M, K, N
     assert np.array_equal(to_bits(tw.gemm_bf16(A, B)), to_bits(C0))
     comm, comp, parent = torch.cuda.Stream(), torch.cuda.Stream(), torch.cuda.Stream()
     C = torch.empty((M, N), dtype=torch.bfloat16, device="cuda:0")
+    out = torch.empty_like(g["residual"])
+    res = torch.empty_like(g["residual"])
     for it in range(30):
         with torch.cuda.stream(parent):
             C.fill_(float("nan"))
-            out, res, C_ = tw.overlap_launch(dict(g, cu_budget=tw.CU_SHARED), dict(A=A, B=B, C=C, cu_budget=0), comm,
-                                             comp, parent=parent, use_parent=True, join=True)
-            oc, rc, cc = out.clone(), res.clone(), C_.clone()
+            if it % 2 == 0:
+                tw.overlap_launch(dict(g, cu_budget=tw.CU_SHARED, out=out, residual_out=res),
+                                  dict(A=A, B=B, C=C, cu_budget=0), comm, comp, parent=parent, use_parent=True, join=True)
+            else:
+                # the two calls made by hand on two streams: tw_gemm_bf16 picks its tiles as for a
+                # launch on its own (the narrow ones where few wide tiles would fill the device)
+                comp.wait_stream(parent)
+                comm.wait_stream(parent)
+                tw.gemm_bf16(A, B, C=C, cu_budget=0, stream=comp)
+                tw.reduce_add_rmsnorm(g["partials"], g["residual"], g["weight"], g["eps"], cu_budget=tw.CU_SHARED,
+                                      out=out, residual_out=res, stream=comm)
+                parent.wait_stream(comp)
+                parent.wait_stream(comm)
+            oc, rc, cc = out.clone(), res.clone(), C.clone()
         parent.synchronize()
         assert np.array_equal(to_bits(oc), to_bits(out0)), it
         assert np.array_equal(to_bits(rc), to_bits(res0)), it
