@@ -141,6 +141,7 @@ def main():
                           eps=cfg["eps"], N=N, H=H, P=P, out=torch.empty_like(resid),
                           res_out=torch.empty_like(resid))
                 ss.append(s_)
+            torch.cuda.synchronize()   # the inputs were drawn on torch's stream, the launches go to ours
             row = {"H": H, "P": P, "N": N, "algorithmic_MB": round(per_set / 1e6, 2)}
             for label, b in (("whole_device", 0), ("shared", tw.CU_SHARED), ("budget32", 32)):
                 fns = [tw.prepare_reduce_add_rmsnorm(x["partials"], x["residual"], x["weight"], x["eps"],
@@ -182,6 +183,7 @@ def main():
             parts = [rnd((T, H), 0.25) for _ in range(P)]
             out, res_out = torch.empty_like(resid), torch.empty_like(resid)
             Y = torch.empty((T, N2), dtype=torch.bfloat16, device=dev)
+            torch.cuda.synchronize()   # inputs drawn on torch's stream, launches on ours
 
             def layer_fn(split_row, schedule=tw.WEAVE_AUTO):
                 def f():
@@ -220,6 +222,7 @@ def main():
                 parts = [rnd((T, H), 0.25) for _ in range(P)]
                 out, res_out = torch.empty_like(resid), torch.empty_like(resid)
                 Y = torch.empty((T, N2), dtype=torch.bfloat16, device=dev)
+                torch.cuda.synchronize()
 
                 def plain():
                     tw.gemm_bf16(X1, W1, C=parts[0], stream=stream)
@@ -280,6 +283,7 @@ def main():
         parts, resid = [rnd((T, H), 0.25) for _ in range(P)], rnd((T, H), 1.0)
         weight = gpu(W.uniform_bf16((H,), 0.5, 1.5, 0, W.STREAM_WEIGHT))
         comm = torch.cuda.Stream()
+        torch.cuda.synchronize()
         k, _, _ = tw.smart_split_point(T, 128, [H, N2], tw.device_cu_count(), gemm_k=[K1, H])
         order = [("unsplit", 0, tw.WEAVE_ORDERED), ("ordered", k, tw.WEAVE_ORDERED), ("chains", k, tw.WEAVE_CHAINS)]
         for name, split_row, schedule in order:
