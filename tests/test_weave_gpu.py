@@ -98,3 +98,47 @@ def test_weave_layer_orders_itself_after_the_parent_stream(tw, torch_cuda, sched
             yc, oc = Y.clone(), out.clone()   # and consumed on it right after
         parent.synchronize()
         assert np.array_equal(to_bits(yc), want[3]) and np.array_equal(to_bits(oc), want[1])
+
+
+@pytest.mark.parametrize("K1,N2", [(1024, 3584), (3584, 1280)])
+def test_weave_layer_at_full_size_gives_the_unsplit_bits_every_time(tw, torch_cuda, K1, N2):
+    """The two block boundaries of the 70B-class layer at T = 4096 (H = 8192, P = 8),
+    co-resident mode, both schedules, several cuts, a dozen launches each: every
+    output must carry the unsplit chain's bits. At this size the kernels really
+    overlap for tens of microseconds, which is when a missing wait or a misplaced
+    event shows; the outputs start as NaNs so that nothing stale can pass. Inputs
+    are drawn on the GPU (seeded); the unsplit chain is the reference, and its own
+    parity with the oracle is the business of the tests above."""
+    torch = torch_cuda
+    T_, H_, P_ = 4096, 8192, 8
+    gen = torch.Generator(device="cuda:0")
+    gen.manual_seed(K1 + N2)
+
+    def rnd(shape, std):
+        return torch.empty(shape, dtype=torch.bfloat16, device="cuda:0").normal_(0.0, std, generator=gen)
+    X1, W1, W2g = rnd((T_, K1), 0.02), rnd((H_, K1), 0.02), rnd((N2, H_), 0.02)
+    parts, resid = [rnd((T_, H_), 0.25) for _ in range(P_)], rnd((T_, H_), 1.0)
+    weight = to_gpu(W.uniform_bf16((H_,), 0.5, 1.5, 0, W.STREAM_WEIGHT))
+    out, res = torch.empty_like(resid), torch.empty_like(resid)
+    Y = torch.empty((T_, N2), dtype=torch.bfloat16, device="cuda:0")
+    sx, sc = torch.cuda.Stream(), torch.cuda.Stream()
+    torch.cuda.synchronize()
+
+    def run(split_row, schedule):
+        with torch.cuda.stream(sx):
+            for t in (parts[0], out, res, Y):
+                t.fill_(float("nan"))
+            tw.weave_layer(X1, W1, parts, resid, weight, 1e-5, W2g, split_row, sx, sc, fused_cu_budget=tw.CU_SHARED,
+                           gemm_cu_budget=0, out=out, residual_out=res, Y=Y, parent=sx, use_parent=True, join=True,
+                           schedule=schedule)
+        torch.cuda.synchronize()
+        return [to_bits(t).copy() for t in (parts[0], out, res, Y)]
+    want = run(0, tw.WEAVE_ORDERED)
+    assert not np.isnan(oracle.bf16_to_f64(want[3])).any()
+    k_smart = tw.smart_split_point(T_, 64, [H_, N2], tw.device_cu_count(), gemm_k=[K1, H_])[0]
+    for it in range(12):
+        schedule = (tw.WEAVE_ORDERED, tw.WEAVE_CHAINS)[it % 2]
+        k = (k_smart, 2048 + 64 * (it % 5), 128 * (1 + it % 7))[it % 3]
+        got = run(k, schedule)
+        for name, g_, w_ in zip(("G1", "out", "residual_out", "Y"), got, want):
+            assert np.array_equal(g_, w_), (it, schedule, k, name, int((g_ != w_).sum()))
