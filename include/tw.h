@@ -212,6 +212,9 @@ int64_t tw_split_point(int64_t N, int64_t multiple);
  *             multiple of 8 (16-byte vectors), else TW_ERR_UNSUPPORTED
  *   cu_budget persistent grid of at most this many workgroups (one per compute
  *             unit); <= 0 or >= the CU count: whole device
+ * The result bits depend on A, B and K only: not on the budget, the layout of B,
+ * nor on the tile shape the launch picks (256 x 128 outputs per workgroup, or
+ * 256 x 64 when the wider tiles would fill at most half of the compute units).
  */
 #define TW_B_NK 0
 #define TW_B_KN 1
