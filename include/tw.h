@@ -309,6 +309,15 @@ tw_status tw_weave_layer(const tw_layer_args *layer, int64_t split_row, void *st
                          void *stream_comm, void *parent, int parent_is_set, int join);
 
 /*
+ * The schedule tw_weave_layer takes for a split boundary of these sizes on a
+ * device with `cus` compute units: TW_WEAVE_ORDERED or TW_WEAVE_CHAINS (the
+ * `schedule` argument itself unless it is TW_WEAVE_AUTO). Host arithmetic only.
+ * Returns -1 on bad arguments.
+ */
+int tw_weave_schedule(int64_t T, int64_t K1, int64_t H, int P, int64_t N2, int fused_cu_budget, int schedule,
+                      int cus);
+
+/*
  * Wave-aware choice of the split row (Section 4.1.1 and Appendix A
  * "Smart-Splitting"; Algorithm 1 finds the offset by profiling because its GEMMs
  * are closed source, here the GEMM's tile grid is known, so the same sweep is

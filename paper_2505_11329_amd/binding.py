@@ -100,6 +100,8 @@ def lib():
                                            ctypes.c_int,
                                            ctypes.POINTER(_i64), ctypes.POINTER(_i64)]
         L.tw_smart_split_point.restype = _i64
+        L.tw_weave_schedule.argtypes = [_i64, _i64, _i64, ctypes.c_int, _i64, ctypes.c_int, ctypes.c_int, ctypes.c_int]
+        L.tw_weave_schedule.restype = ctypes.c_int
         L.tw_fused_layout.argtypes = [_i64] + [ctypes.POINTER(ctypes.c_int)] * 4
         L.tw_fused_layout.restype = ctypes.c_int
         L.tw_should_split.argtypes = [_i64, _i64]
@@ -362,6 +364,12 @@ def weave_layer(X1, W1, partials, residual, weight, eps, W2, split_row, stream_c
                                 _stream_handle(parent) if use_parent else _vp(None),
                                 1 if use_parent else 0, 1 if join else 0), "tw_weave_layer")
     return out, residual_out, Y
+
+
+def weave_schedule(T, K1, H, P, N2, fused_cu_budget=CU_SHARED, schedule=WEAVE_AUTO, cus=256):
+    """tw_weave_schedule: the schedule tw_weave_layer takes for these sizes."""
+    return int(lib().tw_weave_schedule(int(T), int(K1), int(H), int(P), int(N2), int(fused_cu_budget), int(schedule),
+                                       int(cus)))
 
 
 def fused_layout(H):

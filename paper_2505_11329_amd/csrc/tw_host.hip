@@ -227,6 +227,26 @@ static bool takes_chains(const tw_layer_args &layer, const tw_gemm_args &g1, con
     return gemm_us(g1) + fused_us + gemm_us(g2) < 700.0;
 }
 
+int tw_weave_schedule(int64_t T, int64_t K1, int64_t H, int P, int64_t N2, int fused_cu_budget, int schedule,
+                      int cus)
+{
+    if (T < 0 || K1 < 0 || H < 1 || P < 1 || N2 < 0 || cus < 1) return -1;
+    if (schedule != TW_WEAVE_AUTO && schedule != TW_WEAVE_ORDERED && schedule != TW_WEAVE_CHAINS) return -1;
+    tw_layer_args layer = {};
+    layer.schedule = schedule;
+    layer.fused.N = T;
+    layer.fused.H = H;
+    layer.fused.P = P;
+    layer.fused.cu_budget = fused_cu_budget;
+    tw_gemm_args g1 = {}, g2 = {};
+    g1.M = g2.M = T;
+    g1.N = H;
+    g1.K = K1;
+    g2.N = N2;
+    g2.K = H;
+    return takes_chains(layer, g1, g2, cus) ? TW_WEAVE_CHAINS : TW_WEAVE_ORDERED;
+}
+
 tw_status tw_weave_layer(const tw_layer_args *layer, int64_t split_row, void *stream_compute,
                          void *stream_comm, void *parent, int parent_is_set, int join)
 {

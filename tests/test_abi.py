@@ -27,7 +27,7 @@ def test_header_declares_the_documented_entry_points():
     names = declared_functions()
     for must in ("tw_reduce_add_rmsnorm", "tw_split_launch", "tw_split_point", "tw_gemm_bf16",
                  "tw_overlap_launch", "tw_hbm_probe", "tw_device_cu_count", "tw_status_str",
-                 "tw_version", "tw_last_hip_error", "tw_fused_grid", "tw_fused_layout", "tw_reduce_add_rmsnorm_traced"):
+                 "tw_version", "tw_last_hip_error", "tw_fused_grid", "tw_fused_layout", "tw_weave_schedule", "tw_reduce_add_rmsnorm_traced"):
         assert must in names
 
 
@@ -352,6 +352,26 @@ def test_fused_layout_covers_every_row_width_without_idle_waves():
     assert L.tw_fused_layout(12, None, None, None, None) == E_UNSUP
     assert L.tw_fused_layout(65536 + 8, None, None, None, None) == E_UNSUP
     assert L.tw_fused_layout(4096, None, None, None, None) == OK
+
+
+def test_weave_schedule_follows_the_estimated_layer_time():
+    O, C = tw.WEAVE_ORDERED, tw.WEAVE_CHAINS
+    attn = dict(K1=1024, H=8192, P=8, N2=3584)
+    mlp = dict(K1=3584, H=8192, P=8, N2=1280)
+    # short layers: one chain per split; long ones: GEMMs in order on one stream
+    assert [tw.weave_schedule(T, **attn) for T in (1024, 4096, 6144, 8192, 16384)] == [C, C, C, O, O]
+    assert [tw.weave_schedule(T, **mlp) for T in (1024, 4096, 6144, 8192, 16384)] == [C, C, C, O, O]
+    # a smaller model crosses over at a larger batch
+    assert tw.weave_schedule(16384, K1=2048, H=4096, P=2, N2=2048) == C
+    # a fused kernel confined to a CU budget keeps the ordered schedule; a budget that is the
+    # whole device does not count as one
+    assert tw.weave_schedule(4096, fused_cu_budget=32, **attn) == O
+    assert tw.weave_schedule(4096, fused_cu_budget=0, **attn) == C
+    assert tw.weave_schedule(4096, fused_cu_budget=256, **attn) == C
+    # an explicit schedule is passed through
+    assert tw.weave_schedule(4096, schedule=O, **attn) == O and tw.weave_schedule(16384, schedule=C, **attn) == C
+    assert tw.weave_schedule(4096, schedule=7, **attn) == -1 and tw.weave_schedule(-1, **attn) == -1
+    assert tw.weave_schedule(4096, cus=0, **attn) == -1
 
 
 def test_should_split_threshold():
