@@ -10,6 +10,7 @@ from .oracle import (  # noqa: F401
     fused,
     fused_rounded_x,
     unfused,
+    unfused_f32sum,
     fused_mt,
     gemm,
     gemm_samples,

@@ -43,7 +43,8 @@ def _load():
         lib = ctypes.CDLL(_LIB)
         fused_args = [ctypes.POINTER(_u16p), _u16p, _u16p, ctypes.c_float,
                       ctypes.c_int64, ctypes.c_int64, ctypes.c_int, _f64p, _f64p]
-        for name in ("tw_oracle_fused", "tw_oracle_fused_rounded_x", "tw_oracle_unfused"):
+        for name in ("tw_oracle_fused", "tw_oracle_fused_rounded_x", "tw_oracle_unfused",
+                     "tw_oracle_unfused_f32sum"):
             fn = getattr(lib, name)
             fn.argtypes = fused_args
             fn.restype = ctypes.c_int
@@ -111,9 +112,15 @@ def fused_rounded_x(partials, residual, weight, eps):
 
 
 def unfused(partials, residual, weight, eps):
-    """The three-pass pipeline (all-reduce to bf16, residual add + sum of squares, scale from the stored
-    bf16 residual stream). Returns (ref_out, ref_res) like fused()."""
+    """The three-pass pipeline (all-reduce to bf16 = the exact sum rounded once, residual add + sum of
+    squares, scale from the stored bf16 residual stream). Returns (ref_out, ref_res) like fused()."""
     return _fused_call("tw_oracle_unfused", partials, residual, weight, eps)
+
+
+def unfused_f32sum(partials, residual, weight, eps):
+    """Second reading of the same pipeline: the all-reduce accumulates in binary32 in rank order
+    before its one rounding to bf16."""
+    return _fused_call("tw_oracle_unfused_f32sum", partials, residual, weight, eps)
 
 
 def fused_mt(partials, residual, weight, eps, nthreads):

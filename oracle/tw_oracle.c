@@ -22,16 +22,24 @@
  *   The in-switch reduction of the paper is replaced by an explicit sum over
  *   P buffers; the sum itself is the same mathematical object.
  *
- * Readings taken where the paper is silent:
- *   - x used for the sum of squares and for the scaling is the UNROUNDED sum
- *     (tw_oracle_fused). The alternative, where the bf16-rounded x that is
- *     stored to the residual stream also feeds the norm, is provided as
- *     tw_oracle_fused_rounded_x so tests can bound the difference.
+ * Readings taken (the paper's precision statements are in Listing 1 only):
+ *   - tw_oracle_fused: x used for the sum of squares and for the scaling is the
+ *     UNROUNDED sum (fp32 accumulation throughout on the device; this is the
+ *     reading the device path is held to).
+ *   - tw_oracle_fused_rounded_x: Listing 1 as printed keeps the summed vector in
+ *     bf16, takes the sum of squares of that bf16 vector, stores it to the
+ *     residual stream and scales what it reads back from there, i.e. the
+ *     bf16-ROUNDED x feeds the norm. That literal reading is provided too, with
+ *     pins of its own, so tests can bound the difference between the two.
  *   - epsilon sits inside the square root; the mean divides by H.
  *   - bf16 encoding is round-to-nearest-even, NaN stays NaN, overflow -> Inf.
+ *   - tw_oracle_unfused: the all-reduce's bf16 output is the exact sum rounded
+ *     once (the paper does not state the reduction's internal precision);
+ *     tw_oracle_unfused_f32sum is a second, labelled reading in which that sum
+ *     is accumulated in binary32 in rank order before the rounding.
  *
  * All pins for this file live in tests/test_oracle_pins.py (closed forms,
- * invariants, a worked example, exact rational brute force, library RMSNorm
+ * invariants, worked examples, exact rational brute force, library RMSNorm
  * and matmul special cases). Nothing here is "parity unpinned".
  */
 #include <math.h>
@@ -160,40 +168,66 @@ int tw_oracle_fused_rounded_x(const uint16_t *const *partials,
  * Table 1: all-reduce, then residual add + RMSNorm; Section 4.3 describes the
  * standard RMSNorm as two reads of the tensor and one write). Three stages,
  * each a pass over memory with bf16 tensors in between:
- *   1. t = bf16(p_0 + ... + p_{P-1}), the all-reduce's bf16 output. Which bf16
- *      neighbour t lands on is a decision, so it is taken in the precision the
- *      device path takes it in: a binary32 sum in the order p = 0 .. P-1, then
- *      one rounding to nearest even;
+ *   1. t = bf16(p_0 + ... + p_{P-1}), the all-reduce's bf16 output: the sum as
+ *      a real number (binary64 holds it exactly for operands whose exponents
+ *      span fewer than 45 binades), rounded once to nearest even. With
+ *      f32_sum != 0 the second reading: the sum accumulated in binary32 in the
+ *      order p = 0 .. P-1, then rounded;
  *   2. x = t + residual (exact in binary64); the new residual stream is x
  *      (ref_res, unrounded; what is stored is bf16(x)); the sum of squares is
  *      taken over the unrounded x;
  *   3. the stored residual stream is read back: out = bf16(x) * s * w.
  * ref_out is the unrounded result of stage 3. ---- */
-int tw_oracle_unfused(const uint16_t *const *partials, const uint16_t *residual,
-                      const uint16_t *weight, float eps, int64_t N, int64_t H,
-                      int P, double *ref_out, double *ref_res)
+static int unfused_rows(const uint16_t *const *partials, const uint16_t *residual,
+                        const uint16_t *weight, double eps, int64_t N, int64_t H,
+                        int P, int f32_sum, double *ref_out, double *ref_res)
 {
-    if (N < 0 || H <= 0 || P < 1)
-        return -1;
     for (int64_t r = 0; r < N; ++r) {
         const int64_t base = r * H;
         double sumsq = 0.0;
         for (int64_t c = 0; c < H; ++c) {
-            volatile float acc = 0.0f; /* volatile: no excess precision, no contraction */
-            for (int p = 0; p < P; ++p)
-                acc = acc + (float)bf16_to_f64(partials[p][base + c]);
-            const double t = bf16_to_f64(tw_oracle_f64_to_bf16((double)acc));
+            double sum;
+            if (f32_sum) {
+                volatile float acc = 0.0f; /* volatile: no excess precision, no contraction */
+                for (int p = 0; p < P; ++p)
+                    acc = acc + (float)bf16_to_f64(partials[p][base + c]);
+                sum = (double)acc;
+            } else {
+                sum = 0.0;
+                for (int p = 0; p < P; ++p)
+                    sum += bf16_to_f64(partials[p][base + c]);
+            }
+            const double t = bf16_to_f64(tw_oracle_f64_to_bf16(sum));
             const double x = t + bf16_to_f64(residual[base + c]);
             ref_res[base + c] = x;
             sumsq += x * x;
         }
-        const double s = 1.0 / sqrt(sumsq / (double)H + (double)eps);
+        const double s = 1.0 / sqrt(sumsq / (double)H + eps);
         for (int64_t c = 0; c < H; ++c) {
             const double stored = bf16_to_f64(tw_oracle_f64_to_bf16(ref_res[base + c]));
             ref_out[base + c] = stored * s * bf16_to_f64(weight[c]);
         }
     }
     return 0;
+}
+
+int tw_oracle_unfused(const uint16_t *const *partials, const uint16_t *residual,
+                      const uint16_t *weight, float eps, int64_t N, int64_t H,
+                      int P, double *ref_out, double *ref_res)
+{
+    if (N < 0 || H <= 0 || P < 1)
+        return -1;
+    return unfused_rows(partials, residual, weight, (double)eps, N, H, P, 0, ref_out, ref_res);
+}
+
+/* Second reading of stage 1: binary32 accumulation in rank order. */
+int tw_oracle_unfused_f32sum(const uint16_t *const *partials, const uint16_t *residual,
+                             const uint16_t *weight, float eps, int64_t N, int64_t H,
+                             int P, double *ref_out, double *ref_res)
+{
+    if (N < 0 || H <= 0 || P < 1)
+        return -1;
+    return unfused_rows(partials, residual, weight, (double)eps, N, H, P, 1, ref_out, ref_res);
 }
 
 /* ---- row-parallel wrapper: same per-row code, rows dealt out in contiguous
