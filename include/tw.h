@@ -152,6 +152,28 @@ tw_status tw_reduce_add_rmsnorm_traced(const void *const *partials, const void *
  */
 tw_status tw_reduce_add_rmsnorm_unfused(const tw_fused_args *args, void *sum_scratch, void *stream);
 
+/*
+ * tw_reduce_add_rmsnorm_unfused for callers that cannot allocate device memory
+ * or hand over a workspace: code under HIP graph capture, tight serving loops,
+ * harnesses that forbid hipMalloc. Same two launches, same kernels, same bits;
+ * the intermediate sum t goes through a buffer of TW_STATIC_SCRATCH_BYTES that
+ * is part of the library's device image (one copy per GPU, held until the
+ * process ends) instead of through sum_scratch. The call allocates and frees
+ * nothing on host or device. Differences from tw_reduce_add_rmsnorm_unfused:
+ *   - N * H * 2 must not exceed TW_STATIC_SCRATCH_BYTES, else TW_ERR_SHAPE
+ *     (checked on the host before any HIP call; nothing is launched);
+ *   - every call on one GPU uses that GPU's one buffer: two calls whose kernels
+ *     may run at the same time on one GPU (different streams with no ordering
+ *     between them) race on it and give undefined outputs. Calls on one stream,
+ *     or ordered by events, are fine. The buffer keeps the previous call's
+ *     contents; nothing in it has to start at zero, because the first launch
+ *     writes every element of t that the second one reads.
+ * The caller's tensors cannot overlap the buffer, so TW_ERR_ALIAS only reports
+ * the overlaps tw_reduce_add_rmsnorm rejects.
+ */
+#define TW_STATIC_SCRATCH_BYTES (32u << 20) /* 32 MiB: e.g. 2048 rows of H = 8192 */
+tw_status tw_reduce_add_rmsnorm_unfused_static(const tw_fused_args *args, void *stream);
+
 /* Number of workgroups the fused kernel is launched with for these sizes on the
  * current device (0 if N == 0; -1 if the arguments are invalid or no device). */
 int64_t tw_fused_grid(int64_t N, int64_t H, int P, int cu_budget);

@@ -20,6 +20,7 @@ B_NK, B_KN = 0, 1
 CU_SHARED = -1
 WEAVE_AUTO, WEAVE_ORDERED, WEAVE_CHAINS = 0, 1, 2
 MAX_P = 16
+STATIC_SCRATCH_BYTES = 32 << 20
 
 _vp = ctypes.c_void_p
 _i64 = ctypes.c_int64
@@ -83,6 +84,8 @@ def lib():
         L.tw_fused_grid.restype = _i64
         L.tw_reduce_add_rmsnorm_unfused.argtypes = [ctypes.POINTER(FusedArgs), _vp, _vp]
         L.tw_reduce_add_rmsnorm_unfused.restype = ctypes.c_int
+        L.tw_reduce_add_rmsnorm_unfused_static.argtypes = [ctypes.POINTER(FusedArgs), _vp]
+        L.tw_reduce_add_rmsnorm_unfused_static.restype = ctypes.c_int
         L.tw_split_launch.argtypes = [ctypes.POINTER(FusedArgs), _i64, _vp, _vp, _vp, ctypes.c_int, ctypes.c_int]
         L.tw_split_launch.restype = ctypes.c_int
         L.tw_split_point.argtypes = [_i64, _i64]
@@ -258,6 +261,15 @@ def split_launch(partials, residual, weight, eps, split_row, stream_a, stream_b,
                                  1 if use_parent else 0, 1 if join else 0),
            "tw_split_launch")
     return out, residual_out
+def reduce_add_rmsnorm_unfused_static(partials, residual, weight, eps, out, residual_out, stream=None):
+    """tw_reduce_add_rmsnorm_unfused_static: the three-pass ablation with the library's own scratch.
+    `out` and `residual_out` must be given: this call allocates nothing. Returns (out, residual_out)."""
+    a, keep, out, residual_out = _fused_pack(partials, residual, weight, eps, 0, out, residual_out)
+    _check(lib().tw_reduce_add_rmsnorm_unfused_static(ctypes.byref(a), _stream_handle(stream)),
+           "tw_reduce_add_rmsnorm_unfused_static")
+    return out, residual_out
+
+
 
 
 def _gemm_pack(A, B, C, b_layout, cu_budget):

@@ -13,6 +13,8 @@
 // kernels run on the whole device with small workgroups; neither is confined to
 // a CU budget. The results differ from the fused kernel's by the two extra
 // roundings (t and the re-read x).
+#include <mutex>
+
 #include "tw_device.h"
 #include "tw_internal.h"
 
@@ -131,19 +133,44 @@ static hipError_t launch_add_norm(const UnfusedParams &prm, unsigned grid, hipSt
     return launch_kernel(add_norm_kernel<Q>, dim3(grid), dim3(kUThreads), 0, s, prm);
 }
 
-}  // namespace tw
 
-using namespace tw;
+// Scratch of the entry point that allocates nothing: the all-reduce's bf16 output
+// t lives in this file-scope array instead of a caller's buffer. Every GPU the
+// library is loaded on holds its own copy until the process ends. In host code
+// the array's name is only a handle for hipGetSymbolAddress: kernels and copies
+// get the device address that call returned, kept per device.
+static __device__ __align__(256) unsigned char scratch[TW_STATIC_SCRATCH_BYTES];
 
-extern "C" tw_status tw_reduce_add_rmsnorm_unfused(const tw_fused_args *args, void *sum_scratch, void *stream)
+static std::mutex g_scratch_mu;
+static void *g_scratch_ptr[kMaxDevices];  // nullptr = not looked up yet on that device
+
+static tw_status static_scratch(void **ptr)
 {
-    if (!args) return TW_ERR_NULL;
-    const tw_fused_args &a = *args;
+    int dev = 0;
+    TW_HIP(hipGetDevice(&dev));
+    if (dev < 0 || dev >= kMaxDevices) return hip_fail(hipErrorInvalidDevice, "tw_unfused.hip: device id out of range");
+    std::lock_guard<std::mutex> lk(g_scratch_mu);
+    if (!g_scratch_ptr[dev]) {
+        void *p = nullptr;
+        TW_HIP(hipGetSymbolAddress(&p, HIP_SYMBOL(scratch)));
+        if (!p) return hip_fail(hipErrorInvalidSymbol, "tw_unfused.hip: the scratch array has no device address");
+        g_scratch_ptr[dev] = p;
+    }
+    *ptr = g_scratch_ptr[dev];
+    return TW_OK;
+}
+
+// Host-only checks of the unfused call that do not need the scratch address.
+static tw_status validate_unfused(const tw_fused_args &a)
+{
     TW_TRY(validate_fused(a));
-    if (a.N == 0) return TW_OK;
-    if (!sum_scratch) return TW_ERR_NULL;
-    if (!aligned16(sum_scratch)) return TW_ERR_ALIGN;
-    if (a.H > 8192) return TW_ERR_UNSUPPORTED;  // add_norm_kernel covers rows of up to 4 * 256 vectors
+    if (a.N > 0 && a.H > 8192) return TW_ERR_UNSUPPORTED;  // add_norm_kernel covers rows of up to 4 * 256 vectors
+    return TW_OK;
+}
+
+// Both launches of the (already validated) pipeline, t going through sum_scratch.
+static tw_status launch_unfused(const tw_fused_args &a, void *sum_scratch, hipStream_t s)
+{
     const uint64_t bytes = static_cast<uint64_t>(a.N) * static_cast<uint64_t>(a.H) * 2u;
     for (int p = 0; p < a.P; ++p)
         if (ranges_overlap(sum_scratch, bytes, a.partials[p], bytes)) return TW_ERR_ALIAS;
@@ -155,7 +182,6 @@ extern "C" tw_status tw_reduce_add_rmsnorm_unfused(const tw_fused_args *args, vo
 
     int cus = 0;
     TW_TRY(current_cu_count(&cus));
-    hipStream_t s = static_cast<hipStream_t>(stream);
     const int hv = static_cast<int>(a.H / 8);
     const int64_t row_bytes = a.H * 2;
     const int64_t rows_per_launch = kMaxLaunchBytes / row_bytes;
@@ -195,4 +221,34 @@ extern "C" tw_status tw_reduce_add_rmsnorm_unfused(const tw_fused_args *args, vo
         else TW_HIP(launch_add_norm<4>(prm, static_cast<unsigned>(g2), s));
     }
     return TW_OK;
+}
+
+}  // namespace tw
+
+using namespace tw;
+
+extern "C" tw_status tw_reduce_add_rmsnorm_unfused(const tw_fused_args *args, void *sum_scratch, void *stream)
+{
+    if (!args) return TW_ERR_NULL;
+    const tw_fused_args &a = *args;
+    TW_TRY(validate_fused(a));
+    if (a.N == 0) return TW_OK;
+    if (!sum_scratch) return TW_ERR_NULL;
+    if (!aligned16(sum_scratch)) return TW_ERR_ALIGN;
+    TW_TRY(validate_unfused(a));
+    return launch_unfused(a, sum_scratch, static_cast<hipStream_t>(stream));
+}
+
+extern "C" tw_status tw_reduce_add_rmsnorm_unfused_static(const tw_fused_args *args, void *stream)
+{
+    if (!args) return TW_ERR_NULL;
+    const tw_fused_args &a = *args;
+    TW_TRY(validate_unfused(a));
+    // validate_fused has bounded N * H far below 2^62
+    if (static_cast<uint64_t>(a.N) * static_cast<uint64_t>(a.H) * 2u > uint64_t(TW_STATIC_SCRATCH_BYTES))
+        return TW_ERR_SHAPE;
+    if (a.N == 0) return TW_OK;
+    void *t = nullptr;
+    TW_TRY(static_scratch(&t));
+    return launch_unfused(a, t, static_cast<hipStream_t>(stream));
 }

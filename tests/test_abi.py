@@ -174,6 +174,34 @@ def test_split_point_matches_its_definition():
                 want = -(-q // m) * m
             want = min(want, n)
             assert tw.split_point(n, m) == want, (n, m)
+def static_call(n=N, **kw):
+    arr = (VP * P)(addr(0), addr(1))
+    a = FusedArgs(ctypes.cast(arr, ctypes.POINTER(VP)), addr(4), addr(5), 1e-5, n, H, P, 8, addr(6), addr(7))
+    for k, v in kw.items():
+        setattr(a, k, v)
+    return tw.lib().tw_reduce_add_rmsnorm_unfused_static(ctypes.byref(a), VP(None))
+
+
+def test_unfused_static_argument_checks():
+    """The entry point that allocates nothing rejects what does not fit its built-in buffer on the
+    host, before any HIP call."""
+    assert tw.lib().tw_reduce_add_rmsnorm_unfused_static(None, VP(None)) == E_NULL
+    assert static_call(H=60) == E_UNSUP
+    assert static_call(H=8200, n=1) == E_UNSUP
+    assert static_call(n=0) == OK
+    assert static_call(P=0) == E_SHAPE
+    assert static_call(out=addr(7)) == E_ALIAS          # the fused call's own rules still apply
+    limit = tw.STATIC_SCRATCH_BYTES
+    text = open(os.path.join(ROOT, "include", "tw.h")).read()
+    assert re.search(r"#define\s+TW_STATIC_SCRATCH_BYTES\s+\(32u\s*<<\s*20\)", text) and limit == 32 << 20
+    rows = limit // (8192 * 2)
+    # tensors far enough apart not to overlap at this size; one row too many is refused
+    far = lambda i: BASE + i * (1 << 32)
+    arr = (VP * P)(far(0), far(1))
+    a = FusedArgs(ctypes.cast(arr, ctypes.POINTER(VP)), far(4), far(5), 1e-5, rows + 1, 8192, P, 0, far(6), far(7))
+    assert tw.lib().tw_reduce_add_rmsnorm_unfused_static(ctypes.byref(a), VP(None)) == E_SHAPE
+
+
     assert tw.split_point(-5, 128) == 0
     assert tw.split_point(100, 0) == 50
     assert tw.split_point(100, -3) == 50
