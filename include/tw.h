@@ -31,8 +31,12 @@
  *     launches nothing and works (returns its error) on a machine without a GPU.
  *   - Results are a pure function of each row's inputs: bits do not depend on
  *     cu_budget, on N, on the stream, or on whether and where rows were split.
- *   - Thread safety: calls may be made from several host threads; work given to
- *     one stream is ordered by that stream as usual.
+ *   - Thread safety: calls may be made from several host threads at once; work
+ *     given to one stream is ordered by that stream as usual. The events the
+ *     cross-stream entry points order their streams with come from a small ring
+ *     per host thread and device, so one thread's record-then-wait pair can never
+ *     pick up another thread's record. Nothing is allocated per call once a
+ *     thread has made its first few calls on a device (16 events at most).
  */
 #ifndef TW_H_
 #define TW_H_
@@ -123,19 +127,6 @@ tw_status tw_reduce_add_rmsnorm(const void *const *partials, const void *residua
                                 void *stream);
 
 /*
- * Same as tw_reduce_add_rmsnorm, and in addition workgroup g of the launch
- * writes, once, the hardware placement it ran on to hw_ids[2*g] (the raw HW_ID
- * register) and hw_ids[2*g+1] (the raw XCC_ID register), so that "confined to
- * cu_budget compute units" can be evidenced (Section 4.3 / Fig. 9 vary the
- * number of SMs the kernel gets). hw_ids: device uint32 [2 * hw_ids_len];
- * hw_ids_len must be at least the grid size that tw_fused_grid() returns.
- */
-tw_status tw_reduce_add_rmsnorm_traced(const void *const *partials, const void *residual,
-                                       const void *weight, float eps, int64_t N, int64_t H,
-                                       int P, int cu_budget, void *out, void *residual_out,
-                                       uint32_t *hw_ids, int64_t hw_ids_len, void *stream);
-
-/*
  * Ablation: the pipeline the fused kernel replaces (Section 4.2 and Table 1:
  * all-reduce, then residual add + RMSNorm; Section 4.3: a stand-alone RMSNorm
  * reads the tensor twice and writes it once). Two launches on `stream`:
@@ -173,20 +164,6 @@ tw_status tw_reduce_add_rmsnorm_unfused(const tw_fused_args *args, void *sum_scr
  */
 #define TW_STATIC_SCRATCH_BYTES (32u << 20) /* 32 MiB: e.g. 2048 rows of H = 8192 */
 tw_status tw_reduce_add_rmsnorm_unfused_static(const tw_fused_args *args, void *stream);
-
-/* Number of workgroups the fused kernel is launched with for these sizes on the
- * current device (0 if N == 0; -1 if the arguments are invalid or no device). */
-int64_t tw_fused_grid(int64_t N, int64_t H, int P, int cu_budget);
-
-/*
- * How the budgeted fused kernel lays a row of H elements over a workgroup (host
- * arithmetic only, no device needed): waves per row (0: the row is narrower
- * than a wave and takes a power-of-two group of lanes), 16-byte vectors per
- * thread, rows per workgroup trip and threads per workgroup. Any pointer may be
- * NULL. Returns TW_ERR_UNSUPPORTED for an H the kernel does not take.
- */
-tw_status tw_fused_layout(int64_t H, int *waves_per_row, int *vectors_per_thread, int *rows_per_trip,
-                          int *threads_per_workgroup);
 
 /*
  * Two-way token split (Section 4: prefix split T_a, suffix split T_b; every
@@ -331,20 +308,11 @@ tw_status tw_weave_layer(const tw_layer_args *layer, int64_t split_row, void *st
                          void *stream_comm, void *parent, int parent_is_set, int join);
 
 /*
- * The schedule tw_weave_layer takes for a split boundary of these sizes on a
- * device with `cus` compute units: TW_WEAVE_ORDERED or TW_WEAVE_CHAINS (the
- * `schedule` argument itself unless it is TW_WEAVE_AUTO). Host arithmetic only.
- * Returns -1 on bad arguments.
- */
-int tw_weave_schedule(int64_t T, int64_t K1, int64_t H, int P, int64_t N2, int fused_cu_budget, int schedule,
-                      int cus);
-
-/*
  * Wave-aware choice of the split row (Section 4.1.1 and Appendix A
  * "Smart-Splitting"; Algorithm 1 finds the offset by profiling because its GEMMs
  * are closed source, here the GEMM's tile grid is known, so the same sweep is
  * evaluated analytically). A GEMM over r rows with output width n runs
- * ceil(r / tile_m) * ceil(n / tile_n) workgroups, i.e. ceil(that / cus) waves on
+ * ceil(r / 256) * ceil(n / 128) workgroups (the GEMM's output tile), i.e. ceil(that / cus) waves on
  * `cus` compute units, and a wave lasts in proportion to the GEMM's depth k. The
  * cost of a cut is the sum over both splits and all n_gemms GEMMs of waves * k
  * (gemm_k == NULL: every GEMM weighs 1, the cost is the plain wave count). Among
@@ -375,42 +343,39 @@ int64_t tw_smart_split_point(int64_t T, int64_t multiple, const int64_t *gemm_n_
 #define TW_DEFAULT_SPLIT_THRESHOLD 6144
 int tw_should_split(int64_t num_tokens, int64_t threshold);
 
-/* Rows and columns of the output tile one GEMM workgroup computes (a product
- * whose tiles would fill at most half of its compute units is cut into tiles of
- * half this width instead; tw_smart_split_point counts in tiles of this shape). */
-void tw_gemm_tile_shape(int *tile_m, int *tile_n);
+/*
+ * Token threshold for ONE block boundary G1 -> F -> G2 of the given sizes on a
+ * device with `cus` compute units, for callers without a profile of their own
+ * (the paper finds its thresholds by offline profiling, per model: Appendix A
+ * "Selective Enabling of Splitting and Overlap"). The larger of two bounds,
+ * rounded up to whole GEMM row tiles:
+ *   - the fused step of the whole batch, (P + 3) * 2H bytes per row at 5 TB/s,
+ *     must take at least 140 us: below that the cross-stream waits and the
+ *     contention between co-resident kernels cost more than hiding it gains;
+ *   - half the batch must still cut the narrower of the two GEMM outputs
+ *     (min(H, N2) columns) into tiles for at least half of the compute units.
+ * On MI355X this gives 4096 for [T x 1024] x [1024 x 8192] -> F(H = 8192, P = 8)
+ * -> [T x 8192] x [8192 x 3584] and 6656 for the MLP-side boundary with K1 =
+ * 3584, N2 = 1280; profiling puts the break-even points at about 4K and 7K.
+ * Host only. Returns -1 on bad arguments (any size < 1).
+ */
+int64_t tw_split_threshold(int64_t K1, int64_t H, int P, int64_t N2, int cus);
 
 /*
- * Measurement aid (not part of the method): a streaming kernel with the same
- * persistent, CU-budgeted launch shape as the fused kernel, used to measure
- * what a given number of compute units can pull from / push to HBM, and as the
- * copy of known size against which hardware byte counters are scaled.
- *   mode TW_PROBE_READ: reads `bytes` from src (dst gets one 16-byte word per
- *        wave so the loads cannot be dropped; dst needs 256 bytes per compute
- *        unit of the device, 64 KiB on a 256-CU part);
- *   mode TW_PROBE_COPY: dst[0..bytes) = src[0..bytes);
- *   mode TW_PROBE_WRITE: dst[0..bytes) = a constant pattern (src unused, may be NULL).
- * bytes must be a multiple of 16; pointers 16-byte aligned; src and dst must
- * not overlap.
+ * The per-iteration policy of Fig. 3 as one call, for one block boundary: a
+ * batch of fewer than `threshold` tokens runs the chain G1, F, G2 unsplit on
+ * stream_compute (the fused kernel is still used; only splitting and overlap are
+ * switched off); a larger one is cut at the row tw_smart_split_point picks
+ * (candidates at multiples of `multiple`, GEMM widths {H, N2} with depths {K1,
+ * H}, on the GEMMs' compute units) and woven by tw_weave_layer in the schedule
+ * layer->schedule names. threshold <= 0: tw_split_threshold() of this boundary;
+ * multiple <= 0: 64. *split_row (may be NULL) receives the row taken, T meaning
+ * "not split"; it is written before anything is enqueued, also when the launch
+ * then fails. Everything else as for tw_weave_layer, whose bit-exactness across
+ * split rows makes the policy invisible in the results.
  */
-#define TW_PROBE_READ 0
-#define TW_PROBE_COPY 1
-#define TW_PROBE_WRITE 2
-tw_status tw_hbm_probe(const void *src, void *dst, int64_t bytes, int mode, int cu_budget,
-                       void *stream);
-
-/*
- * Measurement aid: the fused kernel's traffic shape without its arithmetic.
- * With the same budgeted launch, every workgroup walks 16 KiB rows; per row it
- * reads n_read streams (src + r * stream_bytes, r < n_read) and writes n_write
- * streams (dst + w * stream_bytes) at the same offset. What
- * it reaches is the ceiling of any kernel with that mix of loads and stores on
- * that many compute units. stream_bytes: a multiple of 16384, at most 2 GiB;
- * 0 <= n_read <= TW_MAX_P + 1, 0 <= n_write <= 4, not both zero. With
- * n_write == 0, dst still needs 16 KiB. src and dst ranges must not overlap.
- */
-tw_status tw_hbm_probe_mixed(const void *src, void *dst, int64_t stream_bytes, int n_read,
-                             int n_write, int cu_budget, void *stream);
+tw_status tw_weave_layer_auto(const tw_layer_args *layer, int64_t threshold, int64_t multiple, void *stream_compute,
+                              void *stream_comm, void *parent, int parent_is_set, int join, int64_t *split_row);
 
 /* Compute units of the current device; -1 when no device can be queried. */
 int tw_device_cu_count(void);

@@ -1,0 +1,115 @@
+/*
+ * tw_measure.h -- measurement and introspection aids of libtw. They live in the
+ * same shared library as the entry points of tw.h but are NOT part of the
+ * method's interface: they expose launch geometry and streaming probes so that
+ * claims about the kernels (how many compute units a budget occupies, what a
+ * compute unit can pull from HBM, which schedule a boundary takes) can be
+ * evidenced from outside. Their signatures may change with the kernels; nothing
+ * in tw.h depends on them. Conventions (device pointers, status codes, checks
+ * before the first HIP call) are those of tw.h.
+ */
+#ifndef TW_MEASURE_H_
+#define TW_MEASURE_H_
+
+#include "tw.h"
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+/*
+ * Same as tw_reduce_add_rmsnorm, and in addition workgroup g of the launch
+ * writes, once, the hardware placement it ran on to hw_ids[2*g] (the raw HW_ID
+ * register) and hw_ids[2*g+1] (the raw XCC_ID register), so that "confined to
+ * cu_budget compute units" can be evidenced (Section 4.3 / Fig. 9 vary the
+ * number of SMs the kernel gets). hw_ids: device uint32 [2 * hw_ids_len];
+ * hw_ids_len must be at least the grid size that tw_fused_grid() returns.
+ */
+tw_status tw_reduce_add_rmsnorm_traced(const void *const *partials, const void *residual,
+                                       const void *weight, float eps, int64_t N, int64_t H,
+                                       int P, int cu_budget, void *out, void *residual_out,
+                                       uint32_t *hw_ids, int64_t hw_ids_len, void *stream);
+
+/* Number of workgroups the fused kernel is launched with for these sizes on the
+ * current device (0 if N == 0; -1 if the arguments are invalid or no device). */
+int64_t tw_fused_grid(int64_t N, int64_t H, int P, int cu_budget);
+
+/*
+ * How the budgeted fused kernel lays a row of H elements over a workgroup (host
+ * arithmetic only, no device needed): waves per row (0: the row is narrower
+ * than a wave and takes a power-of-two group of lanes), 16-byte vectors per
+ * thread, rows per workgroup trip and threads per workgroup. Any pointer may be
+ * NULL. Returns TW_ERR_UNSUPPORTED for an H the kernel does not take.
+ */
+tw_status tw_fused_layout(int64_t H, int *waves_per_row, int *vectors_per_thread, int *rows_per_trip,
+                          int *threads_per_workgroup);
+
+/*
+ * The schedule tw_weave_layer takes for a split boundary of these sizes on a
+ * device with `cus` compute units: TW_WEAVE_ORDERED or TW_WEAVE_CHAINS (the
+ * `schedule` argument itself unless it is TW_WEAVE_AUTO). Host arithmetic only.
+ * Returns -1 on bad arguments.
+ */
+int tw_weave_schedule(int64_t T, int64_t K1, int64_t H, int P, int64_t N2, int fused_cu_budget, int schedule,
+                      int cus);
+
+/* Rows and columns of the output tile one GEMM workgroup computes (a product
+ * whose tiles would fill at most half of its compute units is cut into tiles of
+ * half this width instead; tw_smart_split_point counts in tiles of this shape). */
+void tw_gemm_tile_shape(int *tile_m, int *tile_n);
+
+/*
+ * Measurement aid (not part of the method): a streaming kernel with the same
+ * persistent, CU-budgeted launch shape as the fused kernel, used to measure
+ * what a given number of compute units can pull from / push to HBM, and as the
+ * copy of known size against which hardware byte counters are scaled.
+ *   mode TW_PROBE_READ: reads `bytes` from src (dst gets one 16-byte word per
+ *        wave so the loads cannot be dropped; dst needs 256 bytes per compute
+ *        unit of the device, 64 KiB on a 256-CU part);
+ *   mode TW_PROBE_COPY: dst[0..bytes) = src[0..bytes);
+ *   mode TW_PROBE_WRITE: dst[0..bytes) = a constant pattern (src unused, may be NULL).
+ * bytes must be a multiple of 16; pointers 16-byte aligned; src and dst must
+ * not overlap.
+ */
+#define TW_PROBE_READ 0
+#define TW_PROBE_COPY 1
+#define TW_PROBE_WRITE 2
+tw_status tw_hbm_probe(const void *src, void *dst, int64_t bytes, int mode, int cu_budget,
+                       void *stream);
+
+/*
+ * Measurement aid: the fused kernel's traffic shape without its arithmetic.
+ * With the same budgeted launch, every workgroup walks 16 KiB rows; per row it
+ * reads n_read streams (src + r * stream_bytes, r < n_read) and writes n_write
+ * streams (dst + w * stream_bytes) at the same offset. What
+ * it reaches is the ceiling of any kernel with that mix of loads and stores on
+ * that many compute units. stream_bytes: a multiple of 16384, at most 2 GiB;
+ * 0 <= n_read <= TW_MAX_P + 1, 0 <= n_write <= 4, not both zero. With
+ * n_write == 0, dst still needs 16 KiB. src and dst ranges must not overlap.
+ */
+tw_status tw_hbm_probe_mixed(const void *src, void *dst, int64_t stream_bytes, int n_read,
+                             int n_write, int cu_budget, void *stream);
+
+/*
+ * tw_hbm_probe with the launch shape opened up, to show what the ceiling of a
+ * compute unit does and does not depend on: `threads` per workgroup (a multiple
+ * of 64, at most 1024; still one workgroup per compute unit) and `in_flight`
+ * 16-byte accesses issued per thread before the first is consumed (1, 2, 4, 8 or
+ * 16; others: TW_ERR_UNSUPPORTED). tw_hbm_probe is the case (1024, 8). In
+ * TW_PROBE_READ mode dst needs 256 bytes per compute unit whatever `threads` is.
+ */
+tw_status tw_hbm_probe_shaped(const void *src, void *dst, int64_t bytes, int mode, int cu_budget, int threads,
+                              int in_flight, void *stream);
+
+/*
+ * tw_hbm_probe_mixed with `threads` per workgroup (64, 128, 256, 512 or 1024: a
+ * workgroup then walks rows of threads * 16 bytes; each thread still has n_read
+ * loads in flight). tw_hbm_probe_mixed is the case 1024.
+ */
+tw_status tw_hbm_probe_mixed_shaped(const void *src, void *dst, int64_t stream_bytes, int n_read, int n_write,
+                                    int cu_budget, int threads, void *stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* TW_MEASURE_H_ */

@@ -1,4 +1,4 @@
-"""ctypes binding of include/tw.h. Argument marshalling only.
+"""ctypes binding of include/tw.h and include/tw_measure.h. Argument marshalling only.
 
 Tensors are torch tensors on the GPU (bfloat16, contiguous); the binding passes
 their data_ptr() and sizes. Streams are torch.cuda.Stream objects (or None for
@@ -99,6 +99,11 @@ def lib():
         L.tw_hbm_probe.restype = ctypes.c_int
         L.tw_weave_layer.argtypes = [ctypes.POINTER(LayerArgs), _i64, _vp, _vp, _vp, ctypes.c_int, ctypes.c_int]
         L.tw_weave_layer.restype = ctypes.c_int
+        L.tw_weave_layer_auto.argtypes = [ctypes.POINTER(LayerArgs), _i64, _i64, _vp, _vp, _vp, ctypes.c_int, ctypes.c_int,
+                                          ctypes.POINTER(_i64)]
+        L.tw_weave_layer_auto.restype = ctypes.c_int
+        L.tw_split_threshold.argtypes = [_i64, _i64, ctypes.c_int, _i64, ctypes.c_int]
+        L.tw_split_threshold.restype = _i64
         L.tw_smart_split_point.argtypes = [_i64, _i64, ctypes.POINTER(_i64), ctypes.POINTER(_i64), ctypes.c_int,
                                            ctypes.c_int,
                                            ctypes.POINTER(_i64), ctypes.POINTER(_i64)]
@@ -113,6 +118,11 @@ def lib():
         L.tw_gemm_tile_shape.restype = None
         L.tw_hbm_probe_mixed.argtypes = [_vp, _vp, _i64, ctypes.c_int, ctypes.c_int, ctypes.c_int, _vp]
         L.tw_hbm_probe_mixed.restype = ctypes.c_int
+        L.tw_hbm_probe_shaped.argtypes = [_vp, _vp, _i64, ctypes.c_int, ctypes.c_int, ctypes.c_int, ctypes.c_int, _vp]
+        L.tw_hbm_probe_shaped.restype = ctypes.c_int
+        L.tw_hbm_probe_mixed_shaped.argtypes = [_vp, _vp, _i64, ctypes.c_int, ctypes.c_int, ctypes.c_int, ctypes.c_int,
+                                                _vp]
+        L.tw_hbm_probe_mixed_shaped.restype = ctypes.c_int
         L.tw_device_cu_count.argtypes = []
         L.tw_device_cu_count.restype = ctypes.c_int
         L.tw_status_str.argtypes = [ctypes.c_int]
@@ -251,6 +261,15 @@ def reduce_add_rmsnorm_unfused(partials, residual, weight, eps, out=None, residu
     return out, residual_out
 
 
+def reduce_add_rmsnorm_unfused_static(partials, residual, weight, eps, out, residual_out, stream=None):
+    """tw_reduce_add_rmsnorm_unfused_static: the three-pass ablation with the library's own scratch.
+    `out` and `residual_out` must be given: this call allocates nothing. Returns (out, residual_out)."""
+    a, keep, out, residual_out = _fused_pack(partials, residual, weight, eps, 0, out, residual_out)
+    _check(lib().tw_reduce_add_rmsnorm_unfused_static(ctypes.byref(a), _stream_handle(stream)),
+           "tw_reduce_add_rmsnorm_unfused_static")
+    return out, residual_out
+
+
 def split_launch(partials, residual, weight, eps, split_row, stream_a, stream_b, cu_budget=0,
                  out=None, residual_out=None, parent=None, use_parent=True, join=True):
     """tw_split_launch. parent=None with use_parent=True means torch's current stream."""
@@ -261,15 +280,6 @@ def split_launch(partials, residual, weight, eps, split_row, stream_a, stream_b,
                                  1 if use_parent else 0, 1 if join else 0),
            "tw_split_launch")
     return out, residual_out
-def reduce_add_rmsnorm_unfused_static(partials, residual, weight, eps, out, residual_out, stream=None):
-    """tw_reduce_add_rmsnorm_unfused_static: the three-pass ablation with the library's own scratch.
-    `out` and `residual_out` must be given: this call allocates nothing. Returns (out, residual_out)."""
-    a, keep, out, residual_out = _fused_pack(partials, residual, weight, eps, 0, out, residual_out)
-    _check(lib().tw_reduce_add_rmsnorm_unfused_static(ctypes.byref(a), _stream_handle(stream)),
-           "tw_reduce_add_rmsnorm_unfused_static")
-    return out, residual_out
-
-
 
 
 def _gemm_pack(A, B, C, b_layout, cu_budget):
@@ -337,6 +347,21 @@ def hbm_probe_mixed(src, dst, stream_bytes, n_read, n_write, cu_budget=0, stream
                                     _stream_handle(stream)), "tw_hbm_probe_mixed")
 
 
+def hbm_probe_shaped(src, dst, nbytes, mode, cu_budget=0, threads=1024, in_flight=8, stream=None):
+    """tw_hbm_probe_shaped: tw_hbm_probe with the workgroup size and the accesses in flight per thread given."""
+    _check(lib().tw_hbm_probe_shaped(_vp(src.data_ptr()) if src is not None else _vp(None), _vp(dst.data_ptr()),
+                                     int(nbytes), int(mode), int(cu_budget), int(threads), int(in_flight),
+                                     _stream_handle(stream)), "tw_hbm_probe_shaped")
+
+
+def hbm_probe_mixed_shaped(src, dst, stream_bytes, n_read, n_write, cu_budget=0, threads=1024, stream=None):
+    """tw_hbm_probe_mixed_shaped: tw_hbm_probe_mixed with the workgroup size given."""
+    _check(lib().tw_hbm_probe_mixed_shaped(_vp(src.data_ptr()) if src is not None else _vp(None),
+                                           _vp(dst.data_ptr()), int(stream_bytes), int(n_read), int(n_write),
+                                           int(cu_budget), int(threads), _stream_handle(stream)),
+           "tw_hbm_probe_mixed_shaped")
+
+
 def smart_split_point(T, multiple, gemm_n_out, cus, gemm_k=None):
     """tw_smart_split_point. Returns (split_row, cost_split, cost_unsplit); without gemm_k the costs are
     wave counts."""
@@ -376,6 +401,33 @@ def weave_layer(X1, W1, partials, residual, weight, eps, W2, split_row, stream_c
                                 _stream_handle(parent) if use_parent else _vp(None),
                                 1 if use_parent else 0, 1 if join else 0), "tw_weave_layer")
     return out, residual_out, Y
+
+
+def weave_layer_auto(X1, W1, partials, residual, weight, eps, W2, stream_compute, stream_comm, threshold=0,
+                     multiple=0, fused_cu_budget=CU_SHARED, gemm_cu_budget=0, out=None, residual_out=None, Y=None,
+                     parent=None, use_parent=True, join=True, schedule=WEAVE_AUTO):
+    """tw_weave_layer_auto. Returns (out, residual_out, Y, split_row_taken)."""
+    import torch
+    a, keep, out, residual_out = _fused_pack(partials, residual, weight, eps, fused_cu_budget, out, residual_out)
+    T, H = residual.shape
+    K1 = X1.shape[1]
+    N2 = W2.shape[0]
+    if Y is None:
+        Y = torch.empty((T, N2), dtype=torch.bfloat16, device=residual.device)
+    la = LayerArgs(_bf16_ptr(X1, "X1", (T, K1)), _bf16_ptr(W1, "W1", (H, K1)), K1, a,
+                   _bf16_ptr(W2, "W2", (N2, H)), N2, _bf16_ptr(Y, "Y", (T, N2)), int(gemm_cu_budget), int(schedule))
+    taken = _i64(-1)
+    _check(lib().tw_weave_layer_auto(ctypes.byref(la), int(threshold), int(multiple), _stream_handle(stream_compute),
+                                     _stream_handle(stream_comm),
+                                     _stream_handle(parent) if use_parent else _vp(None),
+                                     1 if use_parent else 0, 1 if join else 0, ctypes.byref(taken)),
+           "tw_weave_layer_auto")
+    return out, residual_out, Y, int(taken.value)
+
+
+def split_threshold(K1, H, P, N2, cus=256):
+    """tw_split_threshold: the built-in token threshold of one block boundary."""
+    return int(lib().tw_split_threshold(int(K1), int(H), int(P), int(N2), int(cus)))
 
 
 def weave_schedule(T, K1, H, P, N2, fused_cu_budget=CU_SHARED, schedule=WEAVE_AUTO, cus=256):

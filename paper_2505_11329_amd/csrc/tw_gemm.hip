@@ -137,17 +137,33 @@ struct Frags {
     bf16x8 a[WM];
     bf16x8 b[WN];
     u32x2 blo[2], bhi[2];
+    // LDS reads that fill one set of fragments = registers (or register pairs)
+    // a wait has to name: WM of A, and WN of B or, stored [K x N], four halves
+    static constexpr int kReads = WM + (B_KN ? 4 : WN);
 };
 // Wait until at most N of this wave's LDS reads are outstanding. The fragments
-// are passed through so that no use of them can be moved above the wait.
+// are passed through so that no use of them can be moved above the wait. Each
+// operand list comes with its length, which wait_lgkm checks against the number
+// of reads that fill the fragments: a tile shape whose reads and waits disagree
+// does not compile.
 #define TW_FRAG_A2(f) "+v"((f).a[0]), "+v"((f).a[1])
+#define TW_FRAG_A2_LEN 2
 #define TW_FRAG_A4(f) TW_FRAG_A2(f), "+v"((f).a[2]), "+v"((f).a[3])
+#define TW_FRAG_A4_LEN 4
 #define TW_FRAG_B1(f) "+v"((f).b[0])
+#define TW_FRAG_B1_LEN 1
 #define TW_FRAG_B2(f) "+v"((f).b[0]), "+v"((f).b[1])
+#define TW_FRAG_B2_LEN 2
 #define TW_FRAG_B4(f) TW_FRAG_B2(f), "+v"((f).b[2]), "+v"((f).b[3])
+#define TW_FRAG_B4_LEN 4
 #define TW_FRAG_B_KN(f) "+v"((f).blo[0]), "+v"((f).bhi[0]), "+v"((f).blo[1]), "+v"((f).bhi[1])
-#define TW_WAIT_LGKM(N, A_OPS, B_OPS) \
-    asm volatile("s_waitcnt lgkmcnt(%[cnt])" : A_OPS, B_OPS : [cnt] "n"(N) : "memory")
+#define TW_FRAG_B_KN_LEN 4
+#define TW_WAIT_LGKM(N, f, A_LIST, B_LIST)                                                               \
+    do {                                                                                                  \
+        static_assert(A_LIST##_LEN + B_LIST##_LEN == std::remove_reference_t<decltype(f)>::kReads,        \
+                      "the wait must name every register an LDS fragment read writes");                   \
+        asm volatile("s_waitcnt lgkmcnt(%[cnt])" : A_LIST(f), B_LIST(f) : [cnt] "n"(N) : "memory");       \
+    } while (0)
 
 // f(integral_constant<int, 0>) ... f(integral_constant<int, N - 1>), unrolled
 template <int... I, typename Fn>
@@ -166,13 +182,13 @@ __device__ __forceinline__ void wait_lgkm(Frags<B_KN, WM, WN> &f)
 {
     static_assert(WM == 2 || WM == 4, "fragment operand lists below");
     static_assert(B_KN ? WN == 2 : (WN == 1 || WN == 2 || WN == 4), "fragment operand lists below");
-    if constexpr (WM == 2 && !B_KN && WN == 1) TW_WAIT_LGKM(N, TW_FRAG_A2(f), TW_FRAG_B1(f));
-    if constexpr (WM == 2 && B_KN) TW_WAIT_LGKM(N, TW_FRAG_A2(f), TW_FRAG_B_KN(f));
-    if constexpr (WM == 4 && B_KN) TW_WAIT_LGKM(N, TW_FRAG_A4(f), TW_FRAG_B_KN(f));
-    if constexpr (WM == 2 && !B_KN && WN == 2) TW_WAIT_LGKM(N, TW_FRAG_A2(f), TW_FRAG_B2(f));
-    if constexpr (WM == 4 && !B_KN && WN == 2) TW_WAIT_LGKM(N, TW_FRAG_A4(f), TW_FRAG_B2(f));
-    if constexpr (WM == 2 && !B_KN && WN == 4) TW_WAIT_LGKM(N, TW_FRAG_A2(f), TW_FRAG_B4(f));
-    if constexpr (WM == 4 && !B_KN && WN == 4) TW_WAIT_LGKM(N, TW_FRAG_A4(f), TW_FRAG_B4(f));
+    if constexpr (WM == 2 && !B_KN && WN == 1) TW_WAIT_LGKM(N, f, TW_FRAG_A2, TW_FRAG_B1);
+    if constexpr (WM == 2 && B_KN) TW_WAIT_LGKM(N, f, TW_FRAG_A2, TW_FRAG_B_KN);
+    if constexpr (WM == 4 && B_KN) TW_WAIT_LGKM(N, f, TW_FRAG_A4, TW_FRAG_B_KN);
+    if constexpr (WM == 2 && !B_KN && WN == 2) TW_WAIT_LGKM(N, f, TW_FRAG_A2, TW_FRAG_B2);
+    if constexpr (WM == 4 && !B_KN && WN == 2) TW_WAIT_LGKM(N, f, TW_FRAG_A4, TW_FRAG_B2);
+    if constexpr (WM == 2 && !B_KN && WN == 4) TW_WAIT_LGKM(N, f, TW_FRAG_A2, TW_FRAG_B4);
+    if constexpr (WM == 4 && !B_KN && WN == 4) TW_WAIT_LGKM(N, f, TW_FRAG_A4, TW_FRAG_B4);
 }
 
 template <bool B_KN, int WM, int WN, int STAGES, int BK>
@@ -197,7 +213,6 @@ __global__ __launch_bounds__(64 * (16 / WM)) void gemm_bf16_kernel(const GemmPar
     static_assert(BK == 64 || BK == 32, "LDS layouts below");
     static_assert(STAGES >= 2 && (STAGES - 2) * kLoads < 64, "vmcnt field");
     static_assert(!B_KN || (WN == 2 && BK == 64), "[K x N] operands: 256 x 128 x 64 tiles only");
-    constexpr int kFragReads = WM + (B_KN ? 4 : WN);  // LDS reads of one sub-step
 
     const int tid = threadIdx.x;
     const int lane = tid & 63;
@@ -252,6 +267,7 @@ __global__ __launch_bounds__(64 * (16 / WM)) void gemm_bf16_kernel(const GemmPar
     }
 
     using F = Frags<B_KN, WM, WN>;
+    constexpr int kFragReads = F::kReads;  // LDS reads of one sub-step: what read_one issues and wait_lgkm names
 
     for (int w = blockIdx.x; w < prm.tiles_per_xcd * kXcds; w += gridDim.x) {
         const int slot_w = w / kXcds;

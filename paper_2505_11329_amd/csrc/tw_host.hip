@@ -1,6 +1,7 @@
 // Host side of libtw that is not tied to one kernel: status strings, device
 // queries, the event pool, the token split and the overlap launch.
 #include <mutex>
+#include <vector>
 
 #include "tw_internal.h"
 
@@ -54,26 +55,62 @@ tw_status allow_dynamic_lds(const void *kernel, int bytes, std::atomic<int> *don
 
 // Events are only used as stream-ordering markers: recorded on one stream and
 // waited on by another within the same call. A wait refers to the record that
-// precedes it, so an event can be recorded again later; a ring of them keeps a
-// comfortable distance between reuses anyway.
-static constexpr int kEventRing = 64;
-static hipEvent_t g_events[kMaxDevices][kEventRing];
-static bool g_event_made[kMaxDevices][kEventRing];
-static int g_event_next[kMaxDevices];
+// precedes it, so an event can be recorded again once its wait has been
+// enqueued. Each host thread draws from a ring of its own (per device): between
+// one thread's record and its wait no other thread can record the same event,
+// whatever the interleaving, and a call uses far fewer events than a ring holds,
+// so a call never meets its own event twice. A thread that ends hands its events
+// to a spare list for later threads; nothing is destroyed (the runtime may
+// already be shutting down when the last thread-local is torn down).
+static constexpr int kEventRing = 16;  // most events one call records: 5 (tw_weave_layer, ordered)
+static std::vector<hipEvent_t> *g_spare_events[kMaxDevices];  // leaked on purpose, guarded by g_mu
+
+struct EventRing {
+    hipEvent_t ev[kMaxDevices][kEventRing];
+    unsigned char made[kMaxDevices];  // events created so far on that device
+    unsigned char next[kMaxDevices];
+    EventRing() : ev(), made(), next() {}
+    ~EventRing()
+    {
+        std::lock_guard<std::mutex> lk(g_mu);
+        for (int d = 0; d < kMaxDevices; ++d) {
+            if (!made[d]) continue;
+            if (!g_spare_events[d]) g_spare_events[d] = new std::vector<hipEvent_t>();
+            for (int i = 0; i < made[d]; ++i) g_spare_events[d]->push_back(ev[d][i]);
+        }
+    }
+};
+static thread_local EventRing t_ring;
 
 tw_status borrow_event(hipEvent_t *ev)
 {
     int dev = 0;
     TW_HIP(hipGetDevice(&dev));
     if (dev < 0 || dev >= kMaxDevices) return hip_fail(hipErrorInvalidDevice, "tw_host.hip: device id out of range");
-    std::lock_guard<std::mutex> lk(g_mu);
-    const int i = g_event_next[dev];
-    g_event_next[dev] = (i + 1) % kEventRing;
-    if (!g_event_made[dev][i]) {
-        TW_HIP(hipEventCreateWithFlags(&g_events[dev][i], hipEventDisableTiming));
-        g_event_made[dev][i] = true;
+    EventRing &r = t_ring;
+    const int i = r.next[dev];
+    r.next[dev] = static_cast<unsigned char>((i + 1) % kEventRing);
+    if (i >= r.made[dev]) {  // slots fill in order, so i == made
+        hipEvent_t e = nullptr;
+        {
+            std::lock_guard<std::mutex> lk(g_mu);
+            std::vector<hipEvent_t> *spare = g_spare_events[dev];
+            if (spare && !spare->empty()) {
+                e = spare->back();
+                spare->pop_back();
+            }
+        }
+        if (!e) {
+            const hipError_t err = hipEventCreateWithFlags(&e, hipEventDisableTiming);
+            if (err != hipSuccess) {
+                r.next[dev] = static_cast<unsigned char>(i);  // the slot stays empty
+                return hip_fail(err, "tw_host.hip: hipEventCreateWithFlags");
+            }
+        }
+        r.ev[dev][i] = e;
+        r.made[dev] = static_cast<unsigned char>(i + 1);
     }
-    *ev = g_events[dev][i];
+    *ev = r.ev[dev][i];
     return TW_OK;
 }
 
@@ -279,8 +316,16 @@ tw_status tw_weave_layer(const tw_layer_args *layer, int64_t split_row, void *st
             if (ranges_overlap(layer->Y, y_bytes, f.partials[p], t_bytes)) return TW_ERR_ALIAS;
         // G1 writes partials[0] before the fused kernel runs: it must not be one of
         // G1's own inputs (checked above) nor the weights of either GEMM
-        if (ranges_overlap(f.partials[0], t_bytes, layer->W2, uint64_t(layer->N2) * uint64_t(f.H) * 2))
-            return TW_ERR_ALIAS;
+        const uint64_t w2_bytes = uint64_t(layer->N2) * uint64_t(f.H) * 2;
+        if (ranges_overlap(f.partials[0], t_bytes, layer->W2, w2_bytes)) return TW_ERR_ALIAS;
+        // one split's fused kernel writes out / residual_out while the other
+        // split's G1 reads X1 and W1 and the first split's G2 reads W2
+        const void *f_outs[2] = {f.out, f.residual_out};
+        for (const void *o : f_outs)
+            if (ranges_overlap(o, t_bytes, layer->X1, uint64_t(T) * uint64_t(layer->K1) * 2) ||
+                ranges_overlap(o, t_bytes, layer->W1, uint64_t(f.H) * uint64_t(layer->K1) * 2) ||
+                ranges_overlap(o, t_bytes, layer->W2, w2_bytes))
+                return TW_ERR_ALIAS;
     }
 
     hipStream_t sx = static_cast<hipStream_t>(stream_compute), sc = static_cast<hipStream_t>(stream_comm);
@@ -349,6 +394,48 @@ int tw_should_split(int64_t num_tokens, int64_t threshold)
 {
     if (threshold <= 0) threshold = TW_DEFAULT_SPLIT_THRESHOLD;
     return num_tokens >= threshold ? 1 : 0;
+}
+
+int64_t tw_split_threshold(int64_t K1, int64_t H, int P, int64_t N2, int cus)
+{
+    if (K1 < 1 || H < 1 || P < 1 || N2 < 1 || cus < 1) return -1;
+    // (1) the fused kernel of the whole batch must be worth hiding: the waits and
+    // the contention of a split schedule cost about what 140 us of fused work
+    // (at the whole device's ~5 TB/s) gain when overlapped
+    const double row_bytes = 2.0 * double(H) * double(P + 3);
+    const int64_t t_gain = static_cast<int64_t>(140.0 * 5.0e6 / row_bytes) + 1;
+    // (2) half a batch must still give the narrower GEMM tiles for half of the
+    // compute units, or its workgroups leave most of the device idle
+    const int64_t n_min = H < N2 ? H : N2;
+    const int64_t col_tiles = (n_min + kGemmTileN - 1) / kGemmTileN;
+    const int64_t row_tiles = ((cus + 1) / 2 + col_tiles - 1) / col_tiles;
+    const int64_t t_fill = 2 * row_tiles * kGemmTileM;
+    const int64_t t = t_gain > t_fill ? t_gain : t_fill;
+    return (t + kGemmTileM - 1) / kGemmTileM * kGemmTileM;
+}
+
+tw_status tw_weave_layer_auto(const tw_layer_args *layer, int64_t threshold, int64_t multiple, void *stream_compute,
+                              void *stream_comm, void *parent, int parent_is_set, int join, int64_t *split_row)
+{
+    if (!layer) return TW_ERR_NULL;
+    const tw_fused_args &f = layer->fused;
+    TW_TRY(validate_fused(f));
+    if (layer->K1 < 0 || layer->N2 < 0) return TW_ERR_SHAPE;
+    const int64_t T = f.N;
+    int64_t k = T;  // unsplit unless the policy says otherwise
+    if (T > 0 && layer->K1 > 0 && layer->N2 > 0) {
+        int cus = 0;
+        TW_TRY(current_cu_count(&cus));
+        if (threshold <= 0) threshold = tw_split_threshold(layer->K1, f.H, f.P, layer->N2, cus);
+        if (tw_should_split(T, threshold)) {
+            const int64_t widths[2] = {f.H, layer->N2}, depths[2] = {layer->K1, f.H};
+            k = tw_smart_split_point(T, multiple > 0 ? multiple : 64, widths, depths, 2,
+                                     resolve_budget(layer->gemm_cu_budget, cus), nullptr, nullptr);
+            if (k < 0) k = T;
+        }
+    }
+    if (split_row) *split_row = k;
+    return tw_weave_layer(layer, k, stream_compute, stream_comm, parent, parent_is_set, join);
 }
 
 void tw_gemm_tile_shape(int *tile_m, int *tile_n)

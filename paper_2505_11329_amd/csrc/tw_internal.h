@@ -7,6 +7,7 @@
 #include <atomic>
 
 #include "tw.h"
+#include "tw_measure.h"
 
 namespace tw {
 

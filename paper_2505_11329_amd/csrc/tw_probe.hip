@@ -1,7 +1,9 @@
 // Measurement aid: a streaming read / copy / write kernel launched with the same
 // shape as the fused kernel (persistent grid of `budget` workgroups of 1024
 // threads, one per compute unit, 16-byte accesses, several in flight per
-// thread). It measures what a CU budget can move to and from HBM, the ceiling
+// thread); the workgroup size and the number of accesses in flight per thread
+// can be varied, to show what the per-compute-unit ceiling does and does not
+// depend on. It measures what a CU budget can move to and from HBM, the ceiling
 // the fused kernel is compared with, and serves as the copy of known size that
 // hardware byte counters are scaled against.
 #include <atomic>
@@ -13,13 +15,14 @@ namespace tw {
 
 static constexpr int kProbeThreads = 1024;
 static constexpr unsigned kProbePadBytes = 96 * 1024;  // one workgroup per compute unit
-static constexpr int kInFlight = 8;
 
-template <int MODE>
+// kInFlight 16-byte accesses per thread are issued before the first is used;
+// the workgroup has blockDim.x threads (a multiple of 64, at most 1024).
+template <int MODE, int kInFlight>
 __global__ __launch_bounds__(kProbeThreads) void probe_kernel(const u32x4 *src, u32x4 *dst, long long n_vec)
 {
-    const long long stride = static_cast<long long>(gridDim.x) * kProbeThreads;
-    long long i = static_cast<long long>(blockIdx.x) * kProbeThreads + threadIdx.x;
+    const long long stride = static_cast<long long>(gridDim.x) * blockDim.x;
+    long long i = static_cast<long long>(blockIdx.x) * blockDim.x + threadIdx.x;
     u32x4 acc = {0u, 0u, 0u, 0u};
     const u32x4 pattern = {0x3f803f80u, 0x3f803f80u, 0x3f803f80u, 0x3f803f80u};
 
@@ -56,7 +59,7 @@ __global__ __launch_bounds__(kProbeThreads) void probe_kernel(const u32x4 *src, 
             acc.z ^= __shfl_xor(acc.z, off, 64);
             acc.w ^= __shfl_xor(acc.w, off, 64);
         }
-        if ((threadIdx.x & 63) == 0) dst[blockIdx.x * (kProbeThreads / 64) + (threadIdx.x >> 6)] = acc;
+        if ((threadIdx.x & 63) == 0) dst[blockIdx.x * (kProbeThreads / 64) + (threadIdx.x >> 6)] = acc;  // 16 slots per workgroup
     }
 }
 
@@ -70,10 +73,11 @@ template <int NR>
 __global__ __launch_bounds__(kProbeThreads) void probe_mixed_kernel(const char *src, char *dst,
                                                                     unsigned stream_bytes, int n_write)
 {
-    const unsigned rows = stream_bytes / (kProbeThreads * 16u);
+    const unsigned row_bytes = blockDim.x * 16u;  // 16 KiB with the fused kernel's 1024 threads
+    const unsigned rows = stream_bytes / row_bytes;
     u32x4 acc = {1u, 2u, 3u, 4u};
     for (unsigned row = blockIdx.x; row < rows; row += gridDim.x) {
-        const unsigned off = row * (kProbeThreads * 16u) + threadIdx.x * 16u;
+        const unsigned off = row * row_bytes + threadIdx.x * 16u;
         u32x4 v[NR > 0 ? NR : 1];
 #pragma unroll
         for (int r = 0; r < NR; ++r) {
@@ -96,12 +100,12 @@ __global__ __launch_bounds__(kProbeThreads) void probe_mixed_kernel(const char *
 
 template <int NR>
 static tw_status launch_mixed(const void *src, void *dst, int64_t stream_bytes, int n_write, unsigned grid,
-                              hipStream_t stream)
+                              unsigned threads, hipStream_t stream)
 {
     auto kern = probe_mixed_kernel<NR>;
     static std::atomic<int> allowed[kMaxDevices];
     TW_TRY(allow_dynamic_lds(reinterpret_cast<const void *>(kern), static_cast<int>(kProbePadBytes), allowed));
-    TW_HIP(launch_kernel(kern, dim3(grid), dim3(kProbeThreads), kProbePadBytes, stream,
+    TW_HIP(launch_kernel(kern, dim3(grid), dim3(threads), kProbePadBytes, stream,
                          static_cast<const char *>(src), static_cast<char *>(dst),
                          static_cast<unsigned>(stream_bytes), n_write));
     return TW_OK;
@@ -109,35 +113,56 @@ static tw_status launch_mixed(const void *src, void *dst, int64_t stream_bytes, 
 
 template <int NR>
 static tw_status dispatch_mixed(int n_read, const void *src, void *dst, int64_t stream_bytes, int n_write,
-                                unsigned grid, hipStream_t stream)
+                                unsigned grid, unsigned threads, hipStream_t stream)
 {
-    if (n_read == NR) return launch_mixed<NR>(src, dst, stream_bytes, n_write, grid, stream);
-    if constexpr (NR > 0) return dispatch_mixed<NR - 1>(n_read, src, dst, stream_bytes, n_write, grid, stream);
+    if (n_read == NR) return launch_mixed<NR>(src, dst, stream_bytes, n_write, grid, threads, stream);
+    if constexpr (NR > 0)
+        return dispatch_mixed<NR - 1>(n_read, src, dst, stream_bytes, n_write, grid, threads, stream);
     return TW_ERR_SHAPE;
 }
 
-template <int MODE>
-static tw_status launch_probe(const void *src, void *dst, int64_t bytes, unsigned grid, hipStream_t stream)
+template <int MODE, int DEPTH>
+static tw_status launch_probe(const void *src, void *dst, int64_t bytes, unsigned grid, unsigned threads,
+                              hipStream_t stream)
 {
-    auto kern = probe_kernel<MODE>;
+    auto kern = probe_kernel<MODE, DEPTH>;
     static std::atomic<int> allowed[kMaxDevices];
     TW_TRY(allow_dynamic_lds(reinterpret_cast<const void *>(kern), static_cast<int>(kProbePadBytes), allowed));
-    TW_HIP(launch_kernel(kern, dim3(grid), dim3(kProbeThreads), kProbePadBytes, stream,
+    TW_HIP(launch_kernel(kern, dim3(grid), dim3(threads), kProbePadBytes, stream,
                          static_cast<const u32x4 *>(src), static_cast<u32x4 *>(dst),
                          static_cast<long long>(bytes / 16)));
     return TW_OK;
 }
 
+template <int MODE>
+static tw_status launch_probe_depth(int depth, const void *src, void *dst, int64_t bytes, unsigned grid,
+                                    unsigned threads, hipStream_t stream)
+{
+    switch (depth) {
+    case 1: return launch_probe<MODE, 1>(src, dst, bytes, grid, threads, stream);
+    case 2: return launch_probe<MODE, 2>(src, dst, bytes, grid, threads, stream);
+    case 4: return launch_probe<MODE, 4>(src, dst, bytes, grid, threads, stream);
+    case 8: return launch_probe<MODE, 8>(src, dst, bytes, grid, threads, stream);
+    case 16: return launch_probe<MODE, 16>(src, dst, bytes, grid, threads, stream);
+    }
+    return TW_ERR_UNSUPPORTED;
+}
+
+static bool probe_threads_ok(int threads) { return threads >= 64 && threads <= kProbeThreads && threads % 64 == 0; }
+
 }  // namespace tw
 
 using namespace tw;
 
-extern "C" tw_status tw_hbm_probe(const void *src, void *dst, int64_t bytes, int mode, int cu_budget,
-                                  void *stream)
+extern "C" tw_status tw_hbm_probe_shaped(const void *src, void *dst, int64_t bytes, int mode, int cu_budget,
+                                         int threads, int in_flight, void *stream)
 {
     if (mode != TW_PROBE_READ && mode != TW_PROBE_COPY && mode != TW_PROBE_WRITE) return TW_ERR_SHAPE;
     if (!dst || (mode != TW_PROBE_WRITE && !src)) return TW_ERR_NULL;
     if (bytes < 0 || bytes % 16 != 0) return TW_ERR_SHAPE;
+    if (!probe_threads_ok(threads)) return TW_ERR_SHAPE;
+    if (in_flight != 1 && in_flight != 2 && in_flight != 4 && in_flight != 8 && in_flight != 16)
+        return TW_ERR_UNSUPPORTED;
     if (!aligned16(dst) || (src && !aligned16(src))) return TW_ERR_ALIGN;
     if (mode == TW_PROBE_COPY && ranges_overlap(src, static_cast<uint64_t>(bytes), dst, static_cast<uint64_t>(bytes)))
         return TW_ERR_ALIAS;
@@ -146,21 +171,30 @@ extern "C" tw_status tw_hbm_probe(const void *src, void *dst, int64_t bytes, int
     TW_TRY(current_cu_count(&cus));
     const unsigned grid = static_cast<unsigned>(resolve_budget(cu_budget, cus));
     hipStream_t s = static_cast<hipStream_t>(stream);
+    const unsigned t = static_cast<unsigned>(threads);
     switch (mode) {
-    case TW_PROBE_READ: return launch_probe<TW_PROBE_READ>(src, dst, bytes, grid, s);
-    case TW_PROBE_COPY: return launch_probe<TW_PROBE_COPY>(src, dst, bytes, grid, s);
-    default: return launch_probe<TW_PROBE_WRITE>(src, dst, bytes, grid, s);
+    case TW_PROBE_READ: return launch_probe_depth<TW_PROBE_READ>(in_flight, src, dst, bytes, grid, t, s);
+    case TW_PROBE_COPY: return launch_probe_depth<TW_PROBE_COPY>(in_flight, src, dst, bytes, grid, t, s);
+    default: return launch_probe_depth<TW_PROBE_WRITE>(in_flight, src, dst, bytes, grid, t, s);
     }
 }
 
-extern "C" tw_status tw_hbm_probe_mixed(const void *src, void *dst, int64_t stream_bytes, int n_read,
-                                        int n_write, int cu_budget, void *stream)
+extern "C" tw_status tw_hbm_probe(const void *src, void *dst, int64_t bytes, int mode, int cu_budget,
+                                  void *stream)
+{
+    return tw_hbm_probe_shaped(src, dst, bytes, mode, cu_budget, kProbeThreads, 8, stream);
+}
+
+extern "C" tw_status tw_hbm_probe_mixed_shaped(const void *src, void *dst, int64_t stream_bytes, int n_read,
+                                               int n_write, int cu_budget, int threads, void *stream)
 {
     if (n_read < 0 || n_read > TW_MAX_P + 1 || n_write < 0 || n_write > 4 || n_read + n_write == 0)
         return TW_ERR_SHAPE;
     if (!dst || (n_read > 0 && !src)) return TW_ERR_NULL;
     if (stream_bytes < 0 || stream_bytes % (kProbeThreads * 16) != 0 || stream_bytes > (int64_t(1) << 31))
         return TW_ERR_SHAPE;
+    // a workgroup's row must divide the 16 KiB granule of stream_bytes
+    if (!probe_threads_ok(threads) || kProbeThreads % threads != 0) return TW_ERR_SHAPE;
     if (!aligned16(dst) || (src && !aligned16(src))) return TW_ERR_ALIGN;
     if (n_read > 0 && n_write > 0 &&
         ranges_overlap(src, static_cast<uint64_t>(stream_bytes) * n_read, dst,
@@ -170,6 +204,12 @@ extern "C" tw_status tw_hbm_probe_mixed(const void *src, void *dst, int64_t stre
     int cus = 0;
     TW_TRY(current_cu_count(&cus));
     const unsigned grid = static_cast<unsigned>(resolve_budget(cu_budget, cus));
-    return dispatch_mixed<TW_MAX_P + 1>(n_read, src, dst, stream_bytes, n_write, grid,
+    return dispatch_mixed<TW_MAX_P + 1>(n_read, src, dst, stream_bytes, n_write, grid, static_cast<unsigned>(threads),
                                         static_cast<hipStream_t>(stream));
+}
+
+extern "C" tw_status tw_hbm_probe_mixed(const void *src, void *dst, int64_t stream_bytes, int n_read,
+                                        int n_write, int cu_budget, void *stream)
+{
+    return tw_hbm_probe_mixed_shaped(src, dst, stream_bytes, n_read, n_write, cu_budget, kProbeThreads, stream);
 }

@@ -17,18 +17,28 @@ VP = ctypes.c_void_p
 OK, E_NULL, E_SHAPE, E_ALIGN, E_ALIAS, E_UNSUP, E_SPLIT, E_HIP = range(8)
 
 
-def declared_functions():
-    text = open(os.path.join(ROOT, "include", "tw.h")).read()
-    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
-    return sorted(set(re.findall(r"\b(tw_[a-z0-9_]+)\s*\(", text)))
+def declared_functions(headers=("tw.h", "tw_measure.h")):
+    names = set()
+    for h in headers:
+        text = open(os.path.join(ROOT, "include", h)).read()
+        text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+        names |= set(re.findall(r"\b(tw_[a-z0-9_]+)\s*\(", text))
+    return sorted(names)
 
 
 def test_header_declares_the_documented_entry_points():
-    names = declared_functions()
+    names = declared_functions(("tw.h",))
     for must in ("tw_reduce_add_rmsnorm", "tw_split_launch", "tw_split_point", "tw_gemm_bf16",
-                 "tw_overlap_launch", "tw_hbm_probe", "tw_device_cu_count", "tw_status_str",
-                 "tw_version", "tw_last_hip_error", "tw_fused_grid", "tw_fused_layout", "tw_weave_schedule", "tw_reduce_add_rmsnorm_traced"):
+                 "tw_overlap_launch", "tw_weave_layer", "tw_weave_layer_auto", "tw_smart_split_point",
+                 "tw_should_split", "tw_split_threshold", "tw_device_cu_count", "tw_status_str",
+                 "tw_version", "tw_last_hip_error"):
         assert must in names
+    # measurement and introspection aids are declared apart from the method's interface
+    aids = declared_functions(("tw_measure.h",))
+    for must in ("tw_hbm_probe", "tw_hbm_probe_mixed", "tw_hbm_probe_shaped", "tw_hbm_probe_mixed_shaped",
+                 "tw_fused_grid", "tw_fused_layout", "tw_weave_schedule", "tw_gemm_tile_shape",
+                 "tw_reduce_add_rmsnorm_traced"):
+        assert must in aids and must not in names
 
 
 def test_library_exports_every_declared_symbol():
@@ -164,16 +174,6 @@ def test_unfused_argument_checks():
     assert unfused_call(scratch=addr(6) + TENSOR - 16) == E_ALIAS
 
 
-def test_split_point_matches_its_definition():
-    # independent statement: the smallest multiple of m that is >= N/2, capped at N
-    for n in list(range(0, 70)) + [127, 128, 129, 255, 256, 1000, 1024, 4096, 16384, 10 ** 12 + 7]:
-        for m in (1, 2, 3, 64, 128, 1000):
-            want = next((k for k in range(0, n + m, m) if 2 * k >= n), n) if n < 10 ** 6 else None
-            if want is None:
-                q = -(-n // 2)
-                want = -(-q // m) * m
-            want = min(want, n)
-            assert tw.split_point(n, m) == want, (n, m)
 def static_call(n=N, **kw):
     arr = (VP * P)(addr(0), addr(1))
     a = FusedArgs(ctypes.cast(arr, ctypes.POINTER(VP)), addr(4), addr(5), 1e-5, n, H, P, 8, addr(6), addr(7))
@@ -202,6 +202,16 @@ def test_unfused_static_argument_checks():
     assert tw.lib().tw_reduce_add_rmsnorm_unfused_static(ctypes.byref(a), VP(None)) == E_SHAPE
 
 
+def test_split_point_matches_its_definition():
+    # independent statement: the smallest multiple of m that is >= N/2, capped at N
+    for n in list(range(0, 70)) + [127, 128, 129, 255, 256, 1000, 1024, 4096, 16384, 10 ** 12 + 7]:
+        for m in (1, 2, 3, 64, 128, 1000):
+            want = next((k for k in range(0, n + m, m) if 2 * k >= n), n) if n < 10 ** 6 else None
+            if want is None:
+                q = -(-n // 2)
+                want = -(-q // m) * m
+            want = min(want, n)
+            assert tw.split_point(n, m) == want, (n, m)
     assert tw.split_point(-5, 128) == 0
     assert tw.split_point(100, 0) == 50
     assert tw.split_point(100, -3) == 50
@@ -252,6 +262,20 @@ def test_probe_argument_checks():
     assert L.tw_hbm_probe(VP(addr(0) + 4), VP(addr(9)), 1024, tw.PROBE_COPY, 8, VP(None)) == E_ALIGN
     assert L.tw_hbm_probe(VP(addr(0)), VP(addr(0) + 512), 1024, tw.PROBE_COPY, 8, VP(None)) == E_ALIAS
     assert L.tw_hbm_probe(VP(addr(0)), VP(addr(9)), 0, tw.PROBE_COPY, 8, VP(None)) == OK
+
+
+def test_shaped_probe_argument_checks():
+    L = tw.lib()
+    ok_args = (VP(addr(0)), VP(addr(9)), 1024, tw.PROBE_COPY, 8)
+    for threads in (0, 32, 100, 1088, -64):
+        assert L.tw_hbm_probe_shaped(*ok_args, threads, 8, VP(None)) == E_SHAPE
+    for depth in (0, 3, 5, 32, -1):
+        assert L.tw_hbm_probe_shaped(*ok_args, 256, depth, VP(None)) == E_UNSUP
+    assert L.tw_hbm_probe_shaped(VP(addr(0)), VP(addr(9)), 0, tw.PROBE_COPY, 8, 192, 16, VP(None)) == OK
+    sb = 16384 * 4
+    for threads in (0, 96, 192, 768, 2048):       # must divide the 1024-vector granule
+        assert L.tw_hbm_probe_mixed_shaped(VP(addr(0)), VP(addr(2000)), sb, 9, 2, 8, threads, VP(None)) == E_SHAPE
+    assert L.tw_hbm_probe_mixed_shaped(VP(addr(0)), VP(addr(2000)), 0, 9, 2, 8, 256, VP(None)) == OK
 
 
 def test_mixed_probe_argument_checks():
@@ -342,6 +366,14 @@ def test_weave_layer_argument_checks():
     la.Y = addr(6)          # Y on top of the fused output it is computed from
     assert L.tw_weave_layer(ctypes.byref(la), 2, VP(1), VP(2), VP(None), 0, 0) == E_ALIAS
     la.Y = addr(13)
+    # a fused output on top of an operand another split's GEMM is still reading
+    for field, target in (("out", 10), ("out", 11), ("out", 12), ("residual_out", 10), ("residual_out", 11),
+                          ("residual_out", 12)):
+        keep = getattr(la.fused, field)
+        setattr(la.fused, field, addr(target))
+        assert L.tw_weave_layer(ctypes.byref(la), 2, VP(1), VP(2), VP(None), 0, 0) == E_ALIAS, (field, target)
+        assert L.tw_weave_layer(ctypes.byref(la), 0, VP(1), VP(2), VP(None), 0, 0) == E_ALIAS, (field, target)
+        setattr(la.fused, field, keep)
     la.fused.H = 60
     assert L.tw_weave_layer(ctypes.byref(la), 2, VP(1), VP(2), VP(None), 0, 0) == E_UNSUP
     la.fused.H = H
@@ -352,6 +384,44 @@ def test_weave_layer_argument_checks():
     for schedule in (tw.WEAVE_AUTO, tw.WEAVE_ORDERED, tw.WEAVE_CHAINS):
         la.schedule = schedule
         assert L.tw_weave_layer(ctypes.byref(la), 0, VP(1), VP(2), VP(None), 0, 0) == OK
+
+
+def test_split_threshold_matches_its_definition():
+    """tw_split_threshold restated: the larger of 'the fused step takes 140 us at 5 TB/s' and 'half the
+    batch still tiles the narrower GEMM output over half of the compute units', in whole 256-row tiles."""
+    import math
+    for (K1, Hh, Pp, N2, cus) in [(1024, 8192, 8, 3584, 256), (3584, 8192, 8, 1280, 256), (3584, 8192, 4, 1280, 256),
+                                  (512, 4096, 2, 4096, 256), (1024, 8192, 8, 3584, 64), (8, 8, 1, 8, 1),
+                                  (4096, 16384, 16, 128, 304)]:
+        t_gain = math.floor(140.0 * 5.0e6 / (2.0 * Hh * (Pp + 3))) + 1
+        col_tiles = -(-min(Hh, N2) // 128)
+        t_fill = 2 * 256 * -(-((cus + 1) // 2) // col_tiles)
+        want = -(-max(t_gain, t_fill) // 256) * 256
+        assert tw.split_threshold(K1, Hh, Pp, N2, cus) == want, (K1, Hh, Pp, N2, cus)
+    assert tw.split_threshold(1024, 8192, 8, 3584, 256) == 4096      # the figures tw.h quotes
+    assert tw.split_threshold(3584, 8192, 8, 1280, 256) == 6656
+    for bad in ((0, 8192, 8, 3584, 256), (1024, 0, 8, 3584, 256), (1024, 8192, 0, 3584, 256),
+                (1024, 8192, 8, 0, 256), (1024, 8192, 8, 3584, 0)):
+        assert tw.split_threshold(*bad) == -1
+
+
+def test_weave_layer_auto_argument_checks():
+    from paper_2505_11329_amd.binding import LayerArgs
+    L = tw.lib()
+    taken = ctypes.c_int64(-7)
+    assert L.tw_weave_layer_auto(None, 0, 0, VP(1), VP(2), VP(None), 0, 0, ctypes.byref(taken)) == E_NULL
+    arr = (VP * P)(addr(0), addr(1))
+    f = FusedArgs(ctypes.cast(arr, ctypes.POINTER(VP)), addr(4), addr(5), 1e-5, N, H, P, 8, addr(6), addr(7))
+    la = LayerArgs(addr(10), addr(11), 64, f, addr(12), 64, addr(13), 0)
+    la.fused.H = 60
+    assert L.tw_weave_layer_auto(ctypes.byref(la), 0, 0, VP(1), VP(2), VP(None), 0, 0, None) == E_UNSUP
+    la.fused.H = H
+    la.K1 = -8
+    assert L.tw_weave_layer_auto(ctypes.byref(la), 0, 0, VP(1), VP(2), VP(None), 0, 0, None) == E_SHAPE
+    la.K1 = 64
+    la.fused.N = 0              # an empty batch: nothing to decide, nothing to launch
+    assert L.tw_weave_layer_auto(ctypes.byref(la), 0, 0, VP(1), VP(2), VP(None), 0, 0, ctypes.byref(taken)) == OK
+    assert taken.value == 0
 
 
 def test_fused_layout_covers_every_row_width_without_idle_waves():

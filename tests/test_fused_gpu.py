@@ -409,3 +409,56 @@ def test_random_shapes_all_modes_agree(tw, torch_cuda):
                                  cu_budget=int(rng.integers(1, 9)))
         torch.cuda.synchronize()
         assert np.array_equal(to_bits(o2), want[0]) and np.array_equal(to_bits(r2), want[1]), (what, "split", k)
+
+
+# ---- several host threads at once -------------------------------------------------
+
+def test_split_launch_from_four_host_threads(tw, torch_cuda):
+    """Calls may come from several host threads: four threads, each with its own parent and split
+    streams and its own tensors, each making 200 split launches whose halves must wait for work
+    enqueued on the parent just before (the inputs are rewritten there every time) and whose outputs
+    the parent reads just after. A wait that ordered against another thread's stream would let a half
+    run on stale inputs or let the parent read an unfinished output."""
+    import threading
+    torch = torch_cuda
+    n_threads, n_calls = 4, 200
+    failures = []
+
+    def worker(t):
+        try:
+            N, H, P = 96 + 32 * t, 2048, 2
+            d = small(N, H, P, seed=500 + t)
+            g = upload(d)
+            want_out, want_res = tw.reduce_add_rmsnorm(g["partials"], g["residual"], g["weight"], g["eps"])
+            master = g["partials"][0].clone()
+            parent, sa, sb = torch.cuda.Stream(), torch.cuda.Stream(), torch.cuda.Stream()
+            out, res = torch.empty_like(want_out), torch.empty_like(want_res)
+            bad = torch.zeros((), dtype=torch.int32, device="cuda:0")
+            torch.cuda.synchronize()
+            k = tw.split_point(N, 32)
+            for i in range(n_calls):
+                with torch.cuda.stream(parent):
+                    g["partials"][0].zero_()
+                    out.zero_()
+                    g["partials"][0].copy_(master)
+                tw.split_launch(g["partials"], g["residual"], g["weight"], g["eps"], k, sa, sb, cu_budget=4 + t,
+                                out=out, residual_out=res, parent=parent, join=True)
+                with torch.cuda.stream(parent):
+                    bad += (out.view(torch.int16) != want_out.view(torch.int16)).any().to(torch.int32)
+                    bad += (res.view(torch.int16) != want_res.view(torch.int16)).any().to(torch.int32)
+                if i % 25 == 24 or i == n_calls - 1:
+                    parent.synchronize()
+                    if int(bad.item()) != 0:
+                        failures.append("thread %d: outputs differ by call %d" % (t, i))
+                        return
+        except Exception as e:  # noqa: BLE001 - reported to the main thread
+            failures.append("thread %d: %r" % (t, e))
+
+    threads = [threading.Thread(target=worker, args=(t,)) for t in range(n_threads)]
+    for th in threads:
+        th.start()
+    for th in threads:
+        th.join(timeout=100)
+    assert not any(th.is_alive() for th in threads), "a worker thread did not finish"
+    torch.cuda.synchronize()
+    assert not failures, failures

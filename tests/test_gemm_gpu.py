@@ -111,25 +111,31 @@ def test_overlap_launch_equals_the_two_calls(tw, torch_cuda):
         assert np.array_equal(to_bits(cc), to_bits(C0))
 
 
+@pytest.mark.parametrize("layout", ["nk", "kn"])
 @pytest.mark.parametrize("M,K,N", [(1024, 2048, 1536), (512, 1024, 4096), (2048, 8192, 1280), (2048, 2048, 4096)])
-def test_overlap_launch_shared_mode_equals_the_two_calls(tw, torch_cuda, M, K, N):
+def test_overlap_launch_shared_mode_equals_the_two_calls(tw, torch_cuda, M, K, N, layout):
     """The co-resident mode: small fused workgroups on every compute unit next to
     the GEMM's. Same bits as the plain calls, on every one of many launches: next
     to the fused kernel the GEMM's LDS reads and loads take longer, which is when
     a missing wait shows (C starts as NaNs, so a store that went astray is seen).
     The shapes cover the narrow tiles (at most half of the compute units filled by
-    wide ones) and the wide tiles."""
+    wide ones) and the wide tiles, for both storage orders of B (the [K x N] one
+    reads its fragments with the transposing LDS read and has waits of its own)."""
     torch = torch_cuda
     cfg = W.CONFIGS["c5_overlap_tp8"]
     d = W.make_fused_inputs(cfg, N=1024)
     g = dict(partials=[to_gpu(p) for p in d["partials"]], residual=to_gpu(d["residual"]),
              weight=to_gpu(d["weight"]), eps=d["eps"])
-    gm = W.make_gemm_inputs(M, K, N, 0.02, seed=0, b_layout="nk")
+    gm = W.make_gemm_inputs(M, K, N, 0.02, seed=0, b_layout=layout)
+    bl = tw.B_NK if layout == "nk" else tw.B_KN
     A, B = to_gpu(gm["A"]), to_gpu(gm["B"])
     out0, res0 = tw.reduce_add_rmsnorm(g["partials"], g["residual"], g["weight"], g["eps"], cu_budget=32)
-    C0 = tw.gemm_bf16(A, B, cu_budget=16)      # alone, wide tiles
+    C0 = tw.gemm_bf16(A, B, b_layout=bl, cu_budget=16)      # alone, wide tiles
     torch.cuda.synchronize()
-    assert np.array_equal(to_bits(tw.gemm_bf16(A, B)), to_bits(C0))
+    assert np.array_equal(to_bits(tw.gemm_bf16(A, B, b_layout=bl)), to_bits(C0))
+    if layout == "kn":      # and the same bits as the other storage order of the same matrix
+        nk = W.make_gemm_inputs(M, K, N, 0.02, seed=0, b_layout="nk")
+        assert np.array_equal(to_bits(tw.gemm_bf16(A, to_gpu(nk["B"]), cu_budget=16)), to_bits(C0))
     comm, comp, parent = torch.cuda.Stream(), torch.cuda.Stream(), torch.cuda.Stream()
     C = torch.empty((M, N), dtype=torch.bfloat16, device="cuda:0")
     out = torch.empty_like(g["residual"])
@@ -139,13 +145,14 @@ def test_overlap_launch_shared_mode_equals_the_two_calls(tw, torch_cuda, M, K, N
             C.fill_(float("nan"))
             if it % 2 == 0:
                 tw.overlap_launch(dict(g, cu_budget=tw.CU_SHARED, out=out, residual_out=res),
-                                  dict(A=A, B=B, C=C, cu_budget=0), comm, comp, parent=parent, use_parent=True, join=True)
+                                  dict(A=A, B=B, C=C, b_layout=bl, cu_budget=0), comm, comp, parent=parent,
+                                  use_parent=True, join=True)
             else:
                 # the two calls made by hand on two streams: tw_gemm_bf16 picks its tiles as for a
                 # launch on its own (the narrow ones where few wide tiles would fill the device)
                 comp.wait_stream(parent)
                 comm.wait_stream(parent)
-                tw.gemm_bf16(A, B, C=C, cu_budget=0, stream=comp)
+                tw.gemm_bf16(A, B, C=C, b_layout=bl, cu_budget=0, stream=comp)
                 tw.reduce_add_rmsnorm(g["partials"], g["residual"], g["weight"], g["eps"], cu_budget=tw.CU_SHARED,
                                       out=out, residual_out=res, stream=comm)
                 parent.wait_stream(comp)

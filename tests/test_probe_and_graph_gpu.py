@@ -97,3 +97,74 @@ def test_weave_layer_can_be_captured_in_a_hip_graph(tw, torch_cuda, schedule):
         with torch.cuda.stream(main):            # eager work between replays
             tw.reduce_add_rmsnorm(parts, resid, weight, f["eps"], cu_budget=8)
         torch.cuda.synchronize()
+
+
+def test_shaped_probes_move_the_same_bytes_in_every_shape(tw, torch_cuda):
+    """Workgroup size and accesses in flight change the launch, not what is copied."""
+    torch = torch_cuda
+    n = (2 << 20) + 4096 + 48
+    src = torch.randint(0, 256, (n,), dtype=torch.uint8, device="cuda:0")
+    sink = torch.zeros(256 * tw.device_cu_count(), dtype=torch.uint8, device="cuda:0")
+    for threads in (64, 192, 256, 512, 1024):
+        for depth in (1, 2, 4, 8, 16):
+            dst = torch.zeros(n + 64, dtype=torch.uint8, device="cuda:0")
+            tw.hbm_probe_shaped(src, dst, n, tw.PROBE_COPY, cu_budget=3, threads=threads, in_flight=depth)
+            tw.hbm_probe_shaped(src, sink, n, tw.PROBE_READ, cu_budget=3, threads=threads, in_flight=depth)
+            torch.cuda.synchronize()
+            assert torch.equal(dst[:n], src) and int(dst[n:].sum()) == 0, (threads, depth)
+    sb = 1 << 20
+    srcs = torch.randint(0, 256, (9 * sb,), dtype=torch.uint8, device="cuda:0")
+    for threads in (64, 256, 512, 1024):
+        dst = torch.zeros(2 * sb + 4096, dtype=torch.uint8, device="cuda:0")
+        tw.hbm_probe_mixed_shaped(srcs, dst, sb, 9, 2, cu_budget=4, threads=threads)
+        torch.cuda.synchronize()
+        # every word of the two write streams was written (the stored words are xors of loaded data:
+        # a zero among them is a 2^-32 event per word)
+        assert int(dst[2 * sb:].sum()) == 0 and int(dst[:2 * sb].view(torch.int32).ne(0).sum()) >= 2 * sb // 4 - 8
+
+
+@pytest.mark.parametrize("N", [1, 16, 256])
+def test_decode_sized_train_of_fused_steps_replays_from_a_graph(tw, torch_cuda, N):
+    """A decode iteration is a train of many small fused steps (two per layer). Captured once into a HIP
+    graph (nothing in the library allocates or clears memory per call, so there is no memset node), every
+    replay must give the eager train's bits; eager work and synchronisations sit between the replays."""
+    torch = torch_cuda
+    H, P, layers = 8192, 8, 12
+    cfg = dict(N=N, H=H, P=P, partial_std=0.25, residual_std=1.0, outlier_frac=0.01, outlier_scale=50.0,
+               eps=1e-5, seed=N)
+    d = W.make_fused_inputs(cfg)
+    parts = [to_gpu(p) for p in d["partials"]]
+    resid0, weight = to_gpu(d["residual"]), to_gpu(d["weight"])
+    resid = torch.empty_like(resid0)
+    outs = [torch.empty_like(resid0) for _ in range(layers)]
+    main = torch.cuda.Stream()
+
+    def train():
+        # the residual stream is carried in place from step to step, as in the paper's kernel
+        for i in range(layers):
+            tw.reduce_add_rmsnorm(parts, resid, weight, d["eps"], cu_budget=(0, tw.CU_SHARED)[i % 2], out=outs[i],
+                                  residual_out=resid, stream=main)
+
+    def reset():
+        with torch.cuda.stream(main):
+            resid.copy_(resid0)
+            for o in outs:
+                o.fill_(float("nan"))
+    reset()
+    train()
+    main.synchronize()
+    want = [to_bits(o).copy() for o in outs] + [to_bits(resid).copy()]
+    assert not np.array_equal(want[0], want[-2])           # the steps do differ
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph, stream=main):
+        train()
+    for rep in range(4):
+        reset()
+        with torch.cuda.stream(main):
+            graph.replay()
+        main.synchronize()
+        got = [to_bits(o) for o in outs] + [to_bits(resid)]
+        for i, (g_, w_) in enumerate(zip(got, want)):
+            assert np.array_equal(g_, w_), (rep, i)
+        tw.reduce_add_rmsnorm(parts, resid0, weight, d["eps"], cu_budget=8)   # eager work between replays
+        torch.cuda.synchronize()

@@ -107,8 +107,8 @@ def test_weave_layer_at_full_size_gives_the_unsplit_bits_every_time(tw, torch_cu
     output must carry the unsplit chain's bits. At this size the kernels really
     overlap for tens of microseconds, which is when a missing wait or a misplaced
     event shows; the outputs start as NaNs so that nothing stale can pass. Inputs
-    are drawn on the GPU (seeded); the unsplit chain is the reference, and its own
-    parity with the oracle is the business of the tests above."""
+    are drawn on the GPU (seeded); the unsplit chain is the reference, and it is
+    itself checked against the oracle on sampled outputs first."""
     torch = torch_cuda
     T_, H_, P_ = 4096, 8192, 8
     gen = torch.Generator(device="cuda:0")
@@ -135,6 +135,26 @@ def test_weave_layer_at_full_size_gives_the_unsplit_bits_every_time(tw, torch_cu
         return [to_bits(t).copy() for t in (parts[0], out, res, Y)]
     want = run(0, tw.WEAVE_ORDERED)
     assert not np.isnan(oracle.bf16_to_f64(want[3])).any()
+
+    # The reference itself against the oracle at this size, stage by stage on sampled outputs, each
+    # stage fed with the bits the previous GPU stage produced: 2048 cells of G1, 192 whole rows of the
+    # fused step, 2048 cells of G2 (the rows straddle every 256-row GEMM tile and both halves).
+    rng = np.random.default_rng(K1 * 7 + N2)
+    rows = np.unique(np.concatenate([rng.integers(0, T_, 180), [0, 1, 255, 256, 2047, 2048, T_ - 2, T_ - 1]]))[:192]
+    ridx = torch.from_numpy(rows).to("cuda:0")
+    ms = rng.integers(0, len(rows), 2048)
+    G1_rows, out_rows, res_rows, Y_rows = (w_[rows] for w_ in want)
+    ns = rng.integers(0, H_, 2048)
+    ref = oracle.gemm_samples(to_bits(X1[ridx]), to_bits(W1), "nk", ms, ns)
+    gemm_tol_check(oracle.bf16_to_f64(G1_rows[ms, ns]), ref, K1, 0.02, 0.02, "G1 at T=4096 (sampled)")
+    ref_out, ref_res = oracle.fused([G1_rows] + [to_bits(p[ridx]) for p in parts[1:]], to_bits(resid[ridx]),
+                                    to_bits(weight), 1e-5)
+    assert_parity(oracle.bf16_to_f64(res_rows), ref_res, "weave residual_out at T=4096 (sampled rows)")
+    assert_parity(oracle.bf16_to_f64(out_rows), ref_out, "weave out at T=4096 (sampled rows)")
+    ns = rng.integers(0, N2, 2048)
+    ref = oracle.gemm_samples(out_rows, to_bits(W2g), "nk", ms, ns)
+    gemm_tol_check(oracle.bf16_to_f64(Y_rows[ms, ns]), ref, H_, 1.1, 0.02, "G2 at T=4096 (sampled)")
+
     k_smart = tw.smart_split_point(T_, 64, [H_, N2], tw.device_cu_count(), gemm_k=[K1, H_])[0]
     for it in range(12):
         schedule = (tw.WEAVE_ORDERED, tw.WEAVE_CHAINS)[it % 2]
@@ -142,3 +162,65 @@ def test_weave_layer_at_full_size_gives_the_unsplit_bits_every_time(tw, torch_cu
         got = run(k, schedule)
         for name, g_, w_ in zip(("G1", "out", "residual_out", "Y"), got, want):
             assert np.array_equal(g_, w_), (it, schedule, k, name, int((g_ != w_).sum()))
+
+
+# ---- the per-iteration policy as one call (Fig. 3) ---------------------------------
+
+def test_weave_layer_auto_applies_threshold_and_smart_split(tw, torch_cuda):
+    """Below the threshold the chain runs unsplit, at or above it the batch is cut where
+    tw_smart_split_point says; either way the bits are the unsplit chain's (which the stagewise test
+    above checks against the oracle on these very inputs)."""
+    torch = torch_cuda
+    g1, f, W2 = make_inputs()
+    streams = (torch.cuda.Stream(), torch.cuda.Stream())
+    want = run_layer(tw, torch, g1, f, W2, 0, streams)
+    cus = tw.device_cu_count()
+    for threshold, multiple, budgets in ((T + 1, 64, (tw.CU_SHARED, 0)), (T, 64, (tw.CU_SHARED, 0)), (512, 32, (32, 224)),
+                                         (1, 0, (0, 0))):
+        X1, W1 = to_gpu(g1["A"]), to_gpu(g1["B"])
+        parts = [torch.zeros((T, H), dtype=torch.bfloat16, device="cuda:0")] + [to_gpu(p) for p in f["partials"][1:]]
+        out, res, Y, taken = tw.weave_layer_auto(X1, W1, parts, to_gpu(f["residual"]), to_gpu(f["weight"]), f["eps"],
+                                                 to_gpu(W2), streams[0], streams[1], threshold=threshold,
+                                                 multiple=multiple, fused_cu_budget=budgets[0],
+                                                 gemm_cu_budget=budgets[1])
+        torch.cuda.synchronize()
+        if T < threshold:
+            assert taken == T
+        else:
+            gemm_cus = budgets[1] if 0 < budgets[1] < cus else cus
+            assert taken == tw.smart_split_point(T, multiple or 64, [H, N2], gemm_cus, gemm_k=[K1, H])[0]
+            assert 0 < taken < T
+        got = (to_bits(parts[0]), to_bits(out), to_bits(res), to_bits(Y))
+        for name, g_, w_ in zip(("G1", "out", "residual_out", "Y"), got, want):
+            assert np.array_equal(g_, w_), (threshold, name)
+
+
+@pytest.mark.parametrize("K1,N2", [(1024, 3584), (3584, 1280)])
+def test_weave_layer_auto_at_full_size_on_both_sides_of_the_built_in_threshold(tw, torch_cuda, K1, N2):
+    """The two 70B-class boundaries (H = 8192, P = 8) with the library's own threshold: one batch just
+    below it, one at it, one above; the policy's outputs carry the bits of the plain unsplit chain."""
+    torch = torch_cuda
+    H_, P_ = 8192, 8
+    thr = tw.split_threshold(K1, H_, P_, N2, tw.device_cu_count())
+    assert thr == (4096 if K1 == 1024 else 6656)
+    gen = torch.Generator(device="cuda:0")
+    gen.manual_seed(K1 * 3 + N2)
+
+    def rnd(shape, std):
+        return torch.empty(shape, dtype=torch.bfloat16, device="cuda:0").normal_(0.0, std, generator=gen)
+    T_max = thr + 640
+    X1, W1, W2g = rnd((T_max, K1), 0.02), rnd((H_, K1), 0.02), rnd((N2, H_), 0.02)
+    parts, resid = [rnd((T_max, H_), 0.25) for _ in range(P_)], rnd((T_max, H_), 1.0)
+    weight = to_gpu(W.uniform_bf16((H_,), 0.5, 1.5, 0, W.STREAM_WEIGHT))
+    sx, sc = torch.cuda.Stream(), torch.cuda.Stream()
+    for T_ in (thr - 256, thr, T_max):
+        args = (X1[:T_], W1, [p[:T_] for p in parts], resid[:T_], weight, 1e-5, W2g)
+        with torch.cuda.stream(sx):
+            want = tw.weave_layer(*args, 0, sx, sc, fused_cu_budget=tw.CU_SHARED, parent=sx)
+            want = [t.clone() for t in (parts[0][:T_],) + want]
+            parts[0][:T_].fill_(float("nan"))
+            out, res, Y, taken = tw.weave_layer_auto(*args, sx, sc, fused_cu_budget=tw.CU_SHARED, parent=sx)
+        torch.cuda.synchronize()
+        assert (taken == T_) == (T_ < thr), (T_, taken)
+        for name, g_, w_ in zip(("G1", "out", "residual_out", "Y"), (parts[0][:T_], out, res, Y), want):
+            assert torch.equal(g_.view(torch.int16), w_.view(torch.int16)), (T_, taken, name)
