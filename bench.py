@@ -30,10 +30,46 @@ MFMA_BF16_PEAK_TFLOPS = 2500.0
 WORKLOAD = "c3_70b_shard_tp8"
 HEADLINE_BUDGET = 32
 # HBM bytes per launch of the headline kernel from hardware counters (FETCH_SIZE and
-# WRITE_SIZE, each scaled by what the same counter reads for a 192 MiB copy); the
-# figures and commands are in profiles/fused_kernel_c3_70b_shard_tp8_budget32.md.
-MEASURED_TRAFFIC_BYTES = {(WORKLOAD, 32): (147653 + 32768) * 1024}
+# WRITE_SIZE, each scaled by what the same counter reads for a 192 MiB copy). They are
+# not measured in this run (counters need the profiler): they are the figures of the
+# named profile, valid for the kernel source whose hash is recorded beside them. A
+# kernel edit changes the hash; the line then reports traffic as null until the
+# profile is taken again (tests/test_bench_contract.py fails on the mismatch too).
+TRAFFIC_FROM_PROFILE = {
+    (WORKLOAD, 32): {
+        "profile": "profiles/fused_kernel_c3_70b_shard_tp8_budget32.md",
+        "kernel": "tw::fused_kernel<8, 1, false>",
+        "fetched_KiB": 147653, "written_KiB": 32768,
+        "kernel_source_sha256_12": "4891af11f486",
+    },
+}
+KERNEL_SOURCES = ("paper_2505_11329_amd/csrc/tw_fused.hip", "paper_2505_11329_amd/csrc/tw_device.h")
 
+
+_streams_tried = [0]
+
+
+def overlapping_stream(tw, torch, others, tries=12):
+    """A new torch stream whose kernels run side by side with those of every stream in `others`. The HIP
+    runtime maps a process's streams onto few hardware queues (4 here) and two streams on one queue
+    never overlap, whatever the events between them say: about every fourth stream torch hands out
+    shares the first one's queue. tw_streams_overlap tells; streams that fail stay in torch's pool."""
+    for _ in range(tries):
+        cand = torch.cuda.Stream()
+        _streams_tried[0] += 1
+        if all(tw.streams_overlap(o, cand) for o in others):
+            return cand
+    raise RuntimeError("no stream found that overlaps with the given ones after %d tries" % tries)
+
+
+def kernel_source_hash():
+    """First 12 hex digits of the SHA-256 over the fused kernel's source files."""
+    import hashlib
+    h = hashlib.sha256()
+    for rel in KERNEL_SOURCES:
+        with open(os.path.join(ROOT, rel), "rb") as f:
+            h.update(f.read())
+    return h.hexdigest()[:12]
 
 def main():
     ap = argparse.ArgumentParser()
@@ -52,7 +88,12 @@ def main():
                     help="instead of the benchmark line: for a range of token counts, the woven layer boundary "
                          "timed at the equal split and at the offsets {0,64,128,192,256,512} past it (the sweep "
                          "of Algorithm 1), next to the row tw_smart_split_point picks without timing anything")
-    ap.add_argument("--counters-run", choices=("fused", "gemm", "weave"), default=None,
+    ap.add_argument("--ceiling", action="store_true",
+                    help="instead of the benchmark line: GB/s per compute unit of plain streaming kernels "
+                         "(tw_hbm_probe_shaped / tw_hbm_probe_mixed_shaped) for budgets 1..32 x workgroup size x "
+                         "accesses in flight x read / copy / 9-read-2-write: the per-CU HBM ceiling the fused "
+                         "kernel is measured against")
+    ap.add_argument("--counters-run", choices=("fused", "gemm", "weave", "probe"), default=None,
                     help="for rocprofv3 --pmc. fused: a few fused launches plus plain copy launches of known "
                          "size (tw_hbm_probe, 192 MiB read + 192 MiB written each) to scale the byte counters "
                          "by. gemm: a few launches of the bf16 GEMM on the overlap demo's shape. weave (for "
@@ -120,6 +161,9 @@ def main():
                 acc[k].append(event_times(fns, iters, warm, stream))
         return {k: round(float(np.median(np.concatenate(v))), 1) for k, v in acc.items()}
 
+    if args.ceiling:
+        ceiling_sweep(tw, torch, np, stream, event_times)
+        return
     if args.sweep:
         def sweep_point(H, P, N, cfgname):
             per_set = (P + 3) * 2 * H * N
@@ -168,7 +212,7 @@ def main():
         return
     if args.split_sweep:
         K1, H, P, N2 = 1024, 8192, 8, 3584
-        comm = torch.cuda.Stream()
+        comm = overlapping_stream(tw, torch, [stream])
         cus = tw.device_cu_count()
         gen = torch.Generator(device=dev)
         gen.manual_seed(7)
@@ -282,7 +326,7 @@ def main():
         X1, W1, W2 = rnd((T, K1), 0.02), rnd((H, K1), 0.02), rnd((N2, H), 0.02)
         parts, resid = [rnd((T, H), 0.25) for _ in range(P)], rnd((T, H), 1.0)
         weight = gpu(W.uniform_bf16((H,), 0.5, 1.5, 0, W.STREAM_WEIGHT))
-        comm = torch.cuda.Stream()
+        comm = overlapping_stream(tw, torch, [stream])
         torch.cuda.synchronize()
         k, _, _ = tw.smart_split_point(T, 128, [H, N2], tw.device_cu_count(), gemm_k=[K1, H])
         order = [("unsplit", 0, tw.WEAVE_ORDERED), ("ordered", k, tw.WEAVE_ORDERED), ("chains", k, tw.WEAVE_CHAINS)]
@@ -297,14 +341,34 @@ def main():
                           "order": [o[0] for o in order]}))
         return
     if args.counters_run == "gemm":
+        # both tile shapes the library builds: the overlap demo's product takes 256 x 128 tiles, the
+        # MLP-side down projection of the same layer ([2048 x 8192] x [8192 x 1280], 80 wide tiles) 256 x 64
         gc = W.CONFIGS["c5_overlap_tp8"]["gemm"]
-        g = W.make_gemm_inputs(gc["M"], gc["K"], gc["N"], gc["std"], 0, "nk")
-        A, B = gpu(g["A"]), gpu(g["B"])
-        C = torch.empty((gc["M"], gc["N"]), dtype=torch.bfloat16, device=dev)
-        for i in range(12):
-            tw.gemm_bf16(A, B, C=C, cu_budget=0, stream=stream)
+        shapes = [(gc["M"], gc["K"], gc["N"]), (gc["M"], gc["K"], 1280)]
+        for (M, K, N) in shapes:
+            g = W.make_gemm_inputs(M, K, N, gc["std"], 0, "nk")
+            A, B = gpu(g["A"]), gpu(g["B"])
+            C = torch.empty((M, N), dtype=torch.bfloat16, device=dev)
+            for i in range(12):
+                tw.gemm_bf16(A, B, C=C, cu_budget=0, stream=stream)
+            torch.cuda.synchronize()
+        print(json.dumps({"counters_run": "gemm", "launches_per_shape": 12,
+                          "flops_per_launch": [2.0 * M * K * N for (M, K, N) in shapes]}))
+        return
+    if args.counters_run == "probe":
+        # plain streaming kernels with the fused kernel's budgeted launch shape, for the L1 request counters
+        pb = 192 << 20
+        src = torch.empty(pb, dtype=torch.uint8, device=dev).random_()
+        dst = torch.empty(pb, dtype=torch.uint8, device=dev)
+        sb = pb // 12
+        sb -= sb % 16384
         torch.cuda.synchronize()
-        print(json.dumps({"counters_run": "gemm", "flops_per_launch": 2.0 * gc["M"] * gc["K"] * gc["N"]}))
+        for i in range(8):
+            tw.hbm_probe(src, dst, pb, tw.PROBE_READ, cu_budget=args.budget, stream=stream)
+            tw.hbm_probe_mixed(src, dst, sb, 9, 2, cu_budget=args.budget, stream=stream)
+        torch.cuda.synchronize()
+        print(json.dumps({"counters_run": "probe", "read_bytes": pb, "mixed_bytes_read": 9 * sb,
+                          "mixed_bytes_written": 2 * sb, "cu_budget": args.budget}))
         return
     if args.counters_run == "fused":
         sets = fused_sets(WORKLOAD, 4)
@@ -359,14 +423,29 @@ def main():
                    "clocks": "not locked (non-root)"},
         "roofline": {"bound": "hbm", "achieved": round(achieved, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
                      "frac": round(achieved / HBM_PEAK_GBS, 4),
-                     "traffic": (round(MEASURED_TRAFFIC_BYTES[(WORKLOAD, args.budget)] / (avg_us * 1e-6) / 1e9, 1)
-                                 if (WORKLOAD, args.budget) in MEASURED_TRAFFIC_BYTES else None),
-                     "traffic_bytes_per_launch": MEASURED_TRAFFIC_BYTES.get((WORKLOAD, args.budget)),
-                     "kernel": "tw::fused_kernel<8,1,false>", "avg_launch_us": round(avg_us, 2),
+                     "traffic": None, "traffic_bytes_per_launch": None,
+                     "kernel": "tw::fused_kernel<8, 1, false>", "avg_launch_us": round(avg_us, 2),
                      "p10_us": round(float(np.percentile(kern_us, 10)), 2),
                      "p50_us": round(float(np.percentile(kern_us, 50)), 2),
-                     "p90_us": round(float(np.percentile(kern_us, 90)), 2)},
+                     "p90_us": round(float(np.percentile(kern_us, 90)), 2),
+                     "target": "north star: >= 0.70 of HBM peak at H=8192, P=8 within <= 32 CUs -- NOT MET, and "
+                               "above what 32 compute units can request from HBM on this part (see "
+                               "hbm_ceiling_per_cu below and bench.py --ceiling)"},
     }
+    tp = TRAFFIC_FROM_PROFILE.get((WORKLOAD, args.budget))
+    rf = result["roofline"]
+    if tp is None:
+        rf["traffic_source"] = "no counter profile for this budget"
+    elif tp["kernel_source_sha256_12"] != kernel_source_hash():
+        rf["traffic_source"] = ("stale: %s was taken for kernel source %s, this build is %s"
+                                % (tp["profile"], tp["kernel_source_sha256_12"], kernel_source_hash()))
+    else:
+        tbytes = (tp["fetched_KiB"] + tp["written_KiB"]) * 1024
+        rf["traffic"] = round(tbytes / (avg_us * 1e-6) / 1e9, 1)
+        rf["traffic_bytes_per_launch"] = tbytes
+        rf["traffic_source"] = "counters in %s (kernel %s, source %s), not measured in this run" % (
+            tp["profile"], tp["kernel"], tp["kernel_source_sha256_12"])
+        assert tp["kernel"] == rf["kernel"]
 
     if not args.no_extras:
         extras(result, tw, W, torch, np, stream, sets, fused_sets, algo_bytes, event_times, interleaved_medians, gpu)
@@ -384,6 +463,26 @@ def extras(result, tw, W, torch, np, stream, sets, fused_sets, algo_bytes, event
     def fused_fns(ss, budget, st=stream):
         return [tw.prepare_reduce_add_rmsnorm(s["partials"], s["residual"], s["weight"], s["eps"], cu_budget=budget,
                                               out=s["out"], residual_out=s["res_out"], stream=st)[0] for s in ss]
+
+    def device_drawn_sets(cfgname, nsets, N, P=None, H=None):
+        """Buffer sets of a configuration's shape and value distributions drawn with torch's generator on
+        the GPU (seeded): for batches too large for the host-side counter-based generator to be quick."""
+        cfg = W.CONFIGS[cfgname]
+        P_, H_ = P or cfg["P"], H or cfg["H"]
+        out_ = []
+        for k in range(nsets):
+            gen = torch.Generator(device="cuda:0")
+            gen.manual_seed(7919 * k + N)
+
+            def rnd(shape, std):
+                return torch.empty(shape, dtype=torch.bfloat16, device="cuda:0").normal_(0.0, std, generator=gen)
+            parts = [rnd((N, H_), cfg["partial_std"]) for _ in range(P_)]
+            resid = rnd((N, H_), cfg["residual_std"])
+            out_.append(dict(partials=parts, residual=resid, eps=cfg["eps"], N=N, H=H_, P=P_,
+                             weight=gpu(W.uniform_bf16((H_,), 0.5, 1.5, 0, W.STREAM_WEIGHT)),
+                             out=torch.empty_like(resid), res_out=torch.empty_like(resid)))
+        torch.cuda.synchronize()      # drawn on torch's stream, launched on ours
+        return out_
 
     # what a budget can stream: read-only and copy probes over 192 MiB buffers, rotated
     pb = 192 << 20
@@ -465,34 +564,49 @@ def extras(result, tw, W, torch, np, stream, sets, fused_sets, algo_bytes, event
     del s2
     torch.cuda.empty_cache()
 
-    # token split (config 4): one launch vs two halves on two streams, makespan on the parent
-    sa, sb = torch.cuda.Stream(), torch.cuda.Stream()
+    # token split (config 4): one launch vs two halves on two streams, makespan on the parent, at all
+    # four token counts. "Per CU budget" is read strictly: the split run gets the same total budget
+    # (b/2 per half); the run where each half gets b (2b compute units in all) is reported beside it.
+    sa = overlapping_stream(tw, torch, [stream])
+    sb = overlapping_stream(tw, torch, [stream, sa])
     split = {}
     cfg4 = W.CONFIGS["c4_split_sweep_tp4"]
-    for N in (1024, 4096):
-        nsets = 4 if N <= 1024 else 2
-        s4 = fused_sets("c4_split_sweep_tp4", nsets, N=N)
+    for N in cfg4["N"]:
+        if N <= 1024:
+            s4 = fused_sets("c4_split_sweep_tp4", 12 if N <= 256 else 4, N=N)
+        else:
+            s4 = device_drawn_sets("c4_split_sweep_tp4", 2, N)   # the host generator is slow at this size
         nb4 = algo_bytes(s4[0])
         k = tw.split_point(N, cfg4["split_multiple"])
+        iters, warm = (40, 6) if N <= 4096 else (10, 3)
         for b in cfg4["cu_budgets"]:
-            t1 = event_times(fused_fns(s4, b), 40, 6, stream)
+            t1 = event_times(fused_fns(s4, b), iters, warm, stream)
 
-            def split_fn(s, b=b, k=k):
+            def split_fn(s, b_half, k=k):
                 def f():
                     with torch.cuda.stream(stream):
-                        tw.split_launch(s["partials"], s["residual"], s["weight"], s["eps"], k, sa, sb, cu_budget=b,
-                                        out=s["out"], residual_out=s["res_out"], parent=stream, use_parent=True,
-                                        join=True)
+                        tw.split_launch(s["partials"], s["residual"], s["weight"], s["eps"], k, sa, sb,
+                                        cu_budget=b_half, out=s["out"], residual_out=s["res_out"], parent=stream,
+                                        use_parent=True, join=True)
                 return f
-            t2 = event_times([split_fn(s) for s in s4], 40, 6, stream)
-            split["N%d_b%d" % (N, b)] = {"unsplit_us": round(float(np.median(t1)), 1),
-                                         "split_us": round(float(np.median(t2)), 1),
-                                         "unsplit_GBps": round(nb4 / np.median(t1) / 1e3, 1),
-                                         "split_GBps": round(nb4 / np.median(t2) / 1e3, 1)}
+            t_eq = event_times([split_fn(s, b // 2) for s in s4], iters, warm, stream)
+            t_2b = event_times([split_fn(s, b) for s in s4], iters, warm, stream)
+            row = {"unsplit_us": round(float(np.median(t1)), 1),
+                   "split_same_total_budget_us": round(float(np.median(t_eq)), 1),
+                   "split_each_half_full_budget_us": round(float(np.median(t_2b)), 1)}
+            if N > 256:     # N = 256 is a latency case: 29 MB, launch- and ramp-bound
+                row.update({"unsplit_GBps": round(nb4 / np.median(t1) / 1e3, 1),
+                            "split_same_total_budget_GBps": round(nb4 / np.median(t_eq) / 1e3, 1),
+                            "split_each_half_full_budget_GBps": round(nb4 / np.median(t_2b) / 1e3, 1)})
+            split["N%d_b%d" % (N, b)] = row
         del s4
         torch.cuda.empty_cache()
     result["split"] = {"workload": "c4_split_sweep_tp4 (H=8192, P=4, k=N/2)", "per_case": split,
-                       "note": "each half gets the budget, so the split run occupies 2x the CUs"}
+                       "note": "b = CU budget of the unsplit launch. split_same_total_budget: each half is confined to "
+                               "b/2 compute units, so both runs occupy b; split_each_half_full_budget: each half "
+                               "gets b (2b occupied). Makespan on the parent stream, fork and join included. N >= "
+                               "4096: inputs drawn on the GPU with the config's distributions; N = 256 reported "
+                               "as latency only"}
 
     # overlap demo (config 5): fused(A, 32 CUs) next to GEMM(B) vs back to back
     cfg5 = W.CONFIGS["c5_overlap_tp8"]
@@ -504,7 +618,9 @@ def extras(result, tw, W, torch, np, stream, sets, fused_sets, algo_bytes, event
     A, B = gpu(g["A"]), gpu(g["B"])
     C = torch.empty((gc["M"], gc["N"]), dtype=torch.bfloat16, device="cuda:0")
     flops = 2.0 * gc["M"] * gc["K"] * gc["N"]
-    comm, comp = torch.cuda.Stream(), torch.cuda.Stream()
+    # every pair of streams whose kernels are meant to overlap is checked to sit on different hardware queues
+    comm = overlapping_stream(tw, torch, [stream])
+    comp = overlapping_stream(tw, torch, [stream, comm])
     cus_total = tw.device_cu_count()
     tf = event_times(fused_fns(s5, 32), 30, 5, stream)
     tg = event_times([lambda: tw.gemm_bf16(A, B, C=C, cu_budget=0, stream=stream)], 30, 5, stream)
@@ -571,8 +687,14 @@ def extras(result, tw, W, torch, np, stream, sets, fused_sets, algo_bytes, event
         return float(np.median(f_us)), float(np.median(g_us))
     cont_f32, cont_g32 = contended(32, cus_total - 32, False)
     cont_fsh, cont_gsh = contended(tw.CU_SHARED, 0, True)
+    best_serial = min(ov["serial32"], ov["serial_whole"])
+    best_overlap = min(ov["budget32"], ov["shared"])
     result["overlap"] = {
         "workload": "c5_overlap_tp8: fused N=2048,H=8192,P=8 @32 CUs || GEMM [2048x8192]x[8192x3584] bf16",
+        "gain_best_overlapped_vs_best_serial": round(best_serial / best_overlap, 3),
+        "best_serial_schedule": "serial_whole_device" if ov["serial_whole"] <= ov["serial32"] else "serial_budget32",
+        "best_overlapped_schedule": "overlapped_shared" if ov["shared"] <= ov["budget32"] else "overlapped_budget32",
+        "budgeted_overlap_beats_best_serial": bool(ov["budget32"] < best_serial),
         "fused_alone_us": round(float(np.median(tf)), 1), "gemm_alone_us": round(float(np.median(tg)), 1),
         "gemm_alone_TFLOPs": round(flops / np.median(tg) / 1e6, 1),
         "gemm_frac_mfma_peak": round(flops / np.median(tg) / 1e6 / MFMA_BF16_PEAK_TFLOPS, 4),
@@ -648,6 +770,219 @@ def extras(result, tw, W, torch, np, stream, sets, fused_sets, algo_bytes, event
                 "picks, then each schedule forced); unsplit_same_budgets = same budgets, no split; unsplit_whole_device = "
                 "each kernel on all CUs in turn, one stream, no events; the schedules take turns in bursts",
     }
+    del X1, W1, W2, parts, resid, out, res_out, Y
+    torch.cuda.empty_cache()
+    budget_grid(result, tw, W, torch, np, stream, event_times, device_drawn_sets)
+    policy_table(result, tw, W, torch, np, stream, comm, interleaved_medians, gpu)
+    decode_trains(result, tw, W, torch, np, stream, gpu)
+    result["streams"] = {"second_streams_checked_with": "tw_streams_overlap", "torch_streams_tried": _streams_tried[0],
+                         "note": "two streams on one hardware queue never overlap; every second stream used for a "
+                                 "split or overlapped schedule here was checked to run side by side with the first"}
+
+
+def budget_grid(result, tw, W, torch, np, stream, event_times, device_drawn_sets):
+    """The analogue of the paper's Fig. 9 / Fig. 22 (latency against the number of SMs, per sequence
+    length): the fused kernel's rate per CU budget, per token count, with the smallest budget that reaches
+    the plateau and the smallest that reaches 70 % of the HBM peak."""
+    H, P = 8192, 8
+    grid = {}
+    budgets = (8, 16, 32, 64, 128, 256)
+    for N in (256, 1024, 4096, 16384):
+        per_set = (P + 3) * 2 * H * N
+        nsets = max(2, min(12, (600 << 20) // per_set + 1))
+        ss = device_drawn_sets("c3_70b_shard_tp8", nsets, N)
+        row = {}
+        for b in budgets + (tw.CU_SHARED,):
+            est_us = per_set / (min(b if b > 0 else 256, 110) * 50e3)      # ~50 GB/s per CU, ~5.5 TB/s at most
+            iters = int(max(6, min(40, 40e3 / est_us)))
+            fns = [tw.prepare_reduce_add_rmsnorm(x["partials"], x["residual"], x["weight"], x["eps"], cu_budget=b,
+                                                 out=x["out"], residual_out=x["res_out"], stream=stream)[0]
+                   for x in ss]
+            t = float(np.median(event_times(fns, iters, 3, stream)))
+            row["shared" if b == tw.CU_SHARED else str(b)] = {"us": round(t, 1), "GBps": round(per_set / t / 1e3, 1)}
+        best = max(v["GBps"] for k_, v in row.items() if k_ != "shared")
+        plateau = next(b for b in budgets if row[str(b)]["GBps"] >= 0.95 * best)
+        seventy = next((b for b in budgets if row[str(b)]["GBps"] >= 0.70 * HBM_PEAK_GBS), None)
+        grid["N%d" % N] = {"per_budget": row, "best_GBps": best, "min_budget_for_plateau": plateau,
+                           "min_budget_for_70pct": seventy,
+                           "shared_reaches_70pct": bool(row["shared"]["GBps"] >= 0.70 * HBM_PEAK_GBS)}
+        del ss
+        torch.cuda.empty_cache()
+    result["budget_grid"] = {
+        "workload": "H=8192, P=8, value distributions of c3 without the outliers, drawn on the GPU; rotating "
+                    "buffer sets of > 600 MB in all",
+        "per_token_count": grid,
+        "note": "plateau = smallest budget within 5 % of the best budget's rate; min_budget_for_70pct = smallest "
+                "budget at or above 5600 GB/s (null: none reaches it). In the paper 8 SMs are close to optimal at "
+                "every length because its kernel is bound by the interconnect; here the kernel is bound by what "
+                "a compute unit can request from HBM, so the plateau needs (nearly) every compute unit"}
+
+
+def policy_table(result, tw, W, torch, np, stream, comm, interleaved_medians, gpu):
+    """Fig. 3 / Appendix A 'Selective Enabling': per token count, the layer boundary run never split,
+    always split, and under the library's policy (tw_weave_layer_auto with its built-in threshold)."""
+    H, P = 8192, 8
+    cus = tw.device_cu_count()
+    weight = gpu(W.uniform_bf16((H,), 0.5, 1.5, 0, W.STREAM_WEIGHT))
+    out_ = {}
+    for name, K1, N2 in (("attention_side", 1024, 3584), ("mlp_side", 3584, 1280)):
+        gen = torch.Generator(device="cuda:0")
+        gen.manual_seed(K1 + N2)
+
+        def rnd(shape, std):
+            return torch.empty(shape, dtype=torch.bfloat16, device="cuda:0").normal_(0.0, std, generator=gen)
+        W1, W2 = rnd((H, K1), 0.02), rnd((N2, H), 0.02)
+        thr = tw.split_threshold(K1, H, P, N2, cus)
+        rows = []
+        for T in (256, 1024, 2048, 4096, 6144, 8192, 16384):
+            X1, resid = rnd((T, K1), 0.02), rnd((T, H), 1.0)
+            parts = [rnd((T, H), 0.25) for _ in range(P)]
+            o, r = torch.empty_like(resid), torch.empty_like(resid)
+            Y = torch.empty((T, N2), dtype=torch.bfloat16, device="cuda:0")
+            torch.cuda.synchronize()
+            kw = dict(fused_cu_budget=tw.CU_SHARED, gemm_cu_budget=0, out=o, residual_out=r, Y=Y, parent=stream,
+                      use_parent=True, join=True)
+            k_smart = tw.smart_split_point(T, 64, [H, N2], cus, gemm_k=[K1, H])[0]
+            taken = []
+
+            def never():
+                with torch.cuda.stream(stream):
+                    tw.weave_layer(X1, W1, parts, resid, weight, 1e-5, W2, 0, stream, comm, **kw)
+
+            def always():
+                with torch.cuda.stream(stream):
+                    tw.weave_layer(X1, W1, parts, resid, weight, 1e-5, W2, k_smart, stream, comm, **kw)
+
+            def policy():
+                with torch.cuda.stream(stream):
+                    taken.append(tw.weave_layer_auto(X1, W1, parts, resid, weight, 1e-5, W2, stream, comm, **kw)[3])
+            iters = 8 if T <= 8192 else 5
+            med = interleaved_medians({"never": never, "always": always, "policy": policy}, rounds=4, iters=iters,
+                                      warm=2)
+            best = min(med["never"], med["always"])
+            rows.append({"T": T, "never_split_us": med["never"], "always_split_us": med["always"],
+                         "policy_us": med["policy"], "policy_split_row": taken[-1], "always_split_row": k_smart,
+                         "policy_over_best": round(med["policy"] / best, 3)})
+            del X1, resid, parts, o, r, Y
+            torch.cuda.empty_cache()
+        out_[name] = {"boundary": "[Tx%d]x[%dx8192] -> fused H=8192 P=8 (shared mode) -> [Tx8192]x[8192x%d]"
+                                  % (K1, K1, N2),
+                      "built_in_threshold_tokens": thr, "rows": rows,
+                      "worst_policy_over_best": max(r_["policy_over_best"] for r_ in rows)}
+    result["policy"] = {
+        "per_boundary": out_,
+        "note": "never = the chain G1, F, G2 unsplit on one stream; always = tw_weave_layer at the row "
+                "tw_smart_split_point picks, whatever T; policy = tw_weave_layer_auto (threshold from "
+                "tw_split_threshold, then the same row). policy_split_row == T means the policy did not split. "
+                "Candidates take turns in bursts, in rotating order; medians of HIP-event timed calls"}
+
+
+def decode_trains(result, tw, W, torch, np, stream, gpu):
+    """Appendix B's decode case: an iteration is a train of many small fused steps (two per layer, 80
+    layers). 160 back-to-back calls, eager against one HIP graph captured once and replayed."""
+    H, P, calls = 8192, 8, 160
+    rows = {}
+    for N in (1, 16, 64, 256):
+        d = W.make_fused_inputs("c3_70b_shard_tp8", N=N)
+        parts = [gpu(p) for p in d["partials"]]
+        resid, weight = gpu(d["residual"]), gpu(d["weight"])
+        o, r = torch.empty_like(resid), torch.empty_like(resid)
+        launch = tw.prepare_reduce_add_rmsnorm(parts, resid, weight, d["eps"], cu_budget=tw.CU_SHARED, out=o,
+                                               residual_out=r, stream=stream)[0]
+
+        def train():
+            for _ in range(calls):
+                launch()
+        train()
+        stream.synchronize()
+        graph = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(graph, stream=stream):
+            train()
+
+        def replay():
+            with torch.cuda.stream(stream):
+                graph.replay()
+        res = {}
+        for label, fn in (("eager", train), ("graph", replay)):
+            wall, host, dev_us = [], [], []
+            for rep in range(12):
+                stream.synchronize()
+                e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+                t0 = time.perf_counter()
+                e0.record(stream)
+                fn()
+                e1.record(stream)
+                t1 = time.perf_counter()
+                stream.synchronize()
+                t2 = time.perf_counter()
+                if rep >= 2:
+                    host.append((t1 - t0) * 1e6 / calls)
+                    wall.append((t2 - t0) * 1e6 / calls)
+                    dev_us.append(e0.elapsed_time(e1) * 1e3 / calls)
+            res[label] = {"wall_us_per_launch": round(float(np.median(wall)), 2),
+                          "device_us_per_launch": round(float(np.median(dev_us)), 2),
+                          "host_us_per_call": round(float(np.median(host)), 2)}
+        res["graph_speedup_wall"] = round(res["eager"]["wall_us_per_launch"] / res["graph"]["wall_us_per_launch"], 3)
+        rows["N%d" % N] = res
+        del graph
+    result["decode_trains"] = {
+        "workload": "160 back-to-back tw_reduce_add_rmsnorm calls (H=8192, P=8, shared mode, same buffers: inputs "
+                    "stay in cache as in a decode step), per call",
+        "per_token_count": rows,
+        "note": "eager: 160 calls through the C ABI (arguments marshalled once), then one synchronisation; graph: "
+                "the same 160 launches captured once with hipStreamBeginCapture and replayed. wall = submit + "
+                "drain per launch; host = time for the calls (or the replay call) to return, per launch; device = "
+                "HIP events around the train"}
+
+
+def ceiling_sweep(tw, torch, np, stream, event_times):
+    """What one compute unit can pull from / push to HBM, and what it does not depend on: budgets x
+    workgroup sizes x accesses in flight for a read-only and a copy stream, budgets x workgroup sizes for
+    the fused kernel's own mix (9 streams read, 2 written). One workgroup per compute unit throughout."""
+    pb = 192 << 20
+    srcs = [torch.empty(pb, dtype=torch.uint8, device="cuda:0").random_() for _ in range(4)]
+    dsts = [torch.empty(pb, dtype=torch.uint8, device="cuda:0") for _ in range(4)]
+    torch.cuda.synchronize()
+    budgets = (1, 2, 4, 8, 16, 32)
+    table = []
+    for mode, mname in ((tw.PROBE_READ, "read"), (tw.PROBE_COPY, "copy")):
+        for threads in (256, 512, 1024):
+            for depth in (1, 2, 4, 8, 16):
+                row = {"stream": mname, "threads_per_workgroup": threads, "accesses_in_flight_per_thread": depth,
+                       "KiB_in_flight_per_cu": threads * depth * 16 // 1024}
+                for b in budgets:
+                    # small budgets move less so that a cell stays in the tens of milliseconds
+                    nbytes = min(pb, (b * 24) << 20)
+                    fns = [(lambda i=i: tw.hbm_probe_shaped(srcs[i], dsts[i], nbytes, mode, cu_budget=b,
+                                                            threads=threads, in_flight=depth, stream=stream))
+                           for i in range(4)]
+                    t = float(np.median(event_times(fns, 8, 2, stream)))
+                    moved = nbytes * (2 if mode == tw.PROBE_COPY else 1)
+                    row["GBps_per_cu_b%d" % b] = round(moved / t / 1e3 / b, 1)
+                table.append(row)
+    sb = pb // 12
+    sb -= sb % 16384
+    for threads in (256, 512, 1024):
+        row = {"stream": "9 read + 2 written", "threads_per_workgroup": threads,
+               "accesses_in_flight_per_thread": 9, "KiB_in_flight_per_cu": threads * 9 * 16 // 1024}
+        for b in budgets:
+            per = min(sb, ((b * 2) << 20) // 16384 * 16384)
+            fns = [(lambda i=i: tw.hbm_probe_mixed_shaped(srcs[i], dsts[i], per, 9, 2, cu_budget=b, threads=threads,
+                                                          stream=stream)) for i in range(4)]
+            t = float(np.median(event_times(fns, 8, 2, stream)))
+            row["GBps_per_cu_b%d" % b] = round(11 * per / t / 1e3 / b, 1)
+        table.append(row)
+    best = {}
+    for b in budgets:
+        for sname in ("read", "copy", "9 read + 2 written"):
+            best["%s_b%d" % (sname.split()[0] if sname != "9 read + 2 written" else "mix", b)] = max(
+                r["GBps_per_cu_b%d" % b] for r in table if r["stream"] == sname)
+    print(json.dumps({"ceiling": table, "best_GBps_per_cu": best,
+                      "needed_for_70pct_of_hbm_peak_in_32_cus_GBps_per_cu": round(0.7 * HBM_PEAK_GBS / 32, 1),
+                      "note": "GB/s per compute unit (copy and mix: bytes read + bytes written); one workgroup per "
+                              "compute unit (each requests 96 KiB of LDS); buffers of 192 MiB rotated four ways, so "
+                              "nothing is served from the 256 MB Infinity Cache; medians of 8 HIP-event timed "
+                              "launches"}))
 
 
 def cpu_baseline(W, np):

@@ -109,6 +109,23 @@ tw_status tw_hbm_probe_shaped(const void *src, void *dst, int64_t bytes, int mod
 tw_status tw_hbm_probe_mixed_shaped(const void *src, void *dst, int64_t stream_bytes, int n_read, int n_write,
                                     int cu_budget, int threads, void *stream);
 
+/*
+ * Do kernels on these two streams run side by side? Two streams of one process
+ * only overlap when the HIP runtime has mapped them to different hardware queues,
+ * and it has few of those (GPU_MAX_HW_QUEUES, 4 by default): of the streams a
+ * process creates, every fourth shares a queue with the first, and work on two
+ * such streams runs strictly one kernel after the other, whatever events say.
+ * The split schedules of tw.h then still give correct results but hide nothing.
+ * This call finds out by running a one-wave kernel that idles for 300 us on each
+ * stream from a common starting point and timing both with events: *overlap is 1
+ * if the later one ends well before 600 us, else 0 (also when stream_a ==
+ * stream_b). Unlike the entry points of tw.h it creates and destroys three
+ * events and BLOCKS until both kernels are done (about 0.3 to 0.6 ms after the
+ * work already on stream_a): call it once when the streams are set up, not per
+ * launch, and not during stream capture.
+ */
+tw_status tw_streams_overlap(void *stream_a, void *stream_b, int *overlap);
+
 #ifdef __cplusplus
 }
 #endif

@@ -123,6 +123,8 @@ def lib():
         L.tw_hbm_probe_mixed_shaped.argtypes = [_vp, _vp, _i64, ctypes.c_int, ctypes.c_int, ctypes.c_int, ctypes.c_int,
                                                 _vp]
         L.tw_hbm_probe_mixed_shaped.restype = ctypes.c_int
+        L.tw_streams_overlap.argtypes = [_vp, _vp, ctypes.POINTER(ctypes.c_int)]
+        L.tw_streams_overlap.restype = ctypes.c_int
         L.tw_device_cu_count.argtypes = []
         L.tw_device_cu_count.restype = ctypes.c_int
         L.tw_status_str.argtypes = [ctypes.c_int]
@@ -360,6 +362,14 @@ def hbm_probe_mixed_shaped(src, dst, stream_bytes, n_read, n_write, cu_budget=0,
                                            _vp(dst.data_ptr()), int(stream_bytes), int(n_read), int(n_write),
                                            int(cu_budget), int(threads), _stream_handle(stream)),
            "tw_hbm_probe_mixed_shaped")
+
+
+def streams_overlap(stream_a, stream_b):
+    """tw_streams_overlap: True if kernels on the two torch streams run side by side (blocks ~0.5 ms)."""
+    yes = ctypes.c_int(0)
+    _check(lib().tw_streams_overlap(_stream_handle(stream_a), _stream_handle(stream_b), ctypes.byref(yes)),
+           "tw_streams_overlap")
+    return bool(yes.value)
 
 
 def smart_split_point(T, multiple, gemm_n_out, cus, gemm_k=None):

@@ -98,6 +98,18 @@ __global__ __launch_bounds__(kProbeThreads) void probe_mixed_kernel(const char *
         reinterpret_cast<u32x4 *>(dst)[threadIdx.x] = acc;
 }
 
+// Occupies one wave for `ticks` of the device's constant-rate wall clock and does
+// nothing else; gives up after max_iters polls whatever the clock says, so the
+// wave always ends (each poll sleeps about a microsecond).
+__global__ __launch_bounds__(64) void spin_kernel(unsigned long long ticks, unsigned max_iters)
+{
+    const unsigned long long t0 = wall_clock64();
+    for (unsigned i = 0; i < max_iters; ++i) {
+        if (wall_clock64() - t0 >= ticks) break;
+        __builtin_amdgcn_s_sleep(32);
+    }
+}
+
 template <int NR>
 static tw_status launch_mixed(const void *src, void *dst, int64_t stream_bytes, int n_write, unsigned grid,
                               unsigned threads, hipStream_t stream)
@@ -212,4 +224,44 @@ extern "C" tw_status tw_hbm_probe_mixed(const void *src, void *dst, int64_t stre
                                         int n_write, int cu_budget, void *stream)
 {
     return tw_hbm_probe_mixed_shaped(src, dst, stream_bytes, n_read, n_write, cu_budget, kProbeThreads, stream);
+}
+
+extern "C" tw_status tw_streams_overlap(void *stream_a, void *stream_b, int *overlap)
+{
+    if (!overlap) return TW_ERR_NULL;
+    *overlap = 0;
+    if (stream_a == stream_b) return TW_OK;
+    hipStream_t a = static_cast<hipStream_t>(stream_a), b = static_cast<hipStream_t>(stream_b);
+    int dev = 0, khz = 0;
+    TW_HIP(hipGetDevice(&dev));
+    TW_HIP(hipDeviceGetAttribute(&khz, hipDeviceAttributeWallClockRate, dev));
+    if (khz <= 0) khz = 100000;  // 100 MHz on this family
+    const double spin_us = 300.0;
+    const unsigned long long ticks = static_cast<unsigned long long>(spin_us * 1e-3 * khz);
+    hipEvent_t ev[3] = {nullptr, nullptr, nullptr};
+    tw_status st = TW_OK;
+    float ms_a = 0.0f, ms_b = 0.0f;
+    auto run = [&]() -> tw_status {
+        for (auto &e : ev) TW_HIP(hipEventCreate(&e));
+        // both kernels become runnable at the same point: after everything already on a
+        TW_HIP(hipEventRecord(ev[0], a));
+        TW_HIP(hipStreamWaitEvent(b, ev[0], 0));
+        TW_HIP(launch_kernel(spin_kernel, dim3(1), dim3(64), 0u, a, ticks, 8192u));
+        TW_HIP(hipEventRecord(ev[1], a));
+        TW_HIP(launch_kernel(spin_kernel, dim3(1), dim3(64), 0u, b, ticks, 8192u));
+        TW_HIP(hipEventRecord(ev[2], b));
+        TW_HIP(hipEventSynchronize(ev[1]));
+        TW_HIP(hipEventSynchronize(ev[2]));
+        TW_HIP(hipEventElapsedTime(&ms_a, ev[0], ev[1]));
+        TW_HIP(hipEventElapsedTime(&ms_b, ev[0], ev[2]));
+        return TW_OK;
+    };
+    st = run();
+    for (auto &e : ev)
+        if (e) (void)hipEventDestroy(e);
+    if (st != TW_OK) return st;
+    // side by side both end about spin_us after the fork; one behind the other, the later ends at twice that
+    const double later_us = 1e3 * (ms_a > ms_b ? ms_a : ms_b);
+    *overlap = later_us < 1.6 * spin_us ? 1 : 0;
+    return TW_OK;
 }

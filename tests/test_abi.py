@@ -37,7 +37,7 @@ def test_header_declares_the_documented_entry_points():
     aids = declared_functions(("tw_measure.h",))
     for must in ("tw_hbm_probe", "tw_hbm_probe_mixed", "tw_hbm_probe_shaped", "tw_hbm_probe_mixed_shaped",
                  "tw_fused_grid", "tw_fused_layout", "tw_weave_schedule", "tw_gemm_tile_shape",
-                 "tw_reduce_add_rmsnorm_traced"):
+                 "tw_reduce_add_rmsnorm_traced", "tw_streams_overlap"):
         assert must in aids and must not in names
 
 
@@ -276,6 +276,13 @@ def test_shaped_probe_argument_checks():
     for threads in (0, 96, 192, 768, 2048):       # must divide the 1024-vector granule
         assert L.tw_hbm_probe_mixed_shaped(VP(addr(0)), VP(addr(2000)), sb, 9, 2, 8, threads, VP(None)) == E_SHAPE
     assert L.tw_hbm_probe_mixed_shaped(VP(addr(0)), VP(addr(2000)), 0, 9, 2, 8, 256, VP(None)) == OK
+
+
+def test_streams_overlap_argument_checks():
+    L = tw.lib()
+    assert L.tw_streams_overlap(VP(1), VP(2), None) == E_NULL
+    yes = ctypes.c_int(7)
+    assert L.tw_streams_overlap(VP(3), VP(3), ctypes.byref(yes)) == OK and yes.value == 0   # one stream: no
 
 
 def test_mixed_probe_argument_checks():

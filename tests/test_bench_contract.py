@@ -25,6 +25,24 @@ def test_help_lists_the_contract_flags():
         assert flag in r.stdout
 
 
+def test_traffic_figure_matches_the_profile_it_cites_and_the_kernel_it_was_taken_for():
+    """roofline.traffic comes from a counter profile, not from the run: the profile must name the
+    benchmark's kernel and hold the same figures, and it must have been taken for the kernel source
+    as it stands (a kernel edit changes the hash and forces the profile to be taken again)."""
+    sys.path.insert(0, ROOT)
+    import bench
+    current = bench.kernel_source_hash()
+    for (workload, budget), tp in bench.TRAFFIC_FROM_PROFILE.items():
+        text = open(os.path.join(ROOT, tp["profile"])).read()
+        assert tp["kernel"] in text, "the profile does not mention %s" % tp["kernel"]
+        assert workload in text and ("cu_budget=%d" % budget) in text
+        assert ("fetched %d KiB" % tp["fetched_KiB"]) in text and ("written %d KiB" % tp["written_KiB"]) in text
+        assert ("kernel source sha256[:12] = %s" % tp["kernel_source_sha256_12"]) in text
+        assert tp["kernel_source_sha256_12"] == current, (
+            "tw_fused.hip / tw_device.h changed since %s was taken: take the counter profile again and "
+            "update TRAFFIC_FROM_PROFILE" % tp["profile"])
+
+
 @pytest.mark.gpu
 def test_benchmark_line_has_the_contract_fields():
     r = subprocess.run([sys.executable, BENCH, "--steps", "20", "--warmup", "5", "--no-extras", "--no-cpu-baseline"],
@@ -42,6 +60,7 @@ def test_benchmark_line_has_the_contract_fields():
     rf = d["roofline"]
     assert rf["bound"] == "hbm" and rf["peak"] == 8000.0 and rf["unit"] == "GB/s"
     assert abs(rf["frac"] - rf["achieved"] / rf["peak"]) < 1e-3
+    assert rf["traffic"] is None or "counters in profiles/" in rf["traffic_source"]
     # whole-job throughput includes the gaps between launches, the kernel's own rate does not
     assert 0.5 * rf["achieved"] < d["value"] <= rf["achieved"] * 1.01
     assert abs(d["ms_per_step"] * 1e3 - rf["avg_launch_us"]) < 0.25 * rf["avg_launch_us"]

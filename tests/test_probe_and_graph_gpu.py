@@ -168,3 +168,19 @@ def test_decode_sized_train_of_fused_steps_replays_from_a_graph(tw, torch_cuda, 
             assert np.array_equal(g_, w_), (rep, i)
         tw.reduce_add_rmsnorm(parts, resid0, weight, d["eps"], cu_budget=8)   # eager work between replays
         torch.cuda.synchronize()
+
+
+def test_streams_overlap_finds_a_partner_stream(tw, torch_cuda):
+    """A stream never overlaps with itself; among a handful of new streams at least one sits on another
+    hardware queue than the first and is reported as running side by side with it, repeatably."""
+    torch = torch_cuda
+    a = torch.cuda.Stream()
+    assert tw.streams_overlap(a, a) is False
+    verdicts = []
+    for _ in range(6):
+        b = torch.cuda.Stream()
+        v = tw.streams_overlap(a, b)
+        assert tw.streams_overlap(a, b) == v and tw.streams_overlap(b, a) == v
+        verdicts.append(v)
+    assert any(verdicts), verdicts
+    torch.cuda.synchronize()
