@@ -146,6 +146,27 @@ def main():
         on_stream.synchronize()
         return np.array([a.elapsed_time(b) for a, b in evs]) * 1e3
 
+    def train_times(fns, trains, length, warm, on_stream):
+        """Per-launch durations (us) from trains of `length` back-to-back launches between ONE pair of HIP
+        events on the launch stream (elapsed / length, one figure per train). A pair of events around a
+        single launch reads about 2 us more than the kernel takes (an empty pair reads 4 us); a train
+        amortises that and agrees with the profiler's kernel trace, at the price of including the gaps
+        between consecutive kernels."""
+        for i in range(warm):
+            fns[i % len(fns)]()
+        on_stream.synchronize()
+        out, k = [], 0
+        for _ in range(trains):
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            e0.record(on_stream)
+            for _ in range(length):
+                fns[k % len(fns)]()
+                k += 1
+            e1.record(on_stream)
+            on_stream.synchronize()
+            out.append(e0.elapsed_time(e1) * 1e3 / length)
+        return np.array(out)
+
     def interleaved_medians(cands, rounds=4, iters=8, warm=2):
         """Median launch time (µs) of each candidate {key: fn or list of fns}. The candidates take turns in
         short bursts so that clock and temperature drift hits all of them alike (the GEMMs are power-limited),
@@ -162,7 +183,7 @@ def main():
         return {k: round(float(np.median(np.concatenate(v))), 1) for k, v in acc.items()}
 
     if args.ceiling:
-        ceiling_sweep(tw, torch, np, stream, event_times)
+        ceiling_sweep(tw, torch, np, stream, train_times)
         return
     if args.sweep:
         def sweep_point(H, P, N, cfgname):
@@ -191,8 +212,8 @@ def main():
                 fns = [tw.prepare_reduce_add_rmsnorm(x["partials"], x["residual"], x["weight"], x["eps"],
                                                      cu_budget=b, out=x["out"], residual_out=x["res_out"],
                                                      stream=stream)[0] for x in ss]
-                iters = 40 if N <= 8192 else 12
-                t = event_times(fns, iters, 4, stream)
+                length = 10 if N <= 8192 else 4
+                t = train_times(fns, 6 if N <= 8192 else 3, length, 4, stream)
                 row[label + "_us"] = round(float(np.median(t)), 2)
                 row[label + "_GBps"] = round(per_set / np.median(t) / 1e3, 1)
             del ss
@@ -208,7 +229,8 @@ def main():
             for H in (1024, 2048, 2560, 3072, 3584, 4096, 5120, 6144, 7168, 8192, 10240, 12288, 16384):
                 hidden.append(sweep_point(H, P, int(180e6 / ((P + 3) * 2 * H)) // 64 * 64, cfgname))
         print(json.dumps({"sweep": rows, "hidden_size_sweep": hidden,
-                          "note": "median of HIP-event timed launches, rotating buffer sets, bf16"}))
+                          "note": "per-launch time from trains of back-to-back launches between one HIP event pair, median "
+                                  "over trains, rotating buffer sets, bf16"}))
         return
     if args.split_sweep:
         K1, H, P, N2 = 1024, 8192, 8, 3584
@@ -396,20 +418,27 @@ def main():
         launches[i % 4]()
     stream.synchronize()
     torch.cuda.synchronize()
-    evs = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(args.steps)]
+    # The timed region holds the K steps and nothing else: one HIP event before the first and one after
+    # the last, on the launch stream. (Event pairs around every single launch, as an earlier version had,
+    # put two extra queue packets between consecutive kernels and read ~2 us more per launch than the
+    # profiler's kernel trace.)
+    ev_begin, ev_end = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
     t0 = time.perf_counter()
+    ev_begin.record(stream)
     for i in range(args.steps):
-        evs[i][0].record(stream)
         launches[i % 4]()
-        evs[i][1].record(stream)
+    ev_end.record(stream)
     stream.synchronize()
     torch.cuda.synchronize()
     t1 = time.perf_counter()
     ms_per_step = (t1 - t0) * 1e3 / args.steps
-    kern_us = np.array([a.elapsed_time(b) for a, b in evs]) * 1e3
-    avg_us = float(kern_us.mean())
+    avg_us = float(ev_begin.elapsed_time(ev_end)) * 1e3 / args.steps
+    # spread of single launches, outside the timed region: an event pair around each of 100 launches
+    kern_us = event_times(launches, min(100, max(10, args.steps)), 4, stream)
     value = nbytes / (ms_per_step * 1e-3) / 1e9
     achieved = nbytes / (avg_us * 1e-6) / 1e9
+    thin = args.budget <= 0 or args.budget >= tw.device_cu_count()
+    kernel_name = "tw::fused_thin_kernel<8, 4, false>" if thin else "tw::fused_kernel<8, 1, false>"
 
     result = {
         "metric": "fused reduce+add+RMSNorm GB/s & % HBM peak at fixed CU budget; overlap makespan",
@@ -424,10 +453,13 @@ def main():
         "roofline": {"bound": "hbm", "achieved": round(achieved, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
                      "frac": round(achieved / HBM_PEAK_GBS, 4),
                      "traffic": None, "traffic_bytes_per_launch": None,
-                     "kernel": "tw::fused_kernel<8, 1, false>", "avg_launch_us": round(avg_us, 2),
-                     "p10_us": round(float(np.percentile(kern_us, 10)), 2),
-                     "p50_us": round(float(np.percentile(kern_us, 50)), 2),
-                     "p90_us": round(float(np.percentile(kern_us, 90)), 2),
+                     "kernel": kernel_name, "avg_launch_us": round(avg_us, 2),
+                     "avg_launch_us_is": "HIP events on the launch stream around the K timed steps, / K",
+                     "single_launch_event_pair_us": {"p10": round(float(np.percentile(kern_us, 10)), 2),
+                                                     "p50": round(float(np.percentile(kern_us, 50)), 2),
+                                                     "p90": round(float(np.percentile(kern_us, 90)), 2),
+                                                     "note": "outside the timed region; a pair of events around "
+                                                             "one launch reads ~2 us more than the kernel takes"},
                      "target": "north star: >= 0.70 of HBM peak at H=8192, P=8 within <= 32 CUs -- NOT MET, and "
                                "above what 32 compute units can request from HBM on this part (see "
                                "hbm_ceiling_per_cu below and bench.py --ceiling)"},
@@ -448,7 +480,8 @@ def main():
         assert tp["kernel"] == rf["kernel"]
 
     if not args.no_extras:
-        extras(result, tw, W, torch, np, stream, sets, fused_sets, algo_bytes, event_times, interleaved_medians, gpu)
+        extras(result, tw, W, torch, np, stream, sets, fused_sets, algo_bytes, event_times, train_times,
+               interleaved_medians, gpu)
     del sets, launches
     torch.cuda.empty_cache()
     if not args.no_cpu_baseline:
@@ -456,7 +489,8 @@ def main():
     print(json.dumps(result))
 
 
-def extras(result, tw, W, torch, np, stream, sets, fused_sets, algo_bytes, event_times, interleaved_medians, gpu):
+def extras(result, tw, W, torch, np, stream, sets, fused_sets, algo_bytes, event_times, train_times,
+               interleaved_medians, gpu):
     """Per-budget table, probe ceilings, split sweep, overlap demo. All outside the timed region."""
     nbytes = algo_bytes(sets[0])
 
@@ -489,21 +523,29 @@ def extras(result, tw, W, torch, np, stream, sets, fused_sets, algo_bytes, event
     srcs = [torch.empty(pb, dtype=torch.uint8, device="cuda:0").random_() for _ in range(4)]
     dsts = [torch.empty(pb, dtype=torch.uint8, device="cuda:0") for _ in range(4)]
     budgets = {}
+
+    def per_launch_us(fns, est_us):
+        """Median per-launch time from trains of 10 back-to-back launches (one event pair per train)."""
+        trains = int(max(4, min(12, 3000.0 / max(est_us, 1.0))))
+        return float(np.median(train_times(fns, trains, 10, 6, stream)))
     for b in (8, 16, 32, 64, 128, 256):
-        t = event_times(fused_fns(sets, b), 60, 8, stream)
-        row = {"us": round(float(np.median(t)), 1), "GBps": round(nbytes / np.median(t) / 1e3, 1),
-               "frac_hbm_peak": round(nbytes / np.median(t) / 1e3 / HBM_PEAK_GBS, 4)}
+        est = nbytes / (min(b, 110) * 50e3)
+        t = per_launch_us(fused_fns(sets, b), est)
+        t_pair = float(np.median(event_times(fused_fns(sets, b), 30, 4, stream)))
+        row = {"us": round(t, 1), "GBps": round(nbytes / t / 1e3, 1),
+               "frac_hbm_peak": round(nbytes / t / 1e3 / HBM_PEAK_GBS, 4),
+               "single_launch_event_pair_us": round(t_pair, 1)}
         fns = [(lambda i=i: tw.hbm_probe(srcs[i], dsts[i], pb, tw.PROBE_READ, cu_budget=b, stream=stream))
                for i in range(4)]
-        tp = event_times(fns, 20, 4, stream)
-        row["probe_read_GBps"] = round(pb / np.median(tp) / 1e3, 1)
+        tp = per_launch_us(fns, est)
+        row["probe_read_GBps"] = round(pb / tp / 1e3, 1)
         # the fused kernel's own mix: P+1 streams read, 2 written, 16 MiB each, no arithmetic
         sb = pb // 12
         sb -= sb % 16384
         fns = [(lambda i=i: tw.hbm_probe_mixed(srcs[i], dsts[i], sb, 9, 2, cu_budget=b, stream=stream))
                for i in range(4)]
-        tp = event_times(fns, 20, 4, stream)
-        row["probe_mix_9r2w_GBps"] = round(11 * sb / np.median(tp) / 1e3, 1)
+        tp = per_launch_us(fns, est)
+        row["probe_mix_9r2w_GBps"] = round(11 * sb / tp / 1e3, 1)
         row["frac_of_mix_probe"] = round(row["GBps"] / row["probe_mix_9r2w_GBps"], 3)
         # where the workgroups ran: distinct (XCC, SE, SH, CU) places decoded from the hardware id registers
         x = sets[0]
@@ -519,16 +561,24 @@ def extras(result, tw, W, torch, np, stream, sets, fused_sets, algo_bytes, event
     # context only: the same launch when its inputs are still in the 256 MB Infinity Cache (as they
     # would be right after the kernels that produce them); one buffer set, no rotation
     for b in (32, 256):
-        t = event_times(fused_fns(sets[:1], b), 40, 8, stream)
-        budgets[str(b)]["inputs_in_infinity_cache_GBps"] = round(nbytes / np.median(t) / 1e3, 1)
-    t = event_times(fused_fns(sets, tw.CU_SHARED), 60, 8, stream)
-    budgets["shared"] = {"us": round(float(np.median(t)), 1), "GBps": round(nbytes / np.median(t) / 1e3, 1),
-                         "frac_hbm_peak": round(nbytes / np.median(t) / 1e3 / HBM_PEAK_GBS, 4),
+        t = per_launch_us(fused_fns(sets[:1], b), nbytes / (min(b, 110) * 50e3))
+        budgets[str(b)]["inputs_in_infinity_cache_GBps"] = round(nbytes / t / 1e3, 1)
+    t = per_launch_us(fused_fns(sets, tw.CU_SHARED), 35.0)
+    t_pair = float(np.median(event_times(fused_fns(sets, tw.CU_SHARED), 30, 4, stream)))
+    budgets["shared"] = {"us": round(t, 1), "GBps": round(nbytes / t / 1e3, 1),
+                         "frac_hbm_peak": round(nbytes / t / 1e3 / HBM_PEAK_GBS, 4),
+                         "single_launch_event_pair_us": round(t_pair, 1),
                          "note": "cu_budget=TW_CU_SHARED run alone: 256-thread workgroups on every CU"}
     result["budgets"] = {"workload": WORKLOAD, "per_budget": budgets,
+                         "timing": "us = median per-launch time over trains of 10 back-to-back launches on rotating "
+                                   "buffer sets, one HIP event pair per train (agrees with the profiler's kernel "
+                                   "trace); single_launch_event_pair_us = an event pair around every launch, which "
+                                   "reads ~2 us more",
                          "note": "probe_read = one stream read; probe_mix_9r2w = 9 streams read + 2 written with "
                                  "the fused kernel's launch shape and access pattern but no arithmetic: the "
-                                 "ceiling that this many compute units allow"}
+                                 "ceiling that this many compute units allow. A budget of 256 (every compute "
+                                 "unit) is a whole-device launch: at this size it takes the small workgroups of "
+                                 "the shared mode"}
     del srcs, dsts
     torch.cuda.empty_cache()
 
@@ -537,8 +587,9 @@ def extras(result, tw, W, torch, np, stream, sets, fused_sets, algo_bytes, event
     nb2 = algo_bytes(s2[0])
     c2 = {}
     for b in (8, 16, 32, 256):
-        t = event_times(fused_fns(s2, b), 60, 8, stream)
-        c2[str(b)] = {"us": round(float(np.median(t)), 1), "GBps": round(nb2 / np.median(t) / 1e3, 1)}
+        t = per_launch_us(fused_fns(s2, b), nb2 / (min(b, 110) * 50e3))
+        c2[str(b)] = {"us": round(t, 1), "GBps": round(nb2 / t / 1e3, 1),
+                      "frac_hbm_peak": round(nb2 / t / 1e3 / HBM_PEAK_GBS, 4)}
     result["config2_8b_tp2"] = c2
 
     # what the single pass saves: the same step as "all-reduce to bf16, then residual add + RMSNorm
@@ -550,8 +601,8 @@ def extras(result, tw, W, torch, np, stream, sets, fused_sets, algo_bytes, event
                                                                  out=x["out"], residual_out=x["res_out"],
                                                                  sum_scratch=sc, stream=stream))
                for x, sc in zip(ss, scr)]
-        t_u = float(np.median(event_times(unf, 60, 8, stream)))
-        t_f = float(np.median(event_times(fused_fns(ss, 0), 60, 8, stream)))
+        t_u = per_launch_us(unf, 50.0)
+        t_f = per_launch_us(fused_fns(ss, 0), 35.0)
         P_, H_, N_ = ss[0]["P"], ss[0]["H"], ss[0]["N"]
         abl[name] = {"fused_us": round(t_f, 1), "unfused_us": round(t_u, 1), "speedup": round(t_u / t_f, 3),
                      "bytes_ratio_unfused_over_fused": round((P_ + 6) / (P_ + 3), 3),
@@ -772,7 +823,7 @@ def extras(result, tw, W, torch, np, stream, sets, fused_sets, algo_bytes, event
     }
     del X1, W1, W2, parts, resid, out, res_out, Y
     torch.cuda.empty_cache()
-    budget_grid(result, tw, W, torch, np, stream, event_times, device_drawn_sets)
+    budget_grid(result, tw, W, torch, np, stream, train_times, device_drawn_sets)
     policy_table(result, tw, W, torch, np, stream, comm, interleaved_medians, gpu)
     decode_trains(result, tw, W, torch, np, stream, gpu)
     result["streams"] = {"second_streams_checked_with": "tw_streams_overlap", "torch_streams_tried": _streams_tried[0],
@@ -780,7 +831,7 @@ def extras(result, tw, W, torch, np, stream, sets, fused_sets, algo_bytes, event
                                  "split or overlapped schedule here was checked to run side by side with the first"}
 
 
-def budget_grid(result, tw, W, torch, np, stream, event_times, device_drawn_sets):
+def budget_grid(result, tw, W, torch, np, stream, train_times, device_drawn_sets):
     """The analogue of the paper's Fig. 9 / Fig. 22 (latency against the number of SMs, per sequence
     length): the fused kernel's rate per CU budget, per token count, with the smallest budget that reaches
     the plateau and the smallest that reaches 70 % of the HBM peak."""
@@ -794,11 +845,12 @@ def budget_grid(result, tw, W, torch, np, stream, event_times, device_drawn_sets
         row = {}
         for b in budgets + (tw.CU_SHARED,):
             est_us = per_set / (min(b if b > 0 else 256, 110) * 50e3)      # ~50 GB/s per CU, ~5.5 TB/s at most
-            iters = int(max(6, min(40, 40e3 / est_us)))
+            length = int(max(2, min(10, 4000.0 / est_us)))
+            trains = int(max(3, min(10, 20e3 / (est_us * length))))
             fns = [tw.prepare_reduce_add_rmsnorm(x["partials"], x["residual"], x["weight"], x["eps"], cu_budget=b,
                                                  out=x["out"], residual_out=x["res_out"], stream=stream)[0]
                    for x in ss]
-            t = float(np.median(event_times(fns, iters, 3, stream)))
+            t = float(np.median(train_times(fns, trains, length, 3, stream)))
             row["shared" if b == tw.CU_SHARED else str(b)] = {"us": round(t, 1), "GBps": round(per_set / t / 1e3, 1)}
         best = max(v["GBps"] for k_, v in row.items() if k_ != "shared")
         plateau = next(b for b in budgets if row[str(b)]["GBps"] >= 0.95 * best)
@@ -810,7 +862,7 @@ def budget_grid(result, tw, W, torch, np, stream, event_times, device_drawn_sets
         torch.cuda.empty_cache()
     result["budget_grid"] = {
         "workload": "H=8192, P=8, value distributions of c3 without the outliers, drawn on the GPU; rotating "
-                    "buffer sets of > 600 MB in all",
+                    "buffer sets of > 600 MB in all; per-launch time from trains of back-to-back launches",
         "per_token_count": grid,
         "note": "plateau = smallest budget within 5 % of the best budget's rate; min_budget_for_70pct = smallest "
                 "budget at or above 5600 GB/s (null: none reaches it). In the paper 8 SMs are close to optimal at "
@@ -935,7 +987,7 @@ def decode_trains(result, tw, W, torch, np, stream, gpu):
                 "HIP events around the train"}
 
 
-def ceiling_sweep(tw, torch, np, stream, event_times):
+def ceiling_sweep(tw, torch, np, stream, train_times):
     """What one compute unit can pull from / push to HBM, and what it does not depend on: budgets x
     workgroup sizes x accesses in flight for a read-only and a copy stream, budgets x workgroup sizes for
     the fused kernel's own mix (9 streams read, 2 written). One workgroup per compute unit throughout."""
@@ -956,7 +1008,7 @@ def ceiling_sweep(tw, torch, np, stream, event_times):
                     fns = [(lambda i=i: tw.hbm_probe_shaped(srcs[i], dsts[i], nbytes, mode, cu_budget=b,
                                                             threads=threads, in_flight=depth, stream=stream))
                            for i in range(4)]
-                    t = float(np.median(event_times(fns, 8, 2, stream)))
+                    t = float(np.median(train_times(fns, 3, 4, 2, stream)))
                     moved = nbytes * (2 if mode == tw.PROBE_COPY else 1)
                     row["GBps_per_cu_b%d" % b] = round(moved / t / 1e3 / b, 1)
                 table.append(row)
@@ -969,7 +1021,7 @@ def ceiling_sweep(tw, torch, np, stream, event_times):
             per = min(sb, ((b * 2) << 20) // 16384 * 16384)
             fns = [(lambda i=i: tw.hbm_probe_mixed_shaped(srcs[i], dsts[i], per, 9, 2, cu_budget=b, threads=threads,
                                                           stream=stream)) for i in range(4)]
-            t = float(np.median(event_times(fns, 8, 2, stream)))
+            t = float(np.median(train_times(fns, 3, 4, 2, stream)))
             row["GBps_per_cu_b%d" % b] = round(11 * per / t / 1e3 / b, 1)
         table.append(row)
     best = {}
@@ -981,8 +1033,8 @@ def ceiling_sweep(tw, torch, np, stream, event_times):
                       "needed_for_70pct_of_hbm_peak_in_32_cus_GBps_per_cu": round(0.7 * HBM_PEAK_GBS / 32, 1),
                       "note": "GB/s per compute unit (copy and mix: bytes read + bytes written); one workgroup per "
                               "compute unit (each requests 96 KiB of LDS); buffers of 192 MiB rotated four ways, so "
-                              "nothing is served from the 256 MB Infinity Cache; medians of 8 HIP-event timed "
-                              "launches"}))
+                              "nothing is served from the 256 MB Infinity Cache; per-launch time from trains of 4 "
+                              "back-to-back launches, median of 3"}))
 
 
 def cpu_baseline(W, np):
