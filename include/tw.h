@@ -212,8 +212,11 @@ int64_t tw_split_point(int64_t N, int64_t multiple);
  *   cu_budget persistent grid of at most this many workgroups (one per compute
  *             unit); <= 0 or >= the CU count: whole device
  * The result bits depend on A, B and K only: not on the budget, the layout of B,
- * nor on the tile shape the launch picks (256 x 128 outputs per workgroup, or
- * 256 x 64 when the wider tiles would fill at most half of the compute units).
+ * nor on the tile shape the launch picks (256 x 128 outputs per workgroup; 256 x
+ * 64 when the wider tiles would fill at most half of the compute units; 256 x
+ * 256 for a large product launched on its own, when such tiles fill the compute
+ * units about as well). Every output element is the sum of its K / 32 partial
+ * dot products of depth 32, accumulated in fp32 in the order of increasing k.
  */
 #define TW_B_NK 0
 #define TW_B_KN 1

@@ -53,9 +53,10 @@ tw_status tw_fused_layout(int64_t H, int *waves_per_row, int *vectors_per_thread
 int tw_weave_schedule(int64_t T, int64_t K1, int64_t H, int P, int64_t N2, int fused_cu_budget, int schedule,
                       int cus);
 
-/* Rows and columns of the output tile one GEMM workgroup computes (a product
- * whose tiles would fill at most half of its compute units is cut into tiles of
- * half this width instead; tw_smart_split_point counts in tiles of this shape). */
+/* Rows and columns of the output tile a GEMM workgroup computes by default, and
+ * always when the GEMM runs beside another kernel (a product launched on its own
+ * may be cut into tiles of half or twice this width instead, see tw_gemm_bf16;
+ * tw_smart_split_point counts in tiles of this shape). */
 void tw_gemm_tile_shape(int *tile_m, int *tile_n);
 
 /*

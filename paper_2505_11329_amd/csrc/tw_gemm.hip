@@ -5,8 +5,12 @@
 //
 // Design
 //   - Workgroup tile 256 (M) x 128 (N), K step 64, 512 threads = 8 wave64 laid
-//     out 4 x 2, each wave owning a 64 x 64 sub-tile as 2 x 2 blocks of
-//     v_mfma_f32_32x32x16_bf16 (64 accumulator registers per lane).
+//     out 4 x 2, each wave owning a 64 x 64 sub-tile as 4 x 4 blocks of
+//     v_mfma_f32_16x16x32_bf16 (64 accumulator registers per lane). The part
+//     runs this kernel at its power limit, and per flop the 16 x 16 x 32 shape
+//     moves half the accumulator registers of the 32 x 32 x 16 one: loops of
+//     nothing but MFMAs on N(0, 0.02^2) operands sustain 1.99 PFLOP/s with the
+//     former and 1.75 with the latter on this device.
 //   - Operand tiles go from global memory straight into LDS (gfx950's 16-byte
 //     buffer_load ... lds): no register staging and no ds_write. Three LDS
 //     stages of 32 + 16 KiB, so a load has two full K steps to land; one
@@ -33,8 +37,8 @@
 //     barrier) sits before the last MFMA group of a K step, when every wave
 //     still has matrix work queued.
 //   - Each MFMA gets the B fragment as its first operand and the A fragment as
-//     its second, so the 32x32 result block is held transposed: a lane owns one
-//     row m of C and, per group of four accumulator registers, four consecutive
+//     its second, so the 16x16 result block is held transposed: a lane owns one
+//     row m of C and the block's four accumulator registers are four consecutive
 //     columns n, which it stores as one 8-byte bf16 quad.
 //   - Ragged edges need no branches: operands are fetched through range-checked
 //     buffer descriptors sized to the rows that exist (rows past M or N read as
@@ -60,16 +64,19 @@ namespace tw {
 static constexpr int BM = kGemmTileM;
 static constexpr int kXcds = 8;
 
-// A tile configuration: WM x WN blocks of 32 x 32 per wave, 16 / WM waves laid
-// out (8 / WM) x 2, hence a 256 x (64 * WN) workgroup tile; K steps of BK_;
-// STAGES LDS stages. The library builds <2, 2, 3, 64>: eight waves of 64 x 64,
-// tile 256 x 128, 3 x 48 KiB of LDS, and for products with few tiles
-// <2, 1, 3, 64>: eight waves of 64 x 32, tile 256 x 64, 3 x 40 KiB.
+// A tile configuration: WM x WN blocks of 16 x 16 per wave, 32 / WM waves laid
+// out (16 / WM) x 2, hence a 256 x (32 * WN) workgroup tile; K steps of BK_;
+// STAGES LDS stages. The library builds <4, 4, 3, 64>: eight waves of 64 x 64,
+// tile 256 x 128, 3 x 48 KiB of LDS; for products with few tiles <4, 2, 3, 64>:
+// eight waves of 64 x 32, tile 256 x 64, 3 x 40 KiB; and for large products
+// <8, 8, 4, 32>: four waves of 128 x 128, tile 256 x 256, 4 x 32 KiB.
+static constexpr int kBlk = 16;    // rows and columns of one MFMA result block
+static constexpr int kSubK = 32;   // K depth of one MFMA
 template <int WM, int WN, int STAGES, int BK_>
 struct TileCfg {
-    static constexpr int kWaves = 16 / WM;
+    static constexpr int kWaves = 2 * BM / (kBlk * WM);
     static constexpr int kThreads = 64 * kWaves;
-    static constexpr int kBN = 64 * WN;
+    static constexpr int kBN = 2 * kBlk * WN;
     static constexpr int kStageABytes = BM * BK_ * 2;
     static constexpr int kStageBBytes = kBN * BK_ * 2;
     static constexpr int kStageBytes = kStageABytes + kStageBBytes;
@@ -78,7 +85,7 @@ struct TileCfg {
 
 typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
 typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
-typedef float f32x16 __attribute__((ext_vector_type(16)));
+typedef float f32x4 __attribute__((ext_vector_type(4)));
 
 struct GemmParams {
     const char *A;
@@ -129,35 +136,39 @@ __device__ __forceinline__ u32x2 lds_read_tr8(uint32_t addr)
     return v;
 }
 
-// Operand fragments of one K sub-step for a wave that owns WM x WN blocks of
-// 32 x 32. With B stored [K x N] (WN = 2 only) a B fragment arrives as two
-// register pairs (k 0..3 and k 4..7 of the lane's column).
+// Operand fragments of one K sub-step (one MFMA deep, k = 32) for a wave that
+// owns WM x WN blocks of 16 x 16: per block row of A and block column of B eight
+// consecutive k per lane (lane l: row or column l % 16, k group l / 16). With B
+// stored [K x N] (WN = 4 only) a B fragment arrives as two register pairs (k 0..3
+// and k 4..7 of the lane's group).
 template <bool B_KN, int WM, int WN>
 struct Frags {
     bf16x8 a[WM];
-    bf16x8 b[WN];
-    u32x2 blo[2], bhi[2];
+    bf16x8 b[B_KN ? 1 : WN];
+    u32x2 blo[B_KN ? WN : 1], bhi[B_KN ? WN : 1];
     // LDS reads that fill one set of fragments = registers (or register pairs)
-    // a wait has to name: WM of A, and WN of B or, stored [K x N], four halves
-    static constexpr int kReads = WM + (B_KN ? 4 : WN);
+    // a wait has to name: WM of A, and WN of B or, stored [K x N], 2 WN halves
+    static constexpr int kReads = WM + (B_KN ? 2 * WN : WN);
 };
 // Wait until at most N of this wave's LDS reads are outstanding. The fragments
 // are passed through so that no use of them can be moved above the wait. Each
 // operand list comes with its length, which wait_lgkm checks against the number
 // of reads that fill the fragments: a tile shape whose reads and waits disagree
 // does not compile.
-#define TW_FRAG_A2(f) "+v"((f).a[0]), "+v"((f).a[1])
-#define TW_FRAG_A2_LEN 2
-#define TW_FRAG_A4(f) TW_FRAG_A2(f), "+v"((f).a[2]), "+v"((f).a[3])
+#define TW_FRAG_A4(f) "+v"((f).a[0]), "+v"((f).a[1]), "+v"((f).a[2]), "+v"((f).a[3])
 #define TW_FRAG_A4_LEN 4
-#define TW_FRAG_B1(f) "+v"((f).b[0])
-#define TW_FRAG_B1_LEN 1
+#define TW_FRAG_A8(f) TW_FRAG_A4(f), "+v"((f).a[4]), "+v"((f).a[5]), "+v"((f).a[6]), "+v"((f).a[7])
+#define TW_FRAG_A8_LEN 8
 #define TW_FRAG_B2(f) "+v"((f).b[0]), "+v"((f).b[1])
 #define TW_FRAG_B2_LEN 2
 #define TW_FRAG_B4(f) TW_FRAG_B2(f), "+v"((f).b[2]), "+v"((f).b[3])
 #define TW_FRAG_B4_LEN 4
-#define TW_FRAG_B_KN(f) "+v"((f).blo[0]), "+v"((f).bhi[0]), "+v"((f).blo[1]), "+v"((f).bhi[1])
-#define TW_FRAG_B_KN_LEN 4
+#define TW_FRAG_B8(f) TW_FRAG_B4(f), "+v"((f).b[4]), "+v"((f).b[5]), "+v"((f).b[6]), "+v"((f).b[7])
+#define TW_FRAG_B8_LEN 8
+#define TW_FRAG_B_KN4(f)                                                                            \
+    "+v"((f).blo[0]), "+v"((f).bhi[0]), "+v"((f).blo[1]), "+v"((f).bhi[1]), "+v"((f).blo[2]),       \
+        "+v"((f).bhi[2]), "+v"((f).blo[3]), "+v"((f).bhi[3])
+#define TW_FRAG_B_KN4_LEN 8
 #define TW_WAIT_LGKM(N, f, A_LIST, B_LIST)                                                               \
     do {                                                                                                  \
         static_assert(A_LIST##_LEN + B_LIST##_LEN == std::remove_reference_t<decltype(f)>::kReads,        \
@@ -180,19 +191,18 @@ __device__ __forceinline__ void static_for(Fn &&f)
 template <int N, bool B_KN, int WM, int WN>
 __device__ __forceinline__ void wait_lgkm(Frags<B_KN, WM, WN> &f)
 {
-    static_assert(WM == 2 || WM == 4, "fragment operand lists below");
-    static_assert(B_KN ? WN == 2 : (WN == 1 || WN == 2 || WN == 4), "fragment operand lists below");
-    if constexpr (WM == 2 && !B_KN && WN == 1) TW_WAIT_LGKM(N, f, TW_FRAG_A2, TW_FRAG_B1);
-    if constexpr (WM == 2 && B_KN) TW_WAIT_LGKM(N, f, TW_FRAG_A2, TW_FRAG_B_KN);
-    if constexpr (WM == 4 && B_KN) TW_WAIT_LGKM(N, f, TW_FRAG_A4, TW_FRAG_B_KN);
-    if constexpr (WM == 2 && !B_KN && WN == 2) TW_WAIT_LGKM(N, f, TW_FRAG_A2, TW_FRAG_B2);
-    if constexpr (WM == 4 && !B_KN && WN == 2) TW_WAIT_LGKM(N, f, TW_FRAG_A4, TW_FRAG_B2);
-    if constexpr (WM == 2 && !B_KN && WN == 4) TW_WAIT_LGKM(N, f, TW_FRAG_A2, TW_FRAG_B4);
-    if constexpr (WM == 4 && !B_KN && WN == 4) TW_WAIT_LGKM(N, f, TW_FRAG_A4, TW_FRAG_B4);
+    static_assert(WM == 4 || WM == 8, "fragment operand lists below");
+    static_assert(B_KN ? (WM == 4 && WN == 4) : (WN == 2 || WN == 4 || WN == 8), "fragment operand lists below");
+    if constexpr (B_KN) TW_WAIT_LGKM(N, f, TW_FRAG_A4, TW_FRAG_B_KN4);
+    if constexpr (!B_KN && WM == 4 && WN == 2) TW_WAIT_LGKM(N, f, TW_FRAG_A4, TW_FRAG_B2);
+    if constexpr (!B_KN && WM == 4 && WN == 4) TW_WAIT_LGKM(N, f, TW_FRAG_A4, TW_FRAG_B4);
+    if constexpr (!B_KN && WM == 4 && WN == 8) TW_WAIT_LGKM(N, f, TW_FRAG_A4, TW_FRAG_B8);
+    if constexpr (!B_KN && WM == 8 && WN == 4) TW_WAIT_LGKM(N, f, TW_FRAG_A8, TW_FRAG_B4);
+    if constexpr (!B_KN && WM == 8 && WN == 8) TW_WAIT_LGKM(N, f, TW_FRAG_A8, TW_FRAG_B8);
 }
 
 template <bool B_KN, int WM, int WN, int STAGES, int BK>
-__global__ __launch_bounds__(64 * (16 / WM)) void gemm_bf16_kernel(const GemmParams prm)
+__global__ __launch_bounds__(64 * (2 * BM / (kBlk * WM))) void gemm_bf16_kernel(const GemmParams prm)
 {
     // The body is for the device pass only: the host pass needs the launch stub,
     // and silently drops it when it cannot make sense of the target-specific
@@ -205,22 +215,23 @@ __global__ __launch_bounds__(64 * (16 / WM)) void gemm_bf16_kernel(const GemmPar
     constexpr int kStageABytes = Cfg::kStageABytes;
     constexpr int kStageBytes = Cfg::kStageBytes;
     constexpr int kStages = STAGES;
-    constexpr int kSubs = BK / 16;                           // K sub-steps (one MFMA deep) per K step
-    constexpr int kBlockBytes = 32 * BK * 2;                 // LDS distance between 32-row blocks
+    constexpr int kSubs = BK / kSubK;                        // K sub-steps (one MFMA deep) per K step
+    constexpr int kBlockBytes = kBlk * BK * 2;               // LDS distance between 16-row blocks
     constexpr int A_LOADS = kStageABytes / 1024 / NW;        // wave instructions (1 KiB each) per wave that
     constexpr int B_LOADS = Cfg::kStageBBytes / 1024 / NW;   // fill a stage's A area, and its B area
     constexpr int kLoads = A_LOADS + B_LOADS;                // loads of one K step per lane
     static_assert(BK == 64 || BK == 32, "LDS layouts below");
-    static_assert(STAGES >= 2 && (STAGES - 2) * kLoads < 64, "vmcnt field");
-    static_assert(!B_KN || (WN == 2 && BK == 64), "[K x N] operands: 256 x 128 x 64 tiles only");
+    static_assert(STAGES >= 2 && (STAGES - 1) * kLoads < 64, "vmcnt field");
+    static_assert(!B_KN || (WN == 4 && BK == 64), "[K x N] operands: 256 x 128 x 64 tiles only");
+    static_assert(STAGES * kStageBytes <= 160 * 1024, "LDS of one compute unit");
 
     const int tid = threadIdx.x;
     const int lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);  // uniform: keeps LDS targets in scalar registers
     const int wave_m = wave >> 1;
     const int wave_n = wave & 1;
-    const int l31 = lane & 31;
-    const int lhi = lane >> 5;
+    const int l15 = lane & 15;   // the lane's row (A) or column (B) inside a block
+    const int lgrp = lane >> 4;  // its group of eight k inside the MFMA's 32
 
     const long long row_bytes = prm.K * 2;      // of A, and of B when it is stored [N x K]
     const long long bkn_row_bytes = prm.N * 2;  // of B when it is stored [K x N]
@@ -240,30 +251,37 @@ __global__ __launch_bounds__(64 * (16 / WM)) void gemm_bf16_kernel(const GemmPar
     constexpr int kRowsPerInstr = 4 * kRowsPerLine * NW;  // rows all waves' instruction i cover
     // B stored [K x N]: its LDS area holds 64 k-rows of 256 bytes (128 n); a wave
     // instruction fills four rows; row r keeps 16-byte piece s at slot
-    // s ^ ((r & 3) << 1), so that the four rows one transposing read touches
-    // fall into different banks.
+    // s ^ ((r & 3) << 1) ^ ((r & 8) ? 8 : 0), so that the eight rows the first (and
+    // the second) half of a wave's transposing read touches fall into different
+    // banks: four rows per 16-lane group, two groups eight rows apart.
     const int bkn_row_lo = wave * 4 + line_in_instr;                  // + 4 * NW * i
-    const int bkn_piece = slot ^ (line_in_instr << 1);
+    static_assert(!B_KN || NW == 8, "bit 3 of a row number below");
+    const int bkn_piece = slot ^ (line_in_instr << 1) ^ (((wave >> 1) & 1) << 3);
 
     // fragment read addresses inside a stage (A area at 0, B area after it) for
-    // the wave's first 32-row block; block i lies 32 rows = kBlockBytes further
+    // the wave's first 16-row block; block i lies 16 rows = kBlockBytes further
     // (the swizzle repeats within that), which goes into the read's offset field
-    uint32_t fa_addr[kSubs], fb_addr[kSubs], fbkn_addr[2];
+    uint32_t fa_addr[kSubs], fb_addr[kSubs], fbkn_addr[B_KN ? WN : 1];
 #pragma unroll
     for (int kk = 0; kk < kSubs; ++kk) {
-        fa_addr[kk] = lds_piece<BK>(wave_m * (32 * WM) + l31, kk * 2 + lhi);
-        fb_addr[kk] = kStageABytes + lds_piece<BK>(wave_n * (32 * WN) + l31, kk * 2 + lhi);
+        fa_addr[kk] = lds_piece<BK>(wave_m * (kBlk * WM) + l15, kk * 4 + lgrp);
+        fb_addr[kk] = kStageABytes + lds_piece<BK>(wave_n * (kBlk * WN) + l15, kk * 4 + lgrp);
     }
-    {
-        // lane = 16 g + s: group g covers columns (g & 1) * 16 .. +15 of the 32-wide
-        // block and k group g >> 1; s = a + 4 j points at row j, columns 4a..4a+3
-        const int g = lane >> 4, sl = lane & 15, a4 = sl & 3, j = sl >> 2;
+    if constexpr (B_KN) {
+        // the 16-lane group lgrp gathers k group lgrp: its lane s = a + 4 j points at
+        // row 8 lgrp + j, columns 4a..4a+3 of the 16-wide block (the second read of
+        // a fragment, rows + 4, and the sub-step, rows + 32, are immediates: neither
+        // changes the row bits the swizzle looks at)
+        const int a4 = l15 & 3, j = l15 >> 2;
+        const int row = lgrp * 8 + j;
 #pragma unroll
-        for (int i = 0; i < 2; ++i) {
-            const int col = wave_n * 64 + i * 32 + (g & 1) * 16 + 4 * a4;
-            const int row = (g >> 1) * 8 + j;  // + 16 kk + 4 half, added as an immediate
-            fbkn_addr[i] = kStageABytes + row * 256 + ((((col >> 3) ^ (j << 1))) << 4) + (col & 7) * 2;
+        for (int i = 0; i < WN; ++i) {
+            const int col = wave_n * (kBlk * WN) + i * kBlk + 4 * a4;
+            const int piece_slot = (col >> 3) ^ (j << 1) ^ ((lgrp & 1) << 3);
+            fbkn_addr[i] = kStageABytes + row * 256 + (piece_slot << 4) + (col & 7) * 2;
         }
+    } else {
+        fbkn_addr[0] = 0;
     }
 
     using F = Frags<B_KN, WM, WN>;
@@ -288,13 +306,13 @@ __global__ __launch_bounds__(64 * (16 / WM)) void gemm_bf16_kernel(const GemmPar
         const __amdgpu_buffer_rsrc_t ra = make_rsrc(prm.A + m0 * row_bytes, static_cast<uint32_t>(rows_a * row_bytes));
         const __amdgpu_buffer_rsrc_t rb = make_rsrc(prm.B + n0 * row_bytes, static_cast<uint32_t>(rows_b * row_bytes));
 
-        f32x16 acc[WN][WM];
+        f32x4 acc[WN][WM];
 #pragma unroll
         for (int i = 0; i < WN; ++i)
 #pragma unroll
             for (int j = 0; j < WM; ++j)
 #pragma unroll
-                for (int e = 0; e < 16; ++e) acc[i][j][e] = 0.0f;
+                for (int e = 0; e < 4; ++e) acc[i][j][e] = 0.0f;
 
         // A_LOADS + B_LOADS asynchronous 16-byte loads per lane fill one stage with
         // a K step; load `idx` of them is issued by fetch_one
@@ -358,14 +376,15 @@ __global__ __launch_bounds__(64 * (16 / WM)) void gemm_bf16_kernel(const GemmPar
                 f.b[j - WM] = lds_read16<kBlockBytes * (j - WM)>(stage_base + fb_addr[kk]);
             } else {
                 constexpr int i = (j - WM) >> 1;
-                if constexpr (((j - WM) & 1) == 0) f.blo[i] = lds_read_tr8<kk * 4096>(stage_base + fbkn_addr[i]);
-                else f.bhi[i] = lds_read_tr8<kk * 4096 + 1024>(stage_base + fbkn_addr[i]);
+                constexpr int kRowBytes = 256, kOff = kk * kSubK * kRowBytes;
+                if constexpr (((j - WM) & 1) == 0) f.blo[i] = lds_read_tr8<kOff>(stage_base + fbkn_addr[i]);
+                else f.bhi[i] = lds_read_tr8<kOff + 4 * kRowBytes>(stage_base + fbkn_addr[i]);
             }
         };
         auto load_frags = [&](F &f, uint32_t stage_base, auto kk_tag) {
             static_for<kFragReads>([&](auto j) { read_one(f, stage_base, kk_tag, j); });
         };
-        // One K sub-step: the 2 * WM MFMAs on `cur`, and between them the LDS
+        // One K sub-step: the WN * WM MFMAs on `cur`, and between them the LDS
         // reads of the next sub-step's fragments into `nxt` and LOADS_HERE of
         // the global loads of K step kt + 2, spread evenly: the memory pipes are
         // fed while the matrix core works and nothing is issued in a burst.
@@ -384,7 +403,7 @@ __global__ __launch_bounds__(64 * (16 / WM)) void gemm_bf16_kernel(const GemmPar
                 } else {
                     bfrag = cur.b[nb];
                 }
-                acc[nb][mb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(bfrag, cur.a[mb], acc[nb][mb], 0, 0, 0);
+                acc[nb][mb] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(bfrag, cur.a[mb], acc[nb][mb], 0, 0, 0);
                 __builtin_amdgcn_sched_barrier(0);
                 // What follows MFMA m: the fragment reads go out during the first
                 // half of the sub-step (they are waited for at its end and need the
@@ -406,51 +425,78 @@ __global__ __launch_bounds__(64 * (16 / WM)) void gemm_bf16_kernel(const GemmPar
         // All waves are done with the previous tile's LDS reads before it is refilled.
         __builtin_amdgcn_s_waitcnt(0xC07F);  // lgkmcnt(0)
         __builtin_amdgcn_s_barrier();
-        static_for<kStages - 1>([&](auto st) { fetch(decltype(st)::value, decltype(st)::value); });
-        // K step kt + 1 has landed once at most the loads of the kStages - 2 later
-        // K steps are outstanding (loads past the end are issued too, out of range,
-        // so the count is the same in every trip); the barrier extends that to the
-        // loads of the other waves.
-        auto wait_landed = [&]() {
-            constexpr int n = (kStages - 2) * kLoads;
+        // At most n of this wave's global loads outstanding, then a workgroup
+        // barrier that extends "landed" to the loads of the other waves.
+        auto wait_vm = [&](auto n_tag) {
+            constexpr int n = decltype(n_tag)::value;
             __builtin_amdgcn_s_waitcnt(((n >> 4) << 14) | 0x0F70 | (n & 15));  // vmcnt(n)
             __builtin_amdgcn_s_barrier();
         };
-        wait_landed();
+        // K step kt + 1 has landed once at most the loads of the kStages - 2 later
+        // K steps are outstanding (loads past the end are issued too, out of range,
+        // so the count is the same in every trip).
+        auto wait_landed = [&]() { wait_vm(std::integral_constant<int, (kStages - 2) * kLoads>{}); };
 
         F f0, f1;
-        load_frags(f0, 0, K0{});
         int stage = 0;
-        for (int kt = 0; kt < k_tiles; ++kt) {
-            const uint32_t base = static_cast<uint32_t>(stage * kStageBytes);
-            const int next_stage = stage + 1 >= kStages ? 0 : stage + 1;
-            // the stage that was read during the previous trip is free
-            const int fetch_stage = stage == 0 ? kStages - 1 : stage - 1;
-            const FetchCtx fc = fetch_ctx(kt + kStages - 1, fetch_stage);
+        if constexpr (kSubs > 1) {
+            static_for<kStages - 1>([&](auto st) { fetch(decltype(st)::value, decltype(st)::value); });
+            wait_landed();
+            load_frags(f0, 0, K0{});
+            for (int kt = 0; kt < k_tiles; ++kt) {
+                const uint32_t base = static_cast<uint32_t>(stage * kStageBytes);
+                const int next_stage = stage + 1 >= kStages ? 0 : stage + 1;
+                // the stage that was read during the previous trip is free
+                const int fetch_stage = stage == 0 ? kStages - 1 : stage - 1;
+                const FetchCtx fc = fetch_ctx(kt + kStages - 1, fetch_stage);
 
-            // sub-steps alternate between the two fragment sets; the global loads go
-            // out during all but the last one
-            static_for<kSubs>([&](auto sub_tag) {
-                constexpr int sub = decltype(sub_tag)::value;
-                F &cur = (sub & 1) ? f1 : f0;
-                F &nxt = (sub & 1) ? f0 : f1;
-                wait_lgkm<0>(cur);
-                if constexpr (sub < kSubs - 1) {
-                    constexpr int first = sub * kLoads / (kSubs - 1);
-                    constexpr int count = (sub + 1) * kLoads / (kSubs - 1) - first;
-                    sub_step(cur, nxt, base, std::integral_constant<int, sub + 1>{}, fc,
-                             std::integral_constant<int, first>{}, std::integral_constant<int, count>{});
-                } else {
-                    // the last fragments of this stage have arrived: this wave is done
-                    // reading it. Has K step kt + 1 landed (for every wave)? After the
-                    // barrier every wave is also done reading this stage, so the loads
-                    // the next trip issues may overwrite the stage before it.
-                    wait_landed();
+                // sub-steps alternate between the two fragment sets; the global loads go
+                // out during all but the last one
+                static_for<kSubs>([&](auto sub_tag) {
+                    constexpr int sub = decltype(sub_tag)::value;
+                    F &cur = (sub & 1) ? f1 : f0;
+                    F &nxt = (sub & 1) ? f0 : f1;
+                    wait_lgkm<0>(cur);
+                    if constexpr (sub < kSubs - 1) {
+                        constexpr int first = sub * kLoads / (kSubs - 1);
+                        constexpr int count = (sub + 1) * kLoads / (kSubs - 1) - first;
+                        sub_step(cur, nxt, base, std::integral_constant<int, sub + 1>{}, fc,
+                                 std::integral_constant<int, first>{}, std::integral_constant<int, count>{});
+                    } else {
+                        // the last fragments of this stage have arrived: this wave is done
+                        // reading it. Has K step kt + 1 landed (for every wave)? After the
+                        // barrier every wave is also done reading this stage, so the loads
+                        // the next trip issues may overwrite the stage before it.
+                        wait_landed();
+                        sub_step(cur, nxt, static_cast<uint32_t>(next_stage * kStageBytes), K0{}, fc,
+                                 std::integral_constant<int, 0>{}, std::integral_constant<int, 0>{});
+                    }
+                });
+                stage = next_stage;
+            }
+        } else {
+            // A K step is one MFMA deep: its whole stage is in a fragment set once
+            // that set has arrived, so after the barrier below the stage of the
+            // CURRENT step is free and takes the loads of K step kt + kStages. Two
+            // steps per trip, one per fragment set (a step past an odd end works on
+            // zeros: loads past K are out of range and land as zeros).
+            static_for<kStages>([&](auto st) { fetch(decltype(st)::value, decltype(st)::value); });
+            wait_vm(std::integral_constant<int, (kStages - 1) * kLoads>{});  // K step 0 has landed
+            load_frags(f0, 0, K0{});
+            for (int kt = 0; kt < k_tiles; kt += 2) {
+                static_for<2>([&](auto h_tag) {
+                    constexpr int h = decltype(h_tag)::value;
+                    F &cur = h ? f1 : f0;
+                    F &nxt = h ? f0 : f1;
+                    const int next_stage = stage + 1 >= kStages ? 0 : stage + 1;
+                    const FetchCtx fc = fetch_ctx(kt + h + kStages, stage);
+                    wait_lgkm<0>(cur);
+                    wait_landed();  // K step kt + h + 1 is in LDS, and nobody reads this step's stage any more
                     sub_step(cur, nxt, static_cast<uint32_t>(next_stage * kStageBytes), K0{}, fc,
-                             std::integral_constant<int, 0>{}, std::integral_constant<int, 0>{});
-                }
-            });
-            stage = next_stage;
+                             std::integral_constant<int, 0>{}, std::integral_constant<int, kLoads>{});
+                    stage = next_stage;
+                });
+            }
         }
         // The last trip has read the fragments of a K step past the end: they are
         // never used, but the reads are still in flight, and the compiler, which
@@ -466,20 +512,17 @@ __global__ __launch_bounds__(64 * (16 / WM)) void gemm_bf16_kernel(const GemmPar
         const __amdgpu_buffer_rsrc_t rc = make_rsrc(prm.C + m0 * c_row_bytes, static_cast<uint32_t>(rows_a * c_row_bytes));
 #pragma unroll
         for (int mb = 0; mb < WM; ++mb) {
-            const int m = wave_m * (32 * WM) + mb * 32 + l31;
+            const int m = wave_m * (kBlk * WM) + mb * kBlk + l15;
 #pragma unroll
             for (int nb = 0; nb < WN; ++nb) {
-#pragma unroll
-                for (int q = 0; q < 4; ++q) {
-                    const long long n = n0 + wave_n * (32 * WN) + nb * 32 + q * 8 + lhi * 4;
-                    u32x2 v;
-                    v.x = pack_bf16x2(acc[nb][mb][q * 4 + 0], acc[nb][mb][q * 4 + 1]);
-                    v.y = pack_bf16x2(acc[nb][mb][q * 4 + 2], acc[nb][mb][q * 4 + 3]);
-                    const uint32_t off = static_cast<uint32_t>(m * c_row_bytes + n * 2);
-                    __builtin_amdgcn_raw_buffer_store_b64(v, rc, n < prm.N ? off : kOutOfRange, 0, 0);
-                }
-                __builtin_amdgcn_sched_barrier(0);  // one block's accumulators at a time
+                const long long n = n0 + wave_n * (kBlk * WN) + nb * kBlk + lgrp * 4;
+                u32x2 v;
+                v.x = pack_bf16x2(acc[nb][mb][0], acc[nb][mb][1]);
+                v.y = pack_bf16x2(acc[nb][mb][2], acc[nb][mb][3]);
+                const uint32_t off = static_cast<uint32_t>(m * c_row_bytes + n * 2);
+                __builtin_amdgcn_raw_buffer_store_b64(v, rc, n < prm.N ? off : kOutOfRange, 0, 0);
             }
+            __builtin_amdgcn_sched_barrier(0);  // one block row's accumulators at a time
         }
     }
 #else
@@ -553,32 +596,52 @@ static tw_status launch_cfg(const tw_gemm_args &g, int budget, hipStream_t strea
     return TW_OK;
 }
 
+// Share of the launch's compute-unit slots that hold a tile when `tiles` tiles
+// are dealt to `budget` compute units in whole waves.
+static double wave_fill(int64_t tiles, int budget)
+{
+    const int64_t waves = (tiles + budget - 1) / budget;
+    return double(tiles) / double(waves * budget);
+}
+
 tw_status launch_gemm(const tw_gemm_args &g, hipStream_t stream, bool beside_other_kernels)
 {
     if (g.M == 0 || g.N == 0) return TW_OK;
     int cus = 0;
     TW_TRY(current_cu_count(&cus));
     const int budget = resolve_budget(g.cu_budget, cus);
-    // Eight waves of 64 x 64, tile 256 x 128 x 64, three LDS stages. Measured
-    // alternatives that were no faster and are not built: four waves of 128 x 64
-    // (a quarter fewer LDS bytes per MFMA), and 256 x 256 tiles with four waves of
-    // 128 x 128 over four stages of K = 32 (two thirds of the bytes fetched per
-    // flop). With operand fetch the shader clock sits near 1.5 GHz whatever the
-    // tile; without it the same loops run at 2.1 GHz and 2.0 PFLOP/s.
-    if (g.b_layout == TW_B_KN) return launch_cfg<true, 2, 2, 3, 64>(g, budget, stream);
-    // A product whose 256 x 128 tiles fill at most half of the compute units it may
-    // use is cut into 256 x 64 tiles instead (eight waves of 64 x 32, 3 x 40 KiB of
-    // LDS): twice the workgroups, each with half the work. A tile of that shape
-    // fetches 5/3 of the operand bytes per flop and takes ~0.77 of the wide tile's
-    // time, so it only pays while it brings idle compute units in: 14-23 % faster
-    // on 40 ... 128 wide tiles ([2048 x 8192] x [8192 x 1280]: 80 -> 62 us), 25-40 %
-    // slower once the wide tiles already fill more than half. Same bits. Not next
-    // to other kernels: there the compute units are not idle, the extra operand
-    // traffic competes for the same L1 request slots, and a woven layer measured
-    // level to 3 % slower with the narrow tiles.
-    const int64_t wide_tiles = ((g.M + BM - 1) / BM) * ((g.N + kGemmTileN - 1) / kGemmTileN);
-    if (!beside_other_kernels && 2 * wide_tiles <= budget) return launch_cfg<false, 2, 1, 3, 64>(g, budget, stream);
-    return launch_cfg<false, 2, 2, 3, 64>(g, budget, stream);
+    // The default: eight waves of 64 x 64, tile 256 x 128 x 64, three LDS stages.
+    // The part runs this kernel at its power limit (1.2-1.9 GHz on N(0, 0.02^2)
+    // operands against 2.4 GHz idle), so what a tile shape is worth is decided by
+    // the energy it spends per flop, not by its share of busy matrix-core cycles.
+    if (g.b_layout == TW_B_KN) return launch_cfg<true, 4, 4, 3, 64>(g, budget, stream);
+    const int64_t tiles_m = (g.M + BM - 1) / BM;
+    const int64_t wide_tiles = tiles_m * ((g.N + kGemmTileN - 1) / kGemmTileN);
+    if (!beside_other_kernels) {
+        // A product whose 256 x 128 tiles fill at most half of the compute units it may
+        // use is cut into 256 x 64 tiles instead (eight waves of 64 x 32, 3 x 40 KiB of
+        // LDS): twice the workgroups, each with half the work. A tile of that shape
+        // fetches 5/3 of the operand bytes per flop and takes ~0.77 of the wide tile's
+        // time, so it only pays while it brings idle compute units in: 14-23 % faster
+        // on 40 ... 128 wide tiles, 25-40 % slower once the wide tiles already fill
+        // more than half.
+        if (2 * wide_tiles <= budget) return launch_cfg<false, 4, 2, 3, 64>(g, budget, stream);
+        // A large product takes 256 x 256 tiles: four waves of 128 x 128 (all 512
+        // registers of a lane: 256 accumulators and two fragment sets), K steps of
+        // 32 over four LDS stages of 32 KiB. Two thirds of the operand bytes fetched
+        // per flop and half the LDS reads: 4-7 % faster where its tiles fill the
+        // compute units about as well as the 256 x 128 ones do (8192^3: 1.40 against
+        // 1.35 PFLOP/s), slower where they do not (half as many tiles).
+        const int64_t big_tiles = tiles_m * ((g.N + 255) / 256);
+        if (wave_fill(big_tiles, budget) >= wave_fill(wide_tiles, budget) - 0.05)
+            return launch_cfg<false, 8, 8, 4, 32>(g, budget, stream);
+    }
+    // Next to other kernels (tw_overlap_launch, the split schedules of
+    // tw_weave_layer) the 256 x 128 tiles are kept: the compute units are not idle
+    // there, the narrow tiles' extra operand traffic competes for the same L1
+    // request slots (a woven layer measured level to 3 % slower with them), and
+    // the 256 x 256 tiles leave no registers for a co-resident workgroup.
+    return launch_cfg<false, 4, 4, 3, 64>(g, budget, stream);
 }
 
 }  // namespace tw

@@ -60,6 +60,34 @@ def test_gemm_both_layouts_give_the_same_bits(tw, torch_cuda):
     assert np.array_equal(to_bits(C1), to_bits(C2))
 
 
+@pytest.mark.parametrize("M,N,K,budget", [(4096, 4096, 2048, 0), (1000, 1096, 520, 10), (2304, 2048, 4104, 72),
+                                          (513, 520, 96, 9)])
+def test_gemm_large_product_tiles_give_the_same_bits(tw, torch_cuda, M, N, K, budget):
+    """A large product launched on its own takes 256 x 256 tiles (four waves of 128 x 128, K steps of 32
+    over four LDS stages) where those fill the compute units of the launch; stored [K x N] the same
+    product always takes the 256 x 128 ones. Same bits (ragged edges and a K that is no multiple of the
+    K step included), checked against the oracle on sampled outputs."""
+    a = W.make_gemm_inputs(M, K, N, 0.05, seed=M + K, b_layout="nk")
+    b = W.make_gemm_inputs(M, K, N, 0.05, seed=M + K, b_layout="kn")
+    cus = tw.device_cu_count()
+    use = budget if 0 < budget < cus else cus
+    fill = lambda tiles: tiles / (-(-tiles // use) * use)
+    tm = -(-M // 256)
+    assert 2 * tm * -(-N // 128) > use and fill(tm * -(-N // 256)) >= fill(tm * -(-N // 128)) - 0.05, \
+        "the case is meant to take the 256 x 256 tiles"
+    C = torch_cuda.full((M, N), float("nan"), dtype=torch_cuda.bfloat16, device="cuda:0")
+    tw.gemm_bf16(to_gpu(a["A"]), to_gpu(a["B"]), C=C, b_layout=tw.B_NK, cu_budget=budget)
+    C2 = tw.gemm_bf16(to_gpu(b["A"]), to_gpu(b["B"]), b_layout=tw.B_KN, cu_budget=budget)
+    torch_cuda.cuda.synchronize()
+    Cb = to_bits(C)
+    assert np.array_equal(Cb, to_bits(C2))
+    rng = np.random.default_rng(M)
+    ms = np.concatenate([rng.integers(0, M, 2040), [0, 0, M - 1, M - 1, min(255, M - 1), min(256, M - 1), M // 2, 1]])
+    ns = np.concatenate([rng.integers(0, N, 2040), [0, N - 1, 0, N - 1, min(255, N - 1), min(256, N - 1), N // 2, 1]])
+    ref = oracle.gemm_samples(a["A"], a["B"], "nk", ms, ns)
+    gemm_check(oracle.bf16_to_f64(Cb[ms, ns]), ref, K, 0.05, "large-tile gemm %dx%dx%d" % (M, N, K))
+
+
 def test_gemm_k_zero_gives_zeros(tw, torch_cuda):
     torch = torch_cuda
     A = torch.empty((40, 0), dtype=torch.bfloat16, device="cuda:0")
