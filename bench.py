@@ -363,14 +363,18 @@ def main():
                           "order": [o[0] for o in order]}))
         return
     if args.counters_run == "gemm":
-        # both tile shapes the library builds: the overlap demo's product takes 256 x 128 tiles, the
-        # MLP-side down projection of the same layer ([2048 x 8192] x [8192 x 1280], 80 wide tiles) 256 x 64
+        # the three tile shapes the library builds: the overlap demo's product takes 256 x 128 tiles, the
+        # MLP-side down projection of the same layer ([2048 x 8192] x [8192 x 1280], 80 wide tiles) 256 x 64,
+        # a large square product 256 x 256
         gc = W.CONFIGS["c5_overlap_tp8"]["gemm"]
-        shapes = [(gc["M"], gc["K"], gc["N"]), (gc["M"], gc["K"], 1280)]
+        shapes = [(gc["M"], gc["K"], gc["N"]), (gc["M"], gc["K"], 1280), (8192, 8192, 8192)]   # the last: 256 x 256
         for (M, K, N) in shapes:
-            g = W.make_gemm_inputs(M, K, N, gc["std"], 0, "nk")
-            A, B = gpu(g["A"]), gpu(g["B"])
+            gen = torch.Generator(device=dev)
+            gen.manual_seed(M + N)
+            A = torch.empty((M, K), dtype=torch.bfloat16, device=dev).normal_(0.0, gc["std"], generator=gen)
+            B = torch.empty((N, K), dtype=torch.bfloat16, device=dev).normal_(0.0, gc["std"], generator=gen)
             C = torch.empty((M, N), dtype=torch.bfloat16, device=dev)
+            torch.cuda.synchronize()
             for i in range(12):
                 tw.gemm_bf16(A, B, C=C, cu_budget=0, stream=stream)
             torch.cuda.synchronize()
@@ -767,6 +771,29 @@ def extras(result, tw, W, torch, np, stream, sets, fused_sets, algo_bytes, event
                 "caller's stream is the compute stream; the schedules take turns in bursts, in rotating order; makespans include fork and join",
     }
     del s5
+    torch.cuda.empty_cache()
+
+    # the GEMM stand-in on its own: the demo's product, the attention-side projection of a 4096-token batch
+    # (short K) and a large square product, against the dense bf16 MFMA peak
+    gem = {}
+    for (M_, N_, K_) in ((gc["M"], gc["N"], gc["K"]), (4096, 8192, 1024), (8192, 8192, 8192)):
+        gen = torch.Generator(device="cuda:0")
+        gen.manual_seed(M_ + K_)
+        A_ = torch.empty((M_, K_), dtype=torch.bfloat16, device="cuda:0").normal_(0.0, gc["std"], generator=gen)
+        B_ = torch.empty((N_, K_), dtype=torch.bfloat16, device="cuda:0").normal_(0.0, gc["std"], generator=gen)
+        C_ = torch.empty((M_, N_), dtype=torch.bfloat16, device="cuda:0")
+        torch.cuda.synchronize()
+        fl = 2.0 * M_ * N_ * K_
+        t = float(np.median(train_times([lambda: tw.gemm_bf16(A_, B_, C=C_, cu_budget=0, stream=stream)],
+                                        5, 4, 3, stream)))
+        gem["%dx%dx%d" % (M_, N_, K_)] = {"us": round(t, 1), "TFLOPs": round(fl / t / 1e6, 1),
+                                          "frac_mfma_peak": round(fl / t / 1e6 / MFMA_BF16_PEAK_TFLOPS, 4)}
+        del A_, B_, C_
+    result["gemm"] = {"per_shape_MxNxK": gem,
+                      "note": "tw_gemm_bf16 alone on the whole device, A and B ~ N(0, 0.02^2) drawn on the GPU, trains of "
+                              "4 launches; peak = 2500 TFLOP/s dense bf16. The part runs these at its power limit "
+                              "(1.2-1.9 GHz against 2.4 GHz idle): a loop of nothing but MFMAs on such operands "
+                              "sustains 1990 TFLOP/s"}
     torch.cuda.empty_cache()
 
     # one woven layer boundary (G1 -> fused -> G2), T = 4096 tokens, attention-side shapes of a 70B-class
