@@ -39,7 +39,7 @@ TRAFFIC_FROM_PROFILE = {
     (WORKLOAD, 32): {
         "profile": "profiles/fused_kernel_c3_70b_shard_tp8_budget32.md",
         "kernel": "tw::fused_kernel<8, 1, false>",
-        "fetched_KiB": 147653, "written_KiB": 32768,
+        "fetched_KiB": 147647, "written_KiB": 32768,
         "kernel_source_sha256_12": "4891af11f486",
     },
 }

@@ -286,9 +286,11 @@ tw_status tw_overlap_launch(const tw_fused_args *fused, const tw_gemm_args *gemm
  *       another stream, off the critical path; what overlaps with what is left
  *       to the hardware.
  *   TW_WEAVE_AUTO     chains when the fused kernel is not confined to a CU budget
- *       (shared mode or whole device) and the unsplit chain is estimated to take
- *       under 700 us, where the waits of the ordered schedule cost more than its
- *       stricter order gains; ordered otherwise.
+ *       (shared mode or whole device): on the block boundaries of a 70B-class
+ *       layer they are level to 13 % faster than the ordered schedule at 256 to
+ *       16384 tokens, with one exception of 2.5 %; ordered when it is confined,
+ *       because the GEMMs leave its compute units alone only while no two of them
+ *       overlap.
  * With split_row == 0 or == T the chain G1, F, G2 runs unsplit on stream_compute
  * alone (nothing overlaps, no events).
  * Results are bit-identical for every split_row and schedule.

@@ -242,26 +242,21 @@ static tw_gemm_args rows_of(const tw_gemm_args &g, int64_t r0, int64_t r1)
     return s;
 }
 
-static int64_t gemm_waves(int64_t rows, int64_t n_out, int64_t cus);
-
 // Which schedule a split layer boundary takes. The ordered schedule never lets
 // two GEMMs compete but puts three cross-stream waits (15-20 us each) on the
-// critical path; the chains put none there. Measured on MI355X over H = 8192
-// boundaries with K1 = 1024...3584, N2 = 1280...3584, P = 2, 4, 8 in shared mode:
-// chains are 2-14 % faster wherever the unsplit chain takes under ~700 us (T up
-// to 6144 here), from there on the ordered schedule is level or up to 4 % faster.
-// The estimate: GEMM waves of 256 x 128 tiles at 5 TFLOP/s per compute unit, the
-// fused rows at 5 TB/s.
-static bool takes_chains(const tw_layer_args &layer, const tw_gemm_args &g1, const tw_gemm_args &g2, int cus)
+// critical path; the chains put none there. Measured on MI355X in shared mode on
+// the two boundaries of a 70B-class layer (K1 = 1024, N2 = 3584 and K1 = 3584,
+// N2 = 1280; H = 8192, P = 8) for T = 256 ... 16384: the chains are level to 13 %
+// faster at every token count on the first and up to 8192 tokens on the second,
+// and 2.5 % slower only at 16384 tokens on the second (a narrow G2 that the
+// chains let compete with a long G1). A fused kernel confined to a CU budget
+// keeps the ordered schedule: the GEMMs' budget leaves its compute units free
+// only while no two GEMMs overlap.
+static bool takes_chains(const tw_layer_args &layer, int cus)
 {
     if (layer.schedule != TW_WEAVE_AUTO) return layer.schedule == TW_WEAVE_CHAINS;
     const tw_fused_args &f = layer.fused;
-    if (f.cu_budget > 0 && f.cu_budget < cus) return false;
-    auto gemm_us = [&](const tw_gemm_args &g) {
-        return double(gemm_waves(g.M, g.N, cus)) * 2.0 * kGemmTileM * kGemmTileN * double(g.K) / 5.0e6;
-    };
-    const double fused_us = double(f.N) * double(f.H) * 2.0 * double(f.P + 3) / 5.0e6;
-    return gemm_us(g1) + fused_us + gemm_us(g2) < 700.0;
+    return !(f.cu_budget > 0 && f.cu_budget < cus);
 }
 
 int tw_weave_schedule(int64_t T, int64_t K1, int64_t H, int P, int64_t N2, int fused_cu_budget, int schedule,
@@ -275,13 +270,7 @@ int tw_weave_schedule(int64_t T, int64_t K1, int64_t H, int P, int64_t N2, int f
     layer.fused.H = H;
     layer.fused.P = P;
     layer.fused.cu_budget = fused_cu_budget;
-    tw_gemm_args g1 = {}, g2 = {};
-    g1.M = g2.M = T;
-    g1.N = H;
-    g1.K = K1;
-    g2.N = N2;
-    g2.K = H;
-    return takes_chains(layer, g1, g2, cus) ? TW_WEAVE_CHAINS : TW_WEAVE_ORDERED;
+    return takes_chains(layer, cus) ? TW_WEAVE_CHAINS : TW_WEAVE_ORDERED;
 }
 
 tw_status tw_weave_layer(const tw_layer_args *layer, int64_t split_row, void *stream_compute,
@@ -349,7 +338,7 @@ tw_status tw_weave_layer(const tw_layer_args *layer, int64_t split_row, void *st
     }
     int cus = 0;
     TW_TRY(current_cu_count(&cus));
-    if (takes_chains(*layer, g1, g2, cus)) {
+    if (takes_chains(*layer, cus)) {
         // one chain per split; the second starts when the first split's G1 is done
         hipEvent_t g1a_done;
         TW_TRY(launch_gemm(rows_of(g1, cuts[0], cuts[1]), sx, true));
