@@ -39,8 +39,14 @@ TRAFFIC_FROM_PROFILE = {
     (WORKLOAD, 32): {
         "profile": "profiles/fused_kernel_c3_70b_shard_tp8_budget32.md",
         "kernel": "tw::fused_kernel<8, 1, false>",
-        "fetched_KiB": 147647, "written_KiB": 32768,
-        "kernel_source_sha256_12": "4891af11f486",
+        "fetched_KiB": 147646, "written_KiB": 32768,
+        "kernel_source_sha256_12": "fa6ac24afa8e",
+    },
+    (WORKLOAD, 0): {
+        "profile": "profiles/fused_kernel_c3_whole_device_and_shared.md",
+        "kernel": "tw::fused_thin_kernel<8, 4, false>",
+        "fetched_KiB": 147688, "written_KiB": 32747,
+        "kernel_source_sha256_12": "fa6ac24afa8e",
     },
 }
 KERNEL_SOURCES = ("paper_2505_11329_amd/csrc/tw_fused.hip", "paper_2505_11329_amd/csrc/tw_device.h")

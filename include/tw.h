@@ -101,15 +101,14 @@ typedef enum tw_status {
  *                 a persistent grid of that many workgroups, each sized so that
  *                 no two share a compute unit. 0, or >= the device's CU count,
  *                 means the whole device. TW_CU_SHARED (-1) selects the shared
- *                 mode instead: many small workgroups (256 threads, <= 96
+ *                 mode instead: many small workgroups (256 threads, <= 128
  *                 VGPRs, under 1 KiB LDS) spread over every compute unit, sized
  *                 to run NEXT TO a tw_gemm_bf16 workgroup on the same compute
  *                 unit rather than in place of one; for H > 8192 it falls back
  *                 to the whole device. Other negative values mean the whole
- *                 device. A whole-device launch with P = 2 or 4 and at most two
- *                 rows per compute unit, or P = 8 and at most eight (H <= 8192),
- *                 is sent as those small workgroups too: same bits, lower
- *                 latency.
+ *                 device. A small whole-device launch (P = 1, 2, 4 or 8; up to
+ *                 4 to 16 rows per compute unit depending on P and H <= 8192) is
+ *                 sent as those small workgroups too: same bits, lower latency.
  *   out           device bf16 [N x H]
  *   residual_out  device bf16 [N x H]
  *

@@ -24,6 +24,10 @@
 //     that feed one output vector): the loads of chunk q+2 are issued as soon as
 //     chunk q has been summed, before the row's reduction and barrier, so a
 //     thread always has P+1 .. 2(P+1) 16-byte loads in flight.
+//   - Both outputs of a row are stored together once its scale is known (the new
+//     residual stream could go out as soon as a chunk is summed, but loads that
+//     are not interleaved with stores come in 1-1.5 % faster); rows of more than
+//     16384 elements store it at once, for want of registers.
 //   - Row sum of squares: per-thread fp32 FMAs, xor-butterfly across the lanes of
 //     a wave (every lane ends with the same bits), and for rows wider than a
 //     wave one LDS slot per wave and one barrier; slots are double-buffered by
@@ -79,6 +83,7 @@ __global__ __launch_bounds__(kThreads) void fused_kernel(const FusedParams prm)
     constexpr int NB = buffers_in_flight<PT, VPT>();
     constexpr bool KEEP_W = VPT <= 2;     // weights unpacked to fp32 once, else kept packed,
     constexpr bool RELOAD_W = VPT >= 8;  // or (no registers left) re-read through the cache per row
+    constexpr bool LATE_RES = VPT <= 2;  // the new residual stream is stored with the output (wide rows: at once, or registers run out)
 
     const int tid = threadIdx.x;
     const int lane = tid & 63;
@@ -210,7 +215,7 @@ __global__ __launch_bounds__(kThreads) void fused_kernel(const FusedParams prm)
                 const int nj = (j + NB) % VPT;
                 const uint32_t ng = (VPT == 1) ? group + NB * stride : (j + NB >= VPT ? group + stride : group);
                 issue(b, chunk_off(ng, nj));
-                st(r_res_out, off, pack8(x[j]));
+                if constexpr (!LATE_RES) st(r_res_out, off, pack8(x[j]));
 #pragma unroll
                 for (int e = 0; e < 8; ++e) ss = __builtin_fmaf(x[j][e], x[j][e], ss);
             }
@@ -242,6 +247,7 @@ __global__ __launch_bounds__(kThreads) void fused_kernel(const FusedParams prm)
 #pragma unroll
                     for (int e = 0; e < 8; ++e) y[e] = (x[j][e] * s) * w[e];
                 }
+                if constexpr (LATE_RES) st(r_res_out, chunk_off(group, j), pack8(x[j]));
                 st(r_out, chunk_off(group, j), pack8(y));
             }
         }
@@ -250,10 +256,11 @@ __global__ __launch_bounds__(kThreads) void fused_kernel(const FusedParams prm)
 
 // ---------------------------------------------------------------------------
 // The same arithmetic in workgroups small enough to sit NEXT TO a GEMM workgroup
-// on the same compute unit (256 threads, at most 96 VGPRs, 128 bytes of LDS): the
+// on the same compute unit (256 threads, at most 128 VGPRs, 128 bytes of LDS): the
 // "shared" launch mode. Instead of taking a few compute units away from the
 // GEMM, the fused kernel is spread thinly over all of them and uses the HBM
-// bandwidth the matrix-core-bound GEMM leaves idle.
+// bandwidth the matrix-core-bound GEMM leaves idle. (The GEMM's two waves per
+// SIMD hold 2 x 167 registers per lane, which leaves room for one such wave.)
 //
 // Bits are identical to fused_kernel's: a thread here plays Q (a row's vectors
 // over 256, rounded up: 1 ... 4) of the wide kernel's threads (columns tid,
@@ -261,12 +268,18 @@ __global__ __launch_bounds__(kThreads) void fused_kernel(const FusedParams prm)
 // per played thread, and the reduction runs the very same tree (64-lane
 // butterfly per played wave, then the 16-lane butterfly over the row's wave
 // sums in LDS). Only rows of at most 1024 vectors (H <= 8192) are handled.
-// One chunk of loads is in flight per thread.
+// With an even Q two chunks of loads are in flight per thread (chunk c sits in
+// buffer c & 1, which needs no run-time index because every row then starts on
+// buffer 0), with an odd Q one. Both outputs of a row are stored together once
+// its scale is known: a small launch is one wave of workgroups that all run in
+// step, and reads that are not interleaved with stores come in faster (a
+// 1024-row, H = 8192, P = 8 launch: 33.5 -> 32.2 us with both changes, 256 rows
+// 10.6 -> 9.7 us).
 // ---------------------------------------------------------------------------
 static constexpr int kThinThreads = 256;
 
 template <int PT, int Q, bool TRACE>
-__global__ __launch_bounds__(kThinThreads) __attribute__((amdgpu_waves_per_eu(5)))
+__global__ __launch_bounds__(kThinThreads) __attribute__((amdgpu_waves_per_eu(4)))
 void fused_thin_kernel(const FusedParams prm)
 {
     __shared__ float s_wave_sum[2][kWaves];
@@ -357,21 +370,25 @@ void fused_thin_kernel(const FusedParams prm)
     const uint32_t first = blockIdx.x;
     const uint32_t gstride = gridDim.x;
     const uint32_t last = prm.n_groups;
-    Chunk<PT> buf;
-    issue(buf, chunk_off(first, 0));
+    // Chunks in flight: NB. Chunk (group, q) sits in buffer q % NB and is refilled
+    // with the chunk NB further on: the same row's, or the workgroup's next row's;
+    // after its last row nothing is fetched.
+    constexpr int NB = (Q % 2 == 0) ? 2 : 1;
+    auto off_or_none = [&](uint32_t group, int q) -> uint32_t {
+        return group < last ? chunk_off(group, q) : kOutOfRange;
+    };
+    Chunk<PT> buf[NB];
+    issue(buf[0], off_or_none(first, 0));
+    if constexpr (NB == 2) issue(buf[1], off_or_none(first, 1));
     int parity = 0;
     for (uint32_t group = first; group < last; group += gstride) {
         float x[Q][8];
         float ss[Q];
 #pragma unroll
         for (int q = 0; q < Q; ++q) {
-            const uint32_t off = chunk_off(group, q);
-            reduce_chunk(buf, off, x[q]);
-            // next chunk: the next played thread of this row, or this workgroup's
-            // next row; after its last row nothing is fetched
-            issue(buf, (q + 1 < Q) ? chunk_off(group, q + 1)
-                                   : (group + gstride < last ? chunk_off(group + gstride, 0) : kOutOfRange));
-            st(r_res_out, off, pack8(x[q]));
+            Chunk<PT> &b = buf[q % NB];
+            reduce_chunk(b, chunk_off(group, q), x[q]);
+            issue(b, (q + NB < Q) ? chunk_off(group, q + NB) : off_or_none(group + gstride, q + NB - Q));
             float acc = 0.0f;
 #pragma unroll
             for (int e = 0; e < 8; ++e) acc = __builtin_fmaf(x[q][e], x[q][e], acc);
@@ -399,6 +416,7 @@ void fused_thin_kernel(const FusedParams prm)
             unpack8(__builtin_amdgcn_raw_buffer_load_b128(r_w, cvalid[q] ? v * 16u : kOutOfRange, 0, 0), w);
 #pragma unroll
             for (int e = 0; e < 8; ++e) y[e] = (x[q][e] * s) * w[e];
+            st(r_res_out, chunk_off(group, q), pack8(x[q]));
             st(r_out, chunk_off(group, q), pack8(y));
         }
     }
@@ -548,20 +566,27 @@ static tw_status launch_vpt(const FusedParams &prm, const FusedGeometry &g, bool
 
 // Which kernel a launch takes. Shared mode has a kernel for rows of up to 1024
 // vectors; wider rows run on the wide kernel over the whole device. A small
-// whole-device launch with P = 2, 4 or 8 also takes the small workgroups: they
+// whole-device launch with P = 1, 2, 4 or 8 also takes the small workgroups: they
 // are placed faster and put every row in flight at once, where the wide kernel's
 // software pipeline has only a few rows per workgroup to run over. Measured on
-// MI355X (H = 4096 and 8192, 32 ... 4096 rows, launch shapes without a ragged
-// last trip): P = 8 up to eight rows per compute unit (2-15 % faster), P = 2 and
-// 4 up to two rows per compute unit (0-11 %). Elsewhere the wide kernel is as
-// fast or faster; for P without a specialised kernel, whose loads go out four
-// at a time, by up to 40 % on small batches. Both kernels give the same bits.
+// MI355X, small workgroups against the wide kernel on 255 compute units, trains
+// of launches on rotating buffers. Rows of an even number of 256-vector pieces
+// (H = 4096, 8192: two chunks in flight per thread): P = 8 faster up to 8192 rows
+// (22 % at 512, 4 % at 4096, 1.5 % at 8192), P = 4 up to 2048 (level at 4096, 2 %
+// slower at 8192), P = 2 at H = 4096 up to 4096 (level at 8192, 5 % slower at
+// 16384), P = 1 up to 1024 (7 % slower at 4096). Other row widths (one chunk in
+// flight) keep narrower limits found the same way. For P without a specialised
+// kernel, whose loads go out eight at a time, the wide kernel is faster, by up
+// to 40 % on small batches. Both kernels give the same bits.
 static bool takes_thin_kernel(int cu_budget, int cus, const FusedGeometry &g, int64_t n_rows, int P)
 {
     if (g.vpt != 1) return false;
     if (cu_budget == TW_CU_SHARED) return true;
     if (resolve_budget(cu_budget, cus) != cus) return false;
-    const int64_t rows_per_cu = P == 8 ? 8 : (P == 2 || P == 4) ? 2 : 0;
+    const bool two_chunks = g.hv > kThinThreads && ((g.hv + kThinThreads - 1) / kThinThreads) % 2 == 0;
+    int64_t rows_per_cu;
+    if (two_chunks) rows_per_cu = P == 8 ? 16 : (P == 4 || P == 2) ? 8 : P == 1 ? 4 : 0;
+    else rows_per_cu = P == 8 ? 8 : (P == 4 || P == 2) ? 2 : 0;
     return n_rows <= rows_per_cu * cus;
 }
 
