@@ -178,17 +178,23 @@ def test_split_waits_for_parent_and_joins(tw, torch_cuda):
 
 # ---- aliasing, special values, empty input ------------------------------------
 
-def test_in_place_residual_and_out_over_a_partial(tw, torch_cuda):
+@pytest.mark.parametrize("N,H,P", [(300, 4096, 4), (700, 8192, 8), (50, 6144, 3), (1000, 1024, 2), (2100, 8192, 1)])
+def test_in_place_residual_and_out_over_a_partial(tw, torch_cuda, N, H, P):
+    """The paper's in-place form in every launch mode: the residual stream updated in place and the output
+    written over one of the partials. Both kernels store a row's outputs only after all of its inputs have
+    been loaded by the very threads that store them, with loads of later rows already in flight."""
     torch = torch_cuda
-    d = small(300, 4096, 4, seed=3)
-    g = upload(d)
-    want = run(tw, torch, g, cu_budget=8)
-    g2 = upload(d)
-    out, res = tw.reduce_add_rmsnorm(g2["partials"], g2["residual"], g2["weight"], g2["eps"], cu_budget=8,
-                                     out=g2["partials"][1], residual_out=g2["residual"])
-    torch.cuda.synchronize()
-    assert out.data_ptr() == g2["partials"][1].data_ptr() and res.data_ptr() == g2["residual"].data_ptr()
-    assert np.array_equal(to_bits(out), want[0]) and np.array_equal(to_bits(res), want[1])
+    d = small(N, H, P, seed=3)
+    want = run(tw, torch, upload(d), cu_budget=8)
+    check_against_oracle(d, want[0], want[1], "in-place reference N=%d H=%d P=%d" % (N, H, P))
+    for budget in (8, 0, tw.CU_SHARED):
+        g2 = upload(d)
+        over = g2["partials"][P - 1]
+        out, res = tw.reduce_add_rmsnorm(g2["partials"], g2["residual"], g2["weight"], g2["eps"], cu_budget=budget,
+                                         out=over, residual_out=g2["residual"])
+        torch.cuda.synchronize()
+        assert out.data_ptr() == over.data_ptr() and res.data_ptr() == g2["residual"].data_ptr()
+        assert np.array_equal(to_bits(out), want[0]) and np.array_equal(to_bits(res), want[1]), budget
 
 
 def test_non_finite_values_stay_in_their_row(tw, torch_cuda):
