@@ -919,7 +919,7 @@ def policy_table(result, tw, W, torch, np, stream, comm, interleaved_medians, gp
         W1, W2 = rnd((H, K1), 0.02), rnd((N2, H), 0.02)
         thr = tw.split_threshold(K1, H, P, N2, cus)
         rows = []
-        for T in (256, 1024, 2048, 4096, 6144, 8192, 16384):
+        for T in (256, 1024, 2048, 4096, 6144, 8192, 12288, 16384, 32768):
             X1, resid = rnd((T, K1), 0.02), rnd((T, H), 1.0)
             parts = [rnd((T, H), 0.25) for _ in range(P)]
             o, r = torch.empty_like(resid), torch.empty_like(resid)
@@ -928,6 +928,9 @@ def policy_table(result, tw, W, torch, np, stream, comm, interleaved_medians, gp
             kw = dict(fused_cu_budget=tw.CU_SHARED, gemm_cu_budget=0, out=o, residual_out=r, Y=Y, parent=stream,
                       use_parent=True, join=True)
             k_smart = tw.smart_split_point(T, 64, [H, N2], cus, gemm_k=[K1, H])[0]
+            # the offline search of Algorithm 1, timed: unsplit, the smart row, and two offsets past the middle
+            k_tuned, tune_us = tw.weave_tune(X1, W1, parts, resid, weight, 1e-5, W2, stream, comm, offsets=(0, 256),
+                                             reps=5, out=o, residual_out=r, Y=Y)
             taken = []
 
             def never():
@@ -941,24 +944,35 @@ def policy_table(result, tw, W, torch, np, stream, comm, interleaved_medians, gp
             def policy():
                 with torch.cuda.stream(stream):
                     taken.append(tw.weave_layer_auto(X1, W1, parts, resid, weight, 1e-5, W2, stream, comm, **kw)[3])
+
+            def tuned():
+                with torch.cuda.stream(stream):
+                    tw.weave_layer(X1, W1, parts, resid, weight, 1e-5, W2, 0 if k_tuned == T else k_tuned, stream, comm,
+                                   **kw)
             iters = 8 if T <= 8192 else 5
-            med = interleaved_medians({"never": never, "always": always, "policy": policy}, rounds=4, iters=iters,
-                                      warm=2)
+            med = interleaved_medians({"never": never, "always": always, "policy": policy, "tuned": tuned}, rounds=4,
+                                      iters=iters, warm=2)
             best = min(med["never"], med["always"])
             rows.append({"T": T, "never_split_us": med["never"], "always_split_us": med["always"],
-                         "policy_us": med["policy"], "policy_split_row": taken[-1], "always_split_row": k_smart,
-                         "policy_over_best": round(med["policy"] / best, 3)})
+                         "policy_us": med["policy"], "tuned_us": med["tuned"], "policy_split_row": taken[-1],
+                         "tuned_split_row": k_tuned, "always_split_row": k_smart,
+                         "policy_over_best": round(med["policy"] / best, 3),
+                         "tuned_over_best": round(med["tuned"] / best, 3)})
             del X1, resid, parts, o, r, Y
             torch.cuda.empty_cache()
         out_[name] = {"boundary": "[Tx%d]x[%dx8192] -> fused H=8192 P=8 (shared mode) -> [Tx8192]x[8192x%d]"
                                   % (K1, K1, N2),
-                      "built_in_threshold_tokens": thr, "rows": rows,
-                      "worst_policy_over_best": max(r_["policy_over_best"] for r_ in rows)}
+                      "built_in_threshold_tokens": thr if thr < 2 ** 62 else "never",
+                      "rows": rows,
+                      "worst_policy_over_best": max(r_["policy_over_best"] for r_ in rows),
+                      "worst_tuned_over_best": max(r_["tuned_over_best"] for r_ in rows)}
     result["policy"] = {
         "per_boundary": out_,
         "note": "never = the chain G1, F, G2 unsplit on one stream; always = tw_weave_layer at the row "
                 "tw_smart_split_point picks, whatever T; policy = tw_weave_layer_auto (threshold from "
-                "tw_split_threshold, then the same row). policy_split_row == T means the policy did not split. "
+                "tw_split_threshold, then the same row); tuned = tw_weave_layer at the row tw_weave_tune reported for "
+                "this batch size beforehand (its timed search over: unsplit, the smart row, the middle, the middle "
+                "+ 256). A split row equal to T means no split. "
                 "Candidates take turns in bursts, in rotating order; medians of HIP-event timed calls"}
 
 

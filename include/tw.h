@@ -351,31 +351,42 @@ int64_t tw_smart_split_point(int64_t T, int64_t multiple, const int64_t *gemm_n_
  * Overlap"): split and overlap only when the batch has at least `threshold`
  * tokens, otherwise run the fused kernel unsplit. threshold <= 0 takes the
  * built-in default for MI355X, TW_DEFAULT_SPLIT_THRESHOLD, found by profiling
- * tw_weave_layer against the unsplit chain on the two block boundaries of a
- * 70B-class layer: the attention-side boundary breaks even at about 4K tokens,
- * the MLP-side one at about 7K, the two together at about 6K (the paper's own
- * thresholds, 1K and 4K tokens, are for its 8xH100 system). Returns 1 to split,
- * 0 not to. Host only.
+ * tw_weave_layer against the unsplit chain on the attention-side block boundary
+ * of a 70B-class layer, which breaks even between 6K and 8K tokens (the paper's
+ * own thresholds, 1K and 4K tokens, are for its 8xH100 system). Returns 1 to
+ * split, 0 not to. Host only.
  */
-#define TW_DEFAULT_SPLIT_THRESHOLD 6144
+#define TW_DEFAULT_SPLIT_THRESHOLD 8192
 int tw_should_split(int64_t num_tokens, int64_t threshold);
 
 /*
  * Token threshold for ONE block boundary G1 -> F -> G2 of the given sizes on a
  * device with `cus` compute units, for callers without a profile of their own
  * (the paper finds its thresholds by offline profiling, per model: Appendix A
- * "Selective Enabling of Splitting and Overlap"). The larger of two bounds,
+ * "Selective Enabling of Splitting and Overlap"; tw_weave_tune below is that
+ * profiling step). TW_NEVER_SPLIT when the GEMM after the fused step is shorter
+ * than the fused step itself (per token 2 H N2 flop at 1 PFLOP/s against
+ * (P + 3) * 2H bytes at 5 TB/s, i.e. N2 < 200 (P + 3)): the second split's fused
+ * kernel then has nothing to hide behind. Otherwise the larger of two bounds,
  * rounded up to whole GEMM row tiles:
  *   - the fused step of the whole batch, (P + 3) * 2H bytes per row at 5 TB/s,
- *     must take at least 140 us: below that the cross-stream waits and the
- *     contention between co-resident kernels cost more than hiding it gains;
+ *     must take at least 290 us: below that the cross-stream waits, the
+ *     contention between co-resident kernels and the smaller GEMM tiles of the
+ *     split schedule cost more than hiding it gains;
  *   - half the batch must still cut the narrower of the two GEMM outputs
  *     (min(H, N2) columns) into tiles for at least half of the compute units.
- * On MI355X this gives 4096 for [T x 1024] x [1024 x 8192] -> F(H = 8192, P = 8)
- * -> [T x 8192] x [8192 x 3584] and 6656 for the MLP-side boundary with K1 =
- * 3584, N2 = 1280; profiling puts the break-even points at about 4K and 7K.
+ * On MI355X this gives 8192 for [T x 1024] x [1024 x 8192] -> F(H = 8192, P = 8)
+ * -> [T x 8192] x [8192 x 3584] and TW_NEVER_SPLIT for the MLP-side boundary
+ * with K1 = 3584, N2 = 1280. Profiling agrees on the whole and not in every
+ * point: the first boundary gains 3 to 16 % from 8K to 24K tokens and loses 5 %
+ * at 32K, where the unsplit GEMMs happen to fill the device with whole waves of
+ * their largest tiles; the second stays within +2 and -6 % of break-even
+ * throughout. What a split gains here comes as much from how the tiles of the
+ * halves and of the whole batch fall on the compute units as from the overlap,
+ * which no single threshold captures: tw_weave_tune measures it.
  * Host only. Returns -1 on bad arguments (any size < 1).
  */
+#define TW_NEVER_SPLIT INT64_MAX
 int64_t tw_split_threshold(int64_t K1, int64_t H, int P, int64_t N2, int cus);
 
 /*
@@ -393,6 +404,34 @@ int64_t tw_split_threshold(int64_t K1, int64_t H, int P, int64_t N2, int cus);
  */
 tw_status tw_weave_layer_auto(const tw_layer_args *layer, int64_t threshold, int64_t multiple, void *stream_compute,
                               void *stream_comm, void *parent, int parent_is_set, int join, int64_t *split_row);
+
+/*
+ * The offline search of Algorithm 1 (Appendix A "Smart-Splitting") and of the
+ * thresholds of Appendix A "Selective Enabling of Splitting and Overlap", for one
+ * block boundary and one batch size: the paper takes both from timing candidate
+ * configurations before serving, not from a formula. Runs the boundary `layer`
+ * unsplit and woven at every candidate row, `reps` rounds with the candidates in
+ * rotating order after one untimed round, timed with events on stream_compute
+ * (fork and join included), and reports the medians:
+ *   us[0]      the unsplit chain
+ *   us[1]      the row tw_smart_split_point picks (multiple, widths {H, N2},
+ *              depths {K1, H}, the GEMMs' compute units)
+ *   us[2 + i]  row tw_split_point(T, multiple) + offsets[i], i < n_offsets
+ * A candidate row outside (0, T), or equal to an earlier candidate, is not run
+ * and reports a negative time. *best_row receives the fastest candidate's row, T
+ * when that is the unsplit chain: pass it to tw_weave_layer for batches of this
+ * size (callers keep such results per token count, as the paper's engine does).
+ * Unlike every other entry point this one WAITS for the device (it synchronises
+ * both streams before returning and between candidates) and creates and destroys
+ * two events: call it at start-up, never under stream capture. The layer's
+ * outputs are left as any tw_weave_layer call leaves them.
+ *   multiple <= 0: 64. offsets may be NULL with n_offsets == 0; n_offsets <= 16.
+ *   reps in 1 .. 64. us: host array of 2 + n_offsets floats. best_row, us: not NULL.
+ * Errors: TW_ERR_NULL, TW_ERR_SHAPE (reps, n_offsets out of range), and whatever
+ * tw_weave_layer returns for the layer; on error *best_row and us are unspecified.
+ */
+tw_status tw_weave_tune(const tw_layer_args *layer, int64_t multiple, const int64_t *offsets, int n_offsets, int reps,
+                        void *stream_compute, void *stream_comm, int64_t *best_row, float *us);
 
 /* Compute units of the current device; -1 when no device can be queried. */
 int tw_device_cu_count(void);

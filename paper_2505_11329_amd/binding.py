@@ -102,6 +102,9 @@ def lib():
         L.tw_weave_layer_auto.argtypes = [ctypes.POINTER(LayerArgs), _i64, _i64, _vp, _vp, _vp, ctypes.c_int, ctypes.c_int,
                                           ctypes.POINTER(_i64)]
         L.tw_weave_layer_auto.restype = ctypes.c_int
+        L.tw_weave_tune.argtypes = [ctypes.POINTER(LayerArgs), _i64, ctypes.POINTER(_i64), ctypes.c_int, ctypes.c_int,
+                                    _vp, _vp, ctypes.POINTER(_i64), ctypes.POINTER(ctypes.c_float)]
+        L.tw_weave_tune.restype = ctypes.c_int
         L.tw_split_threshold.argtypes = [_i64, _i64, ctypes.c_int, _i64, ctypes.c_int]
         L.tw_split_threshold.restype = _i64
         L.tw_smart_split_point.argtypes = [_i64, _i64, ctypes.POINTER(_i64), ctypes.POINTER(_i64), ctypes.c_int,
@@ -433,6 +436,29 @@ def weave_layer_auto(X1, W1, partials, residual, weight, eps, W2, stream_compute
                                      1 if use_parent else 0, 1 if join else 0, ctypes.byref(taken)),
            "tw_weave_layer_auto")
     return out, residual_out, Y, int(taken.value)
+
+
+def weave_tune(X1, W1, partials, residual, weight, eps, W2, stream_compute, stream_comm, offsets=(), reps=5,
+               multiple=0, fused_cu_budget=CU_SHARED, gemm_cu_budget=0, out=None, residual_out=None, Y=None,
+               schedule=WEAVE_AUTO):
+    """tw_weave_tune. Returns (best_row, us): us[0] the unsplit chain, us[1] the smart row, us[2 + i] offsets[i];
+    negative where a candidate was not run. Waits for the device."""
+    import torch
+    a, keep, out, residual_out = _fused_pack(partials, residual, weight, eps, fused_cu_budget, out, residual_out)
+    T, H = residual.shape
+    K1 = X1.shape[1]
+    N2 = W2.shape[0]
+    if Y is None:
+        Y = torch.empty((T, N2), dtype=torch.bfloat16, device=residual.device)
+    la = LayerArgs(_bf16_ptr(X1, "X1", (T, K1)), _bf16_ptr(W1, "W1", (H, K1)), K1, a,
+                   _bf16_ptr(W2, "W2", (N2, H)), N2, _bf16_ptr(Y, "Y", (T, N2)), int(gemm_cu_budget), int(schedule))
+    offs = (_i64 * max(1, len(offsets)))(*[int(o) for o in offsets])
+    us = (ctypes.c_float * (2 + len(offsets)))()
+    best = _i64(-1)
+    _check(lib().tw_weave_tune(ctypes.byref(la), int(multiple), offs, len(offsets), int(reps),
+                               _stream_handle(stream_compute), _stream_handle(stream_comm), ctypes.byref(best), us),
+           "tw_weave_tune")
+    return int(best.value), [float(x) for x in us]
 
 
 def split_threshold(K1, H, P, N2, cus=256):

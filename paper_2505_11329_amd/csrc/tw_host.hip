@@ -1,5 +1,6 @@
 // Host side of libtw that is not tied to one kernel: status strings, device
 // queries, the event pool, the token split and the overlap launch.
+#include <algorithm>
 #include <mutex>
 #include <vector>
 
@@ -339,9 +340,12 @@ tw_status tw_weave_layer(const tw_layer_args *layer, int64_t split_row, void *st
     int cus = 0;
     TW_TRY(current_cu_count(&cus));
     if (takes_chains(*layer, cus)) {
-        // one chain per split; the second starts when the first split's G1 is done
+        // one chain per split; the second starts when the first split's G1 is done.
+        // The first GEMM of the first chain and the last of the second have no fused
+        // kernel beside them (the one runs before any, the other after both): they
+        // take the tile shape of a GEMM launched on its own.
         hipEvent_t g1a_done;
-        TW_TRY(launch_gemm(rows_of(g1, cuts[0], cuts[1]), sx, true));
+        TW_TRY(launch_gemm(rows_of(g1, cuts[0], cuts[1]), sx, false));
         TW_TRY(borrow_event(&g1a_done));
         TW_HIP(hipEventRecord(g1a_done, sx));
         TW_HIP(hipStreamWaitEvent(sc, g1a_done, 0));
@@ -349,7 +353,7 @@ tw_status tw_weave_layer(const tw_layer_args *layer, int64_t split_row, void *st
         TW_TRY(launch_gemm(rows_of(g2, cuts[0], cuts[1]), sx, true));
         TW_TRY(launch_gemm(rows_of(g1, cuts[1], cuts[2]), sc, true));
         TW_TRY(launch_fused(f, cuts[1], cuts[2], nullptr, 0, sc));
-        TW_TRY(launch_gemm(rows_of(g2, cuts[1], cuts[2]), sc, true));
+        TW_TRY(launch_gemm(rows_of(g2, cuts[1], cuts[2]), sc, false));
         if (parent_is_set && join) {
             if (sx != sp) TW_TRY(stream_wait_stream(sp, sx));
             if (sc != sp) TW_TRY(stream_wait_stream(sp, sc));
@@ -388,12 +392,17 @@ int tw_should_split(int64_t num_tokens, int64_t threshold)
 int64_t tw_split_threshold(int64_t K1, int64_t H, int P, int64_t N2, int cus)
 {
     if (K1 < 1 || H < 1 || P < 1 || N2 < 1 || cus < 1) return -1;
-    // (1) the fused kernel of the whole batch must be worth hiding: the waits and
-    // the contention of a split schedule cost about what 140 us of fused work
-    // (at the whole device's ~5 TB/s) gain when overlapped
+    // (1) the GEMM after the fused step must outlast it, or the second split's
+    // fused kernel has nothing to hide behind and the last GEMM waits for it:
+    // per token 2 H N2 flop at 1 PFLOP/s against 2 H (P + 3) bytes at 5 TB/s
+    if (N2 < 200 * int64_t(P + 3)) return TW_NEVER_SPLIT;
+    // (2) the fused kernel of the whole batch must be worth hiding: the waits,
+    // the contention of co-resident kernels and the smaller GEMM tiles of a split
+    // schedule cost about what 290 us of fused work (at the whole device's
+    // ~5 TB/s) gain when overlapped
     const double row_bytes = 2.0 * double(H) * double(P + 3);
-    const int64_t t_gain = static_cast<int64_t>(140.0 * 5.0e6 / row_bytes) + 1;
-    // (2) half a batch must still give the narrower GEMM tiles for half of the
+    const int64_t t_gain = static_cast<int64_t>(290.0 * 5.0e6 / row_bytes) + 1;
+    // (3) half a batch must still give the narrower GEMM tiles for half of the
     // compute units, or its workgroups leave most of the device idle
     const int64_t n_min = H < N2 ? H : N2;
     const int64_t col_tiles = (n_min + kGemmTileN - 1) / kGemmTileN;
@@ -425,6 +434,76 @@ tw_status tw_weave_layer_auto(const tw_layer_args *layer, int64_t threshold, int
     }
     if (split_row) *split_row = k;
     return tw_weave_layer(layer, k, stream_compute, stream_comm, parent, parent_is_set, join);
+}
+
+tw_status tw_weave_tune(const tw_layer_args *layer, int64_t multiple, const int64_t *offsets, int n_offsets, int reps,
+                        void *stream_compute, void *stream_comm, int64_t *best_row, float *us)
+{
+    if (!layer || !best_row || !us || (n_offsets > 0 && !offsets)) return TW_ERR_NULL;
+    if (reps < 1 || reps > 64 || n_offsets < 0 || n_offsets > 16) return TW_ERR_SHAPE;
+    const tw_fused_args &f = layer->fused;
+    TW_TRY(validate_fused(f));
+    if (layer->K1 < 0 || layer->N2 < 0) return TW_ERR_SHAPE;
+    if (multiple <= 0) multiple = 64;
+    const int64_t T = f.N;
+    const int n_cand = 2 + n_offsets;
+    int64_t rows[18];
+    rows[0] = T;  // unsplit
+    for (int i = 1; i < n_cand; ++i) rows[i] = -1;
+    if (T > 0 && layer->K1 > 0 && layer->N2 > 0) {
+        int cus = 0;
+        TW_TRY(current_cu_count(&cus));
+        const int64_t widths[2] = {f.H, layer->N2}, depths[2] = {layer->K1, f.H};
+        rows[1] = tw_smart_split_point(T, multiple, widths, depths, 2, resolve_budget(layer->gemm_cu_budget, cus),
+                                       nullptr, nullptr);
+        const int64_t base = tw_split_point(T, multiple);
+        for (int i = 0; i < n_offsets; ++i) rows[2 + i] = base + offsets[i];
+    }
+    for (int i = 1; i < n_cand; ++i) {
+        if (rows[i] <= 0 || rows[i] >= T) rows[i] = -1;
+        for (int j = 0; j < i && rows[i] > 0; ++j)
+            if (rows[j] == rows[i]) rows[i] = -1;
+    }
+    hipStream_t sx = static_cast<hipStream_t>(stream_compute), sc = static_cast<hipStream_t>(stream_comm);
+    struct Events {  // destroyed on every way out
+        hipEvent_t begin = nullptr, end = nullptr;
+        ~Events()
+        {
+            if (begin) (void)hipEventDestroy(begin);
+            if (end) (void)hipEventDestroy(end);
+        }
+    } ev;
+    TW_HIP(hipEventCreate(&ev.begin));
+    TW_HIP(hipEventCreate(&ev.end));
+    float samples[18][64];
+    for (int r = -1; r < reps; ++r) {  // round -1 is the warm-up
+        for (int c0 = 0; c0 < n_cand; ++c0) {
+            const int c = (c0 + (r < 0 ? 0 : r)) % n_cand;
+            if (rows[c] < 0) continue;
+            TW_HIP(hipStreamSynchronize(sx));
+            TW_HIP(hipStreamSynchronize(sc));
+            TW_HIP(hipEventRecord(ev.begin, sx));
+            TW_TRY(tw_weave_layer(layer, rows[c] == T ? 0 : rows[c], stream_compute, stream_comm, stream_compute, 1, 1));
+            TW_HIP(hipEventRecord(ev.end, sx));
+            TW_HIP(hipEventSynchronize(ev.end));
+            float ms = 0.0f;
+            TW_HIP(hipEventElapsedTime(&ms, ev.begin, ev.end));
+            if (r >= 0) samples[c][r] = ms * 1000.0f;
+        }
+    }
+    TW_HIP(hipStreamSynchronize(sc));
+    int best = 0;
+    for (int c = 0; c < n_cand; ++c) {
+        if (rows[c] < 0) {
+            us[c] = -1.0f;
+            continue;
+        }
+        std::sort(samples[c], samples[c] + reps);
+        us[c] = reps % 2 ? samples[c][reps / 2] : 0.5f * (samples[c][reps / 2 - 1] + samples[c][reps / 2]);
+        if (us[c] < us[best]) best = c;
+    }
+    *best_row = rows[best];
+    return TW_OK;
 }
 
 void tw_gemm_tile_shape(int *tile_m, int *tile_n)

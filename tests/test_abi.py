@@ -29,7 +29,7 @@ def declared_functions(headers=("tw.h", "tw_measure.h")):
 def test_header_declares_the_documented_entry_points():
     names = declared_functions(("tw.h",))
     for must in ("tw_reduce_add_rmsnorm", "tw_split_launch", "tw_split_point", "tw_gemm_bf16",
-                 "tw_overlap_launch", "tw_weave_layer", "tw_weave_layer_auto", "tw_smart_split_point",
+                 "tw_overlap_launch", "tw_weave_layer", "tw_weave_layer_auto", "tw_weave_tune", "tw_smart_split_point",
                  "tw_should_split", "tw_split_threshold", "tw_device_cu_count", "tw_status_str",
                  "tw_version", "tw_last_hip_error"):
         assert must in names
@@ -394,19 +394,26 @@ def test_weave_layer_argument_checks():
 
 
 def test_split_threshold_matches_its_definition():
-    """tw_split_threshold restated: the larger of 'the fused step takes 140 us at 5 TB/s' and 'half the
-    batch still tiles the narrower GEMM output over half of the compute units', in whole 256-row tiles."""
+    """tw_split_threshold restated: never when the GEMM after the fused step is the shorter of the two
+    (N2 < 200 (P + 3)); else the larger of 'the fused step takes 290 us at 5 TB/s' and 'half the batch
+    still tiles the narrower GEMM output over half of the compute units', in whole 256-row tiles."""
     import math
+    never = 2 ** 63 - 1
     for (K1, Hh, Pp, N2, cus) in [(1024, 8192, 8, 3584, 256), (3584, 8192, 8, 1280, 256), (3584, 8192, 4, 1280, 256),
                                   (512, 4096, 2, 4096, 256), (1024, 8192, 8, 3584, 64), (8, 8, 1, 8, 1),
-                                  (4096, 16384, 16, 128, 304)]:
-        t_gain = math.floor(140.0 * 5.0e6 / (2.0 * Hh * (Pp + 3))) + 1
-        col_tiles = -(-min(Hh, N2) // 128)
-        t_fill = 2 * 256 * -(-((cus + 1) // 2) // col_tiles)
-        want = -(-max(t_gain, t_fill) // 256) * 256
+                                  (8, 8, 1, 800, 1), (4096, 16384, 16, 128, 304), (4096, 16384, 16, 3800, 304),
+                                  (1024, 8192, 8, 2200, 256), (1024, 8192, 8, 2192, 256)]:
+        if N2 < 200 * (Pp + 3):
+            want = never
+        else:
+            t_gain = math.floor(290.0 * 5.0e6 / (2.0 * Hh * (Pp + 3))) + 1
+            col_tiles = -(-min(Hh, N2) // 128)
+            t_fill = 2 * 256 * -(-((cus + 1) // 2) // col_tiles)
+            want = -(-max(t_gain, t_fill) // 256) * 256
         assert tw.split_threshold(K1, Hh, Pp, N2, cus) == want, (K1, Hh, Pp, N2, cus)
-    assert tw.split_threshold(1024, 8192, 8, 3584, 256) == 4096      # the figures tw.h quotes
-    assert tw.split_threshold(3584, 8192, 8, 1280, 256) == 6656
+    assert tw.split_threshold(1024, 8192, 8, 3584, 256) == 8192      # the figures tw.h quotes
+    assert tw.split_threshold(3584, 8192, 8, 1280, 256) == never
+    assert not tw.should_split(10 ** 9, never)
     for bad in ((0, 8192, 8, 3584, 256), (1024, 0, 8, 3584, 256), (1024, 8192, 0, 3584, 256),
                 (1024, 8192, 8, 0, 256), (1024, 8192, 8, 3584, 0)):
         assert tw.split_threshold(*bad) == -1
@@ -429,6 +436,32 @@ def test_weave_layer_auto_argument_checks():
     la.fused.N = 0              # an empty batch: nothing to decide, nothing to launch
     assert L.tw_weave_layer_auto(ctypes.byref(la), 0, 0, VP(1), VP(2), VP(None), 0, 0, ctypes.byref(taken)) == OK
     assert taken.value == 0
+
+
+def test_weave_tune_argument_checks():
+    """The offline search refuses bad arguments before it creates an event or launches anything."""
+    from paper_2505_11329_amd.binding import LayerArgs
+    L = tw.lib()
+    best = ctypes.c_int64(-7)
+    us = (ctypes.c_float * 18)()
+    offs = (ctypes.c_int64 * 17)(*range(0, 17 * 64, 64))
+    arr = (VP * P)(addr(0), addr(1))
+    f = FusedArgs(ctypes.cast(arr, ctypes.POINTER(VP)), addr(4), addr(5), 1e-5, N, H, P, 8, addr(6), addr(7))
+    la = LayerArgs(addr(10), addr(11), 64, f, addr(12), 64, addr(13), 0)
+    ok_args = (0, offs, 2, 3, VP(1), VP(2), ctypes.byref(best), us)
+    assert L.tw_weave_tune(None, *ok_args) == E_NULL
+    assert L.tw_weave_tune(ctypes.byref(la), 0, offs, 2, 3, VP(1), VP(2), None, us) == E_NULL
+    assert L.tw_weave_tune(ctypes.byref(la), 0, offs, 2, 3, VP(1), VP(2), ctypes.byref(best), None) == E_NULL
+    assert L.tw_weave_tune(ctypes.byref(la), 0, None, 2, 3, VP(1), VP(2), ctypes.byref(best), us) == E_NULL
+    for reps in (0, -1, 65):
+        assert L.tw_weave_tune(ctypes.byref(la), 0, offs, 2, reps, VP(1), VP(2), ctypes.byref(best), us) == E_SHAPE
+    for n_off in (-1, 17):
+        assert L.tw_weave_tune(ctypes.byref(la), 0, offs, n_off, 3, VP(1), VP(2), ctypes.byref(best), us) == E_SHAPE
+    la.fused.H = 60
+    assert L.tw_weave_tune(ctypes.byref(la), *ok_args) == E_UNSUP
+    la.fused.H = H
+    la.N2 = -8
+    assert L.tw_weave_tune(ctypes.byref(la), *ok_args) == E_SHAPE
 
 
 def test_fused_layout_covers_every_row_width_without_idle_waves():
@@ -478,7 +511,7 @@ def test_weave_schedule_is_chains_unless_the_fused_kernel_has_a_budget():
 
 
 def test_should_split_threshold():
-    assert not tw.should_split(0) and not tw.should_split(6143)
-    assert tw.should_split(6144) and tw.should_split(10 ** 6)
+    assert not tw.should_split(0) and not tw.should_split(8191)
+    assert tw.should_split(8192) and tw.should_split(10 ** 6)
     assert tw.should_split(1024, 1024) and not tw.should_split(1023, 1024)
-    assert tw.should_split(6144, -5) and not tw.should_split(100, 0)
+    assert tw.should_split(8192, -5) and not tw.should_split(100, 0)

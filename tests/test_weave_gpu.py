@@ -198,22 +198,24 @@ def test_weave_layer_auto_applies_threshold_and_smart_split(tw, torch_cuda):
 @pytest.mark.parametrize("K1,N2", [(1024, 3584), (3584, 1280)])
 def test_weave_layer_auto_at_full_size_on_both_sides_of_the_built_in_threshold(tw, torch_cuda, K1, N2):
     """The two 70B-class boundaries (H = 8192, P = 8) with the library's own threshold: one batch just
-    below it, one at it, one above; the policy's outputs carry the bits of the plain unsplit chain."""
+    below it, one at it, one above (the MLP-side boundary, which the built-in rule never splits, is run at
+    the same three sizes); the policy's outputs carry the bits of the plain unsplit chain."""
     torch = torch_cuda
     H_, P_ = 8192, 8
+    never = 2 ** 63 - 1
     thr = tw.split_threshold(K1, H_, P_, N2, tw.device_cu_count())
-    assert thr == (4096 if K1 == 1024 else 6656)
+    assert thr == (8192 if K1 == 1024 else never)
     gen = torch.Generator(device="cuda:0")
     gen.manual_seed(K1 * 3 + N2)
 
     def rnd(shape, std):
         return torch.empty(shape, dtype=torch.bfloat16, device="cuda:0").normal_(0.0, std, generator=gen)
-    T_max = thr + 640
+    T_max = 8192 + 640
     X1, W1, W2g = rnd((T_max, K1), 0.02), rnd((H_, K1), 0.02), rnd((N2, H_), 0.02)
     parts, resid = [rnd((T_max, H_), 0.25) for _ in range(P_)], rnd((T_max, H_), 1.0)
     weight = to_gpu(W.uniform_bf16((H_,), 0.5, 1.5, 0, W.STREAM_WEIGHT))
     sx, sc = torch.cuda.Stream(), torch.cuda.Stream()
-    for T_ in (thr - 256, thr, T_max):
+    for T_ in (8192 - 256, 8192, T_max):
         args = (X1[:T_], W1, [p[:T_] for p in parts], resid[:T_], weight, 1e-5, W2g)
         with torch.cuda.stream(sx):
             want = tw.weave_layer(*args, 0, sx, sc, fused_cu_budget=tw.CU_SHARED, parent=sx)
@@ -224,3 +226,36 @@ def test_weave_layer_auto_at_full_size_on_both_sides_of_the_built_in_threshold(t
         assert (taken == T_) == (T_ < thr), (T_, taken)
         for name, g_, w_ in zip(("G1", "out", "residual_out", "Y"), (parts[0][:T_], out, res, Y), want):
             assert torch.equal(g_.view(torch.int16), w_.view(torch.int16)), (T_, taken, name)
+
+
+def test_weave_tune_times_the_candidates_and_leaves_the_layers_outputs(tw, torch_cuda):
+    """The offline search (Algorithm 1, timed): every candidate that lies inside the batch gets a time,
+    the others a negative one; the row reported is the fastest candidate's; and the buffers hold what any
+    call leaves there, the unsplit chain's bits."""
+    torch = torch_cuda
+    g1, f, W2 = make_inputs()
+    streams = (torch.cuda.Stream(), torch.cuda.Stream())
+    want = run_layer(tw, torch, g1, f, W2, 0, streams, budgets=(tw.CU_SHARED, 0))
+    X1, W1 = to_gpu(g1["A"]), to_gpu(g1["B"])
+    parts = [torch.zeros((T, H), dtype=torch.bfloat16, device="cuda:0")] + [to_gpu(p) for p in f["partials"][1:]]
+    resid, weight, W2g = to_gpu(f["residual"]), to_gpu(f["weight"]), to_gpu(W2)
+    out, res = torch.empty_like(resid), torch.empty_like(resid)
+    Y = torch.empty((T, N2), dtype=torch.bfloat16, device="cuda:0")
+    offsets = (0, 64, -64, 4096, 0)          # one far outside the batch, one repeated
+    best, us = tw.weave_tune(X1, W1, parts, resid, weight, f["eps"], W2g, streams[0], streams[1], offsets=offsets,
+                             reps=3, multiple=64, out=out, residual_out=res, Y=Y)
+    torch.cuda.synchronize()
+    base = tw.split_point(T, 64)
+    smart = tw.smart_split_point(T, 64, [H, N2], tw.device_cu_count(), gemm_k=[K1, H])[0]
+    rows = [T, smart] + [base + o for o in offsets]
+    assert len(us) == 2 + len(offsets) and us[0] > 0 and us[1] > 0
+    seen = set()
+    for i, (row, t) in enumerate(zip(rows, us)):
+        ran = i == 0 or (0 < row < T and row not in seen)
+        assert (t > 0) == ran, (row, t)
+        seen.add(row)
+    timed = [(t, row) for row, t in zip(rows, us) if t > 0]
+    assert best == min(timed)[1]
+    got = (to_bits(parts[0]), to_bits(out), to_bits(res), to_bits(Y))
+    for name, g_, w_ in zip(("G1", "out", "residual_out", "Y"), got, want):
+        assert np.array_equal(g_, w_), name
