@@ -44,6 +44,7 @@ static constexpr int kWaves = kThreads / 64;
 // Dynamic LDS each workgroup requests so that only one fits on a compute unit
 // (gfx950 has 160 KiB per CU).
 static constexpr unsigned kOccupancyPadBytes = 96 * 1024;
+static constexpr int64_t kLastLevelCacheBytes = int64_t(256) << 20;
 
 struct FusedParams {
     const void *partials[TW_MAX_P];
@@ -76,9 +77,10 @@ constexpr int buffers_in_flight()
     return (PT == 0) ? 1 : (((PT + 1) * 8 + 12 * VPT <= 100) ? 2 : 1);
 }
 
-template <int PT, int VPT, bool TRACE>
+template <int PT, int VPT, bool TRACE, bool STREAMED>
 __global__ __launch_bounds__(kThreads) void fused_kernel(const FusedParams prm)
 {
+    constexpr bool streamed = STREAMED;  // see st()
     __shared__ float s_wave_sum[2][kWaves];
     constexpr int NB = buffers_in_flight<PT, VPT>();
     constexpr bool KEEP_W = VPT <= 2;     // weights unpacked to fp32 once, else kept packed,
@@ -215,7 +217,7 @@ __global__ __launch_bounds__(kThreads) void fused_kernel(const FusedParams prm)
                 const int nj = (j + NB) % VPT;
                 const uint32_t ng = (VPT == 1) ? group + NB * stride : (j + NB >= VPT ? group + stride : group);
                 issue(b, chunk_off(ng, nj));
-                if constexpr (!LATE_RES) st(r_res_out, off, pack8(x[j]));
+                if constexpr (!LATE_RES) st(r_res_out, off, pack8(x[j]), streamed);
 #pragma unroll
                 for (int e = 0; e < 8; ++e) ss = __builtin_fmaf(x[j][e], x[j][e], ss);
             }
@@ -247,8 +249,8 @@ __global__ __launch_bounds__(kThreads) void fused_kernel(const FusedParams prm)
 #pragma unroll
                     for (int e = 0; e < 8; ++e) y[e] = (x[j][e] * s) * w[e];
                 }
-                if constexpr (LATE_RES) st(r_res_out, chunk_off(group, j), pack8(x[j]));
-                st(r_out, chunk_off(group, j), pack8(y));
+                if constexpr (LATE_RES) st(r_res_out, chunk_off(group, j), pack8(x[j]), streamed);
+                st(r_out, chunk_off(group, j), pack8(y), streamed);
             }
         }
     }
@@ -278,10 +280,11 @@ __global__ __launch_bounds__(kThreads) void fused_kernel(const FusedParams prm)
 // ---------------------------------------------------------------------------
 static constexpr int kThinThreads = 256;
 
-template <int PT, int Q, bool TRACE>
+template <int PT, int Q, bool TRACE, bool STREAMED>
 __global__ __launch_bounds__(kThinThreads) __attribute__((amdgpu_waves_per_eu(4)))
 void fused_thin_kernel(const FusedParams prm)
 {
+    constexpr bool streamed = STREAMED;  // see st()
     __shared__ float s_wave_sum[2][kWaves];
 
     const int tid = threadIdx.x;
@@ -416,8 +419,8 @@ void fused_thin_kernel(const FusedParams prm)
             unpack8(__builtin_amdgcn_raw_buffer_load_b128(r_w, cvalid[q] ? v * 16u : kOutOfRange, 0, 0), w);
 #pragma unroll
             for (int e = 0; e < 8; ++e) y[e] = (x[q][e] * s) * w[e];
-            st(r_res_out, chunk_off(group, q), pack8(x[q]));
-            st(r_out, chunk_off(group, q), pack8(y));
+            st(r_res_out, chunk_off(group, q), pack8(x[q]), streamed);
+            st(r_out, chunk_off(group, q), pack8(y), streamed);
         }
     }
 }
@@ -493,9 +496,10 @@ tw_status validate_fused(const tw_fused_args &a)
 }
 
 template <int PT, int VPT>
-static tw_status launch_t(const FusedParams &prm, bool trace, int64_t grid, int block, hipStream_t stream)
+static tw_status launch_t(const FusedParams &prm, bool trace, bool streamed, int64_t grid, int block, hipStream_t stream)
 {
-    auto kern = trace ? fused_kernel<PT, VPT, true> : fused_kernel<PT, VPT, false>;
+    auto kern = trace ? fused_kernel<PT, VPT, true, false>
+                      : streamed ? fused_kernel<PT, VPT, false, true> : fused_kernel<PT, VPT, false, false>;
     static std::atomic<int> allowed[2][kMaxDevices];
     TW_TRY(allow_dynamic_lds(reinterpret_cast<const void *>(kern), static_cast<int>(kOccupancyPadBytes),
                              allowed[trace]));
@@ -505,23 +509,24 @@ static tw_status launch_t(const FusedParams &prm, bool trace, int64_t grid, int 
 }
 
 template <int PT, int Q>
-static tw_status launch_thin_t(const FusedParams &prm, bool trace, int64_t grid,
+static tw_status launch_thin_t(const FusedParams &prm, bool trace, bool streamed, int64_t grid,
                                hipStream_t stream)
 {
-    auto kern = trace ? fused_thin_kernel<PT, Q, true> : fused_thin_kernel<PT, Q, false>;
+    auto kern = trace ? fused_thin_kernel<PT, Q, true, false>
+                      : streamed ? fused_thin_kernel<PT, Q, false, true> : fused_thin_kernel<PT, Q, false, false>;
     TW_HIP(launch_kernel(kern, dim3(static_cast<unsigned>(grid)), dim3(kThinThreads), 0u, stream, prm));
     return TW_OK;
 }
 
 template <int PT>
-static tw_status launch_thin(const FusedParams &prm, int q, bool trace, int64_t grid,
+static tw_status launch_thin(const FusedParams &prm, int q, bool trace, bool streamed, int64_t grid,
                              hipStream_t s)
 {
     switch (q) {
-    case 1: return launch_thin_t<PT, 1>(prm, trace, grid, s);
-    case 2: return launch_thin_t<PT, 2>(prm, trace, grid, s);
-    case 3: return launch_thin_t<PT, 3>(prm, trace, grid, s);
-    case 4: return launch_thin_t<PT, 4>(prm, trace, grid, s);
+    case 1: return launch_thin_t<PT, 1>(prm, trace, streamed, grid, s);
+    case 2: return launch_thin_t<PT, 2>(prm, trace, streamed, grid, s);
+    case 3: return launch_thin_t<PT, 3>(prm, trace, streamed, grid, s);
+    case 4: return launch_thin_t<PT, 4>(prm, trace, streamed, grid, s);
     }
     return TW_ERR_UNSUPPORTED;
 }
@@ -550,15 +555,15 @@ static int64_t thin_grid(int64_t n_rows, const ThinGeometry &t, int cus)
 }
 
 template <int PT>
-static tw_status launch_vpt(const FusedParams &prm, const FusedGeometry &g, bool trace, int64_t grid,
+static tw_status launch_vpt(const FusedParams &prm, const FusedGeometry &g, bool trace, bool streamed, int64_t grid,
                             hipStream_t s)
 {
     switch (g.vpt) {
-    case 1: return launch_t<PT, 1>(prm, trace, grid, g.block, s);
-    case 2: return launch_t<PT, 2>(prm, trace, grid, g.block, s);
-    case 4: return launch_t<PT, 4>(prm, trace, grid, g.block, s);
+    case 1: return launch_t<PT, 1>(prm, trace, streamed, grid, g.block, s);
+    case 2: return launch_t<PT, 2>(prm, trace, streamed, grid, g.block, s);
+    case 4: return launch_t<PT, 4>(prm, trace, streamed, grid, g.block, s);
     case 8:
-        if constexpr (PT != 8) return launch_t<PT, 8>(prm, trace, grid, g.block, s);  // P = 8 goes to the any-P kernel
+        if constexpr (PT != 8) return launch_t<PT, 8>(prm, trace, streamed, grid, g.block, s);  // P = 8 goes to the any-P kernel
         break;
     }
     return TW_ERR_UNSUPPORTED;
@@ -607,6 +612,9 @@ tw_status launch_fused(const tw_fused_args &a, int64_t row_begin, int64_t row_en
     rows_per_launch -= rows_per_launch % g.rows_per_iter;
     if (trace && row_end - row_begin > rows_per_launch) return TW_ERR_UNSUPPORTED;
     const bool thin = takes_thin_kernel(a.cu_budget, cus, g, row_end - row_begin, a.P);
+    // outputs that do not fit the last-level cache are stored with the streaming policy (see st());
+    // not under a CU budget, where that is 1 % slower
+    const bool streamed = 2 * (row_end - row_begin) * row_bytes >= kLastLevelCacheBytes && (thin || budget == cus);
     const ThinGeometry tg = thin_geometry(g);
     const int rows_per_group = thin ? tg.rows_per_iter : g.rows_per_iter;
 
@@ -642,11 +650,11 @@ tw_status launch_fused(const tw_fused_args &a, int64_t row_begin, int64_t row_en
 
         if (thin) {
             switch (a.P) {
-            case 1: TW_TRY((launch_thin<1>(prm, tg.q, trace, grid, stream))); break;
-            case 2: TW_TRY((launch_thin<2>(prm, tg.q, trace, grid, stream))); break;
-            case 4: TW_TRY((launch_thin<4>(prm, tg.q, trace, grid, stream))); break;
-            case 8: TW_TRY((launch_thin<8>(prm, tg.q, trace, grid, stream))); break;
-            default: TW_TRY((launch_thin<0>(prm, tg.q, trace, grid, stream))); break;
+            case 1: TW_TRY((launch_thin<1>(prm, tg.q, trace, streamed, grid, stream))); break;
+            case 2: TW_TRY((launch_thin<2>(prm, tg.q, trace, streamed, grid, stream))); break;
+            case 4: TW_TRY((launch_thin<4>(prm, tg.q, trace, streamed, grid, stream))); break;
+            case 8: TW_TRY((launch_thin<8>(prm, tg.q, trace, streamed, grid, stream))); break;
+            default: TW_TRY((launch_thin<0>(prm, tg.q, trace, streamed, grid, stream))); break;
             }
             continue;
         }
@@ -655,11 +663,11 @@ tw_status launch_fused(const tw_fused_args &a, int64_t row_begin, int64_t row_en
         // additions) does.
         const int p_case = (a.P == 8 && g.vpt == 8) ? 0 : a.P;
         switch (p_case) {
-        case 1: TW_TRY((launch_vpt<1>(prm, g, trace, grid, stream))); break;
-        case 2: TW_TRY((launch_vpt<2>(prm, g, trace, grid, stream))); break;
-        case 4: TW_TRY((launch_vpt<4>(prm, g, trace, grid, stream))); break;
-        case 8: TW_TRY((launch_vpt<8>(prm, g, trace, grid, stream))); break;
-        default: TW_TRY((launch_vpt<0>(prm, g, trace, grid, stream))); break;
+        case 1: TW_TRY((launch_vpt<1>(prm, g, trace, streamed, grid, stream))); break;
+        case 2: TW_TRY((launch_vpt<2>(prm, g, trace, streamed, grid, stream))); break;
+        case 4: TW_TRY((launch_vpt<4>(prm, g, trace, streamed, grid, stream))); break;
+        case 8: TW_TRY((launch_vpt<8>(prm, g, trace, streamed, grid, stream))); break;
+        default: TW_TRY((launch_vpt<0>(prm, g, trace, streamed, grid, stream))); break;
         }
     }
     return TW_OK;

@@ -58,7 +58,7 @@ __global__ __launch_bounds__(kUThreads) void allreduce_kernel(const UnfusedParam
             unpack8(ld(make_rsrc(prm.partials[0], prm.n_bytes), off), f);
             for (int p = 1; p < prm.P; ++p) add8(ld(make_rsrc(prm.partials[p], prm.n_bytes), off), f);
         }
-        st(r_sum, off, pack8(f));
+        st(r_sum, off, pack8(f), false);
     }
 }
 
@@ -94,7 +94,7 @@ __global__ __launch_bounds__(kUThreads) void add_norm_kernel(const UnfusedParams
             add8(b[j], x);
 #pragma unroll
             for (int e = 0; e < 8; ++e) ss = fmaf(x[e], x[e], ss);
-            st(r_res_out, off[j], pack8(x));
+            st(r_res_out, off[j], pack8(x), false);
         }
         ss = group_sum(ss, 6);
         if ((tid & 63) == 0) s_wave_sum[parity][tid >> 6] = ss;
@@ -116,7 +116,7 @@ __global__ __launch_bounds__(kUThreads) void add_norm_kernel(const UnfusedParams
             unpack8(wv, w);
 #pragma unroll
             for (int e = 0; e < 8; ++e) x[e] = (x[e] * s) * w[e];
-            st(r_out, off[j], pack8(x));
+            st(r_out, off[j], pack8(x), false);
         }
     }
 }
