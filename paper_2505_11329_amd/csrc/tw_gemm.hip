@@ -20,10 +20,10 @@
 //     which makes the MFMA operand reads free of bank conflicts without padding
 //     (measured: 178 B/clk/CU against 128 for a swizzle that assumes 32 banks,
 //     32 unswizzled; with K steps of 32 a row is a quarter of a line and the
-//     swizzle is a different one, see lds_piece). An LDS-direct load writes 64 consecutive 16-byte slots per
-//     wave instruction, so the swizzle is applied on the global side: the lane
-//     that fills slot s of line l fetches piece (s & 7) ^ (l & 7) of row
-//     2l + (s >> 3).
+//     swizzle is a different one, see lds_piece). An LDS-direct load writes 64
+//     consecutive 16-byte slots per wave instruction, so the swizzle is applied
+//     on the global side: the lane that fills slot s of line l fetches piece
+//     (s & 7) ^ (l & 7) of row 2l + (s >> 3).
 //   - The compiler cannot tell which LDS stage an asynchronous load targets and
 //     would wait for ALL outstanding loads before any LDS read it can see;
 //     operand fragments are therefore read with inline ds_read and the waits
@@ -31,12 +31,18 @@
 //     Dynamic LDS is the kernel's only LDS object, so its byte offsets are LDS
 //     addresses.
 //   - The K loop is software-pipelined by hand, instruction by instruction:
-//     between the MFMAs of one K sub-step (k = 16) a wave issues the LDS reads
+//     between the MFMAs of one K sub-step (k = 32) a wave issues the LDS reads
 //     of the next sub-step's fragments (during the first half, so that they
 //     have the second half to arrive) and its share of the global loads of
 //     K step kt + 2; the "next stage has landed" check (vmcnt + workgroup
 //     barrier) sits before the last MFMA group of a K step, when every wave
 //     still has matrix work queued.
+//   - Large products launched on their own take 256 x 256 tiles instead: four
+//     waves of 128 x 128 (256 accumulator registers per lane), K steps of 64 whose
+//     operand areas rotate through a ring of five 32 KiB LDS slots, one operand's
+//     loads per sub-step (see the K loop). With one wave per SIMD every
+//     instruction between two MFMAs counts: a wave issues one instruction in
+//     four clocks and an MFMA lasts sixteen.
 //   - Each MFMA gets the B fragment as its first operand and the A fragment as
 //     its second, so the 16x16 result block is held transposed: a lane owns one
 //     row m of C and the block's four accumulator registers are four consecutive

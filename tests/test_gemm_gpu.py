@@ -61,10 +61,10 @@ def test_gemm_both_layouts_give_the_same_bits(tw, torch_cuda):
 
 
 @pytest.mark.parametrize("M,N,K,budget", [(4096, 4096, 2048, 0), (1000, 1096, 520, 10), (2304, 2048, 4104, 72),
-                                          (513, 520, 96, 9)])
+                                          (513, 520, 96, 9), (512, 512, 40, 4), (768, 1024, 64, 6), (520, 264, 200, 3)])
 def test_gemm_large_product_tiles_give_the_same_bits(tw, torch_cuda, M, N, K, budget):
-    """A large product launched on its own takes 256 x 256 tiles (four waves of 128 x 128, K steps of 32
-    over four LDS stages) where those fill the compute units of the launch; stored [K x N] the same
+    """A large product launched on its own takes 256 x 256 tiles (four waves of 128 x 128, K steps of 64
+    through a ring of five LDS slots) where those fill the compute units of the launch; stored [K x N] the same
     product always takes the 256 x 128 ones. Same bits (ragged edges and a K that is no multiple of the
     K step included), checked against the oracle on sampled outputs."""
     a = W.make_gemm_inputs(M, K, N, 0.05, seed=M + K, b_layout="nk")
@@ -90,12 +90,13 @@ def test_gemm_large_product_tiles_give_the_same_bits(tw, torch_cuda, M, N, K, bu
 
 def test_gemm_k_zero_gives_zeros(tw, torch_cuda):
     torch = torch_cuda
-    A = torch.empty((40, 0), dtype=torch.bfloat16, device="cuda:0")
-    B = torch.empty((24, 0), dtype=torch.bfloat16, device="cuda:0")
-    C = torch.full((40, 24), 7.0, dtype=torch.bfloat16, device="cuda:0")
-    tw.gemm_bf16(A, B, C=C)
-    torch.cuda.synchronize()
-    assert (to_bits(C) == 0).all()
+    for (M, N, budget) in ((40, 24, 0), (512, 512, 4)):      # the second takes the 256 x 256 tiles
+        A = torch.empty((M, 0), dtype=torch.bfloat16, device="cuda:0")
+        B = torch.empty((N, 0), dtype=torch.bfloat16, device="cuda:0")
+        C = torch.full((M, N), 7.0, dtype=torch.bfloat16, device="cuda:0")
+        tw.gemm_bf16(A, B, C=C, cu_budget=budget)
+        torch.cuda.synchronize()
+        assert (to_bits(C) == 0).all()
 
 
 @pytest.mark.parametrize("layout", ["nk", "kn"])
