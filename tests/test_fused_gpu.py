@@ -275,6 +275,34 @@ def test_batch_longer_than_one_launch_can_address(tw, torch_cuda):
     assert np.array_equal(to_bits(r2[idx]), oracle.f64_to_bf16(ref_res))
 
 
+@pytest.mark.parametrize("N,H,P", [(8200, 8192, 8), (8195, 8192, 2), (16500, 4096, 4), (5500, 12288, 3)])
+def test_outputs_larger_than_the_last_level_cache(tw, torch_cuda, N, H, P):
+    """Calls whose two outputs exceed 256 MiB take the kernels that store with the streaming policy when
+    they run on the whole device or in shared mode, and the ordinary ones under a CU budget: the same
+    bits from all three (every element), and the oracle's on sampled rows. Inputs drawn on the GPU."""
+    torch = torch_cuda
+    assert 2 * N * H * 2 >= 256 << 20
+    gen = torch.Generator(device="cuda:0")
+    gen.manual_seed(N + P)
+    parts = [torch.empty((N, H), device="cuda:0", dtype=torch.bfloat16).normal_(0.0, 0.5, generator=gen)
+             for _ in range(P)]
+    resid = torch.empty((N, H), device="cuda:0", dtype=torch.bfloat16).normal_(0.0, 1.0, generator=gen)
+    w = to_gpu(W.uniform_bf16((H,), 0.5, 1.5, 0, W.STREAM_WEIGHT))
+    want = tw.reduce_add_rmsnorm(parts, resid, w, 1e-5, cu_budget=16)
+    torch.cuda.synchronize()
+    for budget in (0, tw.CU_SHARED):
+        out, res = tw.reduce_add_rmsnorm(parts, resid, w, 1e-5, cu_budget=budget)
+        torch.cuda.synchronize()
+        assert torch.equal(out.view(torch.int16), want[0].view(torch.int16)), budget
+        assert torch.equal(res.view(torch.int16), want[1].view(torch.int16)), budget
+        del out, res
+    rng = np.random.default_rng(N)
+    rows = np.unique(np.concatenate([[0, 1, N - 2, N - 1], rng.integers(0, N, 60)]))
+    idx = torch.from_numpy(rows).to("cuda:0")
+    d = dict(partials=[to_bits(p[idx]) for p in parts], residual=to_bits(resid[idx]), weight=to_bits(w), eps=1e-5)
+    check_against_oracle(d, to_bits(want[0][idx]), to_bits(want[1][idx]), "large outputs N=%d H=%d P=%d" % (N, H, P))
+
+
 def test_traced_launch_reports_distinct_compute_units(tw, torch_cuda):
     """Each workgroup of a budgeted launch sits on its own compute unit: the
     (XCC, SE, CU) triples decoded from the hardware id registers are distinct and
