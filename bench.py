@@ -99,6 +99,8 @@ def main():
                          "(tw_hbm_probe_shaped / tw_hbm_probe_mixed_shaped) for budgets 1..32 x workgroup size x "
                          "accesses in flight x read / copy / 9-read-2-write: the per-CU HBM ceiling the fused "
                          "kernel is measured against")
+    ap.add_argument("--gemm-phases", action="store_true",
+                    help="where the clocks of the 256x256 GEMM tile's K loop go (tw_gemm_bf16_traced), as JSON")
     ap.add_argument("--counters-run", choices=("fused", "gemm", "weave", "probe"), default=None,
                     help="for rocprofv3 --pmc. fused: a few fused launches plus plain copy launches of known "
                          "size (tw_hbm_probe, 192 MiB read + 192 MiB written each) to scale the byte counters "
@@ -190,6 +192,9 @@ def main():
 
     if args.ceiling:
         ceiling_sweep(tw, torch, np, stream, train_times)
+        return
+    if args.gemm_phases:
+        gemm_phases(tw, torch, np, stream, train_times)
         return
     if args.sweep:
         def sweep_point(H, P, N, cfgname):
@@ -1032,6 +1037,53 @@ def decode_trains(result, tw, W, torch, np, stream, gpu):
                 "the same 160 launches captured once with hipStreamBeginCapture and replayed. wall = submit + "
                 "drain per launch; host = time for the calls (or the replay call) to return, per launch; device = "
                 "HIP events around the train"}
+
+
+def gemm_phases(tw, torch, np, stream, train_times):
+    """Per-wave shader clocks of the phases of the 256x256 tile's pipeline (tw_gemm_bf16_traced), next to
+    the plain kernel's time for the same product, for a long-K, a square and a short-K product."""
+    rows = []
+    names = tw.GEMM_PHASE_NAMES
+    for (M, N, K) in ((8192, 8192, 8192), (4096, 4096, 4096), (16384, 8192, 1024)):
+        gen = torch.Generator(device="cuda:0")
+        gen.manual_seed(M + K)
+        A = torch.empty((M, K), dtype=torch.bfloat16, device="cuda:0").normal_(0.0, 0.02, generator=gen)
+        B = torch.empty((N, K), dtype=torch.bfloat16, device="cuda:0").normal_(0.0, 0.02, generator=gen)
+        C = torch.empty((M, N), dtype=torch.bfloat16, device="cuda:0")
+        torch.cuda.synchronize()
+        plain_us = train_times([lambda: tw.gemm_bf16(A, B, C=C, b_layout=tw.B_NK, stream=stream)], trains=6, length=4,
+                               warm=3, on_stream=stream)
+        for _ in range(3):
+            _, cyc = tw.gemm_bf16_traced(A, B, C=C, stream=stream)
+        stream.synchronize()
+        traced_us = train_times([lambda: tw.gemm_bf16_traced(A, B, C=C, stream=stream)], trains=4, length=2, warm=1,
+                                on_stream=stream)
+        c = cyc.cpu().numpy().astype(np.float64)
+        ran = c[:, names.index("tiles")] > 0
+        c = c[ran]
+        tiles = c[:, names.index("tiles")]
+        steps = tiles * (K // 64)
+        per_step = {n: round(float((c[:, names.index(n)] / steps).mean()), 1)
+                    for n in ("sub_step_0", "wait_landed", "barrier", "sub_step_1")}
+        per_tile = {n: round(float((c[:, names.index(n)] / tiles).mean()), 0) for n in ("tile_fill", "tile_stores")}
+        k_step = sum(per_step.values())
+        rows.append({"MxNxK": "%dx%dx%d" % (M, N, K), "plain_us": round(float(np.median(plain_us)), 1),
+                     "traced_us": round(float(np.median(traced_us)), 1), "waves": int(ran.sum()),
+                     "tiles_per_wave": float(tiles.mean()), "K_steps_per_tile": K // 64,
+                     "clocks_per_K_step": per_step, "clocks_per_K_step_total": round(k_step, 1),
+                     "matrix_work_clocks_per_K_step": 2048, "clocks_per_tile": per_tile,
+                     "kernel_clocks_per_wave": round(float(c[:, names.index("kernel")].mean()), 0),
+                     "share_of_kernel": {
+                         "matrix_work": round(float((2048 * steps / c[:, names.index("kernel")]).mean()), 3),
+                         "K_loop": round(float((k_step * steps / c[:, names.index("kernel")]).mean()), 3),
+                         "tile_fill": round(float((c[:, names.index("tile_fill")] / c[:, names.index("kernel")]).mean()), 3),
+                         "tile_stores": round(float((c[:, names.index("tile_stores")] / c[:, names.index("kernel")]).mean()), 3)}})
+        del A, B, C
+        torch.cuda.empty_cache()
+    print(json.dumps({"gemm_phases": rows,
+                      "note": "tw_gemm_bf16_traced: shader clocks per wave, means over the waves that ran; a K step of "
+                              "64 is 128 MFMAs 16x16x32 per wave = 2048 clocks of matrix work on its SIMD; the traced "
+                              "kernel reads the clock around its waits and is a few percent slower than the plain one"}))
 
 
 def ceiling_sweep(tw, torch, np, stream, train_times):

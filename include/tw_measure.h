@@ -30,6 +30,31 @@ tw_status tw_reduce_add_rmsnorm_traced(const void *const *partials, const void *
                                        int P, int cu_budget, void *out, void *residual_out,
                                        uint32_t *hw_ids, int64_t hw_ids_len, void *stream);
 
+/*
+ * tw_gemm_bf16 (B stored [N x K], whole device) with a kernel that also counts,
+ * per wave, the shader clocks it spends in each phase of its K loop: evidence for
+ * where the cycles of the 256 x 256 tile's pipeline go. Only products that
+ * tw_gemm_bf16 would run on 256 x 256 tiles are accepted (TW_ERR_UNSUPPORTED
+ * otherwise). Wave w of workgroup g writes TW_GEMM_PHASES 64-bit sums to
+ * phase_cycles[(g * 4 + w) * TW_GEMM_PHASES + i]:
+ *   0  first sub-step of the K steps (64 MFMAs = 1024 clocks of matrix work each,
+ *      with the loads of one operand and the fragment reads of the second)
+ *   1  waiting for the next K step's loads to have landed
+ *   2  the workgroup barrier of a K step
+ *   3  second sub-step of the K steps (as 0, plus the bookkeeping of the next step)
+ *   4  from the start of a tile to its first MFMA (the pipeline filling)
+ *   5  the stores of a tile
+ *   6  tiles this wave worked on
+ *   7  the kernel from its first to its last instruction
+ * Reading the clock costs a scalar memory read and a wait each time: the traced
+ * kernel is a few percent slower than the plain one. phase_cycles: device memory,
+ * phase_len entries, at least (workgroups, at most one per compute unit) * 4 *
+ * TW_GEMM_PHASES (else TW_ERR_SHAPE). C receives the product as usual.
+ */
+#define TW_GEMM_PHASES 8
+tw_status tw_gemm_bf16_traced(const void *A, const void *B, void *C, int64_t M, int64_t N, int64_t K,
+                              unsigned long long *phase_cycles, int64_t phase_len, void *stream);
+
 /* Number of workgroups the fused kernel is launched with for these sizes on the
  * current device (0 if N == 0; -1 if the arguments are invalid or no device). */
 int64_t tw_fused_grid(int64_t N, int64_t H, int P, int cu_budget);

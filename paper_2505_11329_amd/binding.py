@@ -105,6 +105,8 @@ def lib():
         L.tw_weave_tune.argtypes = [ctypes.POINTER(LayerArgs), _i64, ctypes.POINTER(_i64), ctypes.c_int, ctypes.c_int,
                                     _vp, _vp, ctypes.POINTER(_i64), ctypes.POINTER(ctypes.c_float)]
         L.tw_weave_tune.restype = ctypes.c_int
+        L.tw_gemm_bf16_traced.argtypes = [_vp, _vp, _vp, _i64, _i64, _i64, _vp, _i64, _vp]
+        L.tw_gemm_bf16_traced.restype = ctypes.c_int
         L.tw_split_threshold.argtypes = [_i64, _i64, ctypes.c_int, _i64, ctypes.c_int]
         L.tw_split_threshold.restype = _i64
         L.tw_smart_split_point.argtypes = [_i64, _i64, ctypes.POINTER(_i64), ctypes.POINTER(_i64), ctypes.c_int,
@@ -436,6 +438,29 @@ def weave_layer_auto(X1, W1, partials, residual, weight, eps, W2, stream_compute
                                      1 if use_parent else 0, 1 if join else 0, ctypes.byref(taken)),
            "tw_weave_layer_auto")
     return out, residual_out, Y, int(taken.value)
+
+
+GEMM_PHASES = 8
+GEMM_PHASE_NAMES = ("sub_step_0", "wait_landed", "barrier", "sub_step_1", "tile_fill", "tile_stores", "tiles", "kernel")
+
+
+def gemm_bf16_traced(A, B, C=None, stream=None):
+    """tw_gemm_bf16_traced: C = A [M x K] * B [N x K]^T on 256 x 256 tiles with per-wave phase clocks.
+    Returns (C, cycles) with cycles an int64 tensor [waves, GEMM_PHASES] (device)."""
+    import torch
+    M, K = A.shape
+    N = B.shape[0]
+    if C is None:
+        C = torch.empty((M, N), dtype=torch.bfloat16, device=A.device)
+    waves = device_cu_count() * 4
+    if stream is None:
+        stream = torch.cuda.current_stream()
+    with torch.cuda.stream(stream):      # the zero fill must precede the kernel on the kernel's stream
+        cycles = torch.zeros((waves, GEMM_PHASES), dtype=torch.int64, device=A.device)
+    _check(lib().tw_gemm_bf16_traced(_bf16_ptr(A, "A", (M, K)), _bf16_ptr(B, "B", (N, K)), _bf16_ptr(C, "C", (M, N)),
+                                     M, N, K, _vp(cycles.data_ptr()), cycles.numel(), _stream_handle(stream)),
+           "tw_gemm_bf16_traced")
+    return C, cycles
 
 
 def weave_tune(X1, W1, partials, residual, weight, eps, W2, stream_compute, stream_comm, offsets=(), reps=5,

@@ -70,6 +70,10 @@ namespace tw {
 
 static constexpr int BM = kGemmTileM;
 static constexpr int kXcds = 8;
+// what the tracing variant counts per wave, in shader clocks (tw_measure.h lists them in this order)
+enum { kPhaseSub0, kPhaseLanded, kPhaseBarrier, kPhaseSub1, kPhaseFill, kPhaseStores, kPhaseTiles, kPhaseTotal };
+static constexpr int kGemmPhases = TW_GEMM_PHASES;
+static_assert(kPhaseTotal + 1 == kGemmPhases, "phase list");
 
 // A tile configuration: WM x WN blocks of 16 x 16 per wave, 32 / WM waves laid
 // out (16 / WM) x 2, hence a 256 x (32 * WN) workgroup tile; K steps of BK_;
@@ -108,6 +112,7 @@ struct GemmParams {
     int tiles_m, tiles_n;
     int group_m;        // tile rows per block of the tile ordering
     int tiles_per_xcd;  // ceil(tiles / 8)
+    unsigned long long *phase_cycles;  // tracing variant only: kGemmPhases counters per wave
 };
 
 // Byte offset inside a stage's A (or B) area of the 16-byte piece c of row r,
@@ -226,7 +231,12 @@ __device__ __forceinline__ void wait_lgkm(Frags<B_KN, WM, WN> &f)
     if constexpr (!B_KN && WM == 8 && WN == 8) TW_WAIT_LGKM(N, f, TW_FRAG_A8, TW_FRAG_B8);
 }
 
-template <bool B_KN, int WM, int WN, int STAGES, int BK>
+// TRACE (256 x 256 tiles only): every wave also adds up the shader clocks it
+// spends in each phase of the K loop and of a tile, and writes the sums out at
+// its end (tw_gemm_bf16_traced). Reading the clock costs a scalar memory read and
+// a wait for it each time, so the traced kernel is a few percent slower than the
+// plain one and its figures are for comparing phases, not for the total.
+template <bool B_KN, int WM, int WN, int STAGES, int BK, bool TRACE = false>
 __global__ __launch_bounds__(64 * (2 * BM / (kBlk * WM))) void gemm_bf16_kernel(const GemmParams prm)
 {
     // The body is for the device pass only: the host pass needs the launch stub,
@@ -251,6 +261,16 @@ __global__ __launch_bounds__(64 * (2 * BM / (kBlk * WM))) void gemm_bf16_kernel(
     static_assert(!B_KN || (WN == 4 && BK == 64), "[K x N] operands: 256 x 128 x 64 tiles only");
     static_assert(Cfg::kLdsBytes <= 160 * 1024, "LDS of one compute unit");
     static_assert(!kRing || (kSubs == 2 && !B_KN), "the ring schedule below");
+    static_assert(!TRACE || kRing, "phases are counted in the ring schedule");
+    // shader clock, with nothing of this wave's outstanding on the LDS/scalar counter afterwards
+    auto now = [&]() {
+        const unsigned long long t = __builtin_readcyclecounter();
+        asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
+        return t;
+    };
+    unsigned long long phase[kGemmPhases] = {};
+    unsigned long long t_prev = 0, t_kernel = 0;
+    if constexpr (TRACE) t_kernel = now();
 
     const int tid = threadIdx.x;
     const int lane = tid & 63;
@@ -331,6 +351,8 @@ __global__ __launch_bounds__(64 * (2 * BM / (kBlk * WM))) void gemm_bf16_kernel(
         const int tm = first_tm + in_grp % gsz;
         const int tn = in_grp / gsz;
 
+        unsigned long long t_tile = 0;
+        if constexpr (TRACE) t_tile = now();
         const long long m0 = static_cast<long long>(tm) * BM;
         const long long n0 = static_cast<long long>(tn) * BN;
         const int rows_a = static_cast<int>(min(static_cast<long long>(BM), prm.M - m0));
@@ -521,18 +543,38 @@ __global__ __launch_bounds__(64 * (2 * BM / (kBlk * WM))) void gemm_bf16_kernel(
             });
             wait_vm(std::integral_constant<int, kLoads>{});  // K step 0 has landed
             load_frags(f0, slot_off(0), slot_off(1), K0{});
+            if constexpr (TRACE) {
+                t_prev = now();
+                phase[kPhaseFill] += t_prev - t_tile;
+            }
             // byte offsets of the slots of this K step's A and B, of the next step's, and of the free one
             uint32_t o_a = slot_off(0), o_b = slot_off(1), o_na = slot_off(2), o_nb = slot_off(3), o_free = slot_off(4);
             FetchCtx fc = fetch_ctx(2, o_free, o_a);
             auto nothing = [] {};
             for (int kt = 0; kt < k_tiles; ++kt) {
                 wait_lgkm<0>(f0);
+                if constexpr (TRACE) {
+                    const unsigned long long t = now();
+                    phase[kPhaseSub1] += t - t_prev;  // (of the previous K step; the first one's share is nil)
+                    t_prev = t;
+                }
                 sub_step(f0, f1, o_a, o_b, std::integral_constant<int, 1>{}, fc, std::integral_constant<int, 0>{},
                          std::integral_constant<int, A_LOADS>{}, HalfSlots{}, nothing);
                 wait_lgkm<0>(f1);
                 // K step kt + 1 has landed when only the A loads just issued are outstanding;
                 // after the barrier nobody reads this step's slots any more
-                wait_vm(std::integral_constant<int, A_LOADS>{});
+                if constexpr (TRACE) {
+                    const unsigned long long t0 = now();
+                    phase[kPhaseSub0] += t0 - t_prev;
+                    __builtin_amdgcn_s_waitcnt(((A_LOADS >> 4) << 14) | 0x0F70 | (A_LOADS & 15));
+                    const unsigned long long t1 = now();
+                    phase[kPhaseLanded] += t1 - t0;
+                    __builtin_amdgcn_s_barrier();
+                    t_prev = now();
+                    phase[kPhaseBarrier] += t_prev - t1;
+                } else {
+                    wait_vm(std::integral_constant<int, A_LOADS>{});
+                }
                 sub_step(f1, f0, o_na, o_nb, K0{}, fc, std::integral_constant<int, A_LOADS>{},
                          std::integral_constant<int, B_LOADS>{}, HalfSlots{}, [&] {
                              // late in the sub-step, when its reads and loads are out: the slots
@@ -613,6 +655,12 @@ __global__ __launch_bounds__(64 * (2 * BM / (kBlk * WM))) void gemm_bf16_kernel(
         // fragment sets are still live.
         wait_lgkm<0>(f0);
         wait_lgkm<0>(f1);
+        unsigned long long t_stores = 0;
+        if constexpr (TRACE) {
+            t_stores = now();
+            phase[kPhaseSub1] += t_stores - t_prev;
+            phase[kPhaseTiles] += 1;
+        }
         // the prefetches past the end are still in flight and target LDS
         __builtin_amdgcn_s_waitcnt(0x0F70);  // vmcnt(0)
 
@@ -640,6 +688,14 @@ __global__ __launch_bounds__(64 * (2 * BM / (kBlk * WM))) void gemm_bf16_kernel(
                 __builtin_amdgcn_raw_buffer_store_b64(v, rc, c_off[nb], block_rows_bytes * mb, 0);
             }
             __builtin_amdgcn_sched_barrier(0);  // one block row's accumulators at a time
+        }
+        if constexpr (TRACE) phase[kPhaseStores] += now() - t_stores;
+    }
+    if constexpr (TRACE) {
+        phase[kPhaseTotal] = now() - t_kernel;
+        if (lane == 0) {
+            unsigned long long *dst = prm.phase_cycles + (static_cast<size_t>(blockIdx.x) * NW + wave) * kGemmPhases;
+            for (int i = 0; i < kGemmPhases; ++i) dst[i] = phase[i];
         }
     }
 #else
@@ -669,8 +725,9 @@ tw_status validate_gemm(const tw_gemm_args &g)
     return TW_OK;
 }
 
-template <bool B_KN, int WM, int WN, int STAGES, int BK>
-static tw_status launch_cfg(const tw_gemm_args &g, int budget, hipStream_t stream)
+template <bool B_KN, int WM, int WN, int STAGES, int BK, bool TRACE = false>
+static tw_status launch_cfg(const tw_gemm_args &g, int budget, hipStream_t stream,
+                            unsigned long long *phase_cycles = nullptr, int64_t phase_len = 0)
 {
     using Cfg = TileCfg<WM, WN, STAGES, BK>;
     constexpr int BN = Cfg::kBN;
@@ -681,6 +738,7 @@ static tw_status launch_cfg(const tw_gemm_args &g, int budget, hipStream_t strea
     prm.M = g.M;
     prm.N = g.N;
     prm.K = g.K;
+    prm.phase_cycles = phase_cycles;
     const int64_t tiles_m = (g.M + BM - 1) / BM, tiles_n = (g.N + BN - 1) / BN;
     if (tiles_m * tiles_n > (int64_t(1) << 30)) return TW_ERR_UNSUPPORTED;
     prm.tiles_m = static_cast<int>(tiles_m);
@@ -705,11 +763,12 @@ static tw_status launch_cfg(const tw_gemm_args &g, int budget, hipStream_t strea
     const int64_t slots = int64_t(prm.tiles_per_xcd) * kXcds;
     const unsigned grid = static_cast<unsigned>(slots < budget ? slots : budget);
 
+    if (TRACE && phase_len < int64_t(grid) * Cfg::kWaves * kGemmPhases) return TW_ERR_SHAPE;
     static std::atomic<int> allowed[kMaxDevices];
-    TW_TRY(allow_dynamic_lds(reinterpret_cast<const void *>(gemm_bf16_kernel<B_KN, WM, WN, STAGES, BK>), Cfg::kLdsBytes,
-                             allowed));
-    TW_HIP(launch_kernel(gemm_bf16_kernel<B_KN, WM, WN, STAGES, BK>, dim3(grid), dim3(Cfg::kThreads), Cfg::kLdsBytes,
-                         stream, prm));
+    TW_TRY(allow_dynamic_lds(reinterpret_cast<const void *>(gemm_bf16_kernel<B_KN, WM, WN, STAGES, BK, TRACE>),
+                             Cfg::kLdsBytes, allowed));
+    TW_HIP(launch_kernel(gemm_bf16_kernel<B_KN, WM, WN, STAGES, BK, TRACE>, dim3(grid), dim3(Cfg::kThreads),
+                         Cfg::kLdsBytes, stream, prm));
     return TW_OK;
 }
 
@@ -765,6 +824,22 @@ tw_status launch_gemm(const tw_gemm_args &g, hipStream_t stream, bool beside_oth
 }  // namespace tw
 
 using namespace tw;
+
+extern "C" tw_status tw_gemm_bf16_traced(const void *A, const void *B, void *C, int64_t M, int64_t N, int64_t K,
+                                         unsigned long long *phase_cycles, int64_t phase_len, void *stream)
+{
+    const tw_gemm_args g = {A, B, C, M, N, K, TW_B_NK, 0};
+    TW_TRY(validate_gemm(g));
+    if (!phase_cycles) return TW_ERR_NULL;
+    if (g.M == 0 || g.N == 0) return TW_ERR_UNSUPPORTED;
+    int cus = 0;
+    TW_TRY(current_cu_count(&cus));
+    // only a product that takes the 256 x 256 tiles on the whole device is traced
+    const int64_t tiles_m = (g.M + BM - 1) / BM;
+    const int64_t wide_tiles = tiles_m * ((g.N + kGemmTileN - 1) / kGemmTileN), big_tiles = tiles_m * ((g.N + 255) / 256);
+    if (2 * wide_tiles <= cus || wave_fill(big_tiles, cus) < wave_fill(wide_tiles, cus) - 0.05) return TW_ERR_UNSUPPORTED;
+    return launch_cfg<false, 8, 8, 2, 64, true>(g, cus, static_cast<hipStream_t>(stream), phase_cycles, phase_len);
+}
 
 extern "C" tw_status tw_gemm_bf16(const void *A, const void *B, void *C, int64_t M, int64_t N, int64_t K,
                                   int b_layout, int cu_budget, void *stream)

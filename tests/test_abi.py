@@ -37,7 +37,7 @@ def test_header_declares_the_documented_entry_points():
     aids = declared_functions(("tw_measure.h",))
     for must in ("tw_hbm_probe", "tw_hbm_probe_mixed", "tw_hbm_probe_shaped", "tw_hbm_probe_mixed_shaped",
                  "tw_fused_grid", "tw_fused_layout", "tw_weave_schedule", "tw_gemm_tile_shape",
-                 "tw_reduce_add_rmsnorm_traced", "tw_streams_overlap"):
+                 "tw_reduce_add_rmsnorm_traced", "tw_streams_overlap", "tw_gemm_bf16_traced"):
         assert must in aids and must not in names
 
 
@@ -462,6 +462,17 @@ def test_weave_tune_argument_checks():
     la.fused.H = H
     la.N2 = -8
     assert L.tw_weave_tune(ctypes.byref(la), *ok_args) == E_SHAPE
+
+
+def test_traced_gemm_argument_checks():
+    L = tw.lib()
+    L.tw_gemm_bf16_traced.argtypes = [VP, VP, VP, ctypes.c_int64, ctypes.c_int64, ctypes.c_int64, VP, ctypes.c_int64, VP]
+    small = (256, 128, 64)      # operands of 32, 16 and 64 KiB at the fake addresses
+    assert L.tw_gemm_bf16_traced(addr(0), addr(1), None, *small, addr(6), 1 << 20, None) == E_NULL
+    assert L.tw_gemm_bf16_traced(addr(0), addr(1), addr(3), *small, None, 1 << 20, None) == E_NULL
+    assert L.tw_gemm_bf16_traced(addr(0), addr(1), addr(3), 256, 128, 60, addr(6), 1 << 20, None) == E_UNSUP
+    assert L.tw_gemm_bf16_traced(addr(0), addr(1), addr(3), -1, 128, 64, addr(6), 1 << 20, None) == E_SHAPE
+    assert L.tw_gemm_bf16_traced(addr(0), addr(1), addr(0), *small, addr(6), 1 << 20, None) == E_ALIAS
 
 
 def test_fused_layout_covers_every_row_width_without_idle_waves():

@@ -211,3 +211,33 @@ def test_gemm_random_shapes_both_layouts(tw, torch_cuda):
         assert np.array_equal(to_bits(C1), to_bits(C2)), what
         assert np.array_equal(to_bits(C1), to_bits(C3)), what
         gemm_check(oracle.bf16_to_f64(to_bits(C1)), oracle.gemm(a["A"], a["B"], "nk"), K, 0.3, what)
+
+
+def test_traced_gemm_counts_phases_and_gives_the_same_product(tw, torch_cuda):
+    """The tracing variant of the 256 x 256 kernel: same bits as the plain call; every wave reports the
+    tiles it worked on (all of them together: the tile count), phases that add up to no more than its
+    total, and at least the matrix work's clocks in the two sub-steps (64 MFMAs of 16 clocks per sub-step
+    and K step). Products that would not take those tiles are refused."""
+    torch = torch_cuda
+    M, N, K = 4096, 4096, 1024
+    gen = torch.Generator(device="cuda:0")
+    gen.manual_seed(7)
+    A = torch.empty((M, K), dtype=torch.bfloat16, device="cuda:0").normal_(0.0, 0.05, generator=gen)
+    B = torch.empty((N, K), dtype=torch.bfloat16, device="cuda:0").normal_(0.0, 0.05, generator=gen)
+    want = tw.gemm_bf16(A, B, b_layout=tw.B_NK)
+    C, cycles = tw.gemm_bf16_traced(A, B)
+    torch.cuda.synchronize()
+    assert torch.equal(C.view(torch.int16), want.view(torch.int16))
+    c = cycles.cpu().numpy()
+    names = tw.GEMM_PHASE_NAMES
+    tiles = (M // 256) * (N // 256)
+    ran = c[:, names.index("tiles")] > 0
+    assert ran.sum() == min(tiles, tw.device_cu_count()) * 4
+    assert c[ran, names.index("tiles")].sum() == 4 * tiles
+    parts = c[:, :6].sum(axis=1)
+    assert (parts[ran] <= c[ran, names.index("kernel")]).all() and (c[ran, names.index("kernel")] < 10 ** 8).all()
+    steps = c[ran, names.index("tiles")] * (K // 64)
+    assert (c[ran, names.index("sub_step_0")] >= 1024 * steps).all()
+    assert (c[ran, names.index("sub_step_1")] >= 1024 * steps).all()
+    with pytest.raises(tw.TwError):
+        tw.gemm_bf16_traced(A[:256], B[:128])
