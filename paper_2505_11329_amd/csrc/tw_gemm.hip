@@ -664,65 +664,28 @@ __global__ __launch_bounds__(64 * (2 * BM / (kBlk * WM))) void gemm_bf16_kernel(
         // the prefetches past the end are still in flight and target LDS
         __builtin_amdgcn_s_waitcnt(0x0F70);  // vmcnt(0)
 
-        // Stores: a lane holds four consecutive columns of one row per block. Its byte
-        // offset inside the tile's rows of C is a vector register per block column
-        // (with the column tail folded in), the block row goes into the scalar offset,
-        // which the range check counts too: rows past M are dropped by the descriptor.
+        // Stores. The view of C covers the tile's rows: rows past M are dropped by the range
+        // check, which counts the scalar offset (the rows of the store instruction) too.
         const long long c_row_bytes = prm.N * 2;
         const __amdgpu_buffer_rsrc_t rc = make_rsrc(prm.C + m0 * c_row_bytes, static_cast<uint32_t>(rows_a * c_row_bytes));
-        if constexpr (kRing) {
-            // The 256 x 256 tile goes out through LDS (idle at this point; the ring is
-            // refilled by the next tile): each wave writes its 128 x 128 bf16 results into
-            // a region of its own, rows padded to 288 bytes, and reads them back as 16-byte
-            // pieces, so that a store instruction covers four rows of 256 contiguous bytes
-            // (whole 128-byte lines) instead of sixteen rows of 32, with half as many store
-            // instructions. And no global store is in flight while the accumulators are
-            // read: with all 256 accumulator registers taken the register allocator spills
-            // one, and a reload in the middle of the stores would wait for all of them.
-            constexpr int kRowPitch = kBlk * WN * 2 + 32;             // 288
-            constexpr int kRegion = kBlk * WM * kRowPitch;             // 36 KiB per wave
-            static_assert(NW * kRegion <= Cfg::kLdsBytes, "the waves' staging regions");
-            __builtin_amdgcn_s_barrier();  // every wave has fetched its last fragments: LDS is free
-            const uint32_t region = static_cast<uint32_t>(wave * kRegion);
-            const uint32_t w_addr = region + l15 * kRowPitch + lgrp * 8;
-#pragma unroll
-            for (int mb = 0; mb < WM; ++mb) {
-#pragma unroll
-                for (int nb = 0; nb < WN; ++nb) {
-                    u32x2 v;
-                    v.x = pack_bf16x2(acc[nb][mb][0], acc[nb][mb][1]);
-                    v.y = pack_bf16x2(acc[nb][mb][2], acc[nb][mb][3]);
-                    *reinterpret_cast<__attribute__((address_space(3))) u32x2 *>(
-                        static_cast<uintptr_t>(w_addr + mb * kBlk * kRowPitch + nb * kBlk * 2)) = v;
-                }
-                __builtin_amdgcn_sched_barrier(0);  // one block row's accumulators at a time
-            }
-            __builtin_amdgcn_s_waitcnt(0xC07F);  // lgkmcnt(0): the region is this wave's own, no barrier
-            // piece p = lane % 16 of row lane / 16 + 4 i: columns 8 p ... 8 p + 7 of the wave's 128
-            const int piece_c = lane & 15, row_c = lane >> 4;
-            const int n = static_cast<int>(n0) + wave_n * (kBlk * WN) + piece_c * 8;  // N < 2^23
-            const uint32_t g_off = n < static_cast<int>(prm.N)
-                                       ? static_cast<uint32_t>((wave_m * (kBlk * WM) + row_c) * c_row_bytes) + n * 2
-                                       : kPastK;
-            const uint32_t r_addr = region + row_c * kRowPitch + piece_c * 16;
-            const uint32_t four_rows_bytes = static_cast<uint32_t>(4 * c_row_bytes);
-#pragma unroll
-            for (int i = 0; i < kBlk * WM / 4; ++i) {
-                const u32x4 v = *reinterpret_cast<__attribute__((address_space(3))) u32x4 *>(
-                    static_cast<uintptr_t>(r_addr + i * 4 * kRowPitch));
-                __builtin_amdgcn_raw_buffer_store_b128(v, rc, g_off, four_rows_bytes * i, 0);
-            }
-            if constexpr (TRACE) phase[kPhaseStores] += now() - t_stores;
-            continue;
-        }
-        const uint32_t block_rows_bytes = static_cast<uint32_t>(kBlk * c_row_bytes);
-        uint32_t c_off[WN];
-#pragma unroll
-        for (int nb = 0; nb < WN; ++nb) {
-            const int n = static_cast<int>(n0) + wave_n * (kBlk * WN) + nb * kBlk + lgrp * 4;  // N < 2^23
-            const uint32_t off = static_cast<uint32_t>((wave_m * (kBlk * WM) + l15) * c_row_bytes) + n * 2;
-            c_off[nb] = n < static_cast<int>(prm.N) ? off : kPastK;
-        }
+        // The tile goes out through LDS (idle at this point; the next tile refills it):
+        // each wave writes its bf16 results into a region of its own, rows padded by 32
+        // bytes, and reads them back as 16-byte pieces, so that a store instruction
+        // covers whole rows of the wave's sub-tile (whole 128-byte lines where it is 64
+        // columns wide or more) instead of sixteen rows of 32 bytes, with half as many
+        // store instructions. And no global store is in flight while the accumulators
+        // are read: with all 256 accumulator registers of the 256 x 256 tile taken the
+        // register allocator spills one, and a reload in the middle of the stores would
+        // wait for all of them.
+        constexpr int kRowPitch = kBlk * WN * 2 + 32;
+        constexpr int kRegion = kBlk * WM * kRowPitch;
+        constexpr int kPieces = kBlk * WN * 2 / 16;          // 16-byte pieces per row of the sub-tile
+        constexpr int kRowsPerStore = 64 / kPieces;          // rows one store instruction covers
+        static_assert(NW * kRegion <= Cfg::kLdsBytes && 64 % kPieces == 0 && (kBlk * WM) % kRowsPerStore == 0,
+                      "the waves' staging regions");
+        __builtin_amdgcn_s_barrier();  // every wave has fetched its last fragments: LDS is free
+        const uint32_t region = static_cast<uint32_t>(wave * kRegion);
+        const uint32_t w_addr = region + l15 * kRowPitch + lgrp * 8;
 #pragma unroll
         for (int mb = 0; mb < WM; ++mb) {
 #pragma unroll
@@ -730,9 +693,25 @@ __global__ __launch_bounds__(64 * (2 * BM / (kBlk * WM))) void gemm_bf16_kernel(
                 u32x2 v;
                 v.x = pack_bf16x2(acc[nb][mb][0], acc[nb][mb][1]);
                 v.y = pack_bf16x2(acc[nb][mb][2], acc[nb][mb][3]);
-                __builtin_amdgcn_raw_buffer_store_b64(v, rc, c_off[nb], block_rows_bytes * mb, 0);
+                *reinterpret_cast<__attribute__((address_space(3))) u32x2 *>(
+                    static_cast<uintptr_t>(w_addr + mb * kBlk * kRowPitch + nb * kBlk * 2)) = v;
             }
             __builtin_amdgcn_sched_barrier(0);  // one block row's accumulators at a time
+        }
+        __builtin_amdgcn_s_waitcnt(0xC07F);  // lgkmcnt(0): the region is this wave's own, no barrier
+        // piece lane % kPieces of row lane / kPieces + kRowsPerStore * i
+        const int piece_c = lane % kPieces, row_c = lane / kPieces;
+        const int n = static_cast<int>(n0) + wave_n * (kBlk * WN) + piece_c * 8;  // N < 2^23
+        const uint32_t g_off = n < static_cast<int>(prm.N)
+                                   ? static_cast<uint32_t>((wave_m * (kBlk * WM) + row_c) * c_row_bytes) + n * 2
+                                   : kPastK;
+        const uint32_t r_addr = region + row_c * kRowPitch + piece_c * 16;
+        const uint32_t store_rows_bytes = static_cast<uint32_t>(kRowsPerStore * c_row_bytes);
+#pragma unroll
+        for (int i = 0; i < kBlk * WM / kRowsPerStore; ++i) {
+            const u32x4 v = *reinterpret_cast<__attribute__((address_space(3))) u32x4 *>(
+                static_cast<uintptr_t>(r_addr + i * kRowsPerStore * kRowPitch));
+            __builtin_amdgcn_raw_buffer_store_b128(v, rc, g_off, store_rows_bytes * i, 0);
         }
         if constexpr (TRACE) phase[kPhaseStores] += now() - t_stores;
     }
