@@ -378,10 +378,10 @@ int tw_should_split(int64_t num_tokens, int64_t threshold);
  * On MI355X this gives 8192 for [T x 1024] x [1024 x 8192] -> F(H = 8192, P = 8)
  * -> [T x 8192] x [8192 x 3584] and TW_NEVER_SPLIT for the MLP-side boundary
  * with K1 = 3584, N2 = 1280. Profiling agrees on the whole and not in every
- * point: the first boundary gains 3 to 16 % from 8K to 24K tokens and loses 5 %
- * at 32K, where the unsplit GEMMs happen to fill the device with whole waves of
- * their largest tiles; the second stays within +2 and -6 % of break-even
- * throughout. What a split gains here comes as much from how the tiles of the
+ * point: the first boundary gains 5 % at 8K tokens and 10 to 14 % from 14K to
+ * 24K, is level to 3 % behind at 12K, and loses 2 to 5 % at 32K, where the
+ * unsplit GEMMs happen to fill the device with whole waves of their largest
+ * tiles; the second stays within +4 and -6 % of break-even throughout. What a split gains here comes as much from how the tiles of the
  * halves and of the whole batch fall on the compute units as from the overlap,
  * which no single threshold captures: tw_weave_tune measures it.
  * Host only. Returns -1 on bad arguments (any size < 1).
