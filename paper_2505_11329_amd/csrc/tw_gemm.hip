@@ -769,13 +769,18 @@ static tw_status launch_cfg(const tw_gemm_args &g, int budget, hipStream_t strea
     prm.tiles_n = static_cast<int>(tiles_n);
     const int64_t total = tiles_m * tiles_n;
     prm.tiles_per_xcd = static_cast<int>((total + kXcds - 1) / kXcds);
-    // Block shape of the tile ordering: an XCD's share of tiles_per_xcd tiles
-    // should touch as few distinct rows of A and columns of B as possible.
+    // Block shape of the tile ordering: the tiles an XCD works on at one time (one per
+    // compute unit it contributes to the launch) should touch as few distinct rows of A
+    // and columns of B as possible, i.e. form a block as square as the tile shape lets
+    // them: what they fetch at one K step they fetch once into that XCD's L2. (Sizing the
+    // block by the XCD's whole share of the tile list instead made the blocks twice as
+    // tall as wide for large products: 6 % slower on a 16K-token layer boundary.)
+    const int64_t at_once = (int64_t(budget) + kXcds - 1) / kXcds;
     int best_gm = 1;
     int64_t best_cost = INT64_MAX;
     for (int gm = 1; gm <= 8; gm *= 2) {
         if (gm > tiles_m && gm != 1) break;
-        const int64_t gn = (prm.tiles_per_xcd + gm - 1) / gm;
+        const int64_t gn = (at_once + gm - 1) / gm;
         const int64_t cost = int64_t(gm) * BM + gn * BN;
         if (cost < best_cost) {
             best_cost = cost;
