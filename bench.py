@@ -795,16 +795,26 @@ def extras(result, tw, W, torch, np, stream, sets, fused_sets, algo_bytes, event
         C_ = torch.empty((M_, N_), dtype=torch.bfloat16, device="cuda:0")
         torch.cuda.synchronize()
         fl = 2.0 * M_ * N_ * K_
-        t = float(np.median(train_times([lambda: tw.gemm_bf16(A_, B_, C=C_, cu_budget=0, stream=stream)],
-                                        5, 4, 3, stream)))
+        def vendor():
+            with torch.cuda.stream(stream):
+                torch.matmul(A_, B_.t(), out=C_)
+        # the library's kernel and the vendor library's (through torch.matmul) take turns, twice
+        ts, tv = [], []
+        for _ in range(2):
+            ts.append(train_times([lambda: tw.gemm_bf16(A_, B_, C=C_, cu_budget=0, stream=stream)], 4, 4, 3, stream))
+            tv.append(train_times([vendor], 4, 4, 3, stream))
+        t, v = float(np.median(np.concatenate(ts))), float(np.median(np.concatenate(tv)))
         gem["%dx%dx%d" % (M_, N_, K_)] = {"us": round(t, 1), "TFLOPs": round(fl / t / 1e6, 1),
-                                          "frac_mfma_peak": round(fl / t / 1e6 / MFMA_BF16_PEAK_TFLOPS, 4)}
+                                          "frac_mfma_peak": round(fl / t / 1e6 / MFMA_BF16_PEAK_TFLOPS, 4),
+                                          "vendor_library_us": round(v, 1),
+                                          "speed_over_vendor_library": round(v / t, 3)}
         del A_, B_, C_
     result["gemm"] = {"per_shape_MxNxK": gem,
                       "note": "tw_gemm_bf16 alone on the whole device, A and B ~ N(0, 0.02^2) drawn on the GPU, trains of "
                               "4 launches; peak = 2500 TFLOP/s dense bf16. The part runs these at its power limit "
                               "(1.2-1.9 GHz against 2.4 GHz idle): a loop of nothing but MFMAs on such operands "
-                              "sustains 1990 TFLOP/s"}
+                              "sustains 1990 TFLOP/s. vendor_library_us: torch.matmul (hipBLASLt) on the same tensors, for "
+                              "context"}
     torch.cuda.empty_cache()
 
     # one woven layer boundary (G1 -> fused -> G2), T = 4096 tokens, attention-side shapes of a 70B-class
