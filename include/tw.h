@@ -291,7 +291,8 @@ tw_status tw_overlap_launch(const tw_fused_args *fused, const tw_gemm_args *gemm
  *       because the GEMMs leave its compute units alone only while no two of them
  *       overlap.
  * With split_row == 0 or == T the chain G1, F, G2 runs unsplit on stream_compute
- * alone (nothing overlaps, no events).
+ * alone (nothing overlaps, no events; a fused step asked to share the compute
+ * units, TW_CU_SHARED, has them to itself there and runs as a whole-device launch).
  * Results are bit-identical for every split_row and schedule.
  *
  *   X1, W1, K1   device bf16 [T x K1] and [H x K1] (TW_B_NK), K1 a multiple of 8

@@ -330,9 +330,13 @@ tw_status tw_weave_layer(const tw_layer_args *layer, int64_t split_row, void *st
     const int64_t cuts[3] = {0, (split_row == 0 || split_row == T) ? T : split_row, T};
     const int n_splits = cuts[1] == T ? 1 : 2;
     if (n_splits == 1) {
-        // nothing to weave: the chain runs on the compute stream, with no events
+        // nothing to weave: the chain runs on the compute stream, with no events. A
+        // fused step that was to share the compute units has them to itself here and
+        // takes whichever kernel the whole device runs fastest (same bits).
         TW_TRY(launch_gemm(g1, sx));
-        TW_TRY(launch_fused(f, 0, T, nullptr, 0, sx));
+        tw_fused_args alone = f;
+        if (alone.cu_budget == TW_CU_SHARED) alone.cu_budget = 0;
+        TW_TRY(launch_fused(alone, 0, T, nullptr, 0, sx));
         TW_TRY(launch_gemm(g2, sx));
         if (parent_is_set && join && sx != sp) TW_TRY(stream_wait_stream(sp, sx));
         return TW_OK;
