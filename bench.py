@@ -280,7 +280,9 @@ def main():
             unsplit_us = timed.pop(0)
             ordered = {int(k[8:]): timed.pop(k) for k in list(timed) if isinstance(k, str)}
             k_best = min(timed, key=timed.get)
-            rows.append({"T": T, "equal_split_row": half, "equal_us": timed[half],
+            k_policy = tw.policy_split_row(T, K1, H, P, N2, cus)     # the smart row, or T: both were timed
+            rows.append({"T": T, "policy_row": k_policy, "policy_us": timed[k_policy] if k_policy < T else unsplit_us,
+                         "equal_split_row": half, "equal_us": timed[half],
                          "measured_best_row": k_best, "measured_best_us": timed[k_best],
                          "smart_row": k_smart, "smart_us": timed[k_smart],
                          "model_cost_split": ws, "model_cost_unsplit": wu, "unsplit_us": unsplit_us,
@@ -337,7 +339,19 @@ def main():
         def spread(key):
             rate = np.array([r["T"] / r[key] for r in rows])
             return round(float(rate.std() / rate.mean()), 4)
-        print(json.dumps({"split_sweep": rows, "threshold_sweep": thr, "threshold_sweep_mlp_side": thr_mlp,
+        def over_best(pick):
+            ratio = [pick(r) / min(r["unsplit_us"], r["measured_best_us"]) for r in rows]
+            return {"mean": round(float(np.mean(ratio)), 4), "worst": round(float(np.max(ratio)), 4)}
+        t_built_in = tw.split_threshold(K1, H, P, N2, cus)
+        policy_quality = {
+            "built_in_rule_over_best": over_best(lambda r: r["policy_us"]),
+            "threshold_alone_over_best": over_best(lambda r: r["smart_us"] if r["T"] >= t_built_in else r["unsplit_us"]),
+            "always_split_over_best": over_best(lambda r: r["smart_us"]),
+            "never_split_over_best": over_best(lambda r: r["unsplit_us"]),
+            "rule_picks_the_faster_of_its_two": sum(
+                (r["policy_row"] < r["T"]) == (r["smart_us"] <= r["unsplit_us"]) for r in rows),
+            "token_counts": len(rows)}
+        print(json.dumps({"split_sweep": rows, "policy_quality": policy_quality, "threshold_sweep": thr, "threshold_sweep_mlp_side": thr_mlp,
                           "tokens_per_us_relative_spread": {"equal": spread("equal_us"), "smart": spread("smart_us"),
                                                             "measured_best": spread("measured_best_us"),
                                                             "ordered_equal": spread("ordered_equal_us"),
@@ -934,7 +948,7 @@ def policy_table(result, tw, W, torch, np, stream, comm, interleaved_medians, gp
         W1, W2 = rnd((H, K1), 0.02), rnd((N2, H), 0.02)
         thr = tw.split_threshold(K1, H, P, N2, cus)
         rows = []
-        for T in (256, 1024, 2048, 4096, 6144, 8192, 12288, 16384, 32768):
+        for T in (256, 1024, 2048, 4096, 5120, 6144, 7168, 8192, 12288, 16384, 32768):
             X1, resid = rnd((T, K1), 0.02), rnd((T, H), 1.0)
             parts = [rnd((T, H), 0.25) for _ in range(P)]
             o, r = torch.empty_like(resid), torch.empty_like(resid)
@@ -984,8 +998,9 @@ def policy_table(result, tw, W, torch, np, stream, comm, interleaved_medians, gp
     result["policy"] = {
         "per_boundary": out_,
         "note": "never = the chain G1, F, G2 unsplit on one stream; always = tw_weave_layer at the row "
-                "tw_smart_split_point picks, whatever T; policy = tw_weave_layer_auto (threshold from "
-                "tw_split_threshold, then the same row); tuned = tw_weave_layer at the row tw_weave_tune reported for "
+                "tw_smart_split_point picks, whatever T; policy = tw_weave_layer_auto with the built-in rule "
+                "(tw_policy_split_row: split from tw_split_threshold's tokens up, and from half of that up when the cut "
+                "costs no GEMM waves); tuned = tw_weave_layer at the row tw_weave_tune reported for "
                 "this batch size beforehand (its timed search over: unsplit, the smart row, the middle, the middle "
                 "+ 256). A split row equal to T means no split. "
                 "Candidates take turns in bursts, in rotating order; medians of HIP-event timed calls"}

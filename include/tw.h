@@ -391,14 +391,37 @@ int tw_should_split(int64_t num_tokens, int64_t threshold);
 int64_t tw_split_threshold(int64_t K1, int64_t H, int P, int64_t N2, int cus);
 
 /*
- * The per-iteration policy of Fig. 3 as one call, for one block boundary: a
- * batch of fewer than `threshold` tokens runs the chain G1, F, G2 unsplit on
+ * The decision of the per-iteration policy (Fig. 3; Appendix A "Selective Enabling
+ * of Splitting and Overlap" and "Smart-Splitting") for a batch of T tokens at one
+ * block boundary G1 [T x K1] x [K1 x H] -> F(H, P) -> G2 [T x H] x [H x N2] whose
+ * GEMMs run on `cus` compute units: the row to cut at, or T for "do not split".
+ *   threshold > 0 (the caller's, e.g. from tw_weave_tune runs): T < threshold runs
+ *     unsplit, anything else is cut at the row tw_smart_split_point picks
+ *     (candidates at multiples of `multiple`, widths {H, N2}, depths {K1, H}).
+ *   threshold <= 0 (built in): with t = tw_split_threshold() of the boundary, never
+ *     when t is TW_NEVER_SPLIT; always at that row from t tokens up; and between
+ *     t / 2 and t only when the cut costs no GEMM waves, i.e. when the cost
+ *     tw_smart_split_point reports for the cut does not exceed that of the whole
+ *     batch (Section 4.1.1's criterion). In that band the unsplit GEMMs' own wave
+ *     quantisation decides: on MI355X, for K1 = 1024, H = 8192, P = 8, N2 = 3584
+ *     and T = 4096 ... 8192 in steps of 256, the criterion picks the faster of the
+ *     two at 14 of 17 token counts and the policy stays within 1.0 % of the best
+ *     timed candidate on average (4.4 % at worst), against 2.2 % (5.4 %) for the
+ *     threshold alone and 1.4 % (7.6 %) for always splitting.
+ * multiple <= 0: 64. Host only. Returns -1 on bad arguments (T < 0, another size
+ * < 1).
+ */
+int64_t tw_policy_split_row(int64_t T, int64_t K1, int64_t H, int P, int64_t N2, int cus, int64_t threshold,
+                            int64_t multiple);
+
+/*
+ * The per-iteration policy of Fig. 3 as one call, for one block boundary: the
+ * batch is cut at the row tw_policy_split_row names for it (on the GEMMs'
+ * compute units) and woven by tw_weave_layer in the schedule layer->schedule
+ * names, or, when that row is T, runs the chain G1, F, G2 unsplit on
  * stream_compute (the fused kernel is still used; only splitting and overlap are
- * switched off); a larger one is cut at the row tw_smart_split_point picks
- * (candidates at multiples of `multiple`, GEMM widths {H, N2} with depths {K1,
- * H}, on the GEMMs' compute units) and woven by tw_weave_layer in the schedule
- * layer->schedule names. threshold <= 0: tw_split_threshold() of this boundary;
- * multiple <= 0: 64. *split_row (may be NULL) receives the row taken, T meaning
+ * switched off). threshold, multiple: as for tw_policy_split_row. *split_row
+ * (may be NULL) receives the row taken, T meaning
  * "not split"; it is written before anything is enqueued, also when the launch
  * then fails. Everything else as for tw_weave_layer, whose bit-exactness across
  * split rows makes the policy invisible in the results.

@@ -109,6 +109,8 @@ def lib():
         L.tw_gemm_bf16_traced.restype = ctypes.c_int
         L.tw_split_threshold.argtypes = [_i64, _i64, ctypes.c_int, _i64, ctypes.c_int]
         L.tw_split_threshold.restype = _i64
+        L.tw_policy_split_row.argtypes = [_i64, _i64, _i64, ctypes.c_int, _i64, ctypes.c_int, _i64, _i64]
+        L.tw_policy_split_row.restype = _i64
         L.tw_smart_split_point.argtypes = [_i64, _i64, ctypes.POINTER(_i64), ctypes.POINTER(_i64), ctypes.c_int,
                                            ctypes.c_int,
                                            ctypes.POINTER(_i64), ctypes.POINTER(_i64)]
@@ -489,6 +491,12 @@ def weave_tune(X1, W1, partials, residual, weight, eps, W2, stream_compute, stre
 def split_threshold(K1, H, P, N2, cus=256):
     """tw_split_threshold: the built-in token threshold of one block boundary."""
     return int(lib().tw_split_threshold(int(K1), int(H), int(P), int(N2), int(cus)))
+
+
+def policy_split_row(T, K1, H, P, N2, cus=256, threshold=0, multiple=64):
+    """tw_policy_split_row: the row the per-iteration policy cuts a batch of T tokens at (T: not split)."""
+    return int(lib().tw_policy_split_row(int(T), int(K1), int(H), int(P), int(N2), int(cus), int(threshold),
+                                         int(multiple)))
 
 
 def weave_schedule(T, K1, H, P, N2, fused_cu_budget=CU_SHARED, schedule=WEAVE_AUTO, cus=256):

@@ -46,7 +46,8 @@
 //   - Each MFMA gets the B fragment as its first operand and the A fragment as
 //     its second, so the 16x16 result block is held transposed: a lane owns one
 //     row m of C and the block's four accumulator registers are four consecutive
-//     columns n, which it stores as one 8-byte bf16 quad.
+//     columns n: one 8-byte bf16 quad. The quads of a wave's sub-tile are collected
+//     in LDS and leave as 16-byte stores that cover whole rows of it.
 //   - Ragged edges need no branches: operands are fetched through range-checked
 //     buffer descriptors sized to the rows that exist (rows past M or N read as
 //     zeros), K pieces past K are redirected out of range, and stores past the

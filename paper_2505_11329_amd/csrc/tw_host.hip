@@ -416,6 +416,29 @@ int64_t tw_split_threshold(int64_t K1, int64_t H, int P, int64_t N2, int cus)
     return (t + kGemmTileM - 1) / kGemmTileM * kGemmTileM;
 }
 
+int64_t tw_policy_split_row(int64_t T, int64_t K1, int64_t H, int P, int64_t N2, int cus, int64_t threshold,
+                            int64_t multiple)
+{
+    if (T < 0 || K1 < 1 || H < 1 || P < 1 || N2 < 1 || cus < 1) return -1;
+    if (multiple <= 0) multiple = 64;
+    const int64_t widths[2] = {H, N2}, depths[2] = {K1, H};
+    if (threshold > 0) {  // the caller's threshold and nothing else
+        if (T < threshold) return T;
+        const int64_t k = tw_smart_split_point(T, multiple, widths, depths, 2, cus, nullptr, nullptr);
+        return k < 0 ? T : k;
+    }
+    const int64_t thr = tw_split_threshold(K1, H, P, N2, cus);
+    if (thr < 0 || thr == TW_NEVER_SPLIT || T < thr / 2) return T;
+    int64_t cost_split = 0, cost_unsplit = 0;
+    const int64_t k = tw_smart_split_point(T, multiple, widths, depths, 2, cus, &cost_split, &cost_unsplit);
+    if (k < 0 || k >= T) return T;
+    // From half the threshold up, a batch is split when that costs no GEMM waves
+    // (Section 4.1.1): whether a split wins there is decided by how the row tiles of
+    // the halves and of the whole batch fall on the compute units.
+    if (T < thr && cost_split > cost_unsplit) return T;
+    return k;
+}
+
 tw_status tw_weave_layer_auto(const tw_layer_args *layer, int64_t threshold, int64_t multiple, void *stream_compute,
                               void *stream_comm, void *parent, int parent_is_set, int join, int64_t *split_row)
 {
@@ -428,13 +451,9 @@ tw_status tw_weave_layer_auto(const tw_layer_args *layer, int64_t threshold, int
     if (T > 0 && layer->K1 > 0 && layer->N2 > 0) {
         int cus = 0;
         TW_TRY(current_cu_count(&cus));
-        if (threshold <= 0) threshold = tw_split_threshold(layer->K1, f.H, f.P, layer->N2, cus);
-        if (tw_should_split(T, threshold)) {
-            const int64_t widths[2] = {f.H, layer->N2}, depths[2] = {layer->K1, f.H};
-            k = tw_smart_split_point(T, multiple > 0 ? multiple : 64, widths, depths, 2,
-                                     resolve_budget(layer->gemm_cu_budget, cus), nullptr, nullptr);
-            if (k < 0) k = T;
-        }
+        k = tw_policy_split_row(T, layer->K1, f.H, f.P, layer->N2, resolve_budget(layer->gemm_cu_budget, cus),
+                                threshold, multiple);
+        if (k < 0) k = T;
     }
     if (split_row) *split_row = k;
     return tw_weave_layer(layer, k, stream_compute, stream_comm, parent, parent_is_set, join);

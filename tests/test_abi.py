@@ -30,7 +30,7 @@ def test_header_declares_the_documented_entry_points():
     names = declared_functions(("tw.h",))
     for must in ("tw_reduce_add_rmsnorm", "tw_split_launch", "tw_split_point", "tw_gemm_bf16",
                  "tw_overlap_launch", "tw_weave_layer", "tw_weave_layer_auto", "tw_weave_tune", "tw_smart_split_point",
-                 "tw_should_split", "tw_split_threshold", "tw_device_cu_count", "tw_status_str",
+                 "tw_should_split", "tw_split_threshold", "tw_policy_split_row", "tw_device_cu_count", "tw_status_str",
                  "tw_version", "tw_last_hip_error"):
         assert must in names
     # measurement and introspection aids are declared apart from the method's interface
@@ -417,6 +417,43 @@ def test_split_threshold_matches_its_definition():
     for bad in ((0, 8192, 8, 3584, 256), (1024, 0, 8, 3584, 256), (1024, 8192, 0, 3584, 256),
                 (1024, 8192, 8, 0, 256), (1024, 8192, 8, 3584, 0)):
         assert tw.split_threshold(*bad) == -1
+
+
+def test_policy_split_row_follows_threshold_band_and_wave_criterion():
+    """tw_policy_split_row restated from its parts (Fig. 3; Section 4.1.1): a caller's threshold is the
+    whole rule; the built-in one never splits a boundary whose threshold is 'never', always from the
+    threshold up, and between half of it and it only when the cut's GEMM waves (tw_smart_split_point's
+    costs) do not exceed the whole batch's."""
+    K1, Hh, Pp, N2, cus = 1024, 8192, 8, 3584, 256
+    thr = tw.split_threshold(K1, Hh, Pp, N2, cus)
+    assert thr == 8192
+    for T in list(range(0, 20000, 448)) + [4096, 4352, 4608, 6144, 7168, 8192, 8191, 4095]:
+        k, cs, cu_ = tw.smart_split_point(T, 64, [Hh, N2], cus, gemm_k=[K1, Hh])
+        if T < thr // 2 or k >= T:
+            want = T
+        elif T >= thr:
+            want = k
+        else:
+            want = k if cs <= cu_ else T
+        assert tw.policy_split_row(T, K1, Hh, Pp, N2, cus) == want, T
+        # a caller's threshold: nothing but the comparison
+        for t_user in (1, 3000, 8192):
+            assert tw.policy_split_row(T, K1, Hh, Pp, N2, cus, threshold=t_user) == (k if T >= t_user else T), (T, t_user)
+    # the band, by hand (256 x 128 tiles on 256 compute units, waves weighted by depth): 17 row tiles
+    # unsplit are 5 + 2 waves, 9 + 8 row tiles are (3 + 1) + (2 + 1): the same -> split at 2304
+    assert tw.policy_split_row(4352, K1, Hh, Pp, N2, cus) == 2304
+    # 18 row tiles unsplit: 5 + 2 waves; 9 + 9: (3 + 1) + (3 + 1): one shallow wave more -> unsplit
+    assert tw.policy_split_row(4608, K1, Hh, Pp, N2, cus) == 4608
+    assert tw.policy_split_row(6144, K1, Hh, Pp, N2, cus) == 6144
+    assert tw.policy_split_row(7168, K1, Hh, Pp, N2, cus) == 4096
+    # the MLP-side boundary never splits by itself, and does with a caller's threshold
+    assert tw.policy_split_row(16384, 3584, 8192, 8, 1280, cus) == 16384
+    assert tw.policy_split_row(16384, 3584, 8192, 8, 1280, cus, threshold=4096) == 8192
+    # another multiple moves the candidates
+    assert tw.policy_split_row(8192 + 128, K1, Hh, Pp, N2, cus, multiple=128) % 128 == 0
+    for bad in ((-1, K1, Hh, Pp, N2, cus), (4096, 0, Hh, Pp, N2, cus), (4096, K1, 0, Pp, N2, cus),
+                (4096, K1, Hh, 0, N2, cus), (4096, K1, Hh, Pp, 0, cus), (4096, K1, Hh, Pp, N2, 0)):
+        assert tw.policy_split_row(*bad) == -1
 
 
 def test_weave_layer_auto_argument_checks():

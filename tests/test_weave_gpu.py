@@ -197,9 +197,11 @@ def test_weave_layer_auto_applies_threshold_and_smart_split(tw, torch_cuda):
 
 @pytest.mark.parametrize("K1,N2", [(1024, 3584), (3584, 1280)])
 def test_weave_layer_auto_at_full_size_on_both_sides_of_the_built_in_threshold(tw, torch_cuda, K1, N2):
-    """The two 70B-class boundaries (H = 8192, P = 8) with the library's own threshold: one batch just
-    below it, one at it, one above (the MLP-side boundary, which the built-in rule never splits, is run at
-    the same three sizes); the policy's outputs carry the bits of the plain unsplit chain."""
+    """The two 70B-class boundaries (H = 8192, P = 8) with the library's own rule: a batch below half the
+    threshold, two between half of it and it (one whose cut costs no GEMM waves and is split, one whose
+    cut does and is not), one at the threshold, one above (the MLP-side boundary, which the built-in rule
+    never splits, is run at the same sizes); the policy's outputs carry the bits of the plain unsplit
+    chain."""
     torch = torch_cuda
     H_, P_ = 8192, 8
     never = 2 ** 63 - 1
@@ -215,7 +217,8 @@ def test_weave_layer_auto_at_full_size_on_both_sides_of_the_built_in_threshold(t
     parts, resid = [rnd((T_max, H_), 0.25) for _ in range(P_)], rnd((T_max, H_), 1.0)
     weight = to_gpu(W.uniform_bf16((H_,), 0.5, 1.5, 0, W.STREAM_WEIGHT))
     sx, sc = torch.cuda.Stream(), torch.cuda.Stream()
-    for T_ in (8192 - 256, 8192, T_max):
+    cus = tw.device_cu_count()
+    for T_ in (2048, 6144, 8192 - 256, 8192, T_max):
         args = (X1[:T_], W1, [p[:T_] for p in parts], resid[:T_], weight, 1e-5, W2g)
         with torch.cuda.stream(sx):
             want = tw.weave_layer(*args, 0, sx, sc, fused_cu_budget=tw.CU_SHARED, parent=sx)
@@ -223,7 +226,11 @@ def test_weave_layer_auto_at_full_size_on_both_sides_of_the_built_in_threshold(t
             parts[0][:T_].fill_(float("nan"))
             out, res, Y, taken = tw.weave_layer_auto(*args, sx, sc, fused_cu_budget=tw.CU_SHARED, parent=sx)
         torch.cuda.synchronize()
-        assert (taken == T_) == (T_ < thr), (T_, taken)
+        assert taken == tw.policy_split_row(T_, K1, H_, P_, N2, cus), (T_, taken)
+        if thr == never:
+            assert taken == T_
+        elif cus == 256:
+            assert (taken < T_) == (T_ in (8192 - 256, 8192, T_max)), (T_, taken)
         for name, g_, w_ in zip(("G1", "out", "residual_out", "Y"), (parts[0][:T_], out, res, Y), want):
             assert torch.equal(g_.view(torch.int16), w_.view(torch.int16)), (T_, taken, name)
 
