@@ -220,7 +220,9 @@ int64_t tw_split_point(int64_t N, int64_t multiple);
  *   C         device bf16 [M x N], row-major; must not overlap A or B
  *   M, N, K   >= 0 (any zero: TW_OK, C untouched unless K == 0 and M*N > 0, in
  *             which case C is zero-filled); K must be a multiple of 8 and N a
- *             multiple of 8 (16-byte vectors), else TW_ERR_UNSUPPORTED
+ *             multiple of 8 (16-byte vectors), and K, N <= 2^22, M <= 2^40 (a
+ *             tile's rows are addressed with 32-bit byte offsets), else
+ *             TW_ERR_UNSUPPORTED
  *   cu_budget persistent grid of at most this many workgroups (one per compute
  *             unit); <= 0 or >= the CU count: whole device
  * The result bits depend on A, B and K only: not on the budget, the layout of B,

@@ -233,6 +233,9 @@ def test_gemm_argument_checks():
     assert gemm_call(A=None) == E_NULL
     assert gemm_call(K=12) == E_UNSUP
     assert gemm_call(Nn=12) == E_UNSUP
+    # a tile's rows are addressed with 32-bit byte offsets: K and N stop at 2^22
+    assert gemm_call(K=(1 << 22) + 8) == E_UNSUP
+    assert gemm_call(Nn=(1 << 22) + 8) == E_UNSUP
     assert gemm_call(A=addr(0) + 2) == E_ALIGN
     assert gemm_call(C=addr(0)) == E_ALIAS
     assert gemm_call(C=addr(20) + 16) == E_ALIAS

@@ -99,6 +99,56 @@ def test_gemm_k_zero_gives_zeros(tw, torch_cuda):
         assert (to_bits(C) == 0).all()
 
 
+def test_gemm_at_the_largest_k(tw, torch_cuda):
+    """K = 2^22, the deepest product the entry point accepts: rows of 8 MiB, a full 256-row tile of A is
+    2 GiB, and every byte offset inside it still has to fit the 32 bits a buffer instruction adds up.
+    Inputs drawn on the GPU; rows 0, 63, 64, 191 and 255 of the tile (the first and last rows of the
+    first, second and last load instruction) and two rows of a ragged second tile against the fp64
+    product of those rows."""
+    torch = torch_cuda
+    M, N, K, std = 256 + 3, 16, 1 << 22, 0.02
+    gen = torch.Generator(device="cuda:0")
+    gen.manual_seed(22)
+    A = torch.empty((M, K), dtype=torch.bfloat16, device="cuda:0").normal_(0.0, std, generator=gen)
+    B = torch.empty((N, K), dtype=torch.bfloat16, device="cuda:0").normal_(0.0, std, generator=gen)
+    C = tw.gemm_bf16(A, B)
+    torch.cuda.synchronize()
+    rows = [0, 63, 64, 191, 255, 256, M - 1]
+    ref = oracle.gemm(to_bits(A[rows]), to_bits(B), "nk")
+    gemm_check(oracle.bf16_to_f64(to_bits(C[rows])), ref, K, std, "gemm at K = 2^22")
+    assert np.count_nonzero(to_bits(C)) > 0.99 * M * N
+    del A, B, C
+    torch.cuda.empty_cache()
+
+
+@pytest.mark.parametrize("layout", ["nk", "kn"])
+def test_gemm_taller_than_four_gib(tw, torch_cuda, layout):
+    """M = 1.1 M rows: C is 4.5 GB, so tile base addresses run past 2^32 bytes (row 1048576 of C starts
+    there, row 524288 at 2^31; A passes 2^30 at row 1048576). Rows around those seams, the first, the
+    last (a ragged tile) and random ones against the fp64 product of those rows; [N x K] operands take
+    the 256 x 256 tiles, [K x N] the 256 x 128 ones."""
+    torch = torch_cuda
+    M, N, K, std = 1100000 + 37, 2048, 512, 0.05
+    gen = torch.Generator(device="cuda:0")
+    gen.manual_seed(5)
+    A = torch.empty((M, K), dtype=torch.bfloat16, device="cuda:0").normal_(0.0, std, generator=gen)
+    Bnk = torch.empty((N, K), dtype=torch.bfloat16, device="cuda:0").normal_(0.0, std, generator=gen)
+    B = Bnk if layout == "nk" else Bnk.t().contiguous()
+    C = torch.full((M, N), float("nan"), dtype=torch.bfloat16, device="cuda:0")
+    tw.gemm_bf16(A, B, C=C, b_layout=tw.B_NK if layout == "nk" else tw.B_KN)
+    torch.cuda.synchronize()
+    rng = np.random.default_rng(9)
+    rows = sorted(set([0, 255, 256, 524287, 524288, 1048575, 1048576, 1048577, M - 38, M - 37, M - 1]
+                      + [int(r) for r in rng.integers(0, M, 40)]))
+    idx = torch.tensor(rows, device="cuda:0")
+    ref = oracle.gemm(to_bits(A[idx]), to_bits(Bnk), "nk")
+    gemm_check(oracle.bf16_to_f64(to_bits(C[idx])), ref, K, std, "tall gemm " + layout)
+    # every element was written: no NaN is left anywhere
+    assert not torch.isnan(C).any().item()
+    del A, B, Bnk, C
+    torch.cuda.empty_cache()
+
+
 @pytest.mark.parametrize("layout", ["nk", "kn"])
 def test_gemm_demo_shape_sampled(tw, torch_cuda, layout):
     """[2048 x 8192] x [8192 x 3584], N(0, 0.02^2): 4096 sampled outputs, one by one."""
