@@ -328,6 +328,29 @@ tw_status tw_weave_layer(const tw_layer_args *layer, int64_t split_row, void *st
                          void *stream_comm, void *parent, int parent_is_set, int join);
 
 /*
+ * The same boundary cut into more than two splits: rows [0, cuts[0]), [cuts[0],
+ * cuts[1]), ..., [cuts[n_cuts - 1], T). The paper weaves two splits (Fig. 7b);
+ * this is the same schedule carried on over a longer list, for callers whose
+ * batches cut better into three or four pieces than into two (on MI355X that is
+ * the case where a third or a quarter of the batch is a whole number of GEMM
+ * tile waves and half of it is not: 3 % at 12K tokens and 2 % at 32K on a
+ * 70B-class attention-side boundary; elsewhere two splits are level or better,
+ * and more than four never paid). The splits are woven two at a time exactly as
+ * tw_weave_layer weaves its pair, pair after pair on the same two streams (an
+ * odd split at the end runs as a plain chain on stream_compute); nothing but
+ * stream order links the pairs, so the end of one overlaps the start of the
+ * next. n_cuts == 0 is the unsplit chain, n_cuts == 1 is tw_weave_layer.
+ *   cuts     host array of n_cuts rows, strictly ascending, each in (0, T);
+ *            read during the call only
+ *   n_cuts   0 ... TW_MAX_CUTS
+ * Results are bit-identical for every set of cuts. Errors as for
+ * tw_weave_layer; TW_ERR_SPLIT for cuts out of order or out of range or too many.
+ */
+#define TW_MAX_CUTS 15
+tw_status tw_weave_layer_cuts(const tw_layer_args *layer, const int64_t *cuts, int n_cuts, void *stream_compute,
+                              void *stream_comm, void *parent, int parent_is_set, int join);
+
+/*
  * Wave-aware choice of the split row (Section 4.1.1 and Appendix A
  * "Smart-Splitting"; Algorithm 1 finds the offset by profiling because its GEMMs
  * are closed source, here the GEMM's tile grid is known, so the same sweep is

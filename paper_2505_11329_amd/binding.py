@@ -99,6 +99,9 @@ def lib():
         L.tw_hbm_probe.restype = ctypes.c_int
         L.tw_weave_layer.argtypes = [ctypes.POINTER(LayerArgs), _i64, _vp, _vp, _vp, ctypes.c_int, ctypes.c_int]
         L.tw_weave_layer.restype = ctypes.c_int
+        L.tw_weave_layer_cuts.argtypes = [ctypes.POINTER(LayerArgs), ctypes.POINTER(_i64), ctypes.c_int, _vp, _vp, _vp,
+                                          ctypes.c_int, ctypes.c_int]
+        L.tw_weave_layer_cuts.restype = ctypes.c_int
         L.tw_weave_layer_auto.argtypes = [ctypes.POINTER(LayerArgs), _i64, _i64, _vp, _vp, _vp, ctypes.c_int, ctypes.c_int,
                                           ctypes.POINTER(_i64)]
         L.tw_weave_layer_auto.restype = ctypes.c_int
@@ -417,6 +420,28 @@ def weave_layer(X1, W1, partials, residual, weight, eps, W2, split_row, stream_c
                                 _stream_handle(stream_comm),
                                 _stream_handle(parent) if use_parent else _vp(None),
                                 1 if use_parent else 0, 1 if join else 0), "tw_weave_layer")
+    return out, residual_out, Y
+
+
+def weave_layer_cuts(X1, W1, partials, residual, weight, eps, W2, cuts, stream_compute, stream_comm,
+                     fused_cu_budget=CU_SHARED, gemm_cu_budget=0, out=None, residual_out=None, Y=None, parent=None,
+                     use_parent=True, join=True, schedule=WEAVE_AUTO):
+    """tw_weave_layer_cuts: the boundary over len(cuts) + 1 splits. Returns (out, residual_out, Y)."""
+    import torch
+    a, keep, out, residual_out = _fused_pack(partials, residual, weight, eps, fused_cu_budget, out, residual_out)
+    T, H = residual.shape
+    K1 = X1.shape[1]
+    N2 = W2.shape[0]
+    if Y is None:
+        Y = torch.empty((T, N2), dtype=torch.bfloat16, device=residual.device)
+    la = LayerArgs(_bf16_ptr(X1, "X1", (T, K1)), _bf16_ptr(W1, "W1", (H, K1)), K1, a,
+                   _bf16_ptr(W2, "W2", (N2, H)), N2, _bf16_ptr(Y, "Y", (T, N2)), int(gemm_cu_budget), int(schedule))
+    cuts = [int(c) for c in cuts]
+    arr = (_i64 * max(len(cuts), 1))(*cuts)
+    _check(lib().tw_weave_layer_cuts(ctypes.byref(la), arr, len(cuts), _stream_handle(stream_compute),
+                                     _stream_handle(stream_comm),
+                                     _stream_handle(parent) if use_parent else _vp(None),
+                                     1 if use_parent else 0, 1 if join else 0), "tw_weave_layer_cuts")
     return out, residual_out, Y
 
 

@@ -274,65 +274,117 @@ int tw_weave_schedule(int64_t T, int64_t K1, int64_t H, int P, int64_t N2, int f
     return takes_chains(layer, cus) ? TW_WEAVE_CHAINS : TW_WEAVE_ORDERED;
 }
 
-tw_status tw_weave_layer(const tw_layer_args *layer, int64_t split_row, void *stream_compute,
-                         void *stream_comm, void *parent, int parent_is_set, int join)
+// Checks shared by every way of launching a layer boundary; on TW_OK with T > 0
+// *g1 and *g2 are the two GEMMs over all T rows.
+static tw_status validate_layer(const tw_layer_args *layer, void *stream_compute, void *stream_comm, tw_gemm_args *g1,
+                                tw_gemm_args *g2)
 {
     if (!layer) return TW_ERR_NULL;
     const tw_fused_args &f = layer->fused;
     TW_TRY(validate_fused(f));
     const int64_t T = f.N;
-    if (split_row < 0 || split_row > T) return TW_ERR_SPLIT;
     if (stream_compute == stream_comm) return TW_ERR_SPLIT;
     if (layer->K1 < 0 || layer->N2 < 0) return TW_ERR_SHAPE;
     if (layer->schedule != TW_WEAVE_AUTO && layer->schedule != TW_WEAVE_ORDERED &&
         layer->schedule != TW_WEAVE_CHAINS)
         return TW_ERR_UNSUPPORTED;
     if (T == 0) return TW_OK;
-    const tw_gemm_args g1 = {layer->X1, layer->W1, const_cast<void *>(f.partials[0]), T, f.H, layer->K1,
-                             TW_B_NK, layer->gemm_cu_budget};
-    const tw_gemm_args g2 = {f.out, layer->W2, layer->Y, T, layer->N2, f.H, TW_B_NK, layer->gemm_cu_budget};
-    TW_TRY(validate_gemm(g1));
-    TW_TRY(validate_gemm(g2));
-    {   // Y is written while the other split's fused kernel may still be running:
-        // it must not touch anything that kernel reads or writes, nor G1's operands
-        const uint64_t y_bytes = uint64_t(T) * uint64_t(layer->N2) * 2, t_bytes = uint64_t(T) * uint64_t(f.H) * 2;
-        if (ranges_overlap(layer->Y, y_bytes, f.residual, t_bytes) ||
-            ranges_overlap(layer->Y, y_bytes, f.residual_out, t_bytes) ||
-            ranges_overlap(layer->Y, y_bytes, f.weight, uint64_t(f.H) * 2) ||
-            ranges_overlap(layer->Y, y_bytes, layer->X1, uint64_t(T) * uint64_t(layer->K1) * 2) ||
-            ranges_overlap(layer->Y, y_bytes, layer->W1, uint64_t(f.H) * uint64_t(layer->K1) * 2))
+    *g1 = {layer->X1, layer->W1, const_cast<void *>(f.partials[0]), T, f.H, layer->K1, TW_B_NK, layer->gemm_cu_budget};
+    *g2 = {f.out, layer->W2, layer->Y, T, layer->N2, f.H, TW_B_NK, layer->gemm_cu_budget};
+    TW_TRY(validate_gemm(*g1));
+    TW_TRY(validate_gemm(*g2));
+    // Y is written while the other split's fused kernel may still be running:
+    // it must not touch anything that kernel reads or writes, nor G1's operands
+    const uint64_t y_bytes = uint64_t(T) * uint64_t(layer->N2) * 2, t_bytes = uint64_t(T) * uint64_t(f.H) * 2;
+    if (ranges_overlap(layer->Y, y_bytes, f.residual, t_bytes) ||
+        ranges_overlap(layer->Y, y_bytes, f.residual_out, t_bytes) ||
+        ranges_overlap(layer->Y, y_bytes, f.weight, uint64_t(f.H) * 2) ||
+        ranges_overlap(layer->Y, y_bytes, layer->X1, uint64_t(T) * uint64_t(layer->K1) * 2) ||
+        ranges_overlap(layer->Y, y_bytes, layer->W1, uint64_t(f.H) * uint64_t(layer->K1) * 2))
+        return TW_ERR_ALIAS;
+    for (int p = 0; p < f.P; ++p)
+        if (ranges_overlap(layer->Y, y_bytes, f.partials[p], t_bytes)) return TW_ERR_ALIAS;
+    // G1 writes partials[0] before the fused kernel runs: it must not be one of
+    // G1's own inputs (checked above) nor the weights of either GEMM
+    const uint64_t w2_bytes = uint64_t(layer->N2) * uint64_t(f.H) * 2;
+    if (ranges_overlap(f.partials[0], t_bytes, layer->W2, w2_bytes)) return TW_ERR_ALIAS;
+    // one split's fused kernel writes out / residual_out while the other
+    // split's G1 reads X1 and W1 and the first split's G2 reads W2
+    const void *f_outs[2] = {f.out, f.residual_out};
+    for (const void *o : f_outs)
+        if (ranges_overlap(o, t_bytes, layer->X1, uint64_t(T) * uint64_t(layer->K1) * 2) ||
+            ranges_overlap(o, t_bytes, layer->W1, uint64_t(f.H) * uint64_t(layer->K1) * 2) ||
+            ranges_overlap(o, t_bytes, layer->W2, w2_bytes))
             return TW_ERR_ALIAS;
-        for (int p = 0; p < f.P; ++p)
-            if (ranges_overlap(layer->Y, y_bytes, f.partials[p], t_bytes)) return TW_ERR_ALIAS;
-        // G1 writes partials[0] before the fused kernel runs: it must not be one of
-        // G1's own inputs (checked above) nor the weights of either GEMM
-        const uint64_t w2_bytes = uint64_t(layer->N2) * uint64_t(f.H) * 2;
-        if (ranges_overlap(f.partials[0], t_bytes, layer->W2, w2_bytes)) return TW_ERR_ALIAS;
-        // one split's fused kernel writes out / residual_out while the other
-        // split's G1 reads X1 and W1 and the first split's G2 reads W2
-        const void *f_outs[2] = {f.out, f.residual_out};
-        for (const void *o : f_outs)
-            if (ranges_overlap(o, t_bytes, layer->X1, uint64_t(T) * uint64_t(layer->K1) * 2) ||
-                ranges_overlap(o, t_bytes, layer->W1, uint64_t(f.H) * uint64_t(layer->K1) * 2) ||
-                ranges_overlap(o, t_bytes, layer->W2, w2_bytes))
-                return TW_ERR_ALIAS;
+    return TW_OK;
+}
+
+// Rows [lo, mid) and [mid, hi) of the boundary as one woven pair of splits, the
+// first on sx, the second on sc (mid == hi: rows [lo, hi) as one chain on sx).
+static tw_status weave_pair(const tw_fused_args &f, const tw_gemm_args &g1, const tw_gemm_args &g2, bool chains,
+                            int64_t lo, int64_t mid, int64_t hi, hipStream_t sx, hipStream_t sc)
+{
+    if (mid >= hi) {
+        TW_TRY(launch_gemm(rows_of(g1, lo, hi), sx, false));
+        TW_TRY(launch_fused(f, lo, hi, nullptr, 0, sx));
+        return launch_gemm(rows_of(g2, lo, hi), sx, false);
     }
+    if (chains) {
+        // one chain per split; the second starts when the first split's G1 is done.
+        // The first GEMM of the first chain and the last of the second have no fused
+        // kernel of this pair beside them (the one runs before any, the other after
+        // both): they take the tile shape of a GEMM launched on its own.
+        hipEvent_t g1a_done;
+        TW_TRY(launch_gemm(rows_of(g1, lo, mid), sx, false));
+        TW_TRY(borrow_event(&g1a_done));
+        TW_HIP(hipEventRecord(g1a_done, sx));
+        TW_HIP(hipStreamWaitEvent(sc, g1a_done, 0));
+        TW_TRY(launch_fused(f, lo, mid, nullptr, 0, sx));
+        TW_TRY(launch_gemm(rows_of(g2, lo, mid), sx, true));
+        TW_TRY(launch_gemm(rows_of(g1, mid, hi), sc, true));
+        TW_TRY(launch_fused(f, mid, hi, nullptr, 0, sc));
+        return launch_gemm(rows_of(g2, mid, hi), sc, false);
+    }
+    // compute stream: both G1 first, so the second split's projection is what
+    // runs next to the first split's fused kernel
+    const int64_t cuts[3] = {lo, mid, hi};
+    hipEvent_t g1_done[2], f_done[2];
+    for (int s = 0; s < 2; ++s) {
+        TW_TRY(launch_gemm(rows_of(g1, cuts[s], cuts[s + 1]), sx, true));
+        TW_TRY(borrow_event(&g1_done[s]));
+        TW_HIP(hipEventRecord(g1_done[s], sx));
+    }
+    for (int s = 0; s < 2; ++s) {
+        TW_HIP(hipStreamWaitEvent(sc, g1_done[s], 0));
+        TW_TRY(launch_fused(f, cuts[s], cuts[s + 1], nullptr, 0, sc));
+        TW_TRY(borrow_event(&f_done[s]));
+        TW_HIP(hipEventRecord(f_done[s], sc));
+        TW_HIP(hipStreamWaitEvent(sx, f_done[s], 0));
+        TW_TRY(launch_gemm(rows_of(g2, cuts[s], cuts[s + 1]), sx, true));
+    }
+    return TW_OK;
+}
+
+tw_status tw_weave_layer_cuts(const tw_layer_args *layer, const int64_t *cuts, int n_cuts, void *stream_compute,
+                              void *stream_comm, void *parent, int parent_is_set, int join)
+{
+    tw_gemm_args g1, g2;
+    TW_TRY(validate_layer(layer, stream_compute, stream_comm, &g1, &g2));
+    const tw_fused_args &f = layer->fused;
+    const int64_t T = f.N;
+    if (n_cuts < 0 || n_cuts > TW_MAX_CUTS) return TW_ERR_SPLIT;
+    if (n_cuts > 0 && !cuts) return TW_ERR_NULL;
+    for (int i = 0; i < n_cuts; ++i)
+        if (cuts[i] <= (i ? cuts[i - 1] : 0) || cuts[i] >= T) return TW_ERR_SPLIT;
+    if (T == 0) return TW_OK;
 
     hipStream_t sx = static_cast<hipStream_t>(stream_compute), sc = static_cast<hipStream_t>(stream_comm);
     hipStream_t sp = static_cast<hipStream_t>(parent);
-    if (parent_is_set) {
-        hipEvent_t fork;
-        TW_TRY(borrow_event(&fork));
-        TW_HIP(hipEventRecord(fork, sp));
-        if (sx != sp) TW_HIP(hipStreamWaitEvent(sx, fork, 0));
-        if (sc != sp) TW_HIP(hipStreamWaitEvent(sc, fork, 0));
-    }
-    const int64_t cuts[3] = {0, (split_row == 0 || split_row == T) ? T : split_row, T};
-    const int n_splits = cuts[1] == T ? 1 : 2;
-    if (n_splits == 1) {
+    if (n_cuts == 0) {
         // nothing to weave: the chain runs on the compute stream, with no events. A
         // fused step that was to share the compute units has them to itself here and
         // takes whichever kernel the whole device runs fastest (same bits).
+        if (parent_is_set && sx != sp) TW_TRY(stream_wait_stream(sx, sp));
         TW_TRY(launch_gemm(g1, sx));
         tw_fused_args alone = f;
         if (alone.cu_budget == TW_CU_SHARED) alone.cu_budget = 0;
@@ -341,50 +393,43 @@ tw_status tw_weave_layer(const tw_layer_args *layer, int64_t split_row, void *st
         if (parent_is_set && join && sx != sp) TW_TRY(stream_wait_stream(sp, sx));
         return TW_OK;
     }
+    if (parent_is_set) {
+        hipEvent_t fork;
+        TW_TRY(borrow_event(&fork));
+        TW_HIP(hipEventRecord(fork, sp));
+        if (sx != sp) TW_HIP(hipStreamWaitEvent(sx, fork, 0));
+        if (sc != sp) TW_HIP(hipStreamWaitEvent(sc, fork, 0));
+    }
     int cus = 0;
     TW_TRY(current_cu_count(&cus));
-    if (takes_chains(*layer, cus)) {
-        // one chain per split; the second starts when the first split's G1 is done.
-        // The first GEMM of the first chain and the last of the second have no fused
-        // kernel beside them (the one runs before any, the other after both): they
-        // take the tile shape of a GEMM launched on its own.
-        hipEvent_t g1a_done;
-        TW_TRY(launch_gemm(rows_of(g1, cuts[0], cuts[1]), sx, false));
-        TW_TRY(borrow_event(&g1a_done));
-        TW_HIP(hipEventRecord(g1a_done, sx));
-        TW_HIP(hipStreamWaitEvent(sc, g1a_done, 0));
-        TW_TRY(launch_fused(f, cuts[0], cuts[1], nullptr, 0, sx));
-        TW_TRY(launch_gemm(rows_of(g2, cuts[0], cuts[1]), sx, true));
-        TW_TRY(launch_gemm(rows_of(g1, cuts[1], cuts[2]), sc, true));
-        TW_TRY(launch_fused(f, cuts[1], cuts[2], nullptr, 0, sc));
-        TW_TRY(launch_gemm(rows_of(g2, cuts[1], cuts[2]), sc, false));
-        if (parent_is_set && join) {
-            if (sx != sp) TW_TRY(stream_wait_stream(sp, sx));
-            if (sc != sp) TW_TRY(stream_wait_stream(sp, sc));
-        }
-        return TW_OK;
-    }
-    // compute stream: every G1 first, so the second split's projection is what
-    // runs next to the first split's fused kernel
-    hipEvent_t g1_done[2], f_done[2];
-    for (int s = 0; s < n_splits; ++s) {
-        TW_TRY(launch_gemm(rows_of(g1, cuts[s], cuts[s + 1]), sx, true));
-        TW_TRY(borrow_event(&g1_done[s]));
-        TW_HIP(hipEventRecord(g1_done[s], sx));
-    }
-    for (int s = 0; s < n_splits; ++s) {
-        TW_HIP(hipStreamWaitEvent(sc, g1_done[s], 0));
-        TW_TRY(launch_fused(f, cuts[s], cuts[s + 1], nullptr, 0, sc));
-        TW_TRY(borrow_event(&f_done[s]));
-        TW_HIP(hipEventRecord(f_done[s], sc));
-        TW_HIP(hipStreamWaitEvent(sx, f_done[s], 0));
-        TW_TRY(launch_gemm(rows_of(g2, cuts[s], cuts[s + 1]), sx, true));
+    const bool chains = takes_chains(*layer, cus);
+    // The splits are woven two at a time, pair after pair on the same two streams:
+    // stream order alone keeps a pair's first chain behind the previous pair's first
+    // chain and its second behind the previous second, so no event links the pairs
+    // and the tail of one pair overlaps the head of the next.
+    const int n_splits = n_cuts + 1;
+    auto row = [&](int i) { return i == 0 ? int64_t(0) : i == n_splits ? T : cuts[i - 1]; };
+    for (int s = 0; s < n_splits; s += 2) {
+        const int64_t lo = row(s), mid = row(s + 1), hi = s + 2 <= n_splits ? row(s + 2) : mid;
+        TW_TRY(weave_pair(f, g1, g2, chains, lo, mid, hi, sx, sc));
     }
     if (parent_is_set && join) {
         if (sx != sp) TW_TRY(stream_wait_stream(sp, sx));
         if (sc != sp) TW_TRY(stream_wait_stream(sp, sc));
     }
     return TW_OK;
+}
+
+tw_status tw_weave_layer(const tw_layer_args *layer, int64_t split_row, void *stream_compute,
+                         void *stream_comm, void *parent, int parent_is_set, int join)
+{
+    if (!layer) return TW_ERR_NULL;
+    TW_TRY(validate_fused(layer->fused));
+    const int64_t T = layer->fused.N;
+    if (split_row < 0 || split_row > T) return TW_ERR_SPLIT;
+    const bool whole = split_row == 0 || split_row == T;
+    return tw_weave_layer_cuts(layer, &split_row, whole ? 0 : 1, stream_compute, stream_comm, parent, parent_is_set,
+                               join);
 }
 
 int tw_should_split(int64_t num_tokens, int64_t threshold)

@@ -29,7 +29,7 @@ def declared_functions(headers=("tw.h", "tw_measure.h")):
 def test_header_declares_the_documented_entry_points():
     names = declared_functions(("tw.h",))
     for must in ("tw_reduce_add_rmsnorm", "tw_split_launch", "tw_split_point", "tw_gemm_bf16",
-                 "tw_overlap_launch", "tw_weave_layer", "tw_weave_layer_auto", "tw_weave_tune", "tw_smart_split_point",
+                 "tw_overlap_launch", "tw_weave_layer", "tw_weave_layer_cuts", "tw_weave_layer_auto", "tw_weave_tune", "tw_smart_split_point",
                  "tw_should_split", "tw_split_threshold", "tw_policy_split_row", "tw_device_cu_count", "tw_status_str",
                  "tw_version", "tw_last_hip_error"):
         assert must in names
@@ -394,6 +394,37 @@ def test_weave_layer_argument_checks():
     for schedule in (tw.WEAVE_AUTO, tw.WEAVE_ORDERED, tw.WEAVE_CHAINS):
         la.schedule = schedule
         assert L.tw_weave_layer(ctypes.byref(la), 0, VP(1), VP(2), VP(None), 0, 0) == OK
+
+
+def test_weave_layer_cuts_argument_checks():
+    from paper_2505_11329_amd.binding import LayerArgs
+    L = tw.lib()
+    I64 = ctypes.c_int64
+
+    def call(la, cuts, n=None, sx=1, sc=2):
+        arr = (I64 * max(len(cuts), 1))(*cuts)
+        return L.tw_weave_layer_cuts(ctypes.byref(la) if la is not None else None, arr, len(cuts) if n is None else n,
+                                     VP(sx), VP(sc), VP(None), 0, 0)
+    arr = (VP * P)(addr(0), addr(1))
+    f = FusedArgs(ctypes.cast(arr, ctypes.POINTER(VP)), addr(4), addr(5), 1e-5, N, H, P, 8, addr(6), addr(7))
+    la = LayerArgs(addr(10), addr(11), 64, f, addr(12), 64, addr(13), 0)
+    assert call(None, [2]) == E_NULL
+    assert L.tw_weave_layer_cuts(ctypes.byref(la), None, 1, VP(1), VP(2), VP(None), 0, 0) == E_NULL
+    assert call(la, [2], n=-1) == E_SPLIT
+    assert call(la, list(range(1, 17)), n=16) == E_SPLIT          # more than TW_MAX_CUTS
+    for bad in ([0], [N], [N + 1], [-1], [2, 2], [3, 2], [1, 2, 2], [1, 3, N]):
+        assert call(la, bad) == E_SPLIT, bad
+    assert call(la, [2], sx=3, sc=3) == E_SPLIT
+    la.Y = addr(6)
+    assert call(la, [1, 2, 3]) == E_ALIAS
+    assert call(la, []) == E_ALIAS
+    la.Y = addr(13)
+    la.schedule = 9
+    assert call(la, [1, 2]) == E_UNSUP
+    la.schedule = 0
+    la.fused.N = 0                  # an empty batch has no row to cut at
+    assert call(la, []) == OK
+    assert call(la, [1]) == E_SPLIT
 
 
 def test_split_threshold_matches_its_definition():

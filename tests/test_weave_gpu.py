@@ -77,6 +77,39 @@ def test_weave_layer_stagewise_parity_and_split_invariance(tw, torch_cuda):
                 assert np.array_equal(res, res0) and np.array_equal(Y, Y0), (schedule, budgets, k)
 
 
+def test_weave_layer_cuts_any_number_of_splits_gives_the_unsplit_bits(tw, torch_cuda):
+    """tw_weave_layer_cuts: two, three (an odd split at the end), five and sixteen splits, ragged and
+    one-row pieces, in both schedules and the three launch modes of the fused step, launched behind a
+    parent stream that still holds the writing of an input; every output carries the bits of the
+    unsplit chain (which the stagewise test checks against the oracle on these very inputs)."""
+    torch = torch_cuda
+    g1, f, W2 = make_inputs()
+    streams = (torch.cuda.Stream(), torch.cuda.Stream())
+    want = run_layer(tw, torch, g1, f, W2, 0, streams)
+    X1_src, W1 = to_gpu(g1["A"]), to_gpu(g1["B"])
+    resid, weight, W2g = to_gpu(f["residual"]), to_gpu(f["weight"]), to_gpu(W2)
+    parent = torch.cuda.Stream()
+    cut_sets = ([], [320], [256, 512], [1, 2, 639], [128, 256, 384, 512], [100, 228, 229, 600],
+                list(range(40, 640, 40)))
+    assert len(cut_sets[-1]) == 15
+    for schedule in (tw.WEAVE_ORDERED, tw.WEAVE_CHAINS, tw.WEAVE_AUTO):
+        for budgets in ((32, 224), (tw.CU_SHARED, 0), (0, 0)):
+            for cuts in cut_sets:
+                X1 = torch.zeros_like(X1_src)
+                parts = [torch.full((T, H), float("nan"), dtype=torch.bfloat16, device="cuda:0")] + \
+                        [to_gpu(p) for p in f["partials"][1:]]
+                torch.cuda.synchronize()
+                with torch.cuda.stream(parent):
+                    X1.copy_(X1_src)            # the call must wait for this
+                out, res, Y = tw.weave_layer_cuts(X1, W1, parts, resid, weight, f["eps"], W2g, cuts, streams[0],
+                                                  streams[1], fused_cu_budget=budgets[0], gemm_cu_budget=budgets[1],
+                                                  parent=parent, use_parent=True, join=True, schedule=schedule)
+                parent.synchronize()            # joined: everything is done once the parent is
+                got = (to_bits(parts[0]), to_bits(out), to_bits(res), to_bits(Y))
+                for name, g_, w_ in zip(("G1", "out", "residual_out", "Y"), got, want):
+                    assert np.array_equal(g_, w_), (schedule, budgets, cuts, name)
+
+
 @pytest.mark.parametrize("schedule", [1, 2])   # TW_WEAVE_ORDERED, TW_WEAVE_CHAINS
 def test_weave_layer_orders_itself_after_the_parent_stream(tw, torch_cuda, schedule):
     torch = torch_cuda
