@@ -361,7 +361,8 @@ tw_status tw_weave_layer_cuts(const tw_layer_args *layer, const int64_t *cuts, i
  * (gemm_k == NULL: every GEMM weighs 1, the cost is the plain wave count). Among
  * the candidates k = tw_split_point(T, multiple) + j * multiple (j = 0, 1, 2,
  * ..., k < T, offset at most 512 rows as in Algorithm 1) the cheapest wins; ties
- * go to the smallest offset. Returns T ("do not split") only when tw_split_point
+ * go to the cut that leaves the fewest 256-row GEMM tiles over both splits (a cut
+ * inside a tile makes both splits work on that tile), then to the smallest offset. Returns T ("do not split") only when tw_split_point
  * already does, i.e. for batches too small to cut at that multiple. If not NULL,
  * *cost_split receives the winner's cost and *cost_unsplit that of the whole
  * batch, so the caller can apply the paper's criterion (split waves <= unsplit
@@ -429,10 +430,10 @@ int64_t tw_split_threshold(int64_t K1, int64_t H, int P, int64_t N2, int cus);
  *     tw_smart_split_point reports for the cut does not exceed that of the whole
  *     batch (Section 4.1.1's criterion). In that band the unsplit GEMMs' own wave
  *     quantisation decides: on MI355X, for K1 = 1024, H = 8192, P = 8, N2 = 3584
- *     and T = 4096 ... 8192 in steps of 256, the criterion picks the faster of the
- *     two at 14 of 17 token counts and the policy stays within 1.0 % of the best
- *     timed candidate on average (4.4 % at worst), against 2.2 % (5.4 %) for the
- *     threshold alone and 1.4 % (7.6 %) for always splitting.
+ *     and T = 4096 ... 8192 in steps of 256, the policy stays within 0.7 % of the
+ *     best timed candidate on average (2.7 % at worst), against 1.3 % (4.0 %)
+ *     for the threshold alone and 1.2 % (5.1 %) for always splitting; where it
+ *     picks the slower of the two, the two are within 3 % of each other.
  * multiple <= 0: 64. Host only. Returns -1 on bad arguments (T < 0, another size
  * < 1).
  */

@@ -604,11 +604,16 @@ int64_t tw_smart_split_point(int64_t T, int64_t multiple, const int64_t *gemm_n_
     if (cost_split) *cost_split = unsplit;
     const int64_t base = tw_split_point(T, multiple);
     if (base >= T) return T;
-    int64_t best_k = T, best_cost = INT64_MAX;
+    // among cuts of equal cost, the one whose splits pad the fewest GEMM row tiles
+    // (a cut inside a tile makes both splits work on that tile's rows)
+    auto row_tiles = [](int64_t rows) { return (rows + kGemmTileM - 1) / kGemmTileM; };
+    int64_t best_k = T, best_cost = INT64_MAX, best_tiles = INT64_MAX;
     for (int64_t k = base; k < T && k - base <= 512; k += multiple) {
         const int64_t cost = cost_of(k) + cost_of(T - k);
-        if (cost < best_cost) {
+        const int64_t tiles = row_tiles(k) + row_tiles(T - k);
+        if (cost < best_cost || (cost == best_cost && tiles < best_tiles)) {
             best_cost = cost;
+            best_tiles = tiles;
             best_k = k;
         }
     }

@@ -304,7 +304,8 @@ def test_mixed_probe_argument_checks():
 
 def test_smart_split_point_matches_its_definition():
     """Independent statement of the criterion: among k = base + j*multiple (k < T,
-    offset <= 512) take the fewest total GEMM waves, ties to the smallest k."""
+    offset <= 512) take the fewest total GEMM waves, ties to the fewest 256-row tiles
+    over both splits, then to the smallest k."""
     tm, tn = tw.gemm_tile_shape()
     assert (tm, tn) == (256, 128)
 
@@ -326,14 +327,15 @@ def test_smart_split_point_matches_its_definition():
                         continue
                     cands = [c for c in range(base, T, mult) if c - base <= 512]
                     cost = {c: sum(waves(c, n, cus) + waves(T - c, n, cus) for n in widths) for c in cands}
-                    best = min(cands, key=lambda c: (cost[c], c))
+                    tiles = {c: -(-c // tm) + -(-(T - c) // tm) for c in cands}
+                    best = min(cands, key=lambda c: (cost[c], tiles[c], c))
                     assert (k, ws) == (best, cost[best]), (T, mult, widths, cus)
                     # with depths, a wave of GEMM i weighs depths[i]
                     depths = [1024, 8192, 512][:len(widths)]
                     k, ws, wu = tw.smart_split_point(T, mult, widths, cus, gemm_k=depths)
                     cost = {c: sum((waves(c, n, cus) + waves(T - c, n, cus)) * d for n, d in zip(widths, depths))
                             for c in cands}
-                    best = min(cands, key=lambda c: (cost[c], c))
+                    best = min(cands, key=lambda c: (cost[c], tiles[c], c))
                     assert (k, ws) == (best, cost[best]), (T, mult, widths, cus)
                     assert wu == sum(waves(T, n, cus) * d for n, d in zip(widths, depths))
     # the situation of the paper's example (Section 4.1.1): 300 workgroups (10 row
