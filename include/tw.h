@@ -67,7 +67,7 @@ typedef enum tw_status {
     TW_ERR_ALIGN = 3,       /* a data pointer is not 16-byte aligned              */
     TW_ERR_ALIAS = 4,       /* buffers overlap in a way that is not allowed       */
     TW_ERR_UNSUPPORTED = 5, /* a valid request this build has no kernel for       */
-    TW_ERR_SPLIT = 6,       /* split_row outside [0, N], or the two streams are the same */
+    TW_ERR_SPLIT = 6,       /* split_row outside [0, N], cuts out of range or order, or the two streams are the same */
     TW_ERR_HIP = 7          /* a HIP call failed; see tw_last_hip_error()         */
 } tw_status;
 

@@ -146,7 +146,7 @@ const char *tw_status_str(tw_status s)
     case TW_ERR_ALIGN: return "a data pointer is not 16-byte aligned";
     case TW_ERR_ALIAS: return "buffers overlap in a way that is not allowed";
     case TW_ERR_UNSUPPORTED: return "no kernel for this request";
-    case TW_ERR_SPLIT: return "bad split row or identical streams";
+    case TW_ERR_SPLIT: return "bad split row or cuts, or identical streams";
     case TW_ERR_HIP: return "a HIP call failed (see tw_last_hip_error)";
     }
     return "unknown status";
