@@ -152,6 +152,40 @@ tw_status tw_hbm_probe_mixed_shaped(const void *src, void *dst, int64_t stream_b
  */
 tw_status tw_streams_overlap(void *stream_a, void *stream_b, int *overlap);
 
+/*
+ * A stream whose kernels the hardware confines to n_cus compute units: the other
+ * way of giving the fused kernel "a few SMs" (Section 4.3; Fig. 9), enforced by
+ * the dispatcher instead of by the launch shape (tw_fused_args.cu_budget: a
+ * persistent grid of one workgroup per compute unit). The stream carries a
+ * compute-unit mask with bits [first_cu, first_cu + n_cus) set. On MI355X the
+ * dispatcher deals mask bit i to XCD i mod 8 (probed with the traced launch: bits
+ * 0 ... 31 are four compute units in each of the eight XCDs), so a range whose
+ * length is a multiple of 8 is spread evenly, and two disjoint ranges are
+ * disjoint sets of compute units: [0, 32) for the fused kernel and [32, 256) for
+ * the GEMM is the paper's partition in hardware. A mask that leaves an XCD
+ * without a compute unit is refused by the runtime (TW_ERR_HIP).
+ * Any grid may be launched on such a stream (also cu_budget = 0 or
+ * TW_CU_SHARED); workgroups beyond what the masked units hold wait their turn.
+ * What a confined kernel can pull from HBM is the same either way (one compute
+ * unit sustains ~50-57 GB/s): 1.45-1.5 TB/s for the shared-mode grid on 32 masked
+ * units against 1.6 for the persistent grid of 32 workgroups, which runs as fast
+ * on a masked stream as on an ordinary one. Measured with the overlap demo's pair
+ * (fused kernel on 32 units beside the GEMM on 224): kernels on two masked
+ * streams do run side by side, but forked from and joined into a parent stream
+ * with events the masked pair took 316-328 us against 264-295 on ordinary
+ * streams with the same budgets, and the first dispatch on a new masked stream
+ * starts late (run something on it before timing). So the launch-shape budget
+ * stays the default and the mask is the cross-check that the budget confines
+ * what it says.
+ * The caller owns the stream: it is an ordinary hipStream_t of default priority
+ * on a hardware queue of its own, to be destroyed with tw_stream_destroy (or
+ * hipStreamDestroy) once its work is done. Not for use during stream capture.
+ * Errors: TW_ERR_NULL; TW_ERR_SHAPE (first_cu < 0, n_cus < 1, range beyond the
+ * device's compute units); TW_ERR_HIP.
+ */
+tw_status tw_stream_create_cu_masked(int first_cu, int n_cus, void **stream);
+tw_status tw_stream_destroy(void *stream);
+
 #ifdef __cplusplus
 }
 #endif

@@ -110,6 +110,10 @@ def lib():
         L.tw_weave_tune.restype = ctypes.c_int
         L.tw_gemm_bf16_traced.argtypes = [_vp, _vp, _vp, _i64, _i64, _i64, _vp, _i64, _vp]
         L.tw_gemm_bf16_traced.restype = ctypes.c_int
+        L.tw_stream_create_cu_masked.argtypes = [ctypes.c_int, ctypes.c_int, ctypes.POINTER(_vp)]
+        L.tw_stream_create_cu_masked.restype = ctypes.c_int
+        L.tw_stream_destroy.argtypes = [_vp]
+        L.tw_stream_destroy.restype = ctypes.c_int
         L.tw_split_threshold.argtypes = [_i64, _i64, ctypes.c_int, _i64, ctypes.c_int]
         L.tw_split_threshold.restype = _i64
         L.tw_policy_split_row.argtypes = [_i64, _i64, _i64, ctypes.c_int, _i64, ctypes.c_int, _i64, _i64]
@@ -511,6 +515,33 @@ def weave_tune(X1, W1, partials, residual, weight, eps, W2, stream_compute, stre
                                _stream_handle(stream_compute), _stream_handle(stream_comm), ctypes.byref(best), us),
            "tw_weave_tune")
     return int(best.value), [float(x) for x in us]
+
+
+class CuMaskedStream:
+    """tw_stream_create_cu_masked: a stream confined to n_cus compute units. `.stream` is a
+    torch.cuda.ExternalStream over it; call close() once its work is done."""
+
+    def __init__(self, first_cu, n_cus):
+        import torch
+        h = _vp()
+        _check(lib().tw_stream_create_cu_masked(int(first_cu), int(n_cus), ctypes.byref(h)),
+               "tw_stream_create_cu_masked")
+        self.handle = h.value
+        self.stream = torch.cuda.ExternalStream(self.handle)
+
+    def close(self):
+        if self.handle:
+            self.stream.synchronize()
+            _check(lib().tw_stream_destroy(_vp(self.handle)), "tw_stream_destroy")
+            self.handle = None
+            self.stream = None
+
+    def __enter__(self):
+        return self.stream
+
+    def __exit__(self, *exc):
+        self.close()
+        return False
 
 
 def split_threshold(K1, H, P, N2, cus=256):

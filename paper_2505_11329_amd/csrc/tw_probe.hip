@@ -265,3 +265,28 @@ extern "C" tw_status tw_streams_overlap(void *stream_a, void *stream_b, int *ove
     *overlap = later_us < 1.6 * spin_us ? 1 : 0;
     return TW_OK;
 }
+
+extern "C" tw_status tw_stream_create_cu_masked(int first_cu, int n_cus, void **stream)
+{
+    if (!stream) return TW_ERR_NULL;
+    *stream = nullptr;
+    if (first_cu < 0 || n_cus < 1) return TW_ERR_SHAPE;
+    int cus = 0;
+    TW_TRY(current_cu_count(&cus));
+    if (first_cu > cus - n_cus) return TW_ERR_SHAPE;
+    constexpr int kMaxMaskWords = 32;  // 1024 compute units
+    if (cus > 32 * kMaxMaskWords) return TW_ERR_UNSUPPORTED;
+    uint32_t mask[kMaxMaskWords] = {};
+    for (int b = first_cu; b < first_cu + n_cus; ++b) mask[b / 32] |= 1u << (b % 32);
+    hipStream_t s = nullptr;
+    TW_HIP(hipExtStreamCreateWithCUMask(&s, static_cast<uint32_t>((cus + 31) / 32), mask));
+    *stream = s;
+    return TW_OK;
+}
+
+extern "C" tw_status tw_stream_destroy(void *stream)
+{
+    if (!stream) return TW_ERR_NULL;
+    TW_HIP(hipStreamDestroy(static_cast<hipStream_t>(stream)));
+    return TW_OK;
+}

@@ -37,7 +37,8 @@ def test_header_declares_the_documented_entry_points():
     aids = declared_functions(("tw_measure.h",))
     for must in ("tw_hbm_probe", "tw_hbm_probe_mixed", "tw_hbm_probe_shaped", "tw_hbm_probe_mixed_shaped",
                  "tw_fused_grid", "tw_fused_layout", "tw_weave_schedule", "tw_gemm_tile_shape",
-                 "tw_reduce_add_rmsnorm_traced", "tw_streams_overlap", "tw_gemm_bf16_traced"):
+                 "tw_reduce_add_rmsnorm_traced", "tw_streams_overlap", "tw_gemm_bf16_traced",
+                 "tw_stream_create_cu_masked", "tw_stream_destroy"):
         assert must in aids and must not in names
 
 
@@ -45,6 +46,16 @@ def test_library_exports_every_declared_symbol():
     L = ctypes.CDLL(tw.library_path())
     for name in declared_functions():
         assert hasattr(L, name), "libtw.so does not export %s" % name
+
+
+def test_cu_masked_stream_argument_checks():
+    L = tw.lib()
+    h = VP()
+    assert L.tw_stream_create_cu_masked(0, 32, None) == E_NULL
+    assert L.tw_stream_create_cu_masked(-1, 32, ctypes.byref(h)) == E_SHAPE
+    assert L.tw_stream_create_cu_masked(0, 0, ctypes.byref(h)) == E_SHAPE
+    assert h.value is None
+    assert L.tw_stream_destroy(None) == E_NULL
 
 
 def test_status_strings_and_version():

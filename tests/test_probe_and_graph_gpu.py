@@ -184,3 +184,46 @@ def test_streams_overlap_finds_a_partner_stream(tw, torch_cuda):
         verdicts.append(v)
     assert any(verdicts), verdicts
     torch.cuda.synchronize()
+
+
+def test_cu_masked_streams_confine_kernels_to_disjoint_compute_units(tw, torch_cuda):
+    """tw_stream_create_cu_masked: every workgroup of a launch on the masked stream, whatever its grid,
+    reports a compute unit from a set of exactly n_cus, spread evenly over the XCDs; the sets of two
+    disjoint ranges are disjoint; the two streams run side by side; and the bits are those of an
+    ordinary launch."""
+    torch = torch_cuda
+    cus = tw.device_cu_count()
+    d = W.make_fused_inputs("c3_70b_shard_tp8", N=1024)
+    g = {k: ([to_gpu(p) for p in v] if k == "partials" else to_gpu(v) if k in ("residual", "weight") else v)
+         for k, v in d.items()}
+    want = tw.reduce_add_rmsnorm(g["partials"], g["residual"], g["weight"], g["eps"], cu_budget=32)
+    torch.cuda.synchronize()
+
+    def places_of(stream, budget):
+        out, res, hw = tw.reduce_add_rmsnorm_traced(g["partials"], g["residual"], g["weight"], g["eps"],
+                                                    cu_budget=budget, stream=stream)
+        stream.synchronize()
+        assert torch.equal(out.view(torch.int16), want[0].view(torch.int16))
+        assert torch.equal(res.view(torch.int16), want[1].view(torch.int16))
+        hw = hw.cpu().numpy().astype(np.int64) & 0xFFFFFFFF
+        cu, se, sh, xcc = (hw[:, 0] >> 8) & 0xF, (hw[:, 0] >> 13) & 0x7, (hw[:, 0] >> 12) & 0x1, hw[:, 1] & 0xF
+        return set(zip(xcc.tolist(), se.tolist(), sh.tolist(), cu.tolist()))
+    few, rest = tw.CuMaskedStream(0, 32), tw.CuMaskedStream(32, cus - 32)
+    try:
+        a = places_of(few.stream, tw.CU_SHARED)            # 1024 small workgroups on 32 compute units
+        assert len(a) == 32
+        per_xcd = np.bincount([p[0] for p in a], minlength=8)
+        assert (per_xcd == 4).all(), per_xcd
+        assert places_of(few.stream, 64) <= a              # a persistent grid of 64: two per masked unit, in turn
+        b = places_of(rest.stream, tw.CU_SHARED)
+        assert len(b) == cus - 32 and not (a & b)
+        # (both streams have run kernels by now: the first dispatch on a new queue starts late)
+        assert any(tw.streams_overlap(few.stream, rest.stream) for _ in range(3))
+    finally:
+        few.close()
+        rest.close()
+    for bad in ((0, cus + 1), (cus - 7, 8), (cus, 1)):
+        with pytest.raises(tw.TwError) as e:
+            tw.CuMaskedStream(*bad)
+        assert e.value.status == 2                          # TW_ERR_SHAPE
+
