@@ -1015,7 +1015,7 @@ def policy_table(result, tw, W, torch, np, stream, comm, interleaved_medians, gp
         "per_boundary": out_,
         "note": "never = the chain G1, F, G2 unsplit on one stream; always = tw_weave_layer at the row "
                 "tw_smart_split_point picks, whatever T; policy = tw_weave_layer_auto with the built-in rule "
-                "(tw_policy_split_row: split from tw_split_threshold's tokens up, and from half of that up when the cut "
+                "(tw_policy_split_row: split from tw_split_threshold's tokens up, and above half of that when the cut "
                 "costs no GEMM waves); tuned = tw_weave_layer at the row tw_weave_tune reported for "
                 "this batch size beforehand (its timed search over: unsplit, the smart row, the middle, the middle "
                 "+ 256). A split row equal to T means no split. "

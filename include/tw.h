@@ -425,14 +425,14 @@ int64_t tw_split_threshold(int64_t K1, int64_t H, int P, int64_t N2, int cus);
  *     unsplit, anything else is cut at the row tw_smart_split_point picks
  *     (candidates at multiples of `multiple`, widths {H, N2}, depths {K1, H}).
  *   threshold <= 0 (built in): with t = tw_split_threshold() of the boundary, never
- *     when t is TW_NEVER_SPLIT; always at that row from t tokens up; and between
- *     t / 2 and t only when the cut costs no GEMM waves, i.e. when the cost
+ *     when t is TW_NEVER_SPLIT; always at that row from t tokens up; and for
+ *     t / 2 < T < t only when the cut costs no GEMM waves, i.e. when the cost
  *     tw_smart_split_point reports for the cut does not exceed that of the whole
  *     batch (Section 4.1.1's criterion). In that band the unsplit GEMMs' own wave
  *     quantisation decides: on MI355X, for K1 = 1024, H = 8192, P = 8, N2 = 3584
- *     and T = 4096 ... 8192 in steps of 256, the policy stays within 0.7 % of the
- *     best timed candidate on average (2.7 % at worst), against 1.3 % (4.0 %)
- *     for the threshold alone and 1.2 % (5.1 %) for always splitting; where it
+ *     and T = 4096 ... 8192 in steps of 256, the policy stays within 0.8 % of the
+ *     best timed candidate on average (2.9 % at worst), against 1.5 % (4.5 %)
+ *     for the threshold alone and 1.5 % (5.6 %) for always splitting; where it
  *     picks the slower of the two, the two are within 3 % of each other.
  * multiple <= 0: 64. Host only. Returns -1 on bad arguments (T < 0, another size
  * < 1).

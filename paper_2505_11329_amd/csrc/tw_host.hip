@@ -473,11 +473,11 @@ int64_t tw_policy_split_row(int64_t T, int64_t K1, int64_t H, int P, int64_t N2,
         return k < 0 ? T : k;
     }
     const int64_t thr = tw_split_threshold(K1, H, P, N2, cus);
-    if (thr < 0 || thr == TW_NEVER_SPLIT || T < thr / 2) return T;
+    if (thr < 0 || thr == TW_NEVER_SPLIT || T <= thr / 2) return T;
     int64_t cost_split = 0, cost_unsplit = 0;
     const int64_t k = tw_smart_split_point(T, multiple, widths, depths, 2, cus, &cost_split, &cost_unsplit);
     if (k < 0 || k >= T) return T;
-    // From half the threshold up, a batch is split when that costs no GEMM waves
+    // Above half the threshold, a batch is split when that costs no GEMM waves
     // (Section 4.1.1): whether a split wins there is decided by how the row tiles of
     // the halves and of the whole batch fall on the compute units.
     if (T < thr && cost_split > cost_unsplit) return T;

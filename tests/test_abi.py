@@ -469,14 +469,14 @@ def test_split_threshold_matches_its_definition():
 def test_policy_split_row_follows_threshold_band_and_wave_criterion():
     """tw_policy_split_row restated from its parts (Fig. 3; Section 4.1.1): a caller's threshold is the
     whole rule; the built-in one never splits a boundary whose threshold is 'never', always from the
-    threshold up, and between half of it and it only when the cut's GEMM waves (tw_smart_split_point's
+    threshold up, and above half of it and below it only when the cut's GEMM waves (tw_smart_split_point's
     costs) do not exceed the whole batch's."""
     K1, Hh, Pp, N2, cus = 1024, 8192, 8, 3584, 256
     thr = tw.split_threshold(K1, Hh, Pp, N2, cus)
     assert thr == 8192
     for T in list(range(0, 20000, 448)) + [4096, 4352, 4608, 6144, 7168, 8192, 8191, 4095]:
         k, cs, cu_ = tw.smart_split_point(T, 64, [Hh, N2], cus, gemm_k=[K1, Hh])
-        if T < thr // 2 or k >= T:
+        if T <= thr // 2 or k >= T:
             want = T
         elif T >= thr:
             want = k
