@@ -299,3 +299,51 @@ def test_weave_tune_times_the_candidates_and_leaves_the_layers_outputs(tw, torch
     got = (to_bits(parts[0]), to_bits(out), to_bits(res), to_bits(Y))
     for name, g_, w_ in zip(("G1", "out", "residual_out", "Y"), got, want):
         assert np.array_equal(g_, w_), name
+
+
+def test_weave_layer_random_shapes_cuts_and_schedules(tw, torch_cuda):
+    """Ragged layer boundaries (hidden sizes that are no power of two, odd token counts, P from 1 to 5,
+    GEMM widths and depths that are no multiple of a tile) through tw_weave_layer_cuts with random cuts,
+    schedules and launch modes: every stage of the unsplit chain against the oracle fed with the bits
+    of the stage before, and every woven run bit-equal to the unsplit one."""
+    torch = torch_cuda
+    rng = np.random.default_rng(2505)
+    streams = (torch.cuda.Stream(), torch.cuda.Stream())
+    cus = tw.device_cu_count()
+    for case in range(14):
+        T_ = int(rng.integers(1, 700))
+        H_ = int(rng.choice([64, 264, 520, 1024, 1536, 2048, 4104]))
+        P_ = int(rng.integers(1, 6))
+        K1_ = 8 * int(rng.integers(1, 80))
+        N2_ = 8 * int(rng.integers(1, 70))
+        g1 = W.make_gemm_inputs(T_, K1_, H_, STD, seed=100 + case, b_layout="nk")
+        f = W.make_fused_inputs(dict(N=T_, H=H_, P=P_, partial_std=0.5, residual_std=1.0, outlier_frac=0.01,
+                                     outlier_scale=20.0, eps=1e-5, seed=200 + case))
+        W2 = W.normal_bf16((N2_, H_), 0.05, 300 + case, W.STREAM_GEMM_B)
+        X1, W1, W2g = to_gpu(g1["A"]), to_gpu(g1["B"]), to_gpu(W2)
+        resid, weight = to_gpu(f["residual"]), to_gpu(f["weight"])
+
+        def run_cuts(cuts, schedule, budgets):
+            parts = [torch.full((T_, H_), float("nan"), dtype=torch.bfloat16, device="cuda:0")] + \
+                    [to_gpu(p) for p in f["partials"][1:]]
+            out, res, Y = tw.weave_layer_cuts(X1, W1, parts, resid, weight, f["eps"], W2g, cuts, streams[0], streams[1],
+                                              fused_cu_budget=budgets[0], gemm_cu_budget=budgets[1], schedule=schedule)
+            torch.cuda.synchronize()
+            return to_bits(parts[0]), to_bits(out), to_bits(res), to_bits(Y)
+        what = "case %d: T=%d H=%d P=%d K1=%d N2=%d" % (case, T_, H_, P_, K1_, N2_)
+        C0, out0, res0, Y0 = run_cuts([], tw.WEAVE_AUTO, (0, 0))
+        gemm_tol_check(oracle.bf16_to_f64(C0), oracle.gemm(g1["A"], g1["B"], "nk"), K1_, STD, STD, what + " G1")
+        ref_out, ref_res = oracle.fused([C0] + f["partials"][1:], f["residual"], f["weight"], f["eps"])
+        assert_parity(oracle.bf16_to_f64(res0), ref_res, what + " residual_out")
+        assert_parity(oracle.bf16_to_f64(out0), ref_out, what + " out")
+        # |out| is at most ~sqrt(H) * max|w| on a row that one outlier dominates; its typical size is ~1
+        gemm_tol_check(oracle.bf16_to_f64(Y0), oracle.gemm(out0, W2, "nk"), H_, 1.5, 0.05, what + " G2")
+        for trial in range(3):
+            n_cuts = int(rng.integers(1, min(T_ - 1, 6) + 1)) if T_ > 1 else 0
+            cuts = sorted(int(c) for c in rng.choice(np.arange(1, T_), size=n_cuts, replace=False)) if n_cuts else []
+            schedule = int(rng.choice([tw.WEAVE_AUTO, tw.WEAVE_ORDERED, tw.WEAVE_CHAINS]))
+            budgets = [(32, cus - 32), (tw.CU_SHARED, 0), (0, 0), (8, 16)][int(rng.integers(0, 4))]
+            got = run_cuts(cuts, schedule, budgets)
+            for name, g_, w_ in zip(("G1", "out", "residual_out", "Y"), got, (C0, out0, res0, Y0)):
+                assert np.array_equal(g_, w_), (what, cuts, schedule, budgets, name)
+
