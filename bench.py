@@ -867,8 +867,19 @@ def extras(result, tw, W, torch, np, stream, sets, fused_sets, algo_bytes, event
                                fused_cu_budget=fb, gemm_cu_budget=gb, out=out, residual_out=res_out, Y=Y,
                                parent=stream, use_parent=True, join=True, schedule=schedule)
         return f
+    # the paper's ablation at the level of a layer boundary (Section 5, "fuse only" against the baseline):
+    # the same unsplit chain with the pipeline the fused kernel replaces in its place (all-reduce to bf16,
+    # then residual add + RMSNorm re-reading it)
+    sum_scratch = torch.empty_like(resid)
+
+    def unfused_chain():
+        with torch.cuda.stream(stream):
+            tw.gemm_bf16(X1, W1, C=parts[0], stream=stream)
+            tw.reduce_add_rmsnorm_unfused(parts, resid, weight, d["eps"], out=out, residual_out=res_out,
+                                          sum_scratch=sum_scratch, stream=stream)
+            tw.gemm_bf16(out, W2, C=Y, stream=stream)
     # the schedules take turns in bursts of 8 calls, in rotating order
-    cands = {"unsplit": layer_fn(0, 0, 0)}
+    cands = {"unsplit": layer_fn(0, 0, 0), "unsplit_unfused": unfused_chain}
     plan = {}
     for fb in (32, 64, 96):
         k, ws, wu = tw.smart_split_point(T, 128, [H, N2], cus - fb, gemm_k=[K1, H])
@@ -881,7 +892,9 @@ def extras(result, tw, W, torch, np, stream, sets, fused_sets, algo_bytes, event
     cands["woven_shared_ordered"] = layer_fn(k, tw.CU_SHARED, 0, tw.WEAVE_ORDERED)
     cands["woven_shared_chains"] = layer_fn(k, tw.CU_SHARED, 0, tw.WEAVE_CHAINS)
     med = interleaved_medians(cands, rounds=5, iters=8, warm=2)
-    weave = {"unsplit_whole_device_us": med["unsplit"]}
+    weave = {"unsplit_whole_device_us": med["unsplit"],
+             "unsplit_with_the_unfused_pipeline_us": med["unsplit_unfused"],
+             "fusion_gain_on_the_layer": round(med["unsplit_unfused"] / med["unsplit"], 3)}
     for fb in (32, 64, 96):
         k, ws, wu = plan[fb]
         weave["fused_budget_%d" % fb] = {"split_row": k, "model_cost_split": ws, "model_cost_unsplit": wu,
@@ -897,9 +910,11 @@ def extras(result, tw, W, torch, np, stream, sets, fused_sets, algo_bytes, event
         "note": "woven = tw_weave_layer at the wave-aware split row, fused kernel confined to its budget and the "
                 "GEMMs to the other CUs (fused_shared: co-resident; woven_us with the schedule the library "
                 "picks, then each schedule forced); unsplit_same_budgets = same budgets, no split; unsplit_whole_device = "
-                "each kernel on all CUs in turn, one stream, no events; the schedules take turns in bursts",
+                "each kernel on all CUs in turn, one stream, no events; unsplit_with_the_unfused_pipeline = that chain "
+                "with tw_reduce_add_rmsnorm_unfused in the fused step's place (what fusing alone saves on the layer); "
+                "the schedules take turns in bursts",
     }
-    del X1, W1, W2, parts, resid, out, res_out, Y
+    del X1, W1, W2, parts, resid, out, res_out, Y, sum_scratch
     torch.cuda.empty_cache()
     budget_grid(result, tw, W, torch, np, stream, train_times, device_drawn_sets)
     policy_table(result, tw, W, torch, np, stream, comm, interleaved_medians, gpu)
