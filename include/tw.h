@@ -40,8 +40,8 @@
  *     recorded with. Make one eager call of each kind first (the first call on a
  *     device creates a few events and sets a kernel attribute, which a capture
  *     must not contain). Worth it for decode-sized batches (Appendix B, the
- *     decode paragraph): a train of 160 fused steps of 1 to 64 rows takes 5.8-6.4
- *     us per step launched eagerly and 5.2-5.9 us replayed from one graph, and the
+ *     decode paragraph): a train of 160 fused steps of 1 to 64 rows takes 5.1-6.1
+ *     us per step launched eagerly and 4.5-5.6 us replayed from one graph, and the
  *     host is busy 0.5 instead of 4.1 us per step; from 256 rows on the kernels
  *     themselves fill the time and a graph gains nothing.
  *   - Thread safety: calls may be made from several host threads at once; work
@@ -108,7 +108,10 @@ typedef enum tw_status {
  *                 to the whole device. Other negative values mean the whole
  *                 device. A small whole-device launch (P = 1, 2, 4 or 8; up to
  *                 4 to 16 rows per compute unit depending on P and H <= 8192) is
- *                 sent as those small workgroups too: same bits, lower latency.
+ *                 sent as those small workgroups too: same bits, lower latency;
+ *                 and one of a few dozen rows (decode steps: inputs of at most
+ *                 6 MiB) requests a whole row and the weights at once, one round
+ *                 trip to memory instead of three.
  *   out           device bf16 [N x H]
  *   residual_out  device bf16 [N x H]
  *

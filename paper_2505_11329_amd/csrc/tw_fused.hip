@@ -279,10 +279,21 @@ __global__ __launch_bounds__(kThreads) void fused_kernel(const FusedParams prm)
 // 10.6 -> 9.7 us).
 // ---------------------------------------------------------------------------
 static constexpr int kThinThreads = 256;
+// The all-at-once form is taken by whole-device launches of at most one workgroup per compute
+// unit whose inputs come to at most this many bytes. Measured on MI355X, H = 8192, trains of
+// launches replayed from a graph: P = 8 up to 48 rows 4.4-4.7 us a launch against 5.0-5.2
+// (-11 %), at 256 rows 7.1 against 6.5 (+8 %): beyond a few MB the requests of a launch queue up
+// and two chunks at a time come in faster.
+static constexpr int64_t kDeepInputBytes = 6 << 20;
 
-template <int PT, int Q, bool TRACE, bool STREAMED>
-__global__ __launch_bounds__(kThinThreads) __attribute__((amdgpu_waves_per_eu(4)))
-void fused_thin_kernel(const FusedParams prm)
+// DEEP: the form for batches so small that a launch is one round trip to memory
+// and back (decode steps, Appendix B): a workgroup has one row group only, every
+// chunk of it is requested at once together with the weights, and nothing is
+// refilled. It needs ~200 registers, so it is a kernel of its own
+// (fused_deep_kernel) without the 128-register bound that lets the other one
+// sit beside a GEMM workgroup. Same arithmetic in the same order: same bits.
+template <int PT, int Q, bool TRACE, bool STREAMED, bool DEEP>
+__device__ __forceinline__ void thin_body(const FusedParams &prm)
 {
     constexpr bool streamed = STREAMED;  // see st()
     __shared__ float s_wave_sum[2][kWaves];
@@ -376,13 +387,24 @@ void fused_thin_kernel(const FusedParams prm)
     // Chunks in flight: NB. Chunk (group, q) sits in buffer q % NB and is refilled
     // with the chunk NB further on: the same row's, or the workgroup's next row's;
     // after its last row nothing is fetched.
-    constexpr int NB = (Q % 2 == 0) ? 2 : 1;
+    constexpr int NB = DEEP ? Q : (Q % 2 == 0) ? 2 : 1;
+    static_assert(!DEEP || PT > 0, "the run-time loop over P keeps nothing in flight");
     auto off_or_none = [&](uint32_t group, int q) -> uint32_t {
         return group < last ? chunk_off(group, q) : kOutOfRange;
     };
     Chunk<PT> buf[NB];
     issue(buf[0], off_or_none(first, 0));
-    if constexpr (NB == 2) issue(buf[1], off_or_none(first, 1));
+    if constexpr (NB >= 2) issue(buf[1], off_or_none(first, 1));
+    if constexpr (NB >= 3) issue(buf[2], off_or_none(first, 2));
+    if constexpr (NB >= 4) issue(buf[3], off_or_none(first, 3));
+    static_assert(NB <= 4, "chunks issued above");
+    u32x4 w_ahead[DEEP ? Q : 1];
+    if constexpr (DEEP) {
+#pragma unroll
+        for (int q = 0; q < Q; ++q)
+            w_ahead[q] = __builtin_amdgcn_raw_buffer_load_b128(
+                r_w, cvalid[q] ? (col0 + q * kThinThreads) * 16u : kOutOfRange, 0, 0);
+    }
     int parity = 0;
     for (uint32_t group = first; group < last; group += gstride) {
         float x[Q][8];
@@ -391,7 +413,8 @@ void fused_thin_kernel(const FusedParams prm)
         for (int q = 0; q < Q; ++q) {
             Chunk<PT> &b = buf[q % NB];
             reduce_chunk(b, chunk_off(group, q), x[q]);
-            issue(b, (q + NB < Q) ? chunk_off(group, q + NB) : off_or_none(group + gstride, q + NB - Q));
+            if constexpr (!DEEP)
+                issue(b, (q + NB < Q) ? chunk_off(group, q + NB) : off_or_none(group + gstride, q + NB - Q));
             float acc = 0.0f;
 #pragma unroll
             for (int e = 0; e < 8; ++e) acc = __builtin_fmaf(x[q][e], x[q][e], acc);
@@ -416,13 +439,27 @@ void fused_thin_kernel(const FusedParams prm)
         for (int q = 0; q < Q; ++q) {
             float w[8], y[8];
             const int v = col0 + q * kThinThreads;
-            unpack8(__builtin_amdgcn_raw_buffer_load_b128(r_w, cvalid[q] ? v * 16u : kOutOfRange, 0, 0), w);
+            if constexpr (DEEP) unpack8(w_ahead[q], w);
+            else unpack8(__builtin_amdgcn_raw_buffer_load_b128(r_w, cvalid[q] ? v * 16u : kOutOfRange, 0, 0), w);
 #pragma unroll
             for (int e = 0; e < 8; ++e) y[e] = (x[q][e] * s) * w[e];
             st(r_res_out, chunk_off(group, q), pack8(x[q]), streamed);
             st(r_out, chunk_off(group, q), pack8(y), streamed);
         }
     }
+}
+
+template <int PT, int Q, bool TRACE, bool STREAMED>
+__global__ __launch_bounds__(kThinThreads) __attribute__((amdgpu_waves_per_eu(4)))
+void fused_thin_kernel(const FusedParams prm)
+{
+    thin_body<PT, Q, TRACE, STREAMED, false>(prm);
+}
+
+template <int PT, int Q>
+__global__ __launch_bounds__(kThinThreads) void fused_deep_kernel(const FusedParams prm)
+{
+    thin_body<PT, Q, false, false, true>(prm);
 }
 
 // ---------------------------------------------------------------------------
@@ -518,10 +555,30 @@ static tw_status launch_thin_t(const FusedParams &prm, bool trace, bool streamed
     return TW_OK;
 }
 
+template <int PT, int Q>
+static tw_status launch_deep_t(const FusedParams &prm, int64_t grid, hipStream_t stream)
+{
+    if constexpr (PT > 0) {
+        TW_HIP(launch_kernel(fused_deep_kernel<PT, Q>, dim3(static_cast<unsigned>(grid)), dim3(kThinThreads), 0u,
+                             stream, prm));
+        return TW_OK;
+    }
+    return TW_ERR_UNSUPPORTED;
+}
+
 template <int PT>
-static tw_status launch_thin(const FusedParams &prm, int q, bool trace, bool streamed, int64_t grid,
+static tw_status launch_thin(const FusedParams &prm, int q, bool trace, bool streamed, bool deep, int64_t grid,
                              hipStream_t s)
 {
+    if (deep) {
+        switch (q) {
+        case 1: return launch_deep_t<PT, 1>(prm, grid, s);
+        case 2: return launch_deep_t<PT, 2>(prm, grid, s);
+        case 3: return launch_deep_t<PT, 3>(prm, grid, s);
+        case 4: return launch_deep_t<PT, 4>(prm, grid, s);
+        }
+        return TW_ERR_UNSUPPORTED;
+    }
     switch (q) {
     case 1: return launch_thin_t<PT, 1>(prm, trace, streamed, grid, s);
     case 2: return launch_thin_t<PT, 2>(prm, trace, streamed, grid, s);
@@ -621,8 +678,15 @@ tw_status launch_fused(const tw_fused_args &a, int64_t row_begin, int64_t row_en
     for (int64_t r0 = row_begin; r0 < row_end; r0 += rows_per_launch) {
         const int64_t n_rows = (row_end - r0 < rows_per_launch) ? row_end - r0 : rows_per_launch;
         int64_t grid = 0;
+        bool deep = false;
         if (thin) {
             grid = thin_grid(n_rows, tg, cus);
+            // one row group per workgroup, at most one workgroup per compute unit, few
+            // bytes: the launch is latency-bound, everything is requested at once. Not
+            // in shared mode, whose workgroups must fit beside a GEMM's.
+            const int64_t n_groups = (n_rows + rows_per_group - 1) / rows_per_group;
+            deep = !trace && a.cu_budget != TW_CU_SHARED && (a.P == 1 || a.P == 2 || a.P == 4 || a.P == 8) &&
+                   grid == n_groups && n_groups <= cus && n_rows * row_bytes * (a.P + 1) <= kDeepInputBytes;
         } else {
             grid = fused_grid_size(n_rows, g, budget);
             if (grid > 1024) return TW_ERR_UNSUPPORTED;  // offset arithmetic in the kernel assumes this
@@ -650,11 +714,11 @@ tw_status launch_fused(const tw_fused_args &a, int64_t row_begin, int64_t row_en
 
         if (thin) {
             switch (a.P) {
-            case 1: TW_TRY((launch_thin<1>(prm, tg.q, trace, streamed, grid, stream))); break;
-            case 2: TW_TRY((launch_thin<2>(prm, tg.q, trace, streamed, grid, stream))); break;
-            case 4: TW_TRY((launch_thin<4>(prm, tg.q, trace, streamed, grid, stream))); break;
-            case 8: TW_TRY((launch_thin<8>(prm, tg.q, trace, streamed, grid, stream))); break;
-            default: TW_TRY((launch_thin<0>(prm, tg.q, trace, streamed, grid, stream))); break;
+            case 1: TW_TRY((launch_thin<1>(prm, tg.q, trace, streamed, deep, grid, stream))); break;
+            case 2: TW_TRY((launch_thin<2>(prm, tg.q, trace, streamed, deep, grid, stream))); break;
+            case 4: TW_TRY((launch_thin<4>(prm, tg.q, trace, streamed, deep, grid, stream))); break;
+            case 8: TW_TRY((launch_thin<8>(prm, tg.q, trace, streamed, deep, grid, stream))); break;
+            default: TW_TRY((launch_thin<0>(prm, tg.q, trace, streamed, deep, grid, stream))); break;
             }
             continue;
         }

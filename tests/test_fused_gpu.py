@@ -125,6 +125,22 @@ def test_shapes_and_tails(tw, torch_cuda, N, H, P):
     assert np.array_equal(out, out2) and np.array_equal(res, res2)
 
 
+@pytest.mark.parametrize("H,P", [(8192, 8), (8192, 4), (4096, 2), (2048, 8), (6144, 1), (520, 2)])
+def test_decode_sized_whole_device_launches_on_both_sides_of_the_all_at_once_limit(tw, torch_cuda, H, P):
+    """A whole-device launch of a few rows requests a row and the weights at once (inputs of at most
+    6 MiB, at most one workgroup per compute unit); one row more than that, or the shared mode, takes
+    the two-chunks-at-a-time form. Same bits either way, and the oracle's values."""
+    limit = (6 << 20) // (H * 2 * (P + 1))
+    for N in sorted({1, 2, 7, min(limit, 256), min(limit, 256) + 1}):
+        d = small(N, H, P, seed=31 * N + H + P)
+        g = upload(d)
+        out, res = run(tw, torch_cuda, g, cu_budget=0)
+        check_against_oracle(d, out, res, "decode-sized N=%d H=%d P=%d" % (N, H, P))
+        for budget in (tw.CU_SHARED, 5):
+            out2, res2 = run(tw, torch_cuda, g, cu_budget=budget)
+            assert np.array_equal(out, out2) and np.array_equal(res, res2), (N, budget)
+
+
 def test_every_p_from_1_to_16(tw, torch_cuda):
     for P in range(1, 17):
         d = small(40, 2048, P, seed=P)
