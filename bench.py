@@ -996,6 +996,14 @@ def policy_table(result, tw, W, torch, np, stream, comm, interleaved_medians, gp
             def never():
                 with torch.cuda.stream(stream):
                     tw.weave_layer(X1, W1, parts, resid, weight, 1e-5, W2, 0, stream, comm, **kw)
+            sum_scratch = torch.empty_like(resid)
+
+            def never_unfused():      # the baseline of the paper's ablation: no split, no fused kernel
+                with torch.cuda.stream(stream):
+                    tw.gemm_bf16(X1, W1, C=parts[0], stream=stream)
+                    tw.reduce_add_rmsnorm_unfused(parts, resid, weight, 1e-5, out=o, residual_out=r,
+                                                  sum_scratch=sum_scratch, stream=stream)
+                    tw.gemm_bf16(o, W2, C=Y, stream=stream)
 
             def always():
                 with torch.cuda.stream(stream):
@@ -1010,15 +1018,18 @@ def policy_table(result, tw, W, torch, np, stream, comm, interleaved_medians, gp
                     tw.weave_layer(X1, W1, parts, resid, weight, 1e-5, W2, 0 if k_tuned == T else k_tuned, stream, comm,
                                    **kw)
             iters = 8 if T <= 8192 else 5
-            med = interleaved_medians({"never": never, "always": always, "policy": policy, "tuned": tuned}, rounds=4,
-                                      iters=iters, warm=2)
+            med = interleaved_medians({"never": never, "always": always, "policy": policy, "tuned": tuned,
+                                       "never_unfused": never_unfused}, rounds=4, iters=iters, warm=2)
             best = min(med["never"], med["always"])
             rows.append({"T": T, "never_split_us": med["never"], "always_split_us": med["always"],
-                         "policy_us": med["policy"], "tuned_us": med["tuned"], "policy_split_row": taken[-1],
+                         "policy_us": med["policy"], "tuned_us": med["tuned"],
+                         "never_split_unfused_pipeline_us": med["never_unfused"],
+                         "policy_over_unfused_baseline": round(med["never_unfused"] / med["policy"], 3),
+                         "policy_split_row": taken[-1],
                          "tuned_split_row": k_tuned, "always_split_row": k_smart,
                          "policy_over_best": round(med["policy"] / best, 3),
                          "tuned_over_best": round(med["tuned"] / best, 3)})
-            del X1, resid, parts, o, r, Y
+            del X1, resid, parts, o, r, Y, sum_scratch
             torch.cuda.empty_cache()
         out_[name] = {"boundary": "[Tx%d]x[%dx8192] -> fused H=8192 P=8 (shared mode) -> [Tx8192]x[8192x%d]"
                                   % (K1, K1, N2),
@@ -1033,7 +1044,9 @@ def policy_table(result, tw, W, torch, np, stream, comm, interleaved_medians, gp
                 "(tw_policy_split_row: split from tw_split_threshold's tokens up, and above half of that when the cut "
                 "costs no GEMM waves); tuned = tw_weave_layer at the row tw_weave_tune reported for "
                 "this batch size beforehand (its timed search over: unsplit, the smart row, the middle, the middle "
-                "+ 256). A split row equal to T means no split. "
+                "+ 256). A split row equal to T means no split. never_split_unfused_pipeline = the unsplit chain with "
+                "tw_reduce_add_rmsnorm_unfused in the fused step's place: the baseline of the paper's ablation (no "
+                "fused kernel, no overlap); policy_over_unfused_baseline = what fusion and the policy gain together. "
                 "Candidates take turns in bursts, in rotating order; medians of HIP-event timed calls"}
 
 
