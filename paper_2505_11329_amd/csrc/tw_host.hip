@@ -152,7 +152,7 @@ const char *tw_status_str(tw_status s)
     return "unknown status";
 }
 
-const char *tw_version(void) { return "libtw 0.1 (gfx950)"; }
+const char *tw_version(void) { return "libtw 0.2 (gfx950)"; }
 
 int tw_last_hip_error(void) { return g_last_hip_error; }
 
