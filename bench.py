@@ -918,6 +918,7 @@ def extras(result, tw, W, torch, np, stream, sets, fused_sets, algo_bytes, event
     torch.cuda.empty_cache()
     budget_grid(result, tw, W, torch, np, stream, train_times, device_drawn_sets)
     policy_table(result, tw, W, torch, np, stream, comm, interleaved_medians, gpu)
+    weave_trains(result, tw, W, torch, np, stream, comm, interleaved_medians)
     decode_trains(result, tw, W, torch, np, stream, gpu)
     result["streams"] = {"second_streams_checked_with": "tw_streams_overlap", "torch_streams_tried": _streams_tried[0],
                          "note": "two streams on one hardware queue never overlap; every second stream used for a "
@@ -1048,6 +1049,71 @@ def policy_table(result, tw, W, torch, np, stream, comm, interleaved_medians, gp
                 "tw_reduce_add_rmsnorm_unfused in the fused step's place: the baseline of the paper's ablation (no "
                 "fused kernel, no overlap); policy_over_unfused_baseline = what fusion and the policy gain together. "
                 "Candidates take turns in bursts, in rotating order; medians of HIP-event timed calls"}
+
+
+def weave_trains(result, tw, W, torch, np, stream, comm, interleaved_medians):
+    """Consecutive layer boundaries as an engine would run them (Fig. 7b continues from layer to layer):
+    eight boundaries of a 70B-class TP=8 model (attention side, MLP side, alternating) back to back, unsplit
+    on one stream, woven with a fork and a join around every boundary, and woven with the two splits'
+    chains running on through the boundaries (one fork before the first, one join after the last)."""
+    H, P, L = 8192, 8, 8
+    cus = tw.device_cu_count()
+    gen = torch.Generator(device="cuda:0")
+    gen.manual_seed(11)
+
+    def rnd(shape, std):
+        return torch.empty(shape, dtype=torch.bfloat16, device="cuda:0").normal_(0.0, std, generator=gen)
+    shapes = [(1024, 3584), (3584, 1280)]
+    Ws = [(rnd((H, K1), 0.02), rnd((N2, H), 0.02)) for (K1, N2) in shapes]
+    weight = torch.ones(H, dtype=torch.bfloat16, device="cuda:0")
+    rows_out = []
+    for T in (4096, 8192, 16384):
+        bufs = [dict(X1=rnd((T, K1), 0.02), resid=rnd((T, H), 1.0), parts=[rnd((T, H), 0.25) for _ in range(P)],
+                     o=torch.empty((T, H), dtype=torch.bfloat16, device="cuda:0"),
+                     r=torch.empty((T, H), dtype=torch.bfloat16, device="cuda:0"),
+                     Y=torch.empty((T, N2), dtype=torch.bfloat16, device="cuda:0")) for (K1, N2) in shapes]
+        torch.cuda.synchronize()
+        cut = [tw.smart_split_point(T, 64, [H, N2], cus, gemm_k=[K1, H])[0] for (K1, N2) in shapes]
+
+        def call(i, k, use_parent, join):
+            b, (W1, W2) = bufs[i % 2], Ws[i % 2]
+            tw.weave_layer(b["X1"], W1, b["parts"], b["resid"], weight, 1e-5, W2, k, stream, comm,
+                           fused_cu_budget=tw.CU_SHARED, gemm_cu_budget=0, out=b["o"], residual_out=b["r"], Y=b["Y"],
+                           parent=stream, use_parent=use_parent, join=join)
+
+        def unsplit():
+            with torch.cuda.stream(stream):
+                for i in range(L):
+                    call(i, 0, False, False)
+
+        def woven_each():
+            with torch.cuda.stream(stream):
+                for i in range(L):
+                    call(i, cut[i % 2], True, True)
+
+        def woven_through():
+            with torch.cuda.stream(stream):
+                for i in range(L):
+                    call(i, cut[i % 2], i == 0, False)
+                ev = torch.cuda.Event()
+                ev.record(comm)
+                stream.wait_event(ev)
+        med = interleaved_medians({"unsplit": unsplit, "woven_each": woven_each, "woven_through": woven_through},
+                                  rounds=4, iters=4, warm=1)
+        rows_out.append({"T": T, "unsplit_us_per_boundary": round(med["unsplit"] / L, 1),
+                         "woven_fork_join_each_us_per_boundary": round(med["woven_each"] / L, 1),
+                         "woven_through_us_per_boundary": round(med["woven_through"] / L, 1),
+                         "through_over_unsplit": round(med["woven_through"] / med["unsplit"], 3)})
+        del bufs
+        torch.cuda.empty_cache()
+    result["weave_trains"] = {
+        "workload": "8 consecutive layer boundaries (attention side K1=1024, N2=3584 and MLP side K1=3584, N2=1280 "
+                    "alternating; H=8192, P=8, shared mode), per boundary",
+        "rows": rows_out,
+        "note": "unsplit: every boundary on one stream; woven_fork_join_each: tw_weave_layer with a parent stream and "
+                "join around every boundary (what the per-boundary tables time); woven_through: parent_is_set only on "
+                "the first call and no join, so each split's chain runs on through the boundaries on its own stream, "
+                "and one event joins the second stream at the end"}
 
 
 def decode_trains(result, tw, W, torch, np, stream, gpu):

@@ -308,6 +308,13 @@ tw_status tw_overlap_launch(const tw_fused_args *fused, const tw_gemm_args *gemm
  *   gemm_cu_budget  persistent grid of the GEMMs; pass (CU count - fused.cu_budget)
  *                so that the fused kernel always finds its compute units free
  *   parent, parent_is_set, join   as for tw_split_launch
+ * Consecutive boundaries (the next layer's, on the same two streams) need no fork
+ * and join in between: pass parent_is_set = 1 on the first call only and join = 0
+ * throughout, so that each split's chain runs on through the boundaries on its own
+ * stream as in Fig. 7b, and join the second stream once at the end with an event
+ * (2-3 % less per boundary than a fork and a join around every call, measured on
+ * trains of eight 70B-class boundaries at 4K to 16K tokens). Rows of one split
+ * must then depend only on rows of the same split between the boundaries.
  * The two streams must differ. Buffers must satisfy the aliasing rules of the
  * three operations they take part in.
  */
