@@ -301,6 +301,46 @@ def test_weave_tune_times_the_candidates_and_leaves_the_layers_outputs(tw, torch
         assert np.array_equal(g_, w_), name
 
 
+@pytest.mark.parametrize("schedule", [1, 2])   # TW_WEAVE_ORDERED, TW_WEAVE_CHAINS
+def test_two_boundaries_woven_through_without_a_join_in_between(tw, torch_cuda, schedule):
+    """Consecutive boundaries as an engine runs them: the second boundary's input is the first one's
+    output, only the first call forks from the parent, none joins, and one event joins the second
+    stream at the end. With the same cut in both, every row of a split depends only on rows of that
+    split, so stream order alone carries the dependency; the bits are those of the unsplit pair."""
+    torch = torch_cuda
+    g1, f, W2 = make_inputs()
+    sx, sc, parent = torch.cuda.Stream(), torch.cuda.Stream(), torch.cuda.Stream()
+    X1, W1, W2g = to_gpu(g1["A"]), to_gpu(g1["B"]), to_gpu(W2)
+    resid, weight = to_gpu(f["residual"]), to_gpu(f["weight"])
+    W1b = to_gpu(W.normal_bf16((H, N2), 0.05, 21, W.STREAM_GEMM_B))        # second boundary: [T x N2] x [N2 x H]
+    W2b = to_gpu(W.normal_bf16((K1, H), 0.05, 22, W.STREAM_GEMM_B))
+
+    def run_pair(cut, first_has_parent):
+        parts_a = [torch.full((T, H), float("nan"), dtype=torch.bfloat16, device="cuda:0")] + \
+                  [to_gpu(p) for p in f["partials"][1:]]
+        parts_b = [torch.full((T, H), float("nan"), dtype=torch.bfloat16, device="cuda:0")] + \
+                  [to_gpu(p) for p in f["partials"][1:]]
+        src = torch.zeros_like(X1)
+        torch.cuda.synchronize()
+        with torch.cuda.stream(parent):
+            src.copy_(X1)                                  # the first call must wait for this
+        kw = dict(fused_cu_budget=tw.CU_SHARED, gemm_cu_budget=0, schedule=schedule)
+        out1, res1, Y1 = tw.weave_layer(src, W1, parts_a, resid, weight, f["eps"], W2g, cut, sx, sc, parent=parent,
+                                        use_parent=first_has_parent, join=False, **kw)
+        out2, res2, Y2 = tw.weave_layer(Y1, W1b, parts_b, res1, weight, f["eps"], W2b, cut, sx, sc, parent=None,
+                                        use_parent=False, join=False, **kw)
+        ev = torch.cuda.Event()
+        ev.record(sc)
+        sx.wait_event(ev)
+        sx.synchronize()
+        return [to_bits(t) for t in (Y1, res1, out2, res2, Y2)]
+    want = run_pair(0, True)
+    for cut in (320, 256, 1, T - 1):
+        got = run_pair(cut, True)
+        for name, g_, w_ in zip(("Y1", "res1", "out2", "res2", "Y2"), got, want):
+            assert np.array_equal(g_, w_), (schedule, cut, name)
+
+
 def test_weave_layer_random_shapes_cuts_and_schedules(tw, torch_cuda):
     """Ragged layer boundaries (hidden sizes that are no power of two, odd token counts, P from 1 to 5,
     GEMM widths and depths that are no multiple of a tile) through tw_weave_layer_cuts with random cuts,
