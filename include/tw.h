@@ -311,10 +311,15 @@ tw_status tw_overlap_launch(const tw_fused_args *fused, const tw_gemm_args *gemm
  * Consecutive boundaries (the next layer's, on the same two streams) need no fork
  * and join in between: pass parent_is_set = 1 on the first call only and join = 0
  * throughout, so that each split's chain runs on through the boundaries on its own
- * stream as in Fig. 7b, and join the second stream once at the end with an event
- * (2-3 % less per boundary than a fork and a join around every call, measured on
- * trains of eight 70B-class boundaries at 4K to 16K tokens). Rows of one split
- * must then depend only on rows of the same split between the boundaries.
+ * stream as in Fig. 7b, and join the second stream once at the end with an event.
+ * A call without a parent adds no dependency between the two streams at all (one
+ * chain per split; the compute/communication order keeps its events). Measured on
+ * trains of eight 70B-class boundaries, per boundary: 5 % (4K and 8K tokens) and
+ * 8 % (16K) less than the unsplit train, where a fork and a join around every
+ * call is 2 % more to 3 % less; so an engine that runs through can split from
+ * about 4K tokens (pass that as the threshold: the built-in one is calibrated on
+ * single calls). Rows of one split must then depend only on rows of the same
+ * split between the boundaries.
  * The two streams must differ. Buffers must satisfy the aliasing rules of the
  * three operations they take part in.
  */

@@ -322,7 +322,7 @@ static tw_status validate_layer(const tw_layer_args *layer, void *stream_compute
 // Rows [lo, mid) and [mid, hi) of the boundary as one woven pair of splits, the
 // first on sx, the second on sc (mid == hi: rows [lo, hi) as one chain on sx).
 static tw_status weave_pair(const tw_fused_args &f, const tw_gemm_args &g1, const tw_gemm_args &g2, bool chains,
-                            int64_t lo, int64_t mid, int64_t hi, hipStream_t sx, hipStream_t sc)
+                            bool stagger, int64_t lo, int64_t mid, int64_t hi, hipStream_t sx, hipStream_t sc)
 {
     if (mid >= hi) {
         TW_TRY(launch_gemm(rows_of(g1, lo, hi), sx, false));
@@ -330,15 +330,23 @@ static tw_status weave_pair(const tw_fused_args &f, const tw_gemm_args &g1, cons
         return launch_gemm(rows_of(g2, lo, hi), sx, false);
     }
     if (chains) {
-        // one chain per split; the second starts when the first split's G1 is done.
+        // one chain per split. Where both chains start from the same point (the first
+        // pair of a call that forks from a parent) the second is held back until the
+        // first split's G1 is done, so that the two run out of step: one's fused kernel
+        // beside the other's GEMM. Chains that are already running (a call without a
+        // parent: the next boundary of a train; later pairs of a list of cuts) are out
+        // of step as they are, and holding the second back at every boundary cost 3-4 %
+        // of a boundary on trains of eight.
         // The first GEMM of the first chain and the last of the second have no fused
         // kernel of this pair beside them (the one runs before any, the other after
         // both): they take the tile shape of a GEMM launched on its own.
-        hipEvent_t g1a_done;
         TW_TRY(launch_gemm(rows_of(g1, lo, mid), sx, false));
-        TW_TRY(borrow_event(&g1a_done));
-        TW_HIP(hipEventRecord(g1a_done, sx));
-        TW_HIP(hipStreamWaitEvent(sc, g1a_done, 0));
+        if (stagger) {
+            hipEvent_t g1a_done;
+            TW_TRY(borrow_event(&g1a_done));
+            TW_HIP(hipEventRecord(g1a_done, sx));
+            TW_HIP(hipStreamWaitEvent(sc, g1a_done, 0));
+        }
         TW_TRY(launch_fused(f, lo, mid, nullptr, 0, sx));
         TW_TRY(launch_gemm(rows_of(g2, lo, mid), sx, true));
         TW_TRY(launch_gemm(rows_of(g1, mid, hi), sc, true));
@@ -411,7 +419,7 @@ tw_status tw_weave_layer_cuts(const tw_layer_args *layer, const int64_t *cuts, i
     auto row = [&](int i) { return i == 0 ? int64_t(0) : i == n_splits ? T : cuts[i - 1]; };
     for (int s = 0; s < n_splits; s += 2) {
         const int64_t lo = row(s), mid = row(s + 1), hi = s + 2 <= n_splits ? row(s + 2) : mid;
-        TW_TRY(weave_pair(f, g1, g2, chains, lo, mid, hi, sx, sc));
+        TW_TRY(weave_pair(f, g1, g2, chains, parent_is_set && s == 0, lo, mid, hi, sx, sc));
     }
     if (parent_is_set && join) {
         if (sx != sp) TW_TRY(stream_wait_stream(sp, sx));
