@@ -1090,6 +1090,16 @@ def weave_trains(result, tw, W, torch, np, stream, comm, interleaved_medians):
             with torch.cuda.stream(stream):
                 for i in range(L):
                     call(i, cut[i % 2], True, True)
+        scratch = torch.empty((T, H), dtype=torch.bfloat16, device="cuda:0")
+
+        def unsplit_unfused():      # neither of the paper's two techniques: the baseline of its ablation
+            with torch.cuda.stream(stream):
+                for i in range(L):
+                    b, (W1, W2) = bufs[i % 2], Ws[i % 2]
+                    tw.gemm_bf16(b["X1"], W1, C=b["parts"][0], stream=stream)
+                    tw.reduce_add_rmsnorm_unfused(b["parts"], b["resid"], weight, 1e-5, out=b["o"], residual_out=b["r"],
+                                                  sum_scratch=scratch, stream=stream)
+                    tw.gemm_bf16(b["o"], W2, C=b["Y"], stream=stream)
 
         def woven_through():
             with torch.cuda.stream(stream):
@@ -1098,13 +1108,15 @@ def weave_trains(result, tw, W, torch, np, stream, comm, interleaved_medians):
                 ev = torch.cuda.Event()
                 ev.record(comm)
                 stream.wait_event(ev)
-        med = interleaved_medians({"unsplit": unsplit, "woven_each": woven_each, "woven_through": woven_through},
-                                  rounds=4, iters=4, warm=1)
-        rows_out.append({"T": T, "unsplit_us_per_boundary": round(med["unsplit"] / L, 1),
+        med = interleaved_medians({"unsplit": unsplit, "woven_each": woven_each, "woven_through": woven_through,
+                                   "unsplit_unfused": unsplit_unfused}, rounds=4, iters=4, warm=1)
+        rows_out.append({"T": T, "unsplit_unfused_pipeline_us_per_boundary": round(med["unsplit_unfused"] / L, 1),
+                         "woven_through_gain_over_unfused_unsplit": round(med["unsplit_unfused"] / med["woven_through"], 3),
+                         "unsplit_us_per_boundary": round(med["unsplit"] / L, 1),
                          "woven_fork_join_each_us_per_boundary": round(med["woven_each"] / L, 1),
                          "woven_through_us_per_boundary": round(med["woven_through"] / L, 1),
                          "through_over_unsplit": round(med["woven_through"] / med["unsplit"], 3)})
-        del bufs
+        del bufs, scratch
         torch.cuda.empty_cache()
     result["weave_trains"] = {
         "workload": "8 consecutive layer boundaries (attention side K1=1024, N2=3584 and MLP side K1=3584, N2=1280 "
@@ -1113,7 +1125,9 @@ def weave_trains(result, tw, W, torch, np, stream, comm, interleaved_medians):
         "note": "unsplit: every boundary on one stream; woven_fork_join_each: tw_weave_layer with a parent stream and "
                 "join around every boundary (what the per-boundary tables time); woven_through: parent_is_set only on "
                 "the first call and no join, so each split's chain runs on through the boundaries on its own stream, "
-                "and one event joins the second stream at the end"}
+                "and one event joins the second stream at the end; unsplit_unfused_pipeline: the unsplit train with "
+                "tw_reduce_add_rmsnorm_unfused in the fused step's place (no fused kernel, no overlap), and "
+                "woven_through_gain_over_unfused_unsplit what the two techniques gain together"}
 
 
 def decode_trains(result, tw, W, torch, np, stream, gpu):
