@@ -285,10 +285,12 @@ tw_status tw_overlap_launch(const tw_fused_args *fused, const tw_gemm_args *gemm
  *       and F(b) next to G2(a). No two GEMMs ever compete, but three waits on
  *       another stream (15-20 us each on MI355X) lie on the critical path.
  *   TW_WEAVE_CHAINS   each split is a chain of its own: G1(a) F(a) G2(a) on
- *       stream_compute, G1(b) F(b) G2(b) on stream_comm, the second chain held
- *       back until G1(a) is done so that the two stay out of step. One wait on
- *       another stream, off the critical path; what overlaps with what is left
- *       to the hardware.
+ *       stream_compute, G1(b) F(b) G2(b) on stream_comm. In a call that forks
+ *       from a parent (both chains start at one point) the second chain is held
+ *       back until G1(a) is done so that the two run out of step: one wait on
+ *       another stream, off the critical path. A call without a parent adds no
+ *       dependency between the streams. What overlaps with what is left to the
+ *       hardware.
  *   TW_WEAVE_AUTO     chains when the fused kernel is not confined to a CU budget
  *       (shared mode or whole device): on the block boundaries of a 70B-class
  *       layer they are level to 13 % faster than the ordered schedule at 256 to
