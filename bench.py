@@ -1067,7 +1067,7 @@ def weave_trains(result, tw, W, torch, np, stream, comm, interleaved_medians):
     Ws = [(rnd((H, K1), 0.02), rnd((N2, H), 0.02)) for (K1, N2) in shapes]
     weight = torch.ones(H, dtype=torch.bfloat16, device="cuda:0")
     rows_out = []
-    for T in (4096, 8192, 16384):
+    for T in (2048, 3072, 4096, 5120, 7168, 8192, 12288, 16384, 32768):
         bufs = [dict(X1=rnd((T, K1), 0.02), resid=rnd((T, H), 1.0), parts=[rnd((T, H), 0.25) for _ in range(P)],
                      o=torch.empty((T, H), dtype=torch.bfloat16, device="cuda:0"),
                      r=torch.empty((T, H), dtype=torch.bfloat16, device="cuda:0"),
@@ -1109,7 +1109,7 @@ def weave_trains(result, tw, W, torch, np, stream, comm, interleaved_medians):
                 ev.record(comm)
                 stream.wait_event(ev)
         med = interleaved_medians({"unsplit": unsplit, "woven_each": woven_each, "woven_through": woven_through,
-                                   "unsplit_unfused": unsplit_unfused}, rounds=4, iters=4, warm=1)
+                                   "unsplit_unfused": unsplit_unfused}, rounds=4, iters=4 if T <= 16384 else 2, warm=1)
         rows_out.append({"T": T, "unsplit_unfused_pipeline_us_per_boundary": round(med["unsplit_unfused"] / L, 1),
                          "woven_through_gain_over_unfused_unsplit": round(med["unsplit_unfused"] / med["woven_through"], 3),
                          "unsplit_us_per_boundary": round(med["unsplit"] / L, 1),

@@ -316,11 +316,11 @@ tw_status tw_overlap_launch(const tw_fused_args *fused, const tw_gemm_args *gemm
  * stream as in Fig. 7b, and join the second stream once at the end with an event.
  * A call without a parent adds no dependency between the two streams at all (one
  * chain per split; the compute/communication order keeps its events). Measured on
- * trains of eight 70B-class boundaries, per boundary: 2 to 5 % (4K and 8K tokens)
- * and 8 % (16K) less than the unsplit train, where a fork and a join around every
- * call is 2 % more to 3 % less; so an engine that runs through can split from
- * about 4K tokens (pass that as the threshold: the built-in one is calibrated on
- * single calls). Rows of one split must then depend only on rows of the same
+ * trains of eight 70B-class boundaries, per boundary: 2 to 11 % less than the
+ * unsplit train from 3K to 32K tokens (7 % more at 2K), where a fork and a join
+ * around every call is 3 % more to 5 % less; so an engine that runs through can
+ * split from about 3K tokens (pass that as the threshold: the built-in one is
+ * calibrated on single calls). Rows of one split must then depend only on rows of the same
  * split between the boundaries.
  * The two streams must differ. Buffers must satisfy the aliasing rules of the
  * three operations they take part in.
