@@ -467,7 +467,10 @@ int64_t tw_policy_split_row(int64_t T, int64_t K1, int64_t H, int P, int64_t N2,
  * (may be NULL) receives the row taken, T meaning
  * "not split"; it is written before anything is enqueued, also when the launch
  * then fails. Everything else as for tw_weave_layer, whose bit-exactness across
- * split rows makes the policy invisible in the results.
+ * split rows makes the policy invisible in the results. The row is chosen per
+ * boundary from its shapes: a train of boundaries woven through without joins
+ * (see tw_weave_layer) needs ONE row for all of them, so take it once (e.g. from
+ * tw_policy_split_row for the first boundary) and call tw_weave_layer.
  */
 tw_status tw_weave_layer_auto(const tw_layer_args *layer, int64_t threshold, int64_t multiple, void *stream_compute,
                               void *stream_comm, void *parent, int parent_is_set, int join, int64_t *split_row);
