@@ -1055,7 +1055,8 @@ def weave_trains(result, tw, W, torch, np, stream, comm, interleaved_medians):
     """Consecutive layer boundaries as an engine would run them (Fig. 7b continues from layer to layer):
     eight boundaries of a 70B-class TP=8 model (attention side, MLP side, alternating) back to back, unsplit
     on one stream, woven with a fork and a join around every boundary, and woven with the two splits'
-    chains running on through the boundaries (one fork before the first, one join after the last)."""
+    chains running on through the boundaries (tw_weave_train: one fork before the first, one join after the
+    last)."""
     H, P, L = 8192, 8, 8
     cus = tw.device_cu_count()
     gen = torch.Generator(device="cuda:0")
@@ -1101,13 +1102,13 @@ def weave_trains(result, tw, W, torch, np, stream, comm, interleaved_medians):
                                                   sum_scratch=scratch, stream=stream)
                     tw.gemm_bf16(b["o"], W2, C=b["Y"], stream=stream)
 
+        train = [dict(X1=bufs[i % 2]["X1"], W1=Ws[i % 2][0], partials=bufs[i % 2]["parts"], residual=bufs[i % 2]["resid"],
+                      weight=weight, eps=1e-5, W2=Ws[i % 2][1], out=bufs[i % 2]["o"], residual_out=bufs[i % 2]["r"],
+                      Y=bufs[i % 2]["Y"]) for i in range(L)]
+
         def woven_through():
             with torch.cuda.stream(stream):
-                for i in range(L):
-                    call(i, cut[i % 2], i == 0, False)
-                ev = torch.cuda.Event()
-                ev.record(comm)
-                stream.wait_event(ev)
+                tw.weave_train(train, cut[0], stream, comm, parent=stream, use_parent=True, join=True)
         med = interleaved_medians({"unsplit": unsplit, "woven_each": woven_each, "woven_through": woven_through,
                                    "unsplit_unfused": unsplit_unfused}, rounds=4, iters=4 if T <= 16384 else 2, warm=1)
         rows_out.append({"T": T, "unsplit_unfused_pipeline_us_per_boundary": round(med["unsplit_unfused"] / L, 1),
@@ -1116,16 +1117,16 @@ def weave_trains(result, tw, W, torch, np, stream, comm, interleaved_medians):
                          "woven_fork_join_each_us_per_boundary": round(med["woven_each"] / L, 1),
                          "woven_through_us_per_boundary": round(med["woven_through"] / L, 1),
                          "through_over_unsplit": round(med["woven_through"] / med["unsplit"], 3)})
-        del bufs, scratch
+        del bufs, scratch, train
         torch.cuda.empty_cache()
     result["weave_trains"] = {
         "workload": "8 consecutive layer boundaries (attention side K1=1024, N2=3584 and MLP side K1=3584, N2=1280 "
                     "alternating; H=8192, P=8, shared mode), per boundary",
         "rows": rows_out,
         "note": "unsplit: every boundary on one stream; woven_fork_join_each: tw_weave_layer with a parent stream and "
-                "join around every boundary (what the per-boundary tables time); woven_through: parent_is_set only on "
-                "the first call and no join, so each split's chain runs on through the boundaries on its own stream, "
-                "and one event joins the second stream at the end; unsplit_unfused_pipeline: the unsplit train with "
+                "join around every boundary (what the per-boundary tables time); woven_through: tw_weave_train, one fork "
+                "before the first boundary and one join after the last, each split's chain running on through the "
+                "boundaries on its own stream; unsplit_unfused_pipeline: the unsplit train with "
                 "tw_reduce_add_rmsnorm_unfused in the fused step's place (no fused kernel, no overlap), and "
                 "woven_through_gain_over_unfused_unsplit what the two techniques gain together"}
 

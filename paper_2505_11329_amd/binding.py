@@ -102,6 +102,9 @@ def lib():
         L.tw_weave_layer_cuts.argtypes = [ctypes.POINTER(LayerArgs), ctypes.POINTER(_i64), ctypes.c_int, _vp, _vp, _vp,
                                           ctypes.c_int, ctypes.c_int]
         L.tw_weave_layer_cuts.restype = ctypes.c_int
+        L.tw_weave_train.argtypes = [ctypes.POINTER(LayerArgs), ctypes.c_int, _i64, _vp, _vp, _vp, ctypes.c_int,
+                                     ctypes.c_int]
+        L.tw_weave_train.restype = ctypes.c_int
         L.tw_weave_layer_auto.argtypes = [ctypes.POINTER(LayerArgs), _i64, _i64, _vp, _vp, _vp, ctypes.c_int, ctypes.c_int,
                                           ctypes.POINTER(_i64)]
         L.tw_weave_layer_auto.restype = ctypes.c_int
@@ -447,6 +450,27 @@ def weave_layer_cuts(X1, W1, partials, residual, weight, eps, W2, cuts, stream_c
                                      _stream_handle(parent) if use_parent else _vp(None),
                                      1 if use_parent else 0, 1 if join else 0), "tw_weave_layer_cuts")
     return out, residual_out, Y
+
+
+def weave_train(boundaries, split_row, stream_compute, stream_comm, parent=None, use_parent=True, join=True,
+                fused_cu_budget=CU_SHARED, gemm_cu_budget=0, schedule=WEAVE_AUTO):
+    """tw_weave_train. `boundaries` is a list of dicts(X1, W1, partials, residual, weight, eps, W2, out,
+    residual_out, Y), all with the same number of rows; every tensor must be given. Returns None."""
+    n = len(boundaries)
+    arr = (LayerArgs * max(n, 1))()
+    keep = []
+    for i, b in enumerate(boundaries):
+        a, k, out, residual_out = _fused_pack(b["partials"], b["residual"], b["weight"], b["eps"], fused_cu_budget,
+                                              b["out"], b["residual_out"])
+        T, H = b["residual"].shape
+        K1, N2 = b["X1"].shape[1], b["W2"].shape[0]
+        arr[i] = LayerArgs(_bf16_ptr(b["X1"], "X1", (T, K1)), _bf16_ptr(b["W1"], "W1", (H, K1)), K1, a,
+                           _bf16_ptr(b["W2"], "W2", (N2, H)), N2, _bf16_ptr(b["Y"], "Y", (T, N2)), int(gemm_cu_budget),
+                           int(schedule))
+        keep.append(k)
+    _check(lib().tw_weave_train(arr, n, int(split_row), _stream_handle(stream_compute), _stream_handle(stream_comm),
+                                _stream_handle(parent) if use_parent else _vp(None),
+                                1 if use_parent else 0, 1 if join else 0), "tw_weave_train")
 
 
 def weave_layer_auto(X1, W1, partials, residual, weight, eps, W2, stream_compute, stream_comm, threshold=0,

@@ -428,6 +428,33 @@ tw_status tw_weave_layer_cuts(const tw_layer_args *layer, const int64_t *cuts, i
     return TW_OK;
 }
 
+tw_status tw_weave_train(const tw_layer_args *layers, int n_layers, int64_t split_row, void *stream_compute,
+                         void *stream_comm, void *parent, int parent_is_set, int join)
+{
+    if (n_layers < 0 || n_layers > TW_MAX_TRAIN) return TW_ERR_SHAPE;
+    if (n_layers == 0) return TW_OK;
+    if (!layers) return TW_ERR_NULL;
+    // everything is checked before anything is launched
+    const int64_t T = layers[0].fused.N;
+    for (int i = 0; i < n_layers; ++i) {
+        tw_gemm_args g1, g2;
+        TW_TRY(validate_layer(&layers[i], stream_compute, stream_comm, &g1, &g2));
+        if (layers[i].fused.N != T) return TW_ERR_SHAPE;
+    }
+    if (split_row < 0 || split_row > T) return TW_ERR_SPLIT;
+    const bool whole = split_row == 0 || split_row == T;
+    for (int i = 0; i < n_layers; ++i)
+        TW_TRY(tw_weave_layer_cuts(&layers[i], &split_row, whole ? 0 : 1, stream_compute, stream_comm, parent,
+                                   (i == 0 && parent_is_set) ? 1 : 0, 0));
+    if (parent_is_set && join && T > 0) {
+        hipStream_t sx = static_cast<hipStream_t>(stream_compute), sc = static_cast<hipStream_t>(stream_comm);
+        hipStream_t sp = static_cast<hipStream_t>(parent);
+        if (sx != sp) TW_TRY(stream_wait_stream(sp, sx));
+        if (!whole && sc != sp) TW_TRY(stream_wait_stream(sp, sc));
+    }
+    return TW_OK;
+}
+
 tw_status tw_weave_layer(const tw_layer_args *layer, int64_t split_row, void *stream_compute,
                          void *stream_comm, void *parent, int parent_is_set, int join)
 {

@@ -29,7 +29,7 @@ def declared_functions(headers=("tw.h", "tw_measure.h")):
 def test_header_declares_the_documented_entry_points():
     names = declared_functions(("tw.h",))
     for must in ("tw_reduce_add_rmsnorm", "tw_split_launch", "tw_split_point", "tw_gemm_bf16",
-                 "tw_overlap_launch", "tw_weave_layer", "tw_weave_layer_cuts", "tw_weave_layer_auto", "tw_weave_tune", "tw_smart_split_point",
+                 "tw_overlap_launch", "tw_weave_layer", "tw_weave_layer_cuts", "tw_weave_train", "tw_weave_layer_auto", "tw_weave_tune", "tw_smart_split_point",
                  "tw_should_split", "tw_split_threshold", "tw_policy_split_row", "tw_device_cu_count", "tw_status_str",
                  "tw_version", "tw_last_hip_error"):
         assert must in names
@@ -438,6 +438,41 @@ def test_weave_layer_cuts_argument_checks():
     la.fused.N = 0                  # an empty batch has no row to cut at
     assert call(la, []) == OK
     assert call(la, [1]) == E_SPLIT
+
+
+def test_weave_train_argument_checks():
+    """Every boundary of a train is checked before anything is launched."""
+    from paper_2505_11329_amd.binding import LayerArgs
+    L = tw.lib()
+    arr = (VP * P)(addr(0), addr(1))
+
+    def boundary(n=N):
+        f = FusedArgs(ctypes.cast(arr, ctypes.POINTER(VP)), addr(4), addr(5), 1e-5, n, H, P, 8, addr(6), addr(7))
+        return LayerArgs(addr(10), addr(11), 64, f, addr(12), 64, addr(13), 0)
+    las = (LayerArgs * 3)(boundary(), boundary(), boundary())
+
+    def call(n=3, split=2, sx=1, sc=2, ptr=las):
+        return L.tw_weave_train(ptr, n, split, VP(sx), VP(sc), VP(None), 0, 0)
+    assert call(n=-1) == E_SHAPE
+    assert call(n=4097) == E_SHAPE
+    assert call(n=0, ptr=None) == OK
+    assert call(ptr=None) == E_NULL
+    assert call(split=-1) == E_SPLIT
+    assert call(split=N + 1) == E_SPLIT
+    assert call(sx=3, sc=3) == E_SPLIT
+    las[2].fused.N = N + 1                     # token counts differ
+    assert call() == E_SHAPE
+    las[2].fused.N = N
+    las[1].Y = addr(6)                         # the second boundary's Y on top of its fused output
+    assert call() == E_ALIAS
+    las[1].Y = addr(13)
+    las[2].K1 = 12
+    assert call() == E_UNSUP
+    las[2].K1 = 64
+    for i in range(3):
+        las[i].fused.N = 0                     # an empty train: nothing to launch
+    assert call(split=0) == OK
+    assert call(split=1) == E_SPLIT
 
 
 def test_split_threshold_matches_its_definition():

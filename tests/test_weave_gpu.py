@@ -341,6 +341,46 @@ def test_two_boundaries_woven_through_without_a_join_in_between(tw, torch_cuda, 
             assert np.array_equal(g_, w_), (schedule, cut, name)
 
 
+@pytest.mark.parametrize("schedule", [1, 2])   # TW_WEAVE_ORDERED, TW_WEAVE_CHAINS
+def test_weave_train_of_four_boundaries_gives_the_unsplit_bits(tw, torch_cuda, schedule):
+    """tw_weave_train: four boundaries, each fed by the one before (X1 = previous Y, residual = previous
+    residual_out), forked from a parent that still holds the writing of the first input and joined
+    into it; the woven train's outputs carry the bits of the same train unsplit."""
+    torch = torch_cuda
+    g1, f, W2 = make_inputs()
+    sx, sc, parent = torch.cuda.Stream(), torch.cuda.Stream(), torch.cuda.Stream()
+    X1_src, resid = to_gpu(g1["A"]), to_gpu(f["residual"])
+    weight = to_gpu(f["weight"])
+    dims = [(K1, N2), (N2, K1), (K1, N2), (N2, 64)]             # (depth of G1, width of G2) per boundary
+    Ws = [(to_gpu(W.normal_bf16((H, k), 0.05, 40 + i, W.STREAM_GEMM_B)),
+           to_gpu(W.normal_bf16((n, H), 0.05, 50 + i, W.STREAM_GEMM_B))) for i, (k, n) in enumerate(dims)]
+
+    def run_train(cut):
+        src = torch.zeros_like(X1_src)
+        bs, x, r = [], src, resid
+        for i, (k, n) in enumerate(dims):
+            parts = [torch.full((T, H), float("nan"), dtype=torch.bfloat16, device="cuda:0")] + \
+                    [to_gpu(p) for p in f["partials"][1:]]
+            b = dict(X1=x, W1=Ws[i][0], partials=parts, residual=r, weight=weight, eps=f["eps"], W2=Ws[i][1],
+                     out=torch.empty((T, H), dtype=torch.bfloat16, device="cuda:0"),
+                     residual_out=torch.empty((T, H), dtype=torch.bfloat16, device="cuda:0"),
+                     Y=torch.full((T, n), float("nan"), dtype=torch.bfloat16, device="cuda:0"))
+            bs.append(b)
+            x, r = b["Y"], b["residual_out"]
+        torch.cuda.synchronize()
+        with torch.cuda.stream(parent):
+            src.copy_(X1_src)
+        tw.weave_train(bs, cut, sx, sc, parent=parent, use_parent=True, join=True, schedule=schedule)
+        parent.synchronize()
+        return [to_bits(b[k]) for b in bs for k in ("Y", "residual_out", "out")]
+    want = run_train(0)
+    assert not np.isnan(oracle.bf16_to_f64(want[-3])).any()
+    for cut in (320, 256, 1, T - 1, T):
+        got = run_train(cut)
+        for i, (g_, w_) in enumerate(zip(got, want)):
+            assert np.array_equal(g_, w_), (schedule, cut, i)
+
+
 def test_weave_layer_random_shapes_cuts_and_schedules(tw, torch_cuda):
     """Ragged layer boundaries (hidden sizes that are no power of two, odd token counts, P from 1 to 5,
     GEMM widths and depths that are no multiple of a tile) through tw_weave_layer_cuts with random cuts,
