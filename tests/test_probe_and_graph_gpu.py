@@ -99,6 +99,55 @@ def test_weave_layer_can_be_captured_in_a_hip_graph(tw, torch_cuda, schedule):
         torch.cuda.synchronize()
 
 
+@pytest.mark.parametrize("schedule", [1, 2])   # TW_WEAVE_ORDERED, TW_WEAVE_CHAINS
+def test_weave_train_can_be_captured_in_a_hip_graph(tw, torch_cuda, schedule):
+    """A woven train of boundaries is what an engine would capture once per batch shape: one fork from the
+    caller's stream, the two chains running through three boundaries (each fed by the one before), one
+    join. Every replay must reproduce the eager result bit for bit."""
+    torch = torch_cuda
+    T, K1, H, P, N2 = 512, 256, 2048, 4, 256
+    g1 = W.make_gemm_inputs(T, K1, H, 0.1, seed=3, b_layout="nk")
+    f = W.make_fused_inputs(dict(N=T, H=H, P=P, partial_std=0.5, residual_std=1.0, outlier_frac=0.0,
+                                 outlier_scale=1.0, eps=1e-5, seed=5))
+    X1, weight = to_gpu(g1["A"]), to_gpu(f["weight"])
+    main, comm = torch.cuda.Stream(), torch.cuda.Stream()
+    bs, x, r = [], X1, to_gpu(f["residual"])
+    for i in range(3):
+        b = dict(X1=x, W1=to_gpu(W.normal_bf16((H, K1), 0.1, 60 + i, W.STREAM_GEMM_B)),
+                 partials=[torch.zeros((T, H), dtype=torch.bfloat16, device="cuda:0")] + [to_gpu(p) for p in f["partials"][1:]],
+                 residual=r, weight=weight, eps=f["eps"], W2=to_gpu(W.normal_bf16((N2, H), 0.05, 70 + i, W.STREAM_GEMM_B)),
+                 out=torch.empty((T, H), dtype=torch.bfloat16, device="cuda:0"),
+                 residual_out=torch.empty((T, H), dtype=torch.bfloat16, device="cuda:0"),
+                 Y=torch.empty((T, N2), dtype=torch.bfloat16, device="cuda:0"))
+        bs.append(b)
+        x, r = b["Y"], b["residual_out"]
+
+    def train():
+        tw.weave_train(bs, 256, main, comm, parent=main, use_parent=True, join=True, schedule=schedule)
+    with torch.cuda.stream(main):
+        train()                                   # eager: also the warm-up that capture needs
+    torch.cuda.synchronize()
+    want = [to_bits(b[k]).copy() for b in bs for k in ("Y", "residual_out", "out")]
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph, stream=main):
+        train()
+    for rep in range(3):
+        with torch.cuda.stream(main):
+            for b in bs:
+                b["Y"].zero_()
+                b["out"].zero_()
+                b["residual_out"].zero_()
+                b["partials"][0].zero_()
+            graph.replay()
+        main.synchronize()
+        got = [to_bits(b[k]) for b in bs for k in ("Y", "residual_out", "out")]
+        for i, (g_, w_) in enumerate(zip(got, want)):
+            assert np.array_equal(g_, w_), (rep, i)
+        with torch.cuda.stream(main):            # eager work between replays
+            tw.reduce_add_rmsnorm(bs[0]["partials"], bs[0]["residual"], weight, f["eps"], cu_budget=8)
+        torch.cuda.synchronize()
+
+
 def test_shaped_probes_move_the_same_bytes_in_every_shape(tw, torch_cuda):
     """Workgroup size and accesses in flight change the launch, not what is copied."""
     torch = torch_cuda
