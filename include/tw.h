@@ -393,6 +393,7 @@ tw_status tw_weave_layer_cuts(const tw_layer_args *layer, const int64_t *cuts, i
  * out of range.
  */
 #define TW_MAX_TRAIN 4096
+#define TW_TRAIN_SPLIT_THRESHOLD 3072 /* tokens from which a train of 70B-class boundaries gains when woven (MI355X) */
 tw_status tw_weave_train(const tw_layer_args *layers, int n_layers, int64_t split_row, void *stream_compute,
                          void *stream_comm, void *parent, int parent_is_set, int join);
 
