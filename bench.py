@@ -101,7 +101,7 @@ def main():
                          "kernel is measured against")
     ap.add_argument("--gemm-phases", action="store_true",
                     help="where the clocks of the 256x256 GEMM tile's K loop go (tw_gemm_bf16_traced), as JSON")
-    ap.add_argument("--counters-run", choices=("fused", "gemm", "weave", "probe"), default=None,
+    ap.add_argument("--counters-run", choices=("fused", "gemm", "weave", "probe", "train"), default=None,
                     help="for rocprofv3 --pmc. fused: a few fused launches plus plain copy launches of known "
                          "size (tw_hbm_probe, 192 MiB read + 192 MiB written each) to scale the byte counters "
                          "by. gemm: a few launches of the bf16 GEMM on the overlap demo's shape. weave (for "
@@ -386,6 +386,32 @@ def main():
                 torch.cuda.synchronize()
         print(json.dumps({"counters_run": "weave", "T": T, "split_row": k, "calls_per_schedule": 5,
                           "order": [o[0] for o in order]}))
+        return
+    if args.counters_run == "train":
+        # three unsplit and three woven trains of eight boundaries (attention side, MLP side alternating)
+        # at T = 8192, each followed by a device synchronisation
+        T, H, P, L = 8192, 8192, 8, 8
+        gen = torch.Generator(device=dev)
+        gen.manual_seed(0)
+
+        def rnd(shape, std):
+            return torch.empty(shape, dtype=torch.bfloat16, device=dev).normal_(0.0, std, generator=gen)
+        shapes = [(1024, 3584), (3584, 1280)]
+        weight = gpu(W.uniform_bf16((H,), 0.5, 1.5, 0, W.STREAM_WEIGHT))
+        bufs = [dict(X1=rnd((T, K1), 0.02), W1=rnd((H, K1), 0.02), partials=[rnd((T, H), 0.25) for _ in range(P)],
+                     residual=rnd((T, H), 1.0), weight=weight, eps=1e-5, W2=rnd((N2, H), 0.02),
+                     out=torch.empty((T, H), dtype=torch.bfloat16, device=dev),
+                     residual_out=torch.empty((T, H), dtype=torch.bfloat16, device=dev),
+                     Y=torch.empty((T, N2), dtype=torch.bfloat16, device=dev)) for (K1, N2) in shapes]
+        train = [bufs[i % 2] for i in range(L)]
+        comm = overlapping_stream(tw, torch, [stream])
+        torch.cuda.synchronize()
+        for cut in (0, 0, 0, T // 2, T // 2, T // 2):
+            with torch.cuda.stream(stream):
+                tw.weave_train(train, cut, stream, comm, parent=stream, use_parent=True, join=True)
+            torch.cuda.synchronize()
+        print(json.dumps({"counters_run": "train", "T": T, "boundaries": L, "split_row": T // 2,
+                          "order": ["unsplit"] * 3 + ["woven"] * 3}))
         return
     if args.counters_run == "gemm":
         # the three tile shapes the library builds: the overlap demo's product takes 256 x 128 tiles, the
